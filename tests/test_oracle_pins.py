@@ -1,0 +1,399 @@
+"""Pins for the CPU oracle: it is checked against things other than itself —
+hand-worked fixtures, brute-force sorting, exact identities that follow from
+Eq. (11) and Eq. (8) of the paper (Sec. III.B), closed-form quantiles, and
+special cases that reduce to a library routine. No GPU needed."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_17551_amd import inputs
+from tests.conftest import read_golden
+
+
+def f32(xs):
+    return np.array([float(x) for x in xs], dtype=np.float32)
+
+
+def keys_of(x):
+    return x.view(np.uint32) & np.uint32(0x7FFFFFFF)
+
+
+def brute_force_topk(acc, k):
+    """Definition written out: order all entries by (magnitude desc, index asc), take k."""
+    key = keys_of(acc).astype(np.int64)
+    order = np.lexsort((np.arange(acc.size), -key))  # primary: -key, secondary: index
+    return np.sort(order[:k])
+
+
+def dequant(q, s, block):
+    """fl32(q * s) per entry, scale looked up by block of consecutive kept entries."""
+    j = np.arange(q.size)
+    return (q.astype(np.float32) * s[j // block]).astype(np.float32)
+
+
+# ----------------------------------------------------------------- golden fixtures
+def test_golden_quant_block(oracle):
+    G = read_golden("quant_block.txt")
+    g, e = f32(G["g"]), f32(G["e0"])
+    rc, idx, q, s = oracle.compress(g, e, int(G["k"][0]), int(G["block"][0]))
+    assert rc == oracle.OK
+    assert idx.tolist() == [int(x) for x in G["idx"]]
+    assert q.tolist() == [int(x) for x in G["q"]]
+    assert s.tolist() == [float(x) for x in G["scales"]]
+    assert e.tolist() == f32(G["e1"]).tolist()
+
+
+def test_golden_select_ties(oracle):
+    G = read_golden("select_ties.txt")
+    g, e = f32(G["g"]), f32(G["e0"])
+    rc, idx, q, s = oracle.compress(g, e, int(G["k"][0]), int(G["block"][0]))
+    assert rc == oracle.OK
+    assert idx.tolist() == [int(x) for x in G["idx"]]
+    assert q.tolist() == [int(x) for x in G["q"]]
+    assert s[0] == np.float32(5.0) / np.float32(127.0)
+
+
+def test_golden_ef_two_steps(oracle):
+    G = read_golden("ef_two_steps.txt")
+    e = np.zeros(4, dtype=np.float32)
+    k, block = int(G["k"][0]), int(G["block"][0])
+    rc, idx, q, s = oracle.compress(f32(G["g1"]), e, k, block)
+    assert (rc, idx.tolist(), q.tolist()) == (0, [int(G["idx1"][0])], [int(G["q1"][0])])
+    assert e.tolist() == f32(G["e1"]).tolist()
+    rc, idx, q, s = oracle.compress(f32(G["g2"]), e, k, block)
+    assert (rc, idx.tolist(), q.tolist()) == (0, [int(G["idx2"][0])], [int(G["q2"][0])])
+    assert e.tolist() == f32(G["e2"]).tolist()
+
+
+def test_golden_k_rule(oracle):
+    for n, d, k in read_golden("k_rule.txt")["rows"]:
+        assert oracle.k_from_density(int(n), float(d)) == int(k), (n, d)
+
+
+def test_golden_aggregate(oracle):
+    G = read_golden("aggregate.txt")
+    bufs = []
+    for w in range(3):
+        bufs.append((np.array([int(x) for x in G[f"idx{w}"]], dtype=np.uint32),
+                     np.array([int(x) for x in G[f"q{w}"]], dtype=np.int8), f32(G[f"s{w}"])))
+    rc, out = oracle.decompress_sum(bufs, int(G["n"][0]), int(G["block"][0]))
+    assert rc == 0 and out.tolist() == f32(G["out"]).tolist()
+    # 64-bit indices give the same aggregate
+    bufs64 = [(b[0].astype(np.uint64), b[1], b[2]) for b in bufs]
+    rc, out64 = oracle.decompress_sum(bufs64, int(G["n"][0]), int(G["block"][0]))
+    assert rc == 0 and out64.tolist() == out.tolist()
+
+
+# ----------------------------------------------------------------- selection
+@pytest.mark.parametrize("n,k", [(1, 1), (7, 3), (64, 1), (257, 100), (1000, 10), (4096, 41),
+                                 (4096, 4095), (4096, 4096), (3001, 1500)])
+@pytest.mark.parametrize("alphabet", [(0.0, -0.0, 1.0, -1.0, 2.0), (1.0, -1.0, 1.0000001),
+                                      (0.0, -0.0), (3.0,), (1e-40, -1e-40, 2e-40, 0.0, 1e-38)])
+def test_selection_equals_full_sort_with_ties(oracle, n, k, alphabet):
+    g = inputs.tie_alphabet(n, alphabet, seed=n * 31 + k).numpy()
+    r0 = inputs.tie_alphabet(n, alphabet, seed=n * 17 + k + 5).numpy()
+    acc = (g + r0).astype(np.float32)
+    e = r0.copy()
+    rc, idx, q, s = oracle.compress(g, e, k, 16)
+    assert rc == oracle.OK
+    want = brute_force_topk(acc, k)
+    assert idx.dtype == np.uint32 and np.array_equal(idx.astype(np.int64), want)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_selection_equals_full_sort_gaussian(oracle, seed):
+    n, k = 5000 + 37 * seed, 50 + seed
+    g = inputs.normal(n, 1.0, seed).numpy()
+    r0 = inputs.normal(n, 0.3, seed + 100).numpy()
+    e = r0.copy()
+    rc, idx, q, s = oracle.compress(g, e, k, 8)
+    assert rc == 0
+    assert np.array_equal(idx.astype(np.int64), brute_force_topk((g + r0).astype(np.float32), k))
+    # reduces to a library routine when there are no ties: torch.topk on |acc|
+    tk = torch.topk(torch.from_numpy(np.abs((g + r0).astype(np.float32))), k).indices.numpy()
+    assert np.array_equal(np.sort(tk), idx.astype(np.int64))
+
+
+def test_selection_counts_and_special_cases(oracle):
+    n = 3000
+    g = inputs.normal(n, 1.0, 7).numpy()
+    for k in (1, 2, 299, n - 1, n):
+        e = np.zeros(n, dtype=np.float32)
+        rc, idx, q, s = oracle.compress(g, e, k, 64)
+        assert rc == 0 and idx.size == k
+        assert np.all(np.diff(idx.astype(np.int64)) > 0)          # strictly ascending, unique
+        kept = np.zeros(n, bool)
+        kept[idx] = True
+        kk = keys_of(g)
+        if k < n:
+            assert kk[kept].min() >= kk[~kept].max()               # nothing dropped beats a kept one
+    # k = 1 is the argmax of |acc| with the lowest index on ties
+    g2 = np.array([1, -5, 5, 2, -5], dtype=np.float32)
+    rc, idx, _, _ = oracle.compress(g2, np.zeros(5, np.float32), 1, 4)
+    assert idx.tolist() == [1]
+    # all-equal input: the first k indices
+    rc, idx, _, _ = oracle.compress(np.full(100, -2.5, np.float32), np.zeros(100, np.float32), 33, 8)
+    assert idx.tolist() == list(range(33))
+    # density 1 keeps everything ("identity" on the index set)
+    rc, idx, _, _ = oracle.compress(g, np.zeros(n, np.float32), oracle.k_from_density(n, 1.0), 64)
+    assert idx.tolist() == list(range(n))
+
+
+def test_selection_uses_accumulated_value_not_gradient(oracle):
+    # Eq. (11) only closes if ghat is built from r_t + g: a large residual must win.
+    g = np.array([0.1, 0.2, 0.3, 0.4], np.float32)
+    e = np.array([5.0, 0, 0, 0], np.float32)
+    rc, idx, q, s = oracle.compress(g, e, 1, 4)
+    assert idx.tolist() == [0]
+    assert s[0] == np.float32(np.float32(5.1) / np.float32(127)) and q.tolist() == [127]
+
+
+# ----------------------------------------------------------------- Eq. (11): exact invariant
+def _dists(n, seed):
+    yield "gauss", inputs.normal(n, 1.0, seed).numpy(), inputs.normal(n, 0.5, seed + 1).numpy()
+    yield "t3", inputs.student_t3(n, 1e-3, seed + 2).numpy(), inputs.student_t3(n, 1e-3, seed + 3).numpy()
+    yield ("mix", inputs.outlier_mixture(n, 1e-3, 0.01, 100.0, seed + 4).numpy(),
+           inputs.outlier_mixture(n, 1e-3, 0.01, 100.0, seed + 5).numpy())
+    yield "tiny", inputs.normal(n, 1e-30, seed + 6).numpy(), inputs.normal(n, 1e-30, seed + 7).numpy()
+    yield "huge", inputs.normal(n, 1e30, seed + 8).numpy(), inputs.normal(n, 1e30, seed + 9).numpy()
+    yield "subn", inputs.normal(n, 3e-39, seed + 10).numpy(), inputs.normal(n, 1e-39, seed + 11).numpy()
+
+
+@pytest.mark.parametrize("block", [1, 7, 256])
+def test_transmitted_plus_residual_is_acc_exactly(oracle, block):
+    n = 20000
+    for name, g, r0 in _dists(n, 11):
+        acc = (g + r0).astype(np.float32)
+        for k in (1, 200, 2001, n):
+            e = r0.copy()
+            rc, idx, q, s = oracle.compress(g, e, k, block)
+            assert rc == 0, name
+            d = np.zeros(n, np.float32)
+            d[idx] = dequant(q, s, block)
+            assert np.array_equal((d + e).astype(np.float32), acc), (name, k)   # Eq. (11), exact in fp32
+            # and the subtraction itself was exact: e' = acc - d in real arithmetic
+            assert np.array_equal(acc.astype(np.float64) - d.astype(np.float64), e.astype(np.float64)), (name, k)
+            # not-kept entries carry acc bit for bit
+            mask = np.ones(n, bool)
+            mask[idx] = False
+            assert np.array_equal(e[mask].view(np.uint32), acc[mask].view(np.uint32))
+
+
+def test_bf16_gradient_widens_exactly(oracle):
+    n, k = 10000, 100
+    gb = inputs.student_t3(n, 1e-3, 3).to(torch.bfloat16)
+    r0 = inputs.normal(n, 1e-4, 4).numpy()
+    e1, e2 = r0.copy(), r0.copy()
+    rc1, i1, q1, s1 = oracle.compress(inputs.bf16_bits(gb), e1, k, 32)
+    rc2, i2, q2, s2 = oracle.compress(gb.to(torch.float32).numpy(), e2, k, 32)
+    assert rc1 == rc2 == 0
+    assert np.array_equal(i1, i2) and np.array_equal(q1, q2) and np.array_equal(s1, s2)
+    assert np.array_equal(e1.view(np.uint32), e2.view(np.uint32))
+
+
+# ----------------------------------------------------------------- quantizer properties
+def test_quantizer_properties(oracle):
+    n, k, block = 8192, 8192, 64
+    for name, g, r0 in _dists(n, 23):
+        e = r0.copy()
+        acc = (g + r0).astype(np.float32)
+        rc, idx, q, s = oracle.compress(g, e, k, block)
+        assert rc == 0
+        assert q.min() >= -127 and q.max() <= 127
+        v = acc.reshape(-1, block)
+        amax = np.abs(v).max(axis=1)
+        want_s = (amax / np.float32(127)).astype(np.float32)
+        want_s[want_s < np.finfo(np.float32).tiny] = 0
+        assert np.array_equal(s, want_s), name
+        qb = q.reshape(-1, block)
+        nz = s > 0
+        # the entry attaining amax gets code +-127
+        assert np.all(np.abs(qb[nz]).max(axis=1) == 127), name
+        assert np.all(qb[~nz] == 0)
+        # |v - d| <= s (1/2 + 2^-16): half a step, plus the fp32 rounding of the quotient
+        # (<= 127 * 2^-24 steps) and of the product q*s (<= 127 * 2^-24 steps)
+        d = dequant(q, s, block).reshape(-1, block)
+        err = np.abs(v.astype(np.float64) - d.astype(np.float64))
+        assert np.all(err[nz] <= s.astype(np.float64)[nz][:, None] * (0.5 + 2.0 ** -16)), name
+        # codes are rint(v/s) ties-to-even, computed here in float64 from the fp32 quotient
+        with np.errstate(divide="ignore", invalid="ignore"):
+            quo = (v[nz] / s[nz][:, None]).astype(np.float32)
+        assert np.array_equal(qb[nz], np.clip(np.rint(quo), -127, 127).astype(np.int8)), name
+
+
+def test_quantizer_scale_equivariance_and_zero_block(oracle):
+    n = 512
+    g = inputs.normal(n, 1.0, 5).numpy()
+    rc, idx, q, s = oracle.compress(g, np.zeros(n, np.float32), n, 32)
+    for m in (-20, 3, 40):
+        g2 = np.ldexp(g, m).astype(np.float32)
+        rc2, idx2, q2, s2 = oracle.compress(g2, np.zeros(n, np.float32), n, 32)
+        assert np.array_equal(q, q2) and np.array_equal(np.ldexp(s, m).astype(np.float32), s2)
+    z = np.zeros(64, np.float32)
+    z[1] = -0.0
+    e = z.copy()
+    rc, idx, q, s = oracle.compress(z, e, 64, 32)
+    assert rc == 0 and not q.any() and not s.any() and not e.any()
+    # a block whose scale would be subnormal is sent as zeros and stays in the residual
+    t = np.full(8, 1e-38, np.float32)
+    e = np.zeros(8, np.float32)
+    rc, idx, q, s = oracle.compress(t, e, 8, 8)
+    assert rc == 0 and s[0] == 0 and not q.any() and np.array_equal(e, t)
+
+
+def test_nonfinite_is_reported(oracle):
+    g = inputs.normal(100, 1.0, 1).numpy()
+    for bad in (np.inf, -np.inf, np.nan):
+        g2 = g.copy()
+        g2[37] = bad
+        rc, *_ = oracle.compress(g2, np.zeros(100, np.float32), 5, 4)
+        assert rc == oracle.ERR_NONFINITE
+
+
+def test_argument_errors(oracle):
+    g = np.zeros(10, np.float32)
+    e = np.zeros(10, np.float32)
+    assert oracle.compress(g, e, 0, 4)[0] == oracle.ERR_INVALID_ARG
+    assert oracle.compress(g, e, 11, 4)[0] == oracle.ERR_INVALID_ARG
+    assert oracle.compress(g, e, 3, 0)[0] == oracle.ERR_INVALID_ARG
+    assert oracle.compress(g, e, 3, 4, index_bits=16)[0] == oracle.ERR_INVALID_ARG
+
+
+# ----------------------------------------------------------------- telescoping of Eq. (11)
+def test_error_feedback_telescopes(oracle):
+    n, k, block, steps = 30000, 300, 64, 10
+    e = inputs.normal(n, 0.1, 99).numpy()
+    lhs = e.astype(np.float64).copy()      # sum_t g_t + e_0
+    sent = np.zeros(n, np.float64)         # sum_t d_t
+    amax = 0.0
+    for t in range(steps):
+        g = inputs.normal(n, 1.0, 200 + t).numpy()
+        lhs += g
+        amax = max(amax, float(np.abs(g + e).max()))
+        rc, idx, q, s = oracle.compress(g, e, k, block)
+        assert rc == 0
+        sent[idx] += dequant(q, s, block)
+    # each step contributes one fp32 rounding of acc (the add); the rest is exact
+    assert np.abs(sent + e - lhs).max() <= steps * 2.0 ** -24 * amax * 1.01
+
+
+# ----------------------------------------------------------------- aggregate (Eq. 8 x P)
+def _compress_worker(oracle, n, k, block, seed, bits=32):
+    g = inputs.normal(n, 1.0, seed).numpy()
+    e = np.zeros(n, np.float32)
+    rc, idx, q, s = oracle.compress(g, e, k, block, index_bits=bits)
+    assert rc == 0
+    return idx, q, s
+
+
+def test_aggregate_properties(oracle):
+    n, k, block = 10000, 500, 32
+    b0 = _compress_worker(oracle, n, k, block, 1)
+    # W = 1: d at kept positions, +0 elsewhere
+    rc, out = oracle.decompress_sum([b0], n, block)
+    want = np.zeros(n, np.float32)
+    want[b0[0]] = dequant(b0[1], b0[2], block)
+    assert rc == 0 and np.array_equal(out.view(np.uint32), want.view(np.uint32))
+    # two identical buffers: exactly 2 d (doubling is exact in binary floating point)
+    rc, out2 = oracle.decompress_sum([b0] * 2, n, block)
+    assert np.array_equal(out2, want * np.float32(2))
+    # with power-of-two scales d has at most 7 significant bits, so W d is exact for any small W
+    bp = (b0[0], b0[1], np.exp2(np.floor(np.log2(b0[2]))).astype(np.float32))
+    dp = np.zeros(n, np.float32)
+    dp[bp[0]] = dequant(bp[1], bp[2], block)
+    rc, out7 = oracle.decompress_sum([bp] * 7, n, block)
+    assert np.array_equal(out7, dp * np.float32(7))
+    # different workers: equals the float64 sum within the fp32 summation bound
+    W = 16
+    bufs = [_compress_worker(oracle, n, k, block, 10 + w) for w in range(W)]
+    rc, out = oracle.decompress_sum(bufs, n, block)
+    ref = np.zeros(n, np.float64)
+    mag = np.zeros(n, np.float64)
+    for idx, q, s in bufs:
+        d = dequant(q, s, block).astype(np.float64)
+        ref[idx] += d
+        mag[idx] += np.abs(d)
+    assert np.all(np.abs(out - ref) <= (W - 1) * 2.0 ** -24 * mag + 1e-300)
+    # canonical order: worker by worker fp32 adds (np.add.at on float32 is unbuffered, in order)
+    seq = np.zeros(n, np.float32)
+    for idx, q, s in bufs:
+        seq[idx] = (seq[idx] + dequant(q, s, block)).astype(np.float32)
+    assert np.array_equal(out.view(np.uint32), seq.view(np.uint32))
+    # disjoint supports: any worker order gives the same bytes
+    parts = []
+    for w in range(4):
+        idx = np.arange(w, n, 40, dtype=np.uint32)
+        parts.append((idx, np.full(idx.size, 3 * w - 5, np.int8),
+                      np.full((idx.size + block - 1) // block, 0.125 * (w + 1), np.float32)))
+    rc, o1 = oracle.decompress_sum(parts, n, block)
+    rc, o2 = oracle.decompress_sum(parts[::-1], n, block)
+    assert np.array_equal(o1.view(np.uint32), o2.view(np.uint32))
+
+
+def test_mean_of_uncompressed_gradients_is_recovered_at_density_one(oracle):
+    # With every entry kept, Eq. (8) is recovered up to the int8 error: |mean - g_bar| <= mean(s)/2.
+    n, W, block = 4096, 4, 64
+    gs = [inputs.normal(n, 1.0, 50 + w).numpy() for w in range(W)]
+    bufs, smax = [], np.zeros(n, np.float64)
+    for g in gs:
+        rc, idx, q, s = oracle.compress(g, np.zeros(n, np.float32), n, block)
+        bufs.append((idx, q, s))
+        smax += np.repeat(s.astype(np.float64), block)
+    rc, out = oracle.decompress_sum(bufs, n, block)
+    gbar = np.sum(np.stack(gs).astype(np.float64), axis=0)
+    assert np.all(np.abs(out - gbar) <= smax * 0.5 * 1.001 + 1e-5)
+
+
+# ----------------------------------------------------------------- multi-tensor form
+def test_multi_equals_per_tensor_calls(oracle):
+    sizes = [768, 5, 2304, 1, 4096, 1000]
+    off = inputs.offsets_of(sizes)
+    n = int(off[-1])
+    g = inputs.normal(n, 0.02, 8).numpy()
+    r0 = inputs.normal(n, 0.01, 9).numpy()
+    ks = np.array([oracle.k_from_density(s, 0.01) for s in sizes], dtype=np.int64)
+    block = 4
+    e = r0.copy()
+    rc, idx, q, s = oracle.compress_multi(g, e, off, ks, block)
+    assert rc == 0
+    kp = sp = 0
+    bufs_sep = np.zeros(n, np.float32)
+    for t, sz in enumerate(sizes):
+        a, b = int(off[t]), int(off[t + 1])
+        et = r0[a:b].copy()
+        rc, it, qt, st = oracle.compress(g[a:b].copy(), et, int(ks[t]), block)
+        assert np.array_equal(idx[kp:kp + ks[t]], it + a)
+        assert np.array_equal(q[kp:kp + ks[t]], qt)
+        assert np.array_equal(s[sp:sp + st.size], st)
+        assert np.array_equal(e[a:b], et)
+        bufs_sep[it + a] = dequant(qt, st, block)
+        kp += int(ks[t])
+        sp += st.size
+    assert kp == idx.size and sp == s.size
+    rc, out = oracle.decompress_sum([(idx, q, s)], n, block, ktensor=ks)
+    assert rc == 0 and np.array_equal(out.view(np.uint32), bufs_sep.view(np.uint32))
+
+
+# ----------------------------------------------------------------- closed-form quantiles
+def test_threshold_matches_closed_form_quantile(oracle):
+    from scipy import stats
+    n = 1 << 20
+    # N(0,1), two-sided 1 %: |x| quantile 2.5758
+    g = inputs.workload(1).grad(0, 0, "cpu").numpy()
+    k = oracle.k_from_density(n, 0.01)
+    e = np.zeros(n, np.float32)
+    rc, idx, q, s = oracle.compress(g, e, k, 256)
+    thr = np.abs(g[idx]).min()
+    assert abs(thr / stats.norm.isf(0.005) - 1) < 0.02
+    # Student-t(3) * 1e-3, two-sided 0.5 %
+    g = inputs.student_t3(n, 1e-3, 77).numpy()
+    k = oracle.k_from_density(n, 0.005)
+    rc, idx, q, s = oracle.compress(g, np.zeros(n, np.float32), k, 1024)
+    thr = np.abs(g[idx]).min()
+    assert abs(thr / (1e-3 * stats.t.isf(0.0025, 3)) - 1) < 0.05
+    # outlier mixture with zero residual at 0.1 %: all winners are outliers, N(0, 0.1) two-sided 10 %
+    g = inputs.outlier_mixture(n, 1e-3, 0.01, 100.0, 78).numpy()
+    k = oracle.k_from_density(n, 0.001)
+    rc, idx, q, s = oracle.compress(g, np.zeros(n, np.float32), k, 2048)
+    thr = np.abs(g[idx]).min()
+    assert abs(thr / (0.1 * stats.norm.isf(0.05)) - 1) < 0.05
