@@ -1,0 +1,140 @@
+/* gradcomp — error-feedback top-k gradient compression with per-block int8
+ * quantization, and the matching decompress-and-sum, for one MI355X (gfx950).
+ *
+ * C ABI. Every data pointer is DEVICE memory owned by the caller unless a
+ * comment says "host". The library allocates only its own scratch workspace
+ * (inside gc_ctx); it never frees or resizes caller memory. All work is queued
+ * on the HIP stream the caller passes (a hipStream_t cast to void*; NULL is the
+ * default stream) and the calls return without waiting for it. Argument errors
+ * are returned at once and nothing is written. Conditions that only the device
+ * can see (a non-finite value among the kept entries) are reported by
+ * gc_sync_status().
+ *
+ * One gc_ctx serves one stream at a time: two calls that use the same ctx from
+ * different streams without ordering between them race on its workspace.
+ *
+ * The method (paper Sec. III.B): each worker sends only the k entries of
+ * largest magnitude of its accumulated gradient and keeps the rest as a
+ * residual that re-enters the next step, Eq. (11): r_{t+1} = r_t + g - ghat.
+ * The receiver forms the aggregate of the workers' (compressed) gradients,
+ * Eq. (8); here that aggregate is returned as the plain sum, the 1/P factor is
+ * left to the caller.
+ */
+#ifndef GRADCOMP_H
+#define GRADCOMP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GC_OK = 0,
+  GC_ERR_INVALID_ARG = 1, /* null pointer, size out of range, mismatched buffers */
+  GC_ERR_UNSUPPORTED = 2, /* valid request this build cannot serve (e.g. W too large) */
+  GC_ERR_WORKSPACE = 3,   /* scratch allocation failed */
+  GC_ERR_NONFINITE = 4,   /* Inf/NaN among the kept entries; outputs unspecified */
+  GC_ERR_DEVICE = 5       /* a HIP runtime call failed */
+} gc_status;
+
+typedef enum { GC_F32 = 0, GC_BF16 = 1 } gc_dtype;
+
+typedef struct gc_ctx gc_ctx; /* opaque; owns scratch workspace on one device */
+
+/* A compressed gradient: k (index, code) pairs in ascending index order plus one
+ * fp32 scale per block of `block` consecutive pairs (the last block may be
+ * short). Entry j decodes to (float)q[j] * scales[j / block], rounded to fp32.
+ * For a multi-tensor buffer the pairs of all tensors are concatenated in tensor
+ * order, indices are positions in the flat buffer, and blocks restart at every
+ * tensor boundary (scales are concatenated the same way). */
+typedef struct {
+  void* indices;      /* k entries; uint32_t if index_bits == 32, uint64_t if 64 */
+  int8_t* q;          /* k codes in [-127, 127] */
+  float* scales;      /* gc_num_scales(k, block) entries (multi: sum over tensors) */
+  int64_t n;          /* length of the dense vector the indices point into */
+  int64_t k;          /* number of pairs */
+  int32_t block;      /* pairs per scale */
+  int32_t index_bits; /* 32 or 64; must be 64 when n > 2^32 */
+} gc_buf;
+
+/* Counters of the last compress call, valid after gc_sync_status(). */
+typedef struct {
+  int64_t tensors;          /* tensors in the call */
+  int64_t tensors_sampled;  /* tensors whose candidates were gathered in the streaming pass */
+  int64_t tensors_fallback; /* of those, how many had to be re-selected from the dense residual */
+  int64_t candidates;       /* candidate entries gathered by the streaming pass */
+} gc_stats;
+
+/* Create / destroy a context on HIP device `device`. Workspace grows on the
+ * first call that needs it (that call synchronises the device once). */
+gc_status gc_create(gc_ctx** ctx, int device);
+gc_status gc_destroy(gc_ctx* ctx);
+
+/* k = clamp(ceil(n * density), 1, n), n * density evaluated in IEEE double.
+ * Pure host function. The paper names no k; this is the rule the workloads use. */
+int64_t gc_k_from_density(int64_t n, double density);
+
+/* ceil(k / block): number of scales for k pairs. Pure host function. */
+int64_t gc_num_scales(int64_t k, int32_t block);
+
+/* One error-feedback step of one worker on one flat tensor (Sec. III.B, Eq. 11):
+ *   acc = residual + grad            (one fp32 add per entry; bf16 grad is widened exactly)
+ *   kept = the k entries of largest |acc| (31-bit magnitude pattern; ties to the lower index)
+ *   out  = kept indices ascending, int8 codes q = rint(acc / s) with s = amax/127 per block
+ *          of `block` consecutive kept entries (a zero or subnormal s sends the block as zeros)
+ *   residual = acc - fl32(q * s) at kept entries, acc elsewhere          (updated in place)
+ * grad: n entries of `dtype`, read only. residual: n fp32. 1 <= k <= n, block >= 1,
+ * k < 2^32. out->indices/q/scales must hold k / k / gc_num_scales(k, block) entries;
+ * out->n, out->k, out->block must equal n, k, block. */
+gc_status gc_compress(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual, int64_t n,
+                      int64_t k, int32_t block, const gc_buf* out, void* hip_stream);
+
+/* The same step for T tensors stored back to back in one flat buffer, each with
+ * its own top-k and its own quantization blocks, in one set of launches.
+ * offsets: T+1 host entries, offsets[0] = 0, strictly increasing; tensor t is
+ * [offsets[t], offsets[t+1]). k: T host entries, 1 <= k[t] <= n_t. `out` is one
+ * flat buffer with out->n = offsets[T], out->k = sum k[t] and
+ * sum gc_num_scales(k[t], block) scales. */
+gc_status gc_compress_multi(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual,
+                            const int64_t* offsets, const int64_t* k, int32_t T, int32_t block,
+                            const gc_buf* out, void* hip_stream);
+
+/* Aggregate of W workers' compressed gradients as a dense vector (Eq. 8 without
+ * the 1/P): out[i] = sum over w = 0..W-1, in that order and in fp32, of the
+ * decoded value of worker w at i (0 where w sent nothing). `out` (n fp32) is
+ * fully overwritten. bufs: W host structs; all must have n == `n` and the same
+ * block and index_bits; indices must be ascending and unique within a buffer
+ * (as gc_compress writes them). 1 <= W <= 64. */
+gc_status gc_decompress_sum(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* out, int64_t n,
+                            void* hip_stream);
+
+/* The same for buffers written by gc_compress_multi: k holds the T per-tensor
+ * counts (host; identical for every worker), so that scales are looked up per
+ * tensor. */
+gc_status gc_decompress_sum_multi(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k,
+                                  int32_t T, float* out, int64_t n, void* hip_stream);
+
+/* Wait for `hip_stream` and return GC_ERR_NONFINITE if any compress call since
+ * the last gc_sync_status() saw Inf/NaN among its kept entries, else GC_OK. */
+gc_status gc_sync_status(gc_ctx* ctx, void* hip_stream);
+
+/* Counters of the most recent compress call; call after gc_sync_status(). */
+gc_status gc_last_stats(gc_ctx* ctx, gc_stats* stats);
+
+/* Per-kernel timing with HIP events recorded on the caller's stream around each
+ * launch. gc_profile_enable(ctx, 1) starts a fresh recording; gc_profile_read
+ * waits for the recorded events and returns, for kernel `id` in
+ * [0, gc_profile_num_kernels()), the summed duration in milliseconds and the
+ * number of launches since recording started. */
+gc_status gc_profile_enable(gc_ctx* ctx, int32_t on);
+int32_t gc_profile_num_kernels(void);
+const char* gc_profile_kernel_name(int32_t id);
+gc_status gc_profile_read(gc_ctx* ctx, int32_t id, double* total_ms, int64_t* launches);
+
+const char* gc_status_string(gc_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRADCOMP_H */

@@ -1,0 +1,288 @@
+"""ctypes binding of libgradcomp.so: same names as the C ABI (include/gradcomp.h),
+argument marshalling only. Every step of the path runs in the library's kernels;
+if the library is missing or fails to load this module raises — there is no
+fallback implementation."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+GC_OK, GC_ERR_INVALID_ARG, GC_ERR_UNSUPPORTED, GC_ERR_WORKSPACE, GC_ERR_NONFINITE, GC_ERR_DEVICE = range(6)
+GC_F32, GC_BF16 = 0, 1
+
+
+class GradCompError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {_status_string(status)} (gc_status {status})")
+
+
+class _GcBuf(ctypes.Structure):
+    _fields_ = [("indices", ctypes.c_void_p), ("q", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("n", ctypes.c_int64), ("k", ctypes.c_int64), ("block", ctypes.c_int32),
+                ("index_bits", ctypes.c_int32)]
+
+
+class _GcStats(ctypes.Structure):
+    _fields_ = [("tensors", ctypes.c_int64), ("tensors_sampled", ctypes.c_int64),
+                ("tensors_fallback", ctypes.c_int64), ("candidates", ctypes.c_int64)]
+
+
+EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_compress",
+           "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_multi", "gc_sync_status",
+           "gc_last_stats", "gc_profile_enable", "gc_profile_num_kernels", "gc_profile_kernel_name",
+           "gc_profile_read", "gc_status_string"]
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libgradcomp.so (building it once if it has never been built). Raises if that fails."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.ensure_library()
+    L = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.gc_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int]
+    L.gc_destroy.argtypes = [vp]
+    L.gc_k_from_density.argtypes = [i64, ctypes.c_double]
+    L.gc_k_from_density.restype = i64
+    L.gc_num_scales.argtypes = [i64, i32]
+    L.gc_num_scales.restype = i64
+    L.gc_compress.argtypes = [vp, vp, ctypes.c_int, vp, i64, i64, i32, ctypes.POINTER(_GcBuf), vp]
+    L.gc_compress_multi.argtypes = [vp, vp, ctypes.c_int, vp, vp, vp, i32, i32, ctypes.POINTER(_GcBuf), vp]
+    L.gc_decompress_sum.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i64, vp]
+    L.gc_decompress_sum_multi.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, i64, vp]
+    L.gc_sync_status.argtypes = [vp, vp]
+    L.gc_last_stats.argtypes = [vp, ctypes.POINTER(_GcStats)]
+    L.gc_profile_enable.argtypes = [vp, i32]
+    L.gc_profile_num_kernels.restype = i32
+    L.gc_profile_kernel_name.argtypes = [i32]
+    L.gc_profile_kernel_name.restype = ctypes.c_char_p
+    L.gc_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    L.gc_status_string.argtypes = [ctypes.c_int]
+    L.gc_status_string.restype = ctypes.c_char_p
+    for name in ("gc_create", "gc_destroy", "gc_compress", "gc_compress_multi", "gc_decompress_sum",
+                 "gc_decompress_sum_multi", "gc_sync_status", "gc_last_stats", "gc_profile_enable",
+                 "gc_profile_read"):
+        getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def _status_string(s: int) -> str:
+    return lib().gc_status_string(int(s)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != GC_OK:
+        raise GradCompError(status, where)
+
+
+def k_from_density(n: int, density: float) -> int:
+    return int(lib().gc_k_from_density(int(n), float(density)))
+
+
+def num_scales(k: int, block: int) -> int:
+    return int(lib().gc_num_scales(int(k), int(block)))
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream], device) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream(device)
+    return int(s.cuda_stream)
+
+
+class Context:
+    """Owns the library's scratch workspace on one device (gc_ctx)."""
+
+    def __init__(self, device: int = 0):
+        self.device = int(device)
+        h = ctypes.c_void_p()
+        _check(lib().gc_create(ctypes.byref(h), self.device), "gc_create")
+        self._h = h
+
+    @property
+    def handle(self) -> ctypes.c_void_p:
+        if self._h is None:
+            raise RuntimeError("context destroyed")
+        return self._h
+
+    def destroy(self) -> None:
+        if self._h is not None:
+            lib().gc_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    # ---- profiling helpers (gc_profile_*) ----
+    def profile_enable(self, on: bool = True) -> None:
+        _check(lib().gc_profile_enable(self.handle, 1 if on else 0), "gc_profile_enable")
+
+    def profile_read(self) -> dict:
+        """{kernel name: (total ms, launches)} since profile_enable(True)."""
+        out = {}
+        L = lib()
+        for i in range(L.gc_profile_num_kernels()):
+            ms, cnt = ctypes.c_double(), ctypes.c_int64()
+            _check(L.gc_profile_read(self.handle, i, ctypes.byref(ms), ctypes.byref(cnt)), "gc_profile_read")
+            out[L.gc_profile_kernel_name(i).decode()] = (ms.value, cnt.value)
+        return out
+
+
+@dataclass
+class CompressedBuf:
+    """Device tensors of one compressed gradient (a gc_buf). `indices` holds unsigned values in a
+    signed torch dtype of the same width (int32 for 32-bit, int64 for 64-bit indices)."""
+    indices: torch.Tensor
+    q: torch.Tensor
+    scales: torch.Tensor
+    n: int
+    k: int
+    block: int
+    index_bits: int
+
+    def struct(self) -> _GcBuf:
+        return _GcBuf(self.indices.data_ptr(), self.q.data_ptr(), self.scales.data_ptr(), self.n, self.k,
+                      self.block, self.index_bits)
+
+    def indices_numpy(self) -> np.ndarray:
+        a = self.indices.detach().cpu().numpy()
+        return a.view(np.uint32) if self.index_bits == 32 else a.view(np.uint64)
+
+    @staticmethod
+    def allocate(n: int, k: int, nscales: int, block: int, index_bits: int, device) -> "CompressedBuf":
+        it = torch.int32 if index_bits == 32 else torch.int64
+        return CompressedBuf(torch.empty(k, dtype=it, device=device), torch.empty(k, dtype=torch.int8, device=device),
+                             torch.empty(max(nscales, 1), dtype=torch.float32, device=device)[:nscales],
+                             int(n), int(k), int(block), int(index_bits))
+
+
+def _grad_dtype(grad: torch.Tensor) -> int:
+    if grad.dtype == torch.float32:
+        return GC_F32
+    if grad.dtype == torch.bfloat16:
+        return GC_BF16
+    raise TypeError("grad must be float32 or bfloat16")
+
+
+def _check_dev(t: torch.Tensor, name: str, dtype=None) -> None:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}")
+
+
+def compress(ctx: Context, grad: torch.Tensor, residual: torch.Tensor, k: int, block: int,
+             out: Optional[CompressedBuf] = None, index_bits: Optional[int] = None,
+             stream: Optional[torch.cuda.Stream] = None) -> CompressedBuf:
+    """gc_compress: one error-feedback step on one flat tensor; `residual` is updated in place."""
+    _check_dev(grad, "grad")
+    _check_dev(residual, "residual", torch.float32)
+    n = grad.numel()
+    if residual.numel() != n:
+        raise ValueError("grad and residual differ in length")
+    if index_bits is None:
+        index_bits = 64 if n > (1 << 32) else 32
+    if out is None:
+        kk = max(int(k), 0)
+        out = CompressedBuf.allocate(n, kk, num_scales(kk, block), block, index_bits, grad.device)
+    st = out.struct()
+    rc = lib().gc_compress(ctx.handle, grad.data_ptr(), _grad_dtype(grad), residual.data_ptr(), n, int(k),
+                           int(block), ctypes.byref(st), _stream_ptr(stream, grad.device))
+    _check(rc, "gc_compress")
+    return out
+
+
+def compress_multi(ctx: Context, grad: torch.Tensor, residual: torch.Tensor, offsets: Sequence[int],
+                   ks: Sequence[int], block: int, out: Optional[CompressedBuf] = None,
+                   index_bits: Optional[int] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> CompressedBuf:
+    """gc_compress_multi: per-tensor top-k over tensors stored back to back in one flat buffer."""
+    _check_dev(grad, "grad")
+    _check_dev(residual, "residual", torch.float32)
+    off = np.ascontiguousarray(offsets, dtype=np.int64)
+    kk = np.ascontiguousarray(ks, dtype=np.int64)
+    T = kk.shape[0]
+    if off.shape[0] != T + 1:
+        raise ValueError("offsets must have len(ks) + 1 entries")
+    n = grad.numel()
+    if residual.numel() != n:
+        raise ValueError("grad and residual differ in length")
+    if index_bits is None:
+        index_bits = 64 if n > (1 << 32) else 32
+    if out is None:
+        ktot = int(kk.clip(min=0).sum())
+        stot = int(sum(num_scales(int(x), block) for x in kk))
+        out = CompressedBuf.allocate(n, ktot, stot, block, index_bits, grad.device)
+    st = out.struct()
+    rc = lib().gc_compress_multi(ctx.handle, grad.data_ptr(), _grad_dtype(grad), residual.data_ptr(),
+                                 off.ctypes.data, kk.ctypes.data, T, int(block), ctypes.byref(st),
+                                 _stream_ptr(stream, grad.device))
+    _check(rc, "gc_compress_multi")
+    return out
+
+
+def _buf_array(bufs: List[CompressedBuf]):
+    arr = (_GcBuf * len(bufs))()
+    for i, b in enumerate(bufs):
+        arr[i] = b.struct()
+    return arr
+
+
+def decompress_sum(ctx: Context, bufs: List[CompressedBuf], n: int, out: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """gc_decompress_sum: dense fp32 sum of W workers' compressed gradients (worker order, fp32)."""
+    dev = bufs[0].q.device
+    if out is None:
+        out = torch.empty(int(n), dtype=torch.float32, device=dev)
+    _check_dev(out, "out", torch.float32)
+    arr = _buf_array(bufs)
+    rc = lib().gc_decompress_sum(ctx.handle, arr, len(bufs), out.data_ptr(), int(n), _stream_ptr(stream, dev))
+    _check(rc, "gc_decompress_sum")
+    return out
+
+
+def decompress_sum_multi(ctx: Context, bufs: List[CompressedBuf], ks: Sequence[int], n: int,
+                         out: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """gc_decompress_sum_multi: the same for buffers written by compress_multi."""
+    dev = bufs[0].q.device
+    if out is None:
+        out = torch.empty(int(n), dtype=torch.float32, device=dev)
+    _check_dev(out, "out", torch.float32)
+    kk = np.ascontiguousarray(ks, dtype=np.int64)
+    arr = _buf_array(bufs)
+    rc = lib().gc_decompress_sum_multi(ctx.handle, arr, len(bufs), kk.ctypes.data, kk.shape[0], out.data_ptr(),
+                                       int(n), _stream_ptr(stream, dev))
+    _check(rc, "gc_decompress_sum_multi")
+    return out
+
+
+def sync_status(ctx: Context, stream: Optional[torch.cuda.Stream] = None, raise_on_error: bool = True) -> int:
+    """gc_sync_status: wait for the stream; GC_ERR_NONFINITE if a compress call kept Inf/NaN."""
+    s = stream if stream is not None else torch.cuda.current_stream(ctx.device)
+    rc = lib().gc_sync_status(ctx.handle, int(s.cuda_stream))
+    if raise_on_error:
+        _check(rc, "gc_sync_status")
+    return rc
+
+
+def last_stats(ctx: Context) -> dict:
+    st = _GcStats()
+    _check(lib().gc_last_stats(ctx.handle, ctypes.byref(st)), "gc_last_stats")
+    return {"tensors": st.tensors, "tensors_sampled": st.tensors_sampled,
+            "tensors_fallback": st.tensors_fallback, "candidates": st.candidates}

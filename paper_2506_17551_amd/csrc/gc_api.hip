@@ -1,0 +1,577 @@
+// Host side of libgradcomp: argument checks, the per-shape plan, workspace, launch order
+// and the C ABI declared in include/gradcomp.h.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/gradcomp.h"
+#include "gc_internal.h"
+
+using namespace gc;
+
+namespace {
+
+struct DevBuf {
+  void* p = nullptr;
+  size_t bytes = 0;
+};
+
+struct Plan {  // everything that depends only on (offsets, k, block)
+  std::vector<int64_t> offsets, k;
+  int32_t block = 0;
+  std::vector<TensorDesc> td;
+  int32_t item_len = 0, cap = 0;
+  int64_t nitem_slots = 0, ktotal = 0, stotal = 0;
+  int64_t n_sampled = 0;
+  DevBuf td_dev;
+};
+
+struct DecPlan {  // per-tensor prefix tables for multi-tensor decompress
+  std::vector<int64_t> k;
+  int32_t block = 0;
+  DevBuf kprefix, sprefix;
+};
+
+struct EventPair {
+  hipEvent_t a, b;
+  int32_t id;
+};
+
+}  // namespace
+
+struct gc_ctx {
+  int device = 0;
+  std::vector<Plan*> plans;
+  std::vector<DecPlan*> dplans;
+  // workspace (sized for the largest plan seen)
+  DevBuf ts, shist, hist, item_cnt, item_gt, item_eq, item_goff, item_eoff, cand_val, cand_rel, kept_val,
+      flags, bounds;
+  uint32_t* host_flags = nullptr;  // pinned
+  TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
+  size_t host_ts_cap = 0;
+  const Plan* last_plan = nullptr;
+  // profiling
+  bool prof = false;
+  std::vector<EventPair> ev_used, ev_free;
+};
+
+namespace {
+
+#define GC_HIP(expr)                          \
+  do {                                        \
+    if ((expr) != hipSuccess) {               \
+      (void)hipGetLastError();                \
+      return GC_ERR_DEVICE;                   \
+    }                                         \
+  } while (0)
+
+gc_status ensure(DevBuf& b, size_t bytes) {
+  if (bytes <= b.bytes) return GC_OK;
+  if (b.p) {
+    if (hipDeviceSynchronize() != hipSuccess) return GC_ERR_DEVICE;
+    if (hipFree(b.p) != hipSuccess) return GC_ERR_DEVICE;
+    b.p = nullptr;
+    b.bytes = 0;
+  }
+  size_t want = bytes + bytes / 8 + 256;
+  if (hipMalloc(&b.p, want) != hipSuccess) {
+    (void)hipGetLastError();
+    b.p = nullptr;
+    return GC_ERR_WORKSPACE;
+  }
+  b.bytes = want;
+  return GC_OK;
+}
+
+void release(DevBuf& b) {
+  if (b.p) (void)hipFree(b.p);
+  b.p = nullptr;
+  b.bytes = 0;
+}
+
+int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// ---- plan ------------------------------------------------------------------
+// Tensors large and sparse enough get their candidates from a sampled threshold in
+// the single streaming pass; the rest are selected from the dense residual.
+constexpr int64_t kMinSampledN = 1 << 17;
+constexpr int64_t kMinSampledK = 64;
+constexpr int64_t kMaxDensityInv = 8;  // sampled only if k * 8 <= n
+
+Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t block) {
+  Plan* P = new (std::nothrow) Plan();
+  if (!P) return nullptr;
+  P->offsets.assign(offsets, offsets + T + 1);
+  P->k.assign(k, k + T);
+  P->block = block;
+  const int64_t ntotal = offsets[T];
+  // item length: aim at >= ~16k items so that every CU has several waves, within [1024, 32768]
+  int64_t il = round_up(std::max<int64_t>(ntotal / 16384, 1), kWaveTile);
+  il = std::min<int64_t>(std::max<int64_t>(il, kWaveTile), 32768);
+  P->item_len = (int32_t)il;
+  P->td.resize(T);
+  int64_t item = 0, kp = 0, sp = 0;
+  double max_lambda = 0.0;
+  for (int32_t t = 0; t < T; ++t) {
+    TensorDesc& d = P->td[t];
+    std::memset(&d, 0, sizeof(d));
+    d.off = offsets[t];
+    d.n = offsets[t + 1] - offsets[t];
+    d.k = k[t];
+    d.kprefix = kp;
+    d.sprefix = sp;
+    d.nitems = (d.n + il - 1) / il;
+    d.item_begin = item;
+    d.item_end = item + round_up(d.nitems, kItemsPerGroup);
+    item = d.item_end;
+    kp += d.k;
+    sp += (d.k + block - 1) / block;
+    const bool sampled = d.n >= kMinSampledN && d.k >= kMinSampledK && d.k * kMaxDensityInv <= d.n;
+    d.mode = sampled ? kSampled : kDense;
+    if (sampled) {
+      // sample fraction: about 256 expected winners in the sample, between 1/64 and 1/4 of the data
+      double f = 256.0 / (double)d.k;
+      f = std::min(0.25, std::max(1.0 / 64.0, f));
+      int64_t sl = round_up((int64_t)std::ceil(f * (double)il), kSampleGranule);
+      sl = std::min<int64_t>(sl, il);
+      d.sample_len = (int32_t)sl;
+      const int64_t last_len = d.n - (d.nitems - 1) * il;
+      const int64_t m = (d.nitems - 1) * sl + std::min<int64_t>(sl, last_len);
+      const double ks = (double)d.k * (double)m / (double)d.n;
+      // the threshold must leave at least k entries above it: cover the expected sample count
+      // of winners plus six standard deviations
+      const double target = std::ceil(ks + 6.0 * std::sqrt(ks) + 8.0);
+      d.sample_target = (uint32_t)std::min<double>(target, 4.0e9);
+      const double lambda = target / (double)m * (double)il;  // candidates expected per item
+      max_lambda = std::max(max_lambda, lambda);
+      P->n_sampled++;
+    }
+  }
+  P->nitem_slots = item;
+  P->ktotal = kp;
+  P->stotal = sp;
+  P->cap = (int32_t)std::min<double>(std::ceil(3.0 * max_lambda + 8.0 * std::sqrt(max_lambda) + 32.0),
+                                      (double)il);
+  if (P->n_sampled == 0) P->cap = 1;
+  return P;
+}
+
+bool same_plan(const Plan* P, const int64_t* offsets, const int64_t* k, int32_t T, int32_t block) {
+  return P->block == block && (int32_t)P->k.size() == T &&
+         std::memcmp(P->offsets.data(), offsets, sizeof(int64_t) * (T + 1)) == 0 &&
+         std::memcmp(P->k.data(), k, sizeof(int64_t) * T) == 0;
+}
+
+gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_t T, int32_t block,
+                   Plan** out) {
+  for (size_t i = 0; i < ctx->plans.size(); ++i) {
+    if (same_plan(ctx->plans[i], offsets, k, T, block)) {
+      Plan* P = ctx->plans[i];
+      if (i != 0) {  // keep the most recent first
+        ctx->plans.erase(ctx->plans.begin() + i);
+        ctx->plans.insert(ctx->plans.begin(), P);
+      }
+      *out = P;
+      return GC_OK;
+    }
+  }
+  Plan* P = build_plan(offsets, k, T, block);
+  if (!P) return GC_ERR_WORKSPACE;
+  gc_status st = ensure(P->td_dev, sizeof(TensorDesc) * T);
+  if (st == GC_OK && hipMemcpy(P->td_dev.p, P->td.data(), sizeof(TensorDesc) * T, hipMemcpyHostToDevice) != hipSuccess)
+    st = GC_ERR_DEVICE;
+  const int64_t slots = P->nitem_slots;
+  if (st == GC_OK) st = ensure(ctx->ts, sizeof(TensorState) * T);
+  if (st == GC_OK) st = ensure(ctx->shist, sizeof(unsigned long long) * (size_t)T * kSampleBins);
+  if (st == GC_OK) st = ensure(ctx->hist, sizeof(unsigned long long) * (size_t)T * kSelBins);
+  if (st == GC_OK) st = ensure(ctx->item_cnt, sizeof(uint32_t) * slots);
+  if (st == GC_OK) st = ensure(ctx->item_gt, sizeof(uint32_t) * slots);
+  if (st == GC_OK) st = ensure(ctx->item_eq, sizeof(uint32_t) * slots);
+  if (st == GC_OK) st = ensure(ctx->item_goff, sizeof(long long) * slots);
+  if (st == GC_OK) st = ensure(ctx->item_eoff, sizeof(long long) * slots);
+  if (st == GC_OK) st = ensure(ctx->cand_val, sizeof(float) * (size_t)slots * P->cap);
+  if (st == GC_OK) st = ensure(ctx->cand_rel, sizeof(uint32_t) * (size_t)slots * P->cap);
+  if (st == GC_OK) st = ensure(ctx->kept_val, sizeof(float) * (size_t)P->ktotal);
+  if (st == GC_OK && ctx->host_ts_cap < (size_t)T) {
+    if (ctx->host_ts) (void)hipHostFree(ctx->host_ts);
+    ctx->host_ts = nullptr;
+    ctx->host_ts_cap = 0;
+    if (hipHostMalloc((void**)&ctx->host_ts, sizeof(TensorState) * T, hipHostMallocDefault) != hipSuccess)
+      st = GC_ERR_WORKSPACE;
+    else
+      ctx->host_ts_cap = T;
+  }
+  if (st != GC_OK) {
+    release(P->td_dev);
+    delete P;
+    return st;
+  }
+  ctx->plans.insert(ctx->plans.begin(), P);
+  while (ctx->plans.size() > 8) {
+    Plan* old = ctx->plans.back();
+    ctx->plans.pop_back();
+    if (ctx->last_plan == old) ctx->last_plan = nullptr;
+    (void)hipDeviceSynchronize();
+    release(old->td_dev);
+    delete old;
+  }
+  *out = P;
+  return GC_OK;
+}
+
+// ---- profiling -------------------------------------------------------------
+struct Scope {  // records an event pair around one launch when profiling is on
+  gc_ctx* c;
+  hipStream_t s;
+  EventPair ev;
+  bool on;
+  Scope(gc_ctx* ctx, int32_t id, hipStream_t st) : c(ctx), s(st), on(ctx->prof) {
+    if (!on) return;
+    if (!c->ev_free.empty()) {
+      ev = c->ev_free.back();
+      c->ev_free.pop_back();
+    } else if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) {
+      on = false;
+      return;
+    }
+    ev.id = id;
+    (void)hipEventRecord(ev.a, s);
+  }
+  ~Scope() {
+    if (!on) return;
+    (void)hipEventRecord(ev.b, s);
+    c->ev_used.push_back(ev);
+  }
+};
+
+gc_status launch_status() { return hipGetLastError() == hipSuccess ? GC_OK : GC_ERR_DEVICE; }
+
+gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual,
+                        const int64_t* offsets, const int64_t* k, int32_t T, int32_t block,
+                        const gc_buf* out, void* hip_stream) {
+  if (!ctx || !grad || !residual || !offsets || !k || !out) return GC_ERR_INVALID_ARG;
+  if (T < 1 || block < 1) return GC_ERR_INVALID_ARG;
+  if (dtype != GC_F32 && dtype != GC_BF16) return GC_ERR_INVALID_ARG;
+  if (!out->indices || !out->q || !out->scales) return GC_ERR_INVALID_ARG;
+  if (offsets[0] != 0) return GC_ERR_INVALID_ARG;
+  int64_t ktotal = 0;
+  for (int32_t t = 0; t < T; ++t) {
+    const int64_t nt = offsets[t + 1] - offsets[t];
+    if (nt <= 0 || k[t] < 1 || k[t] > nt) return GC_ERR_INVALID_ARG;
+    ktotal += k[t];
+  }
+  const int64_t n = offsets[T];
+  if (ktotal >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
+  if (out->n != n || out->k != ktotal || out->block != block) return GC_ERR_INVALID_ARG;
+  if (out->index_bits != 32 && out->index_bits != 64) return GC_ERR_INVALID_ARG;
+  if (out->index_bits == 32 && n > (int64_t(1) << 32)) return GC_ERR_INVALID_ARG;
+  const size_t gsz = dtype == GC_F32 ? 4 : 2;
+  if ((reinterpret_cast<uintptr_t>(grad) % gsz) || (reinterpret_cast<uintptr_t>(residual) % 4) ||
+      (reinterpret_cast<uintptr_t>(out->scales) % 4) ||
+      (reinterpret_cast<uintptr_t>(out->indices) % (out->index_bits / 8)))
+    return GC_ERR_INVALID_ARG;
+
+  GC_HIP(hipSetDevice(ctx->device));
+  Plan* P = nullptr;
+  gc_status st = get_plan(ctx, offsets, k, T, block, &P);
+  if (st != GC_OK) return st;
+  if (P->nitem_slots / kItemsPerGroup >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
+
+  Workspace ws;
+  std::memset(&ws, 0, sizeof(ws));
+  ws.td = (const TensorDesc*)P->td_dev.p;
+  ws.ts = (TensorState*)ctx->ts.p;
+  ws.shist = (unsigned long long*)ctx->shist.p;
+  ws.hist = (unsigned long long*)ctx->hist.p;
+  ws.item_cnt = (uint32_t*)ctx->item_cnt.p;
+  ws.item_gt = (uint32_t*)ctx->item_gt.p;
+  ws.item_eq = (uint32_t*)ctx->item_eq.p;
+  ws.item_goff = (long long*)ctx->item_goff.p;
+  ws.item_eoff = (long long*)ctx->item_eoff.p;
+  ws.cand_val = (float*)ctx->cand_val.p;
+  ws.cand_rel = (uint32_t*)ctx->cand_rel.p;
+  ws.kept_val = (float*)ctx->kept_val.p;
+  ws.flags = (uint32_t*)ctx->flags.p;
+  ws.T = T;
+  ws.item_len = P->item_len;
+  ws.cap = P->cap;
+  ws.nitem_slots = P->nitem_slots;
+  OutBuf ob{out->indices, out->q, out->scales, out->index_bits, block};
+  hipStream_t s = (hipStream_t)hip_stream;
+
+  { Scope sc(ctx, kKInit, s); launch_init(ws, s); }
+  if (P->n_sampled > 0) {
+    { Scope sc(ctx, kKSample, s); launch_sample(ws, grad, (int)dtype, residual, s); }
+    { Scope sc(ctx, kKSampleThresh, s); launch_sample_thresh(ws, s); }
+  }
+  { Scope sc(ctx, kKMain, s); launch_main(ws, grad, (int)dtype, residual, s); }
+  for (int level = 0; level < kSelLevels; ++level) {
+    if (level > 0 || P->n_sampled > 0) { Scope sc(ctx, kKHist, s); launch_hist(ws, level, residual, s); }
+    { Scope sc(ctx, kKSelectScan, s); launch_select_scan(ws, level, s); }
+  }
+  { Scope sc(ctx, kKCount, s); launch_count(ws, residual, s); }
+  { Scope sc(ctx, kKItemScan, s); launch_item_scan(ws, s); }
+  { Scope sc(ctx, kKEmit, s); launch_emit(ws, residual, ob, s); }
+  { Scope sc(ctx, kKQuant, s); launch_quant(ws, residual, ob, P->stotal, s); }
+  ctx->last_plan = P;
+  return launch_status();
+}
+
+gc_status get_dec_plan(gc_ctx* ctx, const int64_t* k, int32_t T, int32_t block, DecPlan** out) {
+  for (DecPlan* D : ctx->dplans)
+    if (D->block == block && (int32_t)D->k.size() == T && std::memcmp(D->k.data(), k, sizeof(int64_t) * T) == 0) {
+      *out = D;
+      return GC_OK;
+    }
+  DecPlan* D = new (std::nothrow) DecPlan();
+  if (!D) return GC_ERR_WORKSPACE;
+  D->k.assign(k, k + T);
+  D->block = block;
+  std::vector<long long> kp(T + 1), sp(T + 1);
+  kp[0] = sp[0] = 0;
+  for (int32_t t = 0; t < T; ++t) {
+    kp[t + 1] = kp[t] + k[t];
+    sp[t + 1] = sp[t] + (k[t] + block - 1) / block;
+  }
+  gc_status st = ensure(D->kprefix, sizeof(long long) * (T + 1));
+  if (st == GC_OK) st = ensure(D->sprefix, sizeof(long long) * (T + 1));
+  if (st == GC_OK && (hipMemcpy(D->kprefix.p, kp.data(), sizeof(long long) * (T + 1), hipMemcpyHostToDevice) != hipSuccess ||
+                      hipMemcpy(D->sprefix.p, sp.data(), sizeof(long long) * (T + 1), hipMemcpyHostToDevice) != hipSuccess))
+    st = GC_ERR_DEVICE;
+  if (st != GC_OK) {
+    release(D->kprefix);
+    release(D->sprefix);
+    delete D;
+    return st;
+  }
+  ctx->dplans.insert(ctx->dplans.begin(), D);
+  while (ctx->dplans.size() > 8) {
+    DecPlan* old = ctx->dplans.back();
+    ctx->dplans.pop_back();
+    (void)hipDeviceSynchronize();
+    release(old->kprefix);
+    release(old->sprefix);
+    delete old;
+  }
+  *out = D;
+  return GC_OK;
+}
+
+gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
+                          float* out, int64_t n, void* hip_stream) {
+  if (!ctx || !bufs || !out || W < 1 || n <= 0) return GC_ERR_INVALID_ARG;
+  if (W > kMaxWorkers) return GC_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(out) % 4) return GC_ERR_INVALID_ARG;
+  const int32_t block = bufs[0].block, ib = bufs[0].index_bits;
+  if (block < 1 || (ib != 32 && ib != 64)) return GC_ERR_INVALID_ARG;
+  if (ib == 32 && n > (int64_t(1) << 32)) return GC_ERR_INVALID_ARG;
+  int64_t ksum = 0;
+  if (T > 0) {
+    if (!k) return GC_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < T; ++t) {
+      if (k[t] < 1) return GC_ERR_INVALID_ARG;
+      ksum += k[t];
+    }
+  }
+  DecArgs a;
+  std::memset(&a, 0, sizeof(a));
+  for (int32_t w = 0; w < W; ++w) {
+    const gc_buf& b = bufs[w];
+    if (b.n != n || b.block != block || b.index_bits != ib || b.k < 0) return GC_ERR_INVALID_ARG;
+    if (b.k >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
+    if (b.k > 0 && (!b.indices || !b.q || !b.scales)) return GC_ERR_INVALID_ARG;
+    if (T > 0 && b.k != ksum) return GC_ERR_INVALID_ARG;
+    a.indices[w] = b.indices;
+    a.q[w] = b.q;
+    a.scales[w] = b.scales;
+    a.k[w] = (uint32_t)b.k;
+  }
+  GC_HIP(hipSetDevice(ctx->device));
+  const int64_t ntiles = (n + kDecTile - 1) / kDecTile;
+  if ((ntiles + 3) / 4 >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
+  gc_status st = ensure(ctx->bounds, sizeof(uint32_t) * (size_t)(ntiles + 1) * W);
+  if (st != GC_OK) return st;
+  DecPlan* D = nullptr;
+  if (T > 1) {
+    st = get_dec_plan(ctx, k, T, block, &D);
+    if (st != GC_OK) return st;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  { Scope sc(ctx, kKDecBounds, s); launch_dec_bounds(a, W, ib, ntiles, (uint32_t*)ctx->bounds.p, s); }
+  {
+    Scope sc(ctx, kKDecTiles, s);
+    launch_dec_tiles(a, W, ib, block, n, ntiles, (const uint32_t*)ctx->bounds.p,
+                     D ? (const long long*)D->kprefix.p : nullptr, D ? (const long long*)D->sprefix.p : nullptr,
+                     D ? T : 1, out, s);
+  }
+  return launch_status();
+}
+
+const char* const kKernelNames[kKNum] = {"k_init",  "k_sample", "k_sample_thresh", "k_main",
+                                         "k_hist",  "k_select_scan", "k_count", "k_item_scan",
+                                         "k_emit",  "k_quant", "k_dec_bounds", "k_dec_tiles"};
+
+}  // namespace
+
+extern "C" {
+
+gc_status gc_create(gc_ctx** out, int device) {
+  if (!out) return GC_ERR_INVALID_ARG;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess) {
+    (void)hipGetLastError();
+    return GC_ERR_DEVICE;
+  }
+  if (device < 0 || device >= count) return GC_ERR_INVALID_ARG;
+  GC_HIP(hipSetDevice(device));
+  gc_ctx* c = new (std::nothrow) gc_ctx();
+  if (!c) return GC_ERR_WORKSPACE;
+  c->device = device;
+  gc_status st = ensure(c->flags, sizeof(uint32_t) * 4);
+  if (st == GC_OK && hipMemset(c->flags.p, 0, sizeof(uint32_t) * 4) != hipSuccess) st = GC_ERR_DEVICE;
+  if (st == GC_OK && hipHostMalloc((void**)&c->host_flags, sizeof(uint32_t) * 4, hipHostMallocDefault) != hipSuccess)
+    st = GC_ERR_WORKSPACE;
+  if (st != GC_OK) {
+    release(c->flags);
+    delete c;
+    return st;
+  }
+  *out = c;
+  return GC_OK;
+}
+
+gc_status gc_destroy(gc_ctx* c) {
+  if (!c) return GC_ERR_INVALID_ARG;
+  (void)hipSetDevice(c->device);
+  (void)hipDeviceSynchronize();
+  for (Plan* P : c->plans) { release(P->td_dev); delete P; }
+  for (DecPlan* D : c->dplans) { release(D->kprefix); release(D->sprefix); delete D; }
+  DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->item_cnt, &c->item_gt, &c->item_eq, &c->item_goff,
+                   &c->item_eoff, &c->cand_val, &c->cand_rel, &c->kept_val, &c->flags, &c->bounds};
+  for (DevBuf* b : all) release(*b);
+  if (c->host_flags) (void)hipHostFree(c->host_flags);
+  if (c->host_ts) (void)hipHostFree(c->host_ts);
+  for (auto& e : c->ev_used) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  for (auto& e : c->ev_free) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  delete c;
+  return GC_OK;
+}
+
+int64_t gc_k_from_density(int64_t n, double density) {
+  if (n <= 0) return 0;
+  const double kd = std::ceil((double)n * density);
+  if (!(kd >= 1.0)) return 1;
+  if (kd >= (double)n) return n;
+  return (int64_t)kd;
+}
+
+int64_t gc_num_scales(int64_t k, int32_t block) {
+  if (k <= 0 || block < 1) return 0;
+  return (k + block - 1) / block;
+}
+
+gc_status gc_compress(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual, int64_t n, int64_t k,
+                      int32_t block, const gc_buf* out, void* hip_stream) {
+  if (n <= 0) return GC_ERR_INVALID_ARG;
+  const int64_t offsets[2] = {0, n};
+  return compress_impl(ctx, grad, dtype, residual, offsets, &k, 1, block, out, hip_stream);
+}
+
+gc_status gc_compress_multi(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual,
+                            const int64_t* offsets, const int64_t* k, int32_t T, int32_t block,
+                            const gc_buf* out, void* hip_stream) {
+  return compress_impl(ctx, grad, dtype, residual, offsets, k, T, block, out, hip_stream);
+}
+
+gc_status gc_decompress_sum(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* out, int64_t n,
+                            void* hip_stream) {
+  return decompress_impl(ctx, bufs, W, nullptr, 0, out, n, hip_stream);
+}
+
+gc_status gc_decompress_sum_multi(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
+                                  float* out, int64_t n, void* hip_stream) {
+  if (T < 1) return GC_ERR_INVALID_ARG;
+  return decompress_impl(ctx, bufs, W, k, T, out, n, hip_stream);
+}
+
+gc_status gc_sync_status(gc_ctx* ctx, void* hip_stream) {
+  if (!ctx) return GC_ERR_INVALID_ARG;
+  GC_HIP(hipSetDevice(ctx->device));
+  hipStream_t s = (hipStream_t)hip_stream;
+  GC_HIP(hipMemcpyAsync(ctx->host_flags, ctx->flags.p, sizeof(uint32_t) * 4, hipMemcpyDeviceToHost, s));
+  if (ctx->last_plan)
+    GC_HIP(hipMemcpyAsync(ctx->host_ts, ctx->ts.p, sizeof(TensorState) * ctx->last_plan->td.size(),
+                          hipMemcpyDeviceToHost, s));
+  GC_HIP(hipStreamSynchronize(s));
+  const bool bad = ctx->host_flags[0] != 0u;
+  if (bad) {
+    GC_HIP(hipMemsetAsync(ctx->flags.p, 0, sizeof(uint32_t) * 4, s));
+    GC_HIP(hipStreamSynchronize(s));
+  }
+  return bad ? GC_ERR_NONFINITE : GC_OK;
+}
+
+gc_status gc_last_stats(gc_ctx* ctx, gc_stats* stats) {
+  if (!ctx || !stats) return GC_ERR_INVALID_ARG;
+  std::memset(stats, 0, sizeof(*stats));
+  const Plan* P = ctx->last_plan;
+  if (!P) return GC_OK;
+  stats->tensors = (int64_t)P->td.size();
+  for (size_t t = 0; t < P->td.size(); ++t) {
+    if (P->td[t].mode != kSampled) continue;
+    stats->tensors_sampled++;
+    const TensorState& st = ctx->host_ts[t];
+    stats->candidates += (int64_t)st.cand_total;
+    if (st.overflow || st.cand_total < (unsigned long long)P->td[t].k) stats->tensors_fallback++;
+  }
+  return GC_OK;
+}
+
+gc_status gc_profile_enable(gc_ctx* ctx, int32_t on) {
+  if (!ctx) return GC_ERR_INVALID_ARG;
+  GC_HIP(hipSetDevice(ctx->device));
+  GC_HIP(hipDeviceSynchronize());
+  for (auto& e : ctx->ev_used) ctx->ev_free.push_back(e);
+  ctx->ev_used.clear();
+  ctx->prof = on != 0;
+  return GC_OK;
+}
+
+int32_t gc_profile_num_kernels(void) { return kKNum; }
+
+const char* gc_profile_kernel_name(int32_t id) { return (id >= 0 && id < kKNum) ? kKernelNames[id] : ""; }
+
+gc_status gc_profile_read(gc_ctx* ctx, int32_t id, double* total_ms, int64_t* launches) {
+  if (!ctx || !total_ms || !launches || id < 0 || id >= kKNum) return GC_ERR_INVALID_ARG;
+  GC_HIP(hipSetDevice(ctx->device));
+  double tot = 0.0;
+  int64_t cnt = 0;
+  for (auto& e : ctx->ev_used) {
+    if (e.id != id) continue;
+    GC_HIP(hipEventSynchronize(e.b));
+    float ms = 0.0f;
+    GC_HIP(hipEventElapsedTime(&ms, e.a, e.b));
+    tot += ms;
+    ++cnt;
+  }
+  *total_ms = tot;
+  *launches = cnt;
+  return GC_OK;
+}
+
+const char* gc_status_string(gc_status s) {
+  switch (s) {
+    case GC_OK: return "ok";
+    case GC_ERR_INVALID_ARG: return "invalid argument";
+    case GC_ERR_UNSUPPORTED: return "unsupported size";
+    case GC_ERR_WORKSPACE: return "workspace allocation failed";
+    case GC_ERR_NONFINITE: return "non-finite value among the kept entries";
+    case GC_ERR_DEVICE: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,379 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element on the
+same seeded inputs: kept index sets, int8 codes, scales and residuals must be bit-exact; the
+dense aggregate is compared bit for bit against the oracle's worker-ordered fp32 sum."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_17551_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def gc():
+    import paper_2506_17551_amd as gc_mod
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return gc_mod
+
+
+@pytest.fixture(scope="module")
+def ctx(gc):
+    c = gc.Context(0)
+    yield c
+    c.destroy()
+
+
+def _np_grad(g):
+    return inputs.bf16_bits(g) if g.dtype == torch.bfloat16 else g.cpu().numpy()
+
+
+def bits(a):
+    return a.view(np.uint32)
+
+
+def check_compress(gc, ctx, oracle, g_cpu, e_cpu, k, block, index_bits=32, tag="", expect_fallback=None):
+    """Run one step on both sides from the same bytes; returns (gpu buf, oracle triple, new residual)."""
+    n = g_cpu.numel()
+    print(f"[case] {tag} n={n} k={k} block={block} bits={index_bits} dtype={g_cpu.dtype}", flush=True)
+    e_ref = e_cpu.numpy().copy()
+    rc, idx, q, s = oracle.compress(_np_grad(g_cpu), e_ref, k, block, index_bits=index_bits)
+    assert rc == 0
+    g = g_cpu.to(DEV)
+    e = e_cpu.to(DEV).clone()
+    buf = gc.compress(ctx, g, e, k, block, index_bits=index_bits)
+    gc.sync_status(ctx)
+    st = gc.last_stats(ctx)
+    if expect_fallback is not None:
+        assert (st["tensors_fallback"] > 0) == expect_fallback, st
+    got_idx = buf.indices_numpy()
+    assert np.array_equal(got_idx, idx), f"{tag}: index sets differ"
+    assert np.array_equal(buf.q.cpu().numpy(), q), f"{tag}: codes differ"
+    assert np.array_equal(bits(buf.scales.cpu().numpy()), bits(s)), f"{tag}: scales differ"
+    assert np.array_equal(bits(e.cpu().numpy()), bits(e_ref)), f"{tag}: residuals differ"
+    return buf, (idx, q, s), e.cpu()
+
+
+# ---------------------------------------------------------------------------------- config 1
+def test_config1_three_error_feedback_steps(gc, ctx, oracle):
+    w = inputs.workload(1)
+    k = gc.k_from_density(w.n, w.density)
+    assert k == 10486
+    e = w.residual0(0, "cpu")
+    for step in range(w.steps):
+        g = w.grad(0, step, "cpu")
+        buf, ref, e = check_compress(gc, ctx, oracle, g, e, k, w.block, tag=f"config1 step {step}",
+                                     expect_fallback=False)
+        out = gc.decompress_sum(ctx, [buf], w.n)
+        torch.cuda.synchronize()
+        rc, want = oracle.decompress_sum([ref], w.n, w.block)
+        assert np.array_equal(bits(out.cpu().numpy()), bits(want))
+
+
+# ---------------------------------------------------------------------------------- sizes and tails
+@pytest.mark.parametrize("n,k", [(1, 1), (2, 1), (63, 5), (64, 64), (65, 1), (1023, 100), (1024, 1024),
+                                 (1025, 7), (4097, 4097), (131071, 131), (131072, 1311), (131073, 64),
+                                 (200003, 2001), (1 << 20, 1), (1048583, 10486), (3000017, 3001)])
+def test_ragged_sizes(gc, ctx, oracle, n, k):
+    g = inputs.normal(n, 1.0, n + k)
+    e = inputs.normal(n, 0.5, n + k + 1)
+    check_compress(gc, ctx, oracle, g, e, k, 64, tag="ragged")
+
+
+@pytest.mark.parametrize("block", [1, 3, 64, 255, 256, 257, 1024, 2048, 5000])
+def test_block_sizes(gc, ctx, oracle, block):
+    n, k = 400000, 4000
+    g = inputs.normal(n, 1.0, block)
+    e = inputs.normal(n, 0.1, block + 1)
+    buf, ref, _ = check_compress(gc, ctx, oracle, g, e, k, block, tag="block")
+    out = gc.decompress_sum(ctx, [buf, buf], n)
+    torch.cuda.synchronize()
+    rc, want = oracle.decompress_sum([ref, ref], n, block)
+    assert np.array_equal(bits(out.cpu().numpy()), bits(want))
+
+
+@pytest.mark.parametrize("density", [1.0, 0.5, 0.126, 0.124, 0.05, 1e-4, 1e-6])
+def test_densities(gc, ctx, oracle, density):
+    n = 1_500_000
+    k = gc.k_from_density(n, density)
+    g = inputs.normal(n, 1.0, 5)
+    e = inputs.normal(n, 1.0, 6)
+    buf, ref, _ = check_compress(gc, ctx, oracle, g, e, k, 256, tag=f"density {density}")
+    if density == 1.0:
+        assert np.array_equal(buf.indices_numpy(), np.arange(n, dtype=np.uint32))
+
+
+# ---------------------------------------------------------------------------------- ties
+@pytest.mark.parametrize("alphabet", [(0.0, -0.0, 1.0, -1.0, 2.0), (3.0,), (0.0, -0.0),
+                                      (1.0, -1.0, 1.0000001, 0.99999994), (1e-40, -1e-40, 2e-40, 0.0)])
+@pytest.mark.parametrize("n,k", [(5000, 50), (5000, 4999), (300000, 300), (300000, 150000), (2_000_000, 2000)])
+def test_ties_go_to_the_lower_index(gc, ctx, oracle, alphabet, n, k):
+    g = inputs.tie_alphabet(n, alphabet, seed=n + k)
+    e = inputs.tie_alphabet(n, alphabet, seed=n + k + 9)
+    check_compress(gc, ctx, oracle, g, e, k, 128, tag=f"ties {alphabet}")
+
+
+def test_massive_ties_force_the_dense_route(gc, ctx, oracle):
+    # a sampled tensor whose candidates overflow (all values equal) must be re-selected densely
+    n, k = 1_000_000, 1000
+    g = torch.full((n,), 0.25)
+    e = torch.zeros(n)
+    buf, _, _ = check_compress(gc, ctx, oracle, g, e, k, 256, tag="all-equal", expect_fallback=True)
+    assert np.array_equal(buf.indices_numpy(), np.arange(k, dtype=np.uint32))
+
+
+def test_clustered_winners_force_the_dense_route(gc, ctx, oracle):
+    # all winners sit in one short stretch: the sampled threshold is useless there, the result is not
+    n, k = 2_000_000, 2000
+    g = inputs.normal(n, 1e-3, 41)
+    g[777_000:779_000] += 5.0
+    e = torch.zeros(n)
+    check_compress(gc, ctx, oracle, g, e, k, 256, tag="clustered")
+
+
+# ---------------------------------------------------------------------------------- distributions
+@pytest.mark.parametrize("name", ["t3", "mix", "tiny", "huge", "subnormal", "zeros"])
+def test_value_distributions(gc, ctx, oracle, name):
+    n, k = 600000, 3000
+    if name == "t3":
+        g, e = inputs.student_t3(n, 1e-3, 1), inputs.student_t3(n, 1e-3, 2)
+    elif name == "mix":
+        g, e = inputs.outlier_mixture(n, 1e-3, 0.01, 100.0, 3), inputs.outlier_mixture(n, 1e-3, 0.01, 100.0, 4)
+    elif name == "tiny":
+        g, e = inputs.normal(n, 1e-30, 5), inputs.normal(n, 1e-30, 6)
+    elif name == "huge":
+        g, e = inputs.normal(n, 1e30, 7), inputs.normal(n, 1e30, 8)
+    elif name == "subnormal":
+        g, e = inputs.normal(n, 3e-39, 9), inputs.normal(n, 1e-39, 10)
+    else:
+        g, e = torch.zeros(n), torch.zeros(n)
+        g[1234] = -0.0
+    check_compress(gc, ctx, oracle, g, e, k, 512, tag=name)
+
+
+def test_bf16_gradient(gc, ctx, oracle):
+    w = inputs.workload(4, scale=0.002)  # 2.6M elements, same distribution, density, block
+    k = gc.k_from_density(w.n, w.density)
+    e = w.residual0(0, "cpu")
+    for step in range(3):
+        g = w.grad(0, step, "cpu")
+        assert g.dtype == torch.bfloat16
+        _, _, e = check_compress(gc, ctx, oracle, g, e, k, w.block, tag=f"config4-small step {step}",
+                                 expect_fallback=False)
+    for n in (1, 67, 1029, 262151):
+        g = inputs.student_t3(n, 1e-3, n).to(torch.bfloat16)
+        check_compress(gc, ctx, oracle, g, inputs.normal(n, 1e-4, n + 1), max(1, n // 100), 32, tag="bf16 ragged")
+
+
+def test_64bit_indices_at_small_n(gc, ctx, oracle):
+    n, k = 700001, 701
+    g, e = inputs.normal(n, 1.0, 1), inputs.normal(n, 1.0, 2)
+    buf, ref, _ = check_compress(gc, ctx, oracle, g, e, k, 100, index_bits=64, tag="u64")
+    out = gc.decompress_sum(ctx, [buf] * 3, n)
+    torch.cuda.synchronize()
+    rc, want = oracle.decompress_sum([ref] * 3, n, 100)
+    assert np.array_equal(bits(out.cpu().numpy()), bits(want))
+
+
+def test_unaligned_pointers_take_the_scalar_route(gc, ctx, oracle):
+    n, k = 300001, 3000
+    for go, eo in ((1, 0), (0, 1), (3, 2)):
+        G = inputs.normal(n + 4, 1.0, 11).to(DEV)
+        E = inputs.normal(n + 4, 1.0, 12).to(DEV)
+        g, e = G[go:go + n], E[eo:eo + n]
+        e_ref = e.cpu().numpy().copy()
+        rc, idx, q, s = oracle.compress(g.cpu().numpy().copy(), e_ref, k, 64)
+        buf = gc.compress(ctx, g, e, k, 64)
+        gc.sync_status(ctx)
+        assert np.array_equal(buf.indices_numpy(), idx) and np.array_equal(buf.q.cpu().numpy(), q)
+        assert np.array_equal(bits(e.cpu().numpy()), bits(e_ref))
+    gb = inputs.student_t3(n + 4, 1e-3, 13).to(torch.bfloat16).to(DEV)
+    E = inputs.normal(n + 4, 1e-4, 14).to(DEV)
+    g, e = gb[1:1 + n], E[2:2 + n]
+    e_ref = e.cpu().numpy().copy()
+    rc, idx, q, s = oracle.compress(inputs.bf16_bits(g.cpu().contiguous()), e_ref, k, 64)
+    buf = gc.compress(ctx, g, e, k, 64)
+    gc.sync_status(ctx)
+    assert np.array_equal(buf.indices_numpy(), idx) and np.array_equal(bits(e.cpu().numpy()), bits(e_ref))
+
+
+# ---------------------------------------------------------------------------------- multi-tensor
+def _multi_case(gc, ctx, oracle, sizes, density, block, W, seed, sigma=0.02):
+    off = inputs.offsets_of(sizes)
+    n = int(off[-1])
+    ks = np.array([gc.k_from_density(int(s), density) for s in sizes], dtype=np.int64)
+    bufs, refs = [], []
+    for w in range(W):
+        print(f"[case] multi W={W} worker {w} n={n} T={len(sizes)}", flush=True)
+        g = inputs.normal(n, sigma, seed + 2 * w)
+        e = inputs.normal(n, sigma / 4, seed + 2 * w + 1)
+        e_ref = e.numpy().copy()
+        rc, idx, q, s = oracle.compress_multi(g.numpy(), e_ref, off, ks, block)
+        assert rc == 0
+        gd, ed = g.to(DEV), e.to(DEV)
+        buf = gc.compress_multi(ctx, gd, ed, off, ks, block)
+        gc.sync_status(ctx)
+        assert np.array_equal(buf.indices_numpy(), idx)
+        assert np.array_equal(buf.q.cpu().numpy(), q)
+        assert np.array_equal(bits(buf.scales.cpu().numpy()), bits(s))
+        assert np.array_equal(bits(ed.cpu().numpy()), bits(e_ref))
+        bufs.append(buf)
+        refs.append((idx, q, s))
+    out = gc.decompress_sum_multi(ctx, bufs, ks, n)
+    torch.cuda.synchronize()
+    rc, want = oracle.decompress_sum(refs, n, block, ktensor=ks)
+    assert rc == 0 and np.array_equal(bits(out.cpu().numpy()), bits(want))
+    return gc.last_stats(ctx)
+
+
+def test_multi_tensor_small_mixed(gc, ctx, oracle):
+    sizes = [768, 5, 2304, 1, 4096, 1000, 300001, 7, 262144, 131072, 1025]
+    _multi_case(gc, ctx, oracle, sizes, 0.01, 4, W=3, seed=100)
+
+
+def test_config2_decoder_scaled_eight_workers(gc, ctx, oracle):
+    w = inputs.workload(2, scale=0.05)
+    _multi_case(gc, ctx, oracle, w.sizes, w.density, w.block, W=8, seed=200)
+
+
+def test_config2_decoder_full_size(gc, ctx, oracle):
+    w = inputs.workload(2)
+    st = _multi_case(gc, ctx, oracle, w.sizes, w.density, w.block, W=2, seed=300)
+    assert st["tensors"] == 148 and st["tensors_fallback"] == 0 and st["tensors_sampled"] == 50
+
+
+# ---------------------------------------------------------------------------------- aggregate
+def test_decompress_sum_sixteen_workers_with_collisions(gc, ctx, oracle):
+    n, k, block, W = 1_000_003, 20000, 256, 16
+    bufs, refs = [], []
+    hot = inputs.normal(n, 1.0, 999)  # shared component: many workers keep the same indices
+    for w in range(W):
+        g = inputs.normal(n, 1.0, 50 + w) + 2.0 * hot
+        buf, ref, _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, block, tag=f"agg w{w}")
+        bufs.append(buf)
+        refs.append(ref)
+    counts = np.zeros(n, np.int32)
+    for idx, _, _ in refs:
+        counts[idx] += 1
+    assert (counts >= 3).sum() > 1000  # the order of the fp32 adds matters for these
+    for Wsub in (1, 2, 5, 16):
+        out = gc.decompress_sum(ctx, bufs[:Wsub], n)
+        torch.cuda.synchronize()
+        rc, want = oracle.decompress_sum(refs[:Wsub], n, block)
+        assert np.array_equal(bits(out.cpu().numpy()), bits(want)), Wsub
+    # tolerance form of the same statement: within 1e-6 relative of the float64 sum (or 1 ulp)
+    ref64 = np.zeros(n, np.float64)
+    for idx, q, s in refs:
+        ref64[idx] += (q.astype(np.float32) * s[np.arange(k) // block]).astype(np.float64)
+    got = out.cpu().numpy().astype(np.float64)
+    ulp = np.spacing(np.abs(ref64).astype(np.float32)).astype(np.float64)
+    mag = np.zeros(n, np.float64)
+    for idx, q, s in refs:
+        mag[idx] += np.abs(q.astype(np.float32) * s[np.arange(k) // block])
+    assert np.all(np.abs(got - ref64) <= np.maximum(np.maximum(1e-6 * np.abs(ref64), ulp), (W - 1) * 2.0 ** -24 * mag))
+
+
+def test_decompress_sum_edge_shapes(gc, ctx, oracle):
+    for n, k in ((1, 1), (2047, 3), (2048, 2048), (2049, 1), (10000, 10000), (300000, 1)):
+        g = inputs.normal(n, 1.0, n)
+        buf, ref, _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 8, tag="dec edge")
+        out = torch.full((n + 8,), 7.0, device=DEV)
+        gc.decompress_sum(ctx, [buf, buf, buf], n, out=out[:n])
+        torch.cuda.synchronize()
+        rc, want = oracle.decompress_sum([ref] * 3, n, 8)
+        assert np.array_equal(bits(out[:n].cpu().numpy()), bits(want))
+        assert torch.all(out[n:] == 7.0)  # nothing written past n
+    # an unaligned output pointer
+    n, k = 50001, 500
+    g = inputs.normal(n, 1.0, 3)
+    buf, ref, _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 8, tag="dec unaligned")
+    big = torch.zeros(n + 3, device=DEV)
+    gc.decompress_sum(ctx, [buf], n, out=big[1:1 + n])
+    torch.cuda.synchronize()
+    rc, want = oracle.decompress_sum([ref], n, 8)
+    assert np.array_equal(bits(big[1:1 + n].cpu().numpy()), bits(want))
+
+
+# ---------------------------------------------------------------------------------- behaviour
+def test_runs_are_deterministic(gc, ctx):
+    n, k = 3_000_000, 30000
+    g = inputs.normal(n, 1.0, 1).to(DEV)
+    e0 = inputs.normal(n, 1.0, 2).to(DEV)
+    outs = []
+    for _ in range(3):
+        e = e0.clone()
+        b = gc.compress(ctx, g, e, k, 256)
+        d = gc.decompress_sum(ctx, [b] * 4, n)
+        gc.sync_status(ctx)
+        outs.append((b.indices.clone(), b.q.clone(), b.scales.clone(), e, d))
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+                               b.view(torch.int32) if b.dtype == torch.float32 else b)
+
+
+def test_checkpoint_resume_of_the_residual(gc, ctx):
+    # the residual is the only state carried between steps (Eq. 11): saving and restoring it
+    # between steps changes nothing
+    n, k = 500000, 5000
+    gs = [inputs.normal(n, 1.0, 70 + t).to(DEV) for t in range(3)]
+    e = torch.zeros(n, device=DEV)
+    for g in gs:
+        last = gc.compress(ctx, g, e, k, 256)
+    gc.sync_status(ctx)
+    e2 = torch.zeros(n, device=DEV)
+    gc.compress(ctx, gs[0], e2, k, 256)
+    gc.sync_status(ctx)
+    saved = e2.cpu()
+    ctx2 = gc.Context(0)
+    e3 = saved.to(DEV)
+    for g in gs[1:]:
+        last2 = gc.compress(ctx2, g, e3, k, 256)
+    gc.sync_status(ctx2)
+    assert torch.equal(e.view(torch.int32), e3.view(torch.int32))
+    assert torch.equal(last.indices, last2.indices) and torch.equal(last.q, last2.q)
+    ctx2.destroy()
+
+
+def test_nonfinite_is_reported_and_cleared(gc, ctx):
+    n, k = 400000, 400
+    for bad in (float("inf"), float("-inf"), float("nan")):
+        g = inputs.normal(n, 1.0, 1)
+        g[12345] = bad
+        e = torch.zeros(n, device=DEV)
+        gc.compress(ctx, g.to(DEV), e, k, 64)
+        assert gc.sync_status(ctx, raise_on_error=False) == 4
+        assert gc.sync_status(ctx, raise_on_error=False) == 0  # reported once
+    g = inputs.normal(n, 1.0, 2).to(DEV)
+    gc.compress(ctx, g, torch.zeros(n, device=DEV), k, 64)
+    assert gc.sync_status(ctx, raise_on_error=False) == 0
+
+
+def test_argument_errors_write_nothing(gc, ctx):
+    n = 1000
+    g = inputs.normal(n, 1.0, 1).to(DEV)
+    e = torch.zeros(n, device=DEV)
+    for k, block in ((0, 4), (n + 1, 4), (10, 0), (-3, 4)):
+        with pytest.raises(gc.GradCompError) as ei:
+            gc.compress(ctx, g, e, k, block)
+        assert ei.value.status == 1
+    assert not e.any()
+    good = gc.compress(ctx, g, e, 10, 4)
+    gc.sync_status(ctx)
+    wrong_k = gc.CompressedBuf(good.indices, good.q, good.scales, n, 11, 4, 32)
+    with pytest.raises(gc.GradCompError):
+        gc.compress(ctx, g, e, 10, 4, out=wrong_k)
+    with pytest.raises(gc.GradCompError):
+        gc.decompress_sum(ctx, [good], n + 1)
+    other = gc.CompressedBuf(good.indices, good.q, good.scales, n, 10, 8, 32)
+    with pytest.raises(gc.GradCompError):
+        gc.decompress_sum(ctx, [good, other], n)
+    with pytest.raises(gc.GradCompError) as ei:
+        gc.decompress_sum(ctx, [good] * 65, n)
+    assert ei.value.status == 2
+    with pytest.raises(gc.GradCompError):
+        gc.compress_multi(ctx, g, e, [0, 500, 400], [5, 5], 4)
+    with pytest.raises(ValueError):
+        gc.compress(ctx, g.cpu(), e, 10, 4)
