@@ -1,0 +1,306 @@
+#!/usr/bin/env python3
+"""Benchmark of the gradient-compression hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic gradients:
+W workers' compress calls (error-feedback accumulate, top-k, int8 codes, residual
+write-back) followed by one decompress_sum of the W compressed buffers. Inputs are
+resident in HBM when a timed interval starts; where one GPU cannot hold all W
+workers' gradients at once (the 7B workload), each worker's gradient and residual
+are regenerated in place between the timed intervals, and a step's time is the sum
+of its W compress intervals and its decompress_sum interval.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", type=int, default=5, choices=[1, 2, 4, 5],
+                    help="benchmark workload (default 5: the 7B fp32 gradient the metric is quoted on)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink n (for quick checks; invalid as a result)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="library tuning knob (gc_set_option), e.g. item_len=16384")
+    ap.add_argument("--verify", action="store_true", help="check invariants of the last step on the device")
+    return ap.parse_args()
+
+
+class Timer:
+    """Accumulates device time of intervals on the current stream with event pairs."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.pairs = []
+
+    def __enter__(self):
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        self.pairs.append((a, b))
+        a.record()
+        return self
+
+    def __exit__(self, *exc):
+        self.pairs[-1][1].record()
+
+    def total_ms(self):
+        self.torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in self.pairs)
+
+    def reset(self):
+        self.pairs = []
+
+
+def run_flat(args, gc, inputs, torch, wl, ctx):
+    """Workloads 1, 4, 5: one flat tensor per worker."""
+    dev = "cuda:0"
+    n, W, block = wl.n, wl.W, wl.block
+    k = gc.k_from_density(n, wl.density)
+    nsc = gc.num_scales(k, block)
+    bufs = [gc.CompressedBuf.allocate(n, k, nsc, block, wl.index_bits, dev) for _ in range(W)]
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+    gbytes = 4 if wl.grad_dtype == "f32" else 2
+    total_bytes = (gbytes + 8) * n
+    free, _ = torch.cuda.mem_get_info()
+    # keep every worker's residual resident when it fits (the error-feedback state of each
+    # worker across steps); otherwise regenerate gradient and residual per worker in place
+    resident = (W * 4 * n + 4 * n + gbytes * n * 2) < free * 0.8
+    g32 = torch.empty(n, dtype=torch.float32, device=dev)
+    if resident:
+        res = [wl.residual0(w, dev) for w in range(W)]
+    else:
+        res = [torch.empty(n, dtype=torch.float32, device=dev)]
+    tc, td = Timer(torch), Timer(torch)
+    step_ms = []
+    nsteps = args.warmup + args.steps
+    for step in range(nsteps):
+        if step == args.warmup:
+            torch.cuda.synchronize()
+            ctx.profile_enable(True)
+            tc.reset()
+            td.reset()
+        for w in range(W):
+            g = wl.grad(w, step, dev, out=g32)
+            e = res[w] if resident else wl.residual0(w, dev, out=res[0])
+            torch.cuda.synchronize()
+            with tc:
+                gc.compress(ctx, g, e, k, block, out=bufs[w])
+        with td:
+            gc.decompress_sum(ctx, bufs, n, out=out)
+        gc.sync_status(ctx)
+    torch.cuda.synchronize()
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    ms_c, ms_d = tc.total_ms() / args.steps, td.total_ms() / args.steps
+    stats = gc.last_stats(ctx)
+    info = {"n": n, "k": k, "block": block, "W": W, "index_bits": wl.index_bits,
+            "compress_ms_per_worker": ms_c / W, "decompress_sum_ms": ms_d,
+            "residuals_resident": resident, "fallback_tensors": stats["tensors_fallback"],
+            "candidates_last_call": stats["candidates"]}
+    if args.verify:
+        info["verify"] = verify_flat(gc, torch, wl, ctx, k)
+    return ms_c + ms_d, W * n * gbytes, prof, total_bytes, info
+
+
+def verify_flat(gc, torch, wl, ctx, k):
+    """Size-independent invariants of one compress call, checked on the device."""
+    dev = "cuda:0"
+    n = wl.n
+    g = wl.grad(0, 0, dev)
+    e0 = wl.residual0(0, dev)
+    e = e0.clone()
+    buf = gc.compress(ctx, g, e, k, wl.block)
+    gc.sync_status(ctx)
+    idx = buf.indices.to(torch.int64)
+    if wl.index_bits == 32:
+        idx = idx & 0xFFFFFFFF
+    ok = bool((idx[1:] > idx[:-1]).all()) and int(idx[-1]) < n and idx.numel() == k
+    CH = 1 << 28
+    thr = None
+    kept_abs_min = None
+    for a in range(0, n, CH):
+        b = min(n, a + CH)
+        acc = g[a:b].float() + e0[a:b]
+        sel = idx[(idx >= a) & (idx < b)] - a
+        keptv = acc[sel].abs()
+        if keptv.numel():
+            m = keptv.min()
+            kept_abs_min = m if kept_abs_min is None else torch.minimum(kept_abs_min, m)
+        mask = torch.ones(b - a, dtype=torch.bool, device=dev)
+        mask[sel] = False
+        ok = ok and bool(torch.equal(e[a:b][mask].view(torch.int32), acc[mask].view(torch.int32)))
+        dropped_max = acc[mask].abs().max() if mask.any() else None
+        if dropped_max is not None:
+            thr = dropped_max if thr is None else torch.maximum(thr, dropped_max)
+        del acc, mask
+    ok = ok and (thr is None or bool(kept_abs_min >= thr))
+    return ok
+
+
+def run_multi(args, gc, inputs, torch, wl, ctx):
+    """Workload 2: a list of tensors per worker, per-tensor top-k, one launch set per worker."""
+    import numpy as np
+    dev = "cuda:0"
+    off = inputs.offsets_of(wl.sizes)
+    n, W, block = wl.n, wl.W, wl.block
+    ks = np.array([gc.k_from_density(int(s), wl.density) for s in wl.sizes], dtype=np.int64)
+    ktot = int(ks.sum())
+    stot = int(sum(gc.num_scales(int(x), block) for x in ks))
+    bufs = [gc.CompressedBuf.allocate(n, ktot, stot, block, 32, dev) for _ in range(W)]
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+    grads = [None] * W
+    res = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(W)]
+    tc, td = Timer(torch), Timer(torch)
+    for step in range(args.warmup + args.steps):
+        if step == args.warmup:
+            torch.cuda.synchronize()
+            ctx.profile_enable(True)
+            tc.reset()
+            td.reset()
+        for w in range(W):
+            grads[w] = wl.grad(w, step, dev, out=grads[w])
+        torch.cuda.synchronize()
+        with tc:
+            for w in range(W):
+                gc.compress_multi(ctx, grads[w], res[w], off, ks, block, out=bufs[w])
+        with td:
+            gc.decompress_sum_multi(ctx, bufs, ks, n, out=out)
+        gc.sync_status(ctx)
+    torch.cuda.synchronize()
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    ms_c, ms_d = tc.total_ms() / args.steps, td.total_ms() / args.steps
+    stats = gc.last_stats(ctx)
+    info = {"n": n, "k": ktot, "tensors": len(wl.sizes), "block": block, "W": W,
+            "compress_ms_per_worker": ms_c / W, "decompress_sum_ms": ms_d,
+            "fallback_tensors": stats["tensors_fallback"], "note": wl.note}
+    return ms_c + ms_d, W * n * 4, prof, 12 * n, info
+
+
+def cpu_baseline(inputs, wl_config):
+    """The CPU oracle, as it stands, timed on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import gc_oracle
+    gc_oracle.build()
+    n, W = 1 << 27, 16
+    if wl_config == 1:
+        n, W = 1 << 20, 1
+    wl = inputs.workload(wl_config)
+    wl.n = n
+    if wl.sizes is not None:  # multi-tensor workload: time its flat equivalent
+        wl.sizes = None
+    k = gc_oracle.k_from_density(n, wl.density)
+    refs = []
+    t_total = 0.0
+    for w in range(W):
+        g = wl.grad(w, 0, "cpu")
+        gnp = inputs.bf16_bits(g) if g.dtype != __import__("torch").float32 else g.numpy()
+        e = wl.residual0(w, "cpu").numpy()
+        t0 = time.perf_counter()
+        rc, idx, q, s = gc_oracle.compress(gnp, e, k, wl.block)
+        t_total += time.perf_counter() - t0
+        assert rc == 0
+        refs.append((idx, q, s))
+    t0 = time.perf_counter()
+    rc, _ = gc_oracle.decompress_sum(refs, n, wl.block)
+    t_total += time.perf_counter() - t0
+    gbytes = 4 if wl.grad_dtype == "f32" else 2
+    return {"value": W * n * gbytes / t_total / 1e9, "unit": "GB/s of gradient processed", "cores": 1,
+            "kind": "oracle",
+            "sample": f"{W} workers x {n} elements of the same distribution, density {wl.density}, "
+                      f"block {wl.block}: compress x{W} + decompress_sum(W={W}), {t_total:.1f} s on one thread "
+                      f"(host has {os.cpu_count()} logical cores)"}
+
+
+def read_traffic(name):
+    """HBM bytes per k_main launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE),
+    kept as a small text file under profiles/ next to the profile it came from."""
+    path = os.path.join(ROOT, "profiles", f"k_main_{name}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the aggregation is a local reduction over W "
+              "buffers in one GPU's HBM); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2506_17551_amd as gc
+    from paper_2506_17551_amd import inputs
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    wl = inputs.workload(args.workload, args.scale)
+    ctx = gc.Context(0)
+    for opt in args.option:
+        name, val = opt.split("=")
+        ctx.set_option(name, int(val))
+    t_wall = time.time()
+    if wl.sizes is not None:
+        ms_step, grad_bytes, prof, main_bytes, info = run_multi(args, gc, inputs, torch, wl, ctx)
+    else:
+        ms_step, grad_bytes, prof, main_bytes, info = run_flat(args, gc, inputs, torch, wl, ctx)
+    wall = time.time() - t_wall
+    value = grad_bytes / (ms_step * 1e-3) / 1e9
+    km_ms, km_n = prof.get("k_main", (0.0, 0))
+    km_avg = km_ms / max(km_n, 1)
+    achieved = main_bytes / (km_avg * 1e-3) / 1e9 if km_avg > 0 else 0.0
+    kernels = {name: {"ms_total": round(ms, 4), "launches": cnt, "ms_avg": round(ms / cnt, 5)}
+               for name, (ms, cnt) in prof.items() if cnt}
+    result = {
+        "metric": "compress+decompress_sum GB/s of gradient processed and % of MI355X HBM peak",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if wl.grad_dtype == "f32" else "bf16->f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name + ("" if args.scale >= 1.0 else f" (scaled x{args.scale}: not a result)"),
+                   **info,
+                   "timed_region": "sum over the step of W compress intervals + 1 decompress_sum interval "
+                                   "(HIP events on the launch stream); per-worker input generation is untimed",
+                   "pct_hbm_peak_whole_path_algorithmic": round(
+                       100.0 * ((main_bytes * info["W"] + 4 * wl.n) / (ms_step * 1e-3) / 1e9) / HBM_PEAK_GBS, 2),
+                   "wall_s_including_generation": round(wall, 1)},
+        "roofline": {"bound": "hbm", "kernel": "k_main", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": read_traffic(wl.name) if args.scale >= 1.0 else None,
+                     "algorithmic_bytes_per_launch": main_bytes, "avg_launch_ms": round(km_avg, 5),
+                     "launches": km_n},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(inputs, args.workload)
+    ctx.destroy()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

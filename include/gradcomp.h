@@ -132,6 +132,12 @@ int32_t gc_profile_num_kernels(void);
 const char* gc_profile_kernel_name(int32_t id);
 gc_status gc_profile_read(gc_ctx* ctx, int32_t id, double* total_ms, int64_t* launches);
 
+/* Tuning knobs; the defaults are chosen for MI355X and results never depend on them.
+ *   "item_len"   elements one wavefront streams as one contiguous piece (multiple of 1024;
+ *                0 = choose from the total size). Applies to plans built afterwards.
+ * Unknown names or out-of-range values return GC_ERR_INVALID_ARG. */
+gc_status gc_set_option(gc_ctx* ctx, const char* name, int64_t value);
+
 const char* gc_status_string(gc_status s);
 
 #ifdef __cplusplus

@@ -38,7 +38,7 @@ class _GcStats(ctypes.Structure):
 EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_compress",
            "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_multi", "gc_sync_status",
            "gc_last_stats", "gc_profile_enable", "gc_profile_num_kernels", "gc_profile_kernel_name",
-           "gc_profile_read", "gc_status_string"]
+           "gc_profile_read", "gc_set_option", "gc_status_string"]
 
 _lib = None
 
@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
     L.gc_profile_kernel_name.argtypes = [i32]
     L.gc_profile_kernel_name.restype = ctypes.c_char_p
     L.gc_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    L.gc_set_option.argtypes = [vp, ctypes.c_char_p, i64]
+    L.gc_set_option.restype = ctypes.c_int
     L.gc_status_string.argtypes = [ctypes.c_int]
     L.gc_status_string.restype = ctypes.c_char_p
     for name in ("gc_create", "gc_destroy", "gc_compress", "gc_compress_multi", "gc_decompress_sum",
@@ -125,6 +127,9 @@ class Context:
             self.destroy()
         except Exception:
             pass
+
+    def set_option(self, name: str, value: int) -> None:
+        _check(lib().gc_set_option(self.handle, name.encode(), int(value)), "gc_set_option")
 
     # ---- profiling helpers (gc_profile_*) ----
     def profile_enable(self, on: bool = True) -> None:

@@ -52,6 +52,7 @@ struct gc_ctx {
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
   size_t host_ts_cap = 0;
   const Plan* last_plan = nullptr;
+  int64_t opt_item_len = 0;  // 0 = automatic
   // profiling
   bool prof = false;
   std::vector<EventPair> ev_used, ev_free;
@@ -100,7 +101,7 @@ constexpr int64_t kMinSampledN = 1 << 17;
 constexpr int64_t kMinSampledK = 64;
 constexpr int64_t kMaxDensityInv = 8;  // sampled only if k * 8 <= n
 
-Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t block) {
+Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t block, int64_t opt_item_len) {
   Plan* P = new (std::nothrow) Plan();
   if (!P) return nullptr;
   P->offsets.assign(offsets, offsets + T + 1);
@@ -110,6 +111,7 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
   // item length: aim at >= ~16k items so that every CU has several waves, within [1024, 32768]
   int64_t il = round_up(std::max<int64_t>(ntotal / 16384, 1), kWaveTile);
   il = std::min<int64_t>(std::max<int64_t>(il, kWaveTile), 32768);
+  if (opt_item_len > 0) il = opt_item_len;
   P->item_len = (int32_t)il;
   P->td.resize(T);
   int64_t item = 0, kp = 0, sp = 0;
@@ -177,7 +179,7 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
       return GC_OK;
     }
   }
-  Plan* P = build_plan(offsets, k, T, block);
+  Plan* P = build_plan(offsets, k, T, block, ctx->opt_item_len);
   if (!P) return GC_ERR_WORKSPACE;
   gc_status st = ensure(P->td_dev, sizeof(TensorDesc) * T);
   if (st == GC_OK && hipMemcpy(P->td_dev.p, P->td.data(), sizeof(TensorDesc) * T, hipMemcpyHostToDevice) != hipSuccess)
@@ -538,6 +540,23 @@ gc_status gc_profile_enable(gc_ctx* ctx, int32_t on) {
   ctx->ev_used.clear();
   ctx->prof = on != 0;
   return GC_OK;
+}
+
+gc_status gc_set_option(gc_ctx* ctx, const char* name, int64_t value) {
+  if (!ctx || !name) return GC_ERR_INVALID_ARG;
+  if (std::strcmp(name, "item_len") == 0) {
+    if (value < 0 || value % kWaveTile != 0 || value > (int64_t(1) << 30)) return GC_ERR_INVALID_ARG;
+    if (value != ctx->opt_item_len) {  // cached plans were cut with the old length
+      GC_HIP(hipSetDevice(ctx->device));
+      GC_HIP(hipDeviceSynchronize());
+      for (Plan* P : ctx->plans) { release(P->td_dev); delete P; }
+      ctx->plans.clear();
+      ctx->last_plan = nullptr;
+    }
+    ctx->opt_item_len = value;
+    return GC_OK;
+  }
+  return GC_ERR_INVALID_ARG;
 }
 
 int32_t gc_profile_num_kernels(void) { return kKNum; }
