@@ -22,9 +22,9 @@ struct Plan {  // everything that depends only on (offsets, k, block)
   std::vector<int64_t> offsets, k;
   int32_t block = 0;
   std::vector<TensorDesc> td;
-  int32_t item_len = 0, cap = 0;
-  int64_t nitem_slots = 0, ktotal = 0, stotal = 0;
-  int64_t n_sampled = 0;
+  int32_t cap = 0;            // candidate slots per group
+  int64_t ngroups = 0, nsgran = 0, cand_total_cap = 0, ktotal = 0, stotal = 0;
+  int64_t n_sampled = 0, est_chunks = 0;
   DevBuf td_dev;
 };
 
@@ -46,13 +46,13 @@ struct gc_ctx {
   std::vector<Plan*> plans;
   std::vector<DecPlan*> dplans;
   // workspace (sized for the largest plan seen)
-  DevBuf ts, shist, hist, item_cnt, item_gt, item_eq, item_goff, item_eoff, cand_val, cand_rel, kept_val,
-      flags, bounds;
+  DevBuf ts, shist, hist, grp_cnt, grp_part, grp_off, tg_base, slot_val, slot_rel, cand_val, cand_idx, ch_gt,
+      ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, flags, bounds;
   uint32_t* host_flags = nullptr;  // pinned
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
   size_t host_ts_cap = 0;
   const Plan* last_plan = nullptr;
-  int64_t opt_item_len = 0;  // 0 = automatic
+  int64_t opt_main_lds_pad = 49152;  // dynamic LDS of the streaming pass: 3 workgroups per CU
   // profiling
   bool prof = false;
   std::vector<EventPair> ev_used, ev_free;
@@ -101,20 +101,14 @@ constexpr int64_t kMinSampledN = 1 << 17;
 constexpr int64_t kMinSampledK = 64;
 constexpr int64_t kMaxDensityInv = 8;  // sampled only if k * 8 <= n
 
-Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t block, int64_t opt_item_len) {
+Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t block) {
   Plan* P = new (std::nothrow) Plan();
   if (!P) return nullptr;
   P->offsets.assign(offsets, offsets + T + 1);
   P->k.assign(k, k + T);
   P->block = block;
-  const int64_t ntotal = offsets[T];
-  // item length: aim at >= ~16k items so that every CU has several waves, within [1024, 32768]
-  int64_t il = round_up(std::max<int64_t>(ntotal / 16384, 1), kWaveTile);
-  il = std::min<int64_t>(std::max<int64_t>(il, kWaveTile), 32768);
-  if (opt_item_len > 0) il = opt_item_len;
-  P->item_len = (int32_t)il;
   P->td.resize(T);
-  int64_t item = 0, kp = 0, sp = 0;
+  int64_t grp = 0, kp = 0, sp = 0, sg = 0, cb = 0, est = 0;
   double max_lambda = 0.0;
   for (int32_t t = 0; t < T; ++t) {
     TensorDesc& d = P->td[t];
@@ -124,38 +118,46 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
     d.k = k[t];
     d.kprefix = kp;
     d.sprefix = sp;
-    d.nitems = (d.n + il - 1) / il;
-    d.item_begin = item;
-    d.item_end = item + round_up(d.nitems, kItemsPerGroup);
-    item = d.item_end;
+    d.group_begin = grp;
+    d.ngroups = (d.n + kGroup - 1) / kGroup;
+    grp += d.ngroups;
     kp += d.k;
     sp += (d.k + block - 1) / block;
+    d.sgran_begin = sg;
+    d.cand_begin = cb;
     const bool sampled = d.n >= kMinSampledN && d.k >= kMinSampledK && d.k * kMaxDensityInv <= d.n;
     d.mode = sampled ? kSampled : kDense;
     if (sampled) {
-      // sample fraction: about 256 expected winners in the sample, between 1/64 and 1/4 of the data
+      // sample about 256 expected winners, between 1/64 and 1/4 of the data
       double f = 256.0 / (double)d.k;
       f = std::min(0.25, std::max(1.0 / 64.0, f));
-      int64_t sl = round_up((int64_t)std::ceil(f * (double)il), kSampleGranule);
-      sl = std::min<int64_t>(sl, il);
-      d.sample_len = (int32_t)sl;
-      const int64_t last_len = d.n - (d.nitems - 1) * il;
-      const int64_t m = (d.nitems - 1) * sl + std::min<int64_t>(sl, last_len);
-      const double ks = (double)d.k * (double)m / (double)d.n;
+      const int64_t stride = std::max<int64_t>(4, std::min<int64_t>(64, (int64_t)std::floor(1.0 / f)));
+      d.sample_stride = (int32_t)stride;
+      d.nsgran = (d.n / kSampleGranule) / stride;  // whole granules only; >= 8 since n >= 2^17
+      sg += round_up(d.nsgran, 4);
+      const double m = (double)d.nsgran * kSampleGranule;
+      const double ks = (double)d.k * m / (double)d.n;
       // the threshold must leave at least k entries above it: cover the expected sample count
       // of winners plus six standard deviations
       const double target = std::ceil(ks + 6.0 * std::sqrt(ks) + 8.0);
       d.sample_target = (uint32_t)std::min<double>(target, 4.0e9);
-      const double lambda = target / (double)m * (double)il;  // candidates expected per item
-      max_lambda = std::max(max_lambda, lambda);
+      max_lambda = std::max(max_lambda, target / m * (double)kGroup);  // candidates expected per group
+      d.cand_cap = std::min<int64_t>(d.n, 4 * d.k + 4096);
+      cb += d.cand_cap;
+      est += (std::min<int64_t>(d.cand_cap, 2 * d.k) + kGroup - 1) / kGroup + 1;
       P->n_sampled++;
+    } else {
+      est += d.ngroups;
     }
   }
-  P->nitem_slots = item;
+  P->ngroups = grp;
+  P->nsgran = sg;
+  P->cand_total_cap = cb;
   P->ktotal = kp;
   P->stotal = sp;
-  P->cap = (int32_t)std::min<double>(std::ceil(3.0 * max_lambda + 8.0 * std::sqrt(max_lambda) + 32.0),
-                                      (double)il);
+  P->est_chunks = est;
+  const double cap = std::ceil(3.0 * max_lambda + 8.0 * std::sqrt(max_lambda) + 16.0);
+  P->cap = (int32_t)std::min<double>(round_up((int64_t)cap, 16), (double)kGroup);
   if (P->n_sampled == 0) P->cap = 1;
   return P;
 }
@@ -179,22 +181,35 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
       return GC_OK;
     }
   }
-  Plan* P = build_plan(offsets, k, T, block, ctx->opt_item_len);
+  Plan* P = build_plan(offsets, k, T, block);
   if (!P) return GC_ERR_WORKSPACE;
   gc_status st = ensure(P->td_dev, sizeof(TensorDesc) * T);
   if (st == GC_OK && hipMemcpy(P->td_dev.p, P->td.data(), sizeof(TensorDesc) * T, hipMemcpyHostToDevice) != hipSuccess)
     st = GC_ERR_DEVICE;
-  const int64_t slots = P->nitem_slots;
+  const size_t ng = (size_t)P->ngroups, nent = ng * 4;
+  const size_t ngp = (ng + kScanBlock - 1) / kScanBlock, ncp = (nent + kScanBlock - 1) / kScanBlock;
   if (st == GC_OK) st = ensure(ctx->ts, sizeof(TensorState) * T);
   if (st == GC_OK) st = ensure(ctx->shist, sizeof(unsigned long long) * (size_t)T * kSampleBins);
   if (st == GC_OK) st = ensure(ctx->hist, sizeof(unsigned long long) * (size_t)T * kSelBins);
-  if (st == GC_OK) st = ensure(ctx->item_cnt, sizeof(uint32_t) * slots);
-  if (st == GC_OK) st = ensure(ctx->item_gt, sizeof(uint32_t) * slots);
-  if (st == GC_OK) st = ensure(ctx->item_eq, sizeof(uint32_t) * slots);
-  if (st == GC_OK) st = ensure(ctx->item_goff, sizeof(long long) * slots);
-  if (st == GC_OK) st = ensure(ctx->item_eoff, sizeof(long long) * slots);
-  if (st == GC_OK) st = ensure(ctx->cand_val, sizeof(float) * (size_t)slots * P->cap);
-  if (st == GC_OK) st = ensure(ctx->cand_rel, sizeof(uint32_t) * (size_t)slots * P->cap);
+  if (st == GC_OK) st = ensure(ctx->grp_cnt, sizeof(uint32_t) * ng);
+  if (st == GC_OK) st = ensure(ctx->grp_part, sizeof(unsigned long long) * ngp);
+  if (st == GC_OK) st = ensure(ctx->grp_off, sizeof(long long) * ng);
+  if (st == GC_OK) st = ensure(ctx->tg_base, sizeof(long long) * (T + 1));
+  if (P->n_sampled > 0) {
+    if (st == GC_OK) st = ensure(ctx->slot_val, sizeof(float) * ng * P->cap);
+    if (st == GC_OK) st = ensure(ctx->slot_rel, sizeof(uint32_t) * ng * P->cap);
+    if (st == GC_OK) st = ensure(ctx->cand_val, sizeof(float) * (size_t)P->cand_total_cap);
+    if (st == GC_OK) st = ensure(ctx->cand_idx, sizeof(long long) * (size_t)P->cand_total_cap);
+  }
+  if (st == GC_OK) st = ensure(ctx->ch_gt, sizeof(uint32_t) * nent);
+  if (st == GC_OK) st = ensure(ctx->ch_eq, sizeof(uint32_t) * nent);
+  if (st == GC_OK) st = ensure(ctx->ch_part_gt, sizeof(unsigned long long) * ncp);
+  if (st == GC_OK) st = ensure(ctx->ch_part_eq, sizeof(unsigned long long) * ncp);
+  if (st == GC_OK) st = ensure(ctx->ch_goff, sizeof(long long) * nent);
+  if (st == GC_OK) st = ensure(ctx->ch_eoff, sizeof(long long) * nent);
+  if (st == GC_OK) st = ensure(ctx->tb_g, sizeof(long long) * T);
+  if (st == GC_OK) st = ensure(ctx->tb_e, sizeof(long long) * T);
+  if (st == GC_OK) st = ensure(ctx->totals, sizeof(long long) * 4);
   if (st == GC_OK) st = ensure(ctx->kept_val, sizeof(float) * (size_t)P->ktotal);
   if (st == GC_OK && ctx->host_ts_cap < (size_t)T) {
     if (ctx->host_ts) (void)hipHostFree(ctx->host_ts);
@@ -279,7 +294,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   Plan* P = nullptr;
   gc_status st = get_plan(ctx, offsets, k, T, block, &P);
   if (st != GC_OK) return st;
-  if (P->nitem_slots / kItemsPerGroup >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
+  if (P->ngroups >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
 
   Workspace ws;
   std::memset(&ws, 0, sizeof(ws));
@@ -287,34 +302,51 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   ws.ts = (TensorState*)ctx->ts.p;
   ws.shist = (unsigned long long*)ctx->shist.p;
   ws.hist = (unsigned long long*)ctx->hist.p;
-  ws.item_cnt = (uint32_t*)ctx->item_cnt.p;
-  ws.item_gt = (uint32_t*)ctx->item_gt.p;
-  ws.item_eq = (uint32_t*)ctx->item_eq.p;
-  ws.item_goff = (long long*)ctx->item_goff.p;
-  ws.item_eoff = (long long*)ctx->item_eoff.p;
+  ws.grp_cnt = (uint32_t*)ctx->grp_cnt.p;
+  ws.grp_part = (unsigned long long*)ctx->grp_part.p;
+  ws.grp_off = (long long*)ctx->grp_off.p;
+  ws.tg_base = (long long*)ctx->tg_base.p;
+  ws.slot_val = (float*)ctx->slot_val.p;
+  ws.slot_rel = (uint32_t*)ctx->slot_rel.p;
   ws.cand_val = (float*)ctx->cand_val.p;
-  ws.cand_rel = (uint32_t*)ctx->cand_rel.p;
+  ws.cand_idx = (long long*)ctx->cand_idx.p;
+  ws.ch_gt = (uint32_t*)ctx->ch_gt.p;
+  ws.ch_eq = (uint32_t*)ctx->ch_eq.p;
+  ws.ch_part_gt = (unsigned long long*)ctx->ch_part_gt.p;
+  ws.ch_part_eq = (unsigned long long*)ctx->ch_part_eq.p;
+  ws.ch_goff = (long long*)ctx->ch_goff.p;
+  ws.ch_eoff = (long long*)ctx->ch_eoff.p;
+  ws.tb_g = (long long*)ctx->tb_g.p;
+  ws.tb_e = (long long*)ctx->tb_e.p;
+  ws.totals = (long long*)ctx->totals.p;
   ws.kept_val = (float*)ctx->kept_val.p;
   ws.flags = (uint32_t*)ctx->flags.p;
   ws.T = T;
-  ws.item_len = P->item_len;
   ws.cap = P->cap;
-  ws.nitem_slots = P->nitem_slots;
+  ws.ngroups = P->ngroups;
+  ws.nsgran = P->nsgran;
+  ws.max_chunks = P->ngroups;
+  ws.est_chunk_wgs = (int32_t)std::min<int64_t>(P->est_chunks, 1 << 20);
+  ws.main_lds_pad = (int32_t)ctx->opt_main_lds_pad;
   OutBuf ob{out->indices, out->q, out->scales, out->index_bits, block};
   hipStream_t s = (hipStream_t)hip_stream;
+  const bool any_sampled = P->n_sampled > 0;
 
   { Scope sc(ctx, kKInit, s); launch_init(ws, s); }
-  if (P->n_sampled > 0) {
+  if (any_sampled) {
     { Scope sc(ctx, kKSample, s); launch_sample(ws, grad, (int)dtype, residual, s); }
     { Scope sc(ctx, kKSampleThresh, s); launch_sample_thresh(ws, s); }
   }
   { Scope sc(ctx, kKMain, s); launch_main(ws, grad, (int)dtype, residual, s); }
+  if (any_sampled) { Scope sc(ctx, kKGroupScan, s); launch_group_scan(ws, s); }
+  { Scope sc(ctx, kKRoute, s); launch_route(ws, s); }
+  if (any_sampled) { Scope sc(ctx, kKGather, s); launch_gather(ws, s); }
   for (int level = 0; level < kSelLevels; ++level) {
-    if (level > 0 || P->n_sampled > 0) { Scope sc(ctx, kKHist, s); launch_hist(ws, level, residual, s); }
+    { Scope sc(ctx, kKHist, s); launch_hist(ws, level, residual, s); }
     { Scope sc(ctx, kKSelectScan, s); launch_select_scan(ws, level, s); }
   }
   { Scope sc(ctx, kKCount, s); launch_count(ws, residual, s); }
-  { Scope sc(ctx, kKItemScan, s); launch_item_scan(ws, s); }
+  { Scope sc(ctx, kKChunkScan, s); launch_chunk_scan(ws, s); }
   { Scope sc(ctx, kKEmit, s); launch_emit(ws, residual, ob, s); }
   { Scope sc(ctx, kKQuant, s); launch_quant(ws, residual, ob, P->stotal, s); }
   ctx->last_plan = P;
@@ -411,9 +443,9 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   return launch_status();
 }
 
-const char* const kKernelNames[kKNum] = {"k_init",  "k_sample", "k_sample_thresh", "k_main",
-                                         "k_hist",  "k_select_scan", "k_count", "k_item_scan",
-                                         "k_emit",  "k_quant", "k_dec_bounds", "k_dec_tiles"};
+const char* const kKernelNames[kKNum] = {"k_init", "k_sample", "k_sample_thresh", "k_main", "k_group_scan",
+                                         "k_route", "k_gather", "k_hist", "k_select_scan", "k_count",
+                                         "k_chunk_scan", "k_emit", "k_quant", "k_dec_bounds", "k_dec_tiles"};
 
 }  // namespace
 
@@ -451,8 +483,10 @@ gc_status gc_destroy(gc_ctx* c) {
   (void)hipDeviceSynchronize();
   for (Plan* P : c->plans) { release(P->td_dev); delete P; }
   for (DecPlan* D : c->dplans) { release(D->kprefix); release(D->sprefix); delete D; }
-  DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->item_cnt, &c->item_gt, &c->item_eq, &c->item_goff,
-                   &c->item_eoff, &c->cand_val, &c->cand_rel, &c->kept_val, &c->flags, &c->bounds};
+  DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
+                   &c->slot_val, &c->slot_rel, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
+                   &c->ch_part_gt, &c->ch_part_eq, &c->ch_goff, &c->ch_eoff, &c->tb_g, &c->tb_e,
+                   &c->totals, &c->kept_val, &c->flags, &c->bounds};
   for (DevBuf* b : all) release(*b);
   if (c->host_flags) (void)hipHostFree(c->host_flags);
   if (c->host_ts) (void)hipHostFree(c->host_ts);
@@ -527,7 +561,7 @@ gc_status gc_last_stats(gc_ctx* ctx, gc_stats* stats) {
     stats->tensors_sampled++;
     const TensorState& st = ctx->host_ts[t];
     stats->candidates += (int64_t)st.cand_total;
-    if (st.overflow || st.cand_total < (unsigned long long)P->td[t].k) stats->tensors_fallback++;
+    if (!st.use_cand) stats->tensors_fallback++;
   }
   return GC_OK;
 }
@@ -544,16 +578,9 @@ gc_status gc_profile_enable(gc_ctx* ctx, int32_t on) {
 
 gc_status gc_set_option(gc_ctx* ctx, const char* name, int64_t value) {
   if (!ctx || !name) return GC_ERR_INVALID_ARG;
-  if (std::strcmp(name, "item_len") == 0) {
-    if (value < 0 || value % kWaveTile != 0 || value > (int64_t(1) << 30)) return GC_ERR_INVALID_ARG;
-    if (value != ctx->opt_item_len) {  // cached plans were cut with the old length
-      GC_HIP(hipSetDevice(ctx->device));
-      GC_HIP(hipDeviceSynchronize());
-      for (Plan* P : ctx->plans) { release(P->td_dev); delete P; }
-      ctx->plans.clear();
-      ctx->last_plan = nullptr;
-    }
-    ctx->opt_item_len = value;
+  if (std::strcmp(name, "main_lds_pad") == 0) {
+    if (value < 0 || value > 65536) return GC_ERR_INVALID_ARG;
+    ctx->opt_main_lds_pad = value;
     return GC_OK;
   }
   return GC_ERR_INVALID_ARG;

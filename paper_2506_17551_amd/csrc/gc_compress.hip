@@ -1,26 +1,28 @@
 // Compress side: error-feedback accumulate, exact magnitude top-k, per-block int8
 // codes and the fused residual write-back (paper Sec. III.B, Eq. 11), for gfx950.
 //
-// Shape of the computation
-//   The flat gradient is cut into ITEMS of item_len consecutive elements; one
-//   wavefront owns one item, one workgroup owns kItemsPerGroup consecutive items of one tensor.
-//   1. k_sample       reads a small slice of every item, forms acc = g + e there and
-//                     histograms the top 13 key bits; k_sample_thresh turns that into a
-//                     candidate threshold t_lo that, with overwhelming probability, is
-//                     below the true k-th largest key.
-//   2. k_main         the one full streaming pass: acc = g + e with 128-bit loads, acc
-//                     written over e, and every entry with key >= t_lo appended, in
-//                     ascending index order, to the item's candidate slots.
-//   3. k_hist / k_select_scan (x3)  exact radix select of the k-th largest key T and the
-//                     tie quota over the candidates (LDS histograms per workgroup).
-//   4. k_count / k_item_scan / k_emit   ordered compaction (wavefront ballot + prefix) of
-//                     the kept entries: key > T, or key == T among the first `quota` such.
-//   5. k_quant        per block of kept entries: amax, scale, int8 codes, and the residual
-//                     at the kept positions (acc - q*s).
-//   Small or high-density tensors skip 1 and the candidate gathering: k_main histograms the
-//   first digit itself and steps 3-4 read the dense residual (which then holds acc). A
-//   sampled tensor whose candidates turn out to be too few (or overflow their slots) takes
-//   the same dense route, so the result never depends on the sample.
+// Shape of the computation (one call = one worker's step over T tensors)
+//   1. k_sample / k_sample_thresh   read one 256-element granule out of every `stride`,
+//        form acc = g + e there, histogram the top 13 key bits in LDS and pick a candidate
+//        threshold t_lo that, with overwhelming probability, lies below the k-th largest key.
+//   2. k_main   THE streaming pass, the only one that touches every element: a workgroup
+//        streams one group of 4096 consecutive elements with 128-bit loads, writes
+//        acc = g + e over e, and appends every entry with key >= t_lo, in ascending index
+//        order (wavefront ballots + a 4-entry LDS prefix), to the group's candidate slots.
+//        Workgroups are short-lived and few per CU: HBM sees a narrow window of addresses
+//        that moves through the arrays once, which is what gets closest to its streaming rate.
+//   3. k_group_scan / k_route / k_gather   prefix-sum the groups' counts and pack all
+//        candidates of a tensor into one dense ascending array.
+//   4. k_hist / k_select_scan (x3)   exact radix select (LDS histograms per workgroup) of the
+//        k-th largest key T and the tie quota, over the dense candidates.
+//   5. k_count / k_chunk_scan / k_emit   ordered compaction (wavefront ballot + prefix) of the
+//        kept entries: key > T, or key == T among the first `quota` such entries.
+//   6. k_quant   per block of kept entries: amax, scale, int8 codes, and the residual at the
+//        kept positions, acc - q*s (Eq. 11 with ghat = q*s).
+//   Small or dense tensors skip 1 and 3: steps 4-5 then read the residual itself (it holds
+//   acc after step 2). A sampled tensor whose candidates turn out too few, too many, or too
+//   clustered for their slots takes that same dense route, decided on the device; the result
+//   never depends on the sample, only the time does.
 #include "gc_internal.h"
 
 namespace gc {
@@ -33,28 +35,57 @@ __device__ __forceinline__ uint32_t mbcnt64(uint64_t m) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 __device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
-__device__ __forceinline__ float bf16_widen(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
 template <typename G> __device__ __forceinline__ float load_grad(const G* g, int64_t i);
 template <> __device__ __forceinline__ float load_grad<float>(const float* g, int64_t i) { return g[i]; }
 template <> __device__ __forceinline__ float load_grad<uint16_t>(const uint16_t* g, int64_t i) {
-  return bf16_widen(g[i]);
+  return __uint_as_float((uint32_t)g[i] << 16);  // bf16 -> fp32 is exact
 }
 
-// Largest t with td[t].item_begin <= item.
-__device__ __forceinline__ int find_tensor_by_item(const TensorDesc* td, int T, int64_t item, int hint) {
+template <typename G> struct GradVec;
+template <> struct GradVec<float> {
+  static __device__ __forceinline__ f32x4 load(const float* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  }
+  static constexpr uint32_t kAlignMask = 15u;
+};
+template <> struct GradVec<uint16_t> {
+  static __device__ __forceinline__ f32x4 load(const uint16_t* p) {
+    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+    f32x4 r;
+    r.x = __uint_as_float(v.x << 16);
+    r.y = __uint_as_float(v.x & 0xFFFF0000u);
+    r.z = __uint_as_float(v.y << 16);
+    r.w = __uint_as_float(v.y & 0xFFFF0000u);
+    return r;
+  }
+  static constexpr uint32_t kAlignMask = 7u;
+};
+
+// Largest t in [0, T) with begin(t) <= x (begin is non-decreasing, begin(0) <= x).
+template <typename F>
+__device__ __forceinline__ int find_last_le(int T, long long x, int hint, F begin) {
   if (T == 1) return 0;
-  if (item >= td[hint].item_begin && item < td[hint].item_end) return hint;
+  if (begin(hint) <= x && (hint + 1 == T || begin(hint + 1) > x)) return hint;
   int lo = 0, hi = T - 1;
   while (lo < hi) {
-    int mid = (lo + hi + 1) >> 1;
-    if (td[mid].item_begin <= item) lo = mid; else hi = mid - 1;
+    const int mid = (lo + hi + 1) >> 1;
+    if (begin(mid) <= x) lo = mid; else hi = mid - 1;
   }
   return lo;
 }
 
-__device__ __forceinline__ bool fast_path_failed(const TensorState& st, const TensorDesc& d) {
-  return st.overflow != 0u || st.cand_total < (unsigned long long)d.k;
+// Sum over the block of one value per thread (blockDim.x a multiple of 64, <= 1024).
+__device__ __forceinline__ unsigned long long block_sum(unsigned long long v, unsigned long long* sh) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[wave] = v;
+  __syncthreads();
+  unsigned long long t = 0;
+  for (int w = 0; w < nw; ++w) t += sh[w];
+  return t;
 }
 
 // ---------------------------------------------------------------- k_init
@@ -62,20 +93,26 @@ __global__ __launch_bounds__(256) void k_init(Workspace ws) {
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   const int64_t ns = (int64_t)ws.T * kSampleBins, nh = (int64_t)ws.T * kSelBins;
+  const int64_t ngp = (ws.ngroups + kScanBlock - 1) / kScanBlock;
+  const int64_t ncp = (ws.max_chunks * 4 + kScanBlock - 1) / kScanBlock;
   for (int64_t i = tid; i < ns; i += stride) ws.shist[i] = 0ull;
   for (int64_t i = tid; i < nh; i += stride) ws.hist[i] = 0ull;
+  for (int64_t i = tid; i < ngp; i += stride) ws.grp_part[i] = 0ull;
+  for (int64_t i = tid; i < ncp; i += stride) { ws.ch_part_gt[i] = 0ull; ws.ch_part_eq[i] = 0ull; }
   for (int64_t i = tid; i < ws.T; i += stride) {
     TensorState z;
-    z.cand_total = 0ull; z.k_rem = 0ull; z.t_lo = 0u; z.overflow = 0u; z.prefix = 0u; z.pad_ = 0u;
+    z.k_rem = 0ull; z.vlen = 0; z.achunk_begin = 0; z.cand_total = 0;
+    z.t_lo = 0u; z.overflow = 0u; z.prefix = 0u; z.use_cand = 0u;
     ws.ts[i] = z;
   }
+  if (tid == 0) ws.totals[0] = 0;
 }
 
 // ---------------------------------------------------------------- LDS histogram flush
 template <int NB>
 __device__ __forceinline__ void flush_lds_hist(uint32_t* lh, unsigned long long* gh) {
   for (int b = threadIdx.x; b < NB; b += blockDim.x) {
-    uint32_t v = lh[b];
+    const uint32_t v = lh[b];
     if (v) {
       atomicAdd(&gh[b], (unsigned long long)v);
       lh[b] = 0u;
@@ -84,23 +121,26 @@ __device__ __forceinline__ void flush_lds_hist(uint32_t* lh, unsigned long long*
 }
 
 // ---------------------------------------------------------------- k_sample
-__device__ __forceinline__ uint32_t item_hash(uint64_t li) {
-  uint64_t x = li * 0x9E3779B97F4A7C15ull;
+__device__ __forceinline__ uint32_t mix_hash(uint64_t x) {
+  x *= 0x9E3779B97F4A7C15ull;
   return (uint32_t)(x >> 33);
 }
 
 template <typename G>
 __global__ __launch_bounds__(256) void k_sample(Workspace ws, const G* __restrict__ g,
-                                                const float* __restrict__ e, int64_t ngroups) {
+                                                const float* __restrict__ e) {
   __shared__ uint32_t lh[kSampleBins];
-  for (int b = threadIdx.x; b < kSampleBins; b += blockDim.x) lh[b] = 0u;
+  for (int b = threadIdx.x; b < kSampleBins; b += 256) lh[b] = 0u;
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int cur = -1;
-  for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
-    const int t = find_tensor_by_item(ws.td, ws.T, grp * kItemsPerGroup, cur < 0 ? 0 : cur);
+  // A workgroup takes 4 consecutive sampled-granule slots per iteration, one per wavefront. Every
+  // tensor's slots start at a multiple of 4 and are padded to a multiple of 4, so one iteration
+  // never mixes tensors and the LDS histogram can be flushed when the tensor changes.
+  for (int64_t s0 = (int64_t)blockIdx.x * 4; s0 < ws.nsgran; s0 += (int64_t)gridDim.x * 4) {
+    const int t = find_last_le(ws.T, s0, cur < 0 ? 0 : cur, [&](int i) { return (long long)ws.td[i].sgran_begin; });
     if (t != cur) {
-      if (cur >= 0 && ws.td[cur].mode == kSampled) {
+      if (cur >= 0) {
         __syncthreads();
         flush_lds_hist<kSampleBins>(lh, ws.shist + (int64_t)cur * kSampleBins);
         __syncthreads();
@@ -108,20 +148,30 @@ __global__ __launch_bounds__(256) void k_sample(Workspace ws, const G* __restric
       cur = t;
     }
     const TensorDesc d = ws.td[t];
-    if (d.mode != kSampled) continue;
-    const int64_t li = grp * kItemsPerGroup + wave - d.item_begin;
-    if (li >= d.nitems) continue;
-    const int64_t ioff = li * ws.item_len;
-    const uint32_t len = (uint32_t)min((int64_t)ws.item_len, d.n - ioff);
-    const uint32_t slen = min((uint32_t)d.sample_len, len);
-    const uint32_t nphase = (len - slen) / kSampleGranule + 1u;
-    const int64_t base = d.off + ioff + (int64_t)(item_hash((uint64_t)li) % nphase) * kSampleGranule;
-    for (uint32_t j = lane; j < slen; j += 64) {
-      const float acc = __fadd_rn(load_grad<G>(g, base + j), e[base + j]);
-      atomicAdd(&lh[key_of(acc) >> kSampleShift], 1u);
+    const int64_t ls = s0 + wave - d.sgran_begin;  // sgran_begin is a multiple of 4 and nsgran padded
+    if (ls >= d.nsgran) continue;
+    const int64_t gran = ls * d.sample_stride + (int64_t)(mix_hash((uint64_t)ls) % (uint32_t)d.sample_stride);
+    const int64_t base = d.off + gran * kSampleGranule;
+    const G* gp = g + base;
+    const float* ep = e + base;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(gp) & GradVec<G>::kAlignMask) == 0) &&
+                         ((reinterpret_cast<uintptr_t>(ep) & 15u) == 0);
+    if (aligned) {
+      const f32x4 gv = GradVec<G>::load(gp + lane * 4);
+      const f32x4 ev = *reinterpret_cast<const f32x4*>(ep + lane * 4);
+      atomicAdd(&lh[key_of(__fadd_rn(gv.x, ev.x)) >> kSampleShift], 1u);
+      atomicAdd(&lh[key_of(__fadd_rn(gv.y, ev.y)) >> kSampleShift], 1u);
+      atomicAdd(&lh[key_of(__fadd_rn(gv.z, ev.z)) >> kSampleShift], 1u);
+      atomicAdd(&lh[key_of(__fadd_rn(gv.w, ev.w)) >> kSampleShift], 1u);
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int j = c * 64 + lane;
+        atomicAdd(&lh[key_of(__fadd_rn(load_grad<G>(gp, j), ep[j])) >> kSampleShift], 1u);
+      }
     }
   }
-  if (cur >= 0 && ws.td[cur].mode == kSampled) {
+  if (cur >= 0) {
     __syncthreads();
     flush_lds_hist<kSampleBins>(lh, ws.shist + (int64_t)cur * kSampleBins);
   }
@@ -129,7 +179,7 @@ __global__ __launch_bounds__(256) void k_sample(Workspace ws, const G* __restric
 
 // ---------------------------------------------------------------- crossing search
 // Largest bin b with sum_{j >= b} h[j] >= target; `above` = sum_{j > b} h[j].
-// If the total is below target: b = 0. All threads of a 256-thread block call it;
+// If the total is below target: b = 0. All 256 threads of the block call it;
 // the result is valid in every thread.
 template <int NB>
 __device__ void find_from_top(const unsigned long long* __restrict__ h, unsigned long long target,
@@ -154,7 +204,6 @@ __device__ void find_from_top(const unsigned long long* __restrict__ h, unsigned
       if (acc + h[b] >= target) break;
       acc += h[b];
     }
-    if (c == 0 && b == 0) { /* total may be below target: bin 0 either way */ }
     s_bin = (uint32_t)b;
     s_above = acc;
   }
@@ -176,162 +225,264 @@ __global__ __launch_bounds__(256) void k_sample_thresh(Workspace ws) {
 }
 
 // ---------------------------------------------------------------- k_main
-// Append this lane's candidates of one row (4 consecutive elements per lane, lanes
-// ascending) to the item's slots in ascending index order.
-__device__ __forceinline__ void emit_row(bool c0, bool c1, bool c2, bool c3, f32x4 a, uint32_t rel,
-                                         uint32_t& cnt, uint32_t cap, float* __restrict__ cv,
-                                         uint32_t* __restrict__ cr) {
-  const uint64_t m0 = __ballot(c0), m1 = __ballot(c1), m2 = __ballot(c2), m3 = __ballot(c3);
-  if ((m0 | m1 | m2 | m3) == 0ull) return;
-  uint32_t r = cnt + mbcnt64(m0) + mbcnt64(m1) + mbcnt64(m2) + mbcnt64(m3);
-  if (c0) { if (r < cap) { cv[r] = a.x; cr[r] = rel; } ++r; }
-  if (c1) { if (r < cap) { cv[r] = a.y; cr[r] = rel + 1u; } ++r; }
-  if (c2) { if (r < cap) { cv[r] = a.z; cr[r] = rel + 2u; } ++r; }
-  if (c3) { if (r < cap) { cv[r] = a.w; cr[r] = rel + 3u; } }
-  cnt += (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
-}
-
-template <typename G> struct GradVec;
-template <> struct GradVec<float> {
-  static __device__ __forceinline__ f32x4 load(const float* p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-  }
-  static constexpr uint32_t kAlignMask = 15u;
-};
-template <> struct GradVec<uint16_t> {
-  static __device__ __forceinline__ f32x4 load(const uint16_t* p) {
-    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
-    f32x4 r;
-    r.x = __uint_as_float(v.x << 16);
-    r.y = __uint_as_float(v.x & 0xFFFF0000u);
-    r.z = __uint_as_float(v.y << 16);
-    r.w = __uint_as_float(v.y & 0xFFFF0000u);
-    return r;
-  }
-  static constexpr uint32_t kAlignMask = 7u;
-};
-
 template <typename G>
 __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict__ g, float* __restrict__ e) {
-  __shared__ uint32_t lh[kSelBins];
+  extern __shared__ char lds_pad[];  // dynamic LDS only limits how many workgroups share a CU
+  __shared__ uint32_t wcnt[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t item = (int64_t)blockIdx.x * kItemsPerGroup + wave;
-  const int t = find_tensor_by_item(ws.td, ws.T, (int64_t)blockIdx.x * kItemsPerGroup, 0);
+  const int64_t grp = blockIdx.x;
+  const int t = find_last_le(ws.T, grp, 0, [&](int i) { return (long long)ws.td[i].group_begin; });
   const TensorDesc d = ws.td[t];
-  const bool dense = d.mode == kDense;  // uniform over the workgroup
-  if (dense) {
-    for (int b = threadIdx.x; b < kSelBins; b += 256) lh[b] = 0u;
-    __syncthreads();
+  const int64_t goff = (grp - d.group_begin) * kGroup;
+  const int64_t glen = min((int64_t)kGroup, d.n - goff);  // >= 1 by construction of the plan
+  const int wstart = wave * kWaveTile;
+  const int wlen = (int)max((int64_t)0, min((int64_t)kWaveTile, glen - wstart));
+  const bool sampled = d.mode == kSampled;
+  const uint32_t t_lo = sampled ? ws.ts[t].t_lo : 0xFFFFFFFFu;  // no key reaches 0xFFFFFFFF
+  const G* gp = g + d.off + goff + wstart;
+  float* ep = e + d.off + goff + wstart;
+  const bool vec = wlen == kWaveTile && ((reinterpret_cast<uintptr_t>(gp) & GradVec<G>::kAlignMask) == 0) &&
+                   ((reinterpret_cast<uintptr_t>(ep) & 15u) == 0);
+  f32x4 a[4];
+  uint32_t rank[4] = {0u, 0u, 0u, 0u};
+  uint32_t flags = 0u, mycnt = 0u;
+  if (vec) {
+    f32x4 gv[4], ev[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) gv[u] = GradVec<G>::load(gp + u * 256 + lane * 4);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) ev[u] = *reinterpret_cast<const f32x4*>(ep + u * 256 + lane * 4);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      a[u].x = __fadd_rn(gv[u].x, ev[u].x);
+      a[u].y = __fadd_rn(gv[u].y, ev[u].y);
+      a[u].z = __fadd_rn(gv[u].z, ev[u].z);
+      a[u].w = __fadd_rn(gv[u].w, ev[u].w);
+      __builtin_nontemporal_store(a[u], reinterpret_cast<f32x4*>(ep + u * 256 + lane * 4));
+      const bool c0 = key_of(a[u].x) >= t_lo, c1 = key_of(a[u].y) >= t_lo, c2 = key_of(a[u].z) >= t_lo,
+                 c3 = key_of(a[u].w) >= t_lo;
+      const uint64_t m0 = __ballot(c0), m1 = __ballot(c1), m2 = __ballot(c2), m3 = __ballot(c3);
+      rank[u] = mycnt + mbcnt64(m0) + mbcnt64(m1) + mbcnt64(m2) + mbcnt64(m3);
+      flags |= ((uint32_t)c0 | ((uint32_t)c1 << 1) | ((uint32_t)c2 << 2) | ((uint32_t)c3 << 3)) << (4 * u);
+      mycnt += (uint32_t)(__popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3));
+    }
+  } else {
+    // tail group of a tensor, or addresses that are not 16-byte aligned: one element per lane
+    for (int j0 = 0; j0 < wlen; j0 += 64) {
+      const int j = j0 + lane;
+      bool c = false;
+      if (j < wlen) {
+        const float acc = __fadd_rn(load_grad<G>(gp, j), ep[j]);
+        ep[j] = acc;
+        c = key_of(acc) >= t_lo;
+      }
+      mycnt += (uint32_t)__popcll(__ballot(c));
+    }
   }
-  const int64_t li = item - d.item_begin;
-  if (li < d.nitems) {
-    const int64_t ioff = li * ws.item_len;
-    const int64_t start = d.off + ioff;
-    const uint32_t len = (uint32_t)min((int64_t)ws.item_len, d.n - ioff);
-    const uint32_t t_lo = dense ? 0u : ws.ts[t].t_lo;
-    const uint32_t cap = (uint32_t)ws.cap;
-    float* __restrict__ cv = ws.cand_val + item * (int64_t)cap;
-    uint32_t* __restrict__ cr = ws.cand_rel + item * (int64_t)cap;
-    uint32_t cnt = 0;
-    const G* gp = g + start;
-    float* ep = e + start;
-    uint32_t base = 0;
-    const bool aligned = ((reinterpret_cast<uintptr_t>(gp) & GradVec<G>::kAlignMask) == 0) &&
-                         ((reinterpret_cast<uintptr_t>(ep) & 15u) == 0);
-    if (aligned) {
-      for (; base + kWaveTile <= len; base += kWaveTile) {
-        f32x4 gv[4], ev[4];
+  if (!sampled) {  // uniform over the workgroup: a dense tensor gathers no candidates
+    if (threadIdx.x == 0) ws.grp_cnt[grp] = 0u;
+    return;
+  }
+  if (lane == 0) wcnt[wave] = mycnt;
+  __syncthreads();
+  uint32_t before = 0u, tot = 0u;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) gv[u] = GradVec<G>::load(gp + base + u * 256 + lane * 4);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) ev[u] = *reinterpret_cast<const f32x4*>(ep + base + u * 256 + lane * 4);
+  for (int w = 0; w < 4; ++w) {
+    const uint32_t c = wcnt[w];
+    if (w < wave) before += c;
+    tot += c;
+  }
+  const uint32_t cap = (uint32_t)ws.cap;
+  if (tot) {
+    float* __restrict__ cv = ws.slot_val + grp * (int64_t)cap;
+    uint32_t* __restrict__ cr = ws.slot_rel + grp * (int64_t)cap;
+    if (vec) {
+      if (flags) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          f32x4 a;
-          a.x = __fadd_rn(gv[u].x, ev[u].x);
-          a.y = __fadd_rn(gv[u].y, ev[u].y);
-          a.z = __fadd_rn(gv[u].z, ev[u].z);
-          a.w = __fadd_rn(gv[u].w, ev[u].w);
-          __builtin_nontemporal_store(a, reinterpret_cast<f32x4*>(ep + base + u * 256 + lane * 4));
-          const uint32_t k0 = key_of(a.x), k1 = key_of(a.y), k2 = key_of(a.z), k3 = key_of(a.w);
-          if (dense) {
-            atomicAdd(&lh[k0 >> 20], 1u);
-            atomicAdd(&lh[k1 >> 20], 1u);
-            atomicAdd(&lh[k2 >> 20], 1u);
-            atomicAdd(&lh[k3 >> 20], 1u);
-          } else {
-            emit_row(k0 >= t_lo, k1 >= t_lo, k2 >= t_lo, k3 >= t_lo, a, base + u * 256 + lane * 4, cnt,
-                     cap, cv, cr);
+          const uint32_t f = (flags >> (4 * u)) & 15u;
+          if (f) {
+            uint32_t r = before + rank[u];
+            const uint32_t rel = (uint32_t)(wstart + u * 256 + lane * 4);
+            if (f & 1u) { if (r < cap) { cv[r] = a[u].x; cr[r] = rel; } ++r; }
+            if (f & 2u) { if (r < cap) { cv[r] = a[u].y; cr[r] = rel + 1u; } ++r; }
+            if (f & 4u) { if (r < cap) { cv[r] = a[u].z; cr[r] = rel + 2u; } ++r; }
+            if (f & 8u) { if (r < cap) { cv[r] = a[u].w; cr[r] = rel + 3u; } }
           }
         }
       }
-    }
-    // tail of the item, or the whole item when its addresses are not 16-byte aligned
-    for (uint32_t j0 = base; j0 < len; j0 += 64) {
-      const uint32_t j = j0 + lane;
-      const bool valid = j < len;
-      float a = 0.0f;
-      if (valid) {
-        a = __fadd_rn(load_grad<G>(gp, j), ep[j]);
-        ep[j] = a;
-      }
-      const uint32_t key = key_of(a);
-      if (dense) {
-        if (valid) atomicAdd(&lh[key >> 20], 1u);
-      } else {
-        const bool c = valid && key >= t_lo;
-        const uint64_t m = __ballot(c);
-        if (m) {
-          const uint32_t r = cnt + mbcnt64(m);
-          if (c && r < cap) { cv[r] = a; cr[r] = j; }
-          cnt += (uint32_t)__popcll(m);
+    } else if (mycnt) {
+      // second look at what this wave just wrote (acc is in e now)
+      uint32_t r0 = before;
+      for (int j0 = 0; j0 < wlen; j0 += 64) {
+        const int j = j0 + lane;
+        float acc = 0.0f;
+        bool c = false;
+        if (j < wlen) {
+          acc = ep[j];
+          c = key_of(acc) >= t_lo;
         }
+        const uint64_t m = __ballot(c);
+        const uint32_t r = r0 + mbcnt64(m);
+        if (c && r < cap) { cv[r] = acc; cr[r] = (uint32_t)(wstart + j); }
+        r0 += (uint32_t)__popcll(m);
       }
     }
-    if (!dense && lane == 0) {
-      ws.item_cnt[item] = min(cnt, cap);
-      if (cnt > cap) ws.ts[t].overflow = 1u;
-      if (cnt) atomicAdd(&ws.ts[t].cand_total, (unsigned long long)cnt);
-    }
-  } else if (!dense && lane == 0) {
-    ws.item_cnt[item] = 0u;
   }
-  if (dense) {
+  if (threadIdx.x == 0) {
+    const uint32_t kept = min(tot, cap);
+    ws.grp_cnt[grp] = kept;
+    if (kept) atomicAdd(&ws.grp_part[grp / kScanBlock], (unsigned long long)kept);
+    if (tot > cap) ws.ts[t].overflow = 1u;
+  }
+}
+
+// ---------------------------------------------------------------- block-wise exclusive scan
+// Exclusive prefix of v[0..n) inside block `b` of kScanBlock entries, on top of the sum of all
+// earlier blocks (taken from the block sums `part`). 256 threads, 4 entries each; the scanned
+// values of the block are also left in `lds_out` (kScanBlock + 1 entries, last = block end).
+__device__ __forceinline__ void scan_block(const uint32_t* __restrict__ v, int64_t n,
+                                           const unsigned long long* __restrict__ part, int64_t b,
+                                           long long* __restrict__ out, long long* lds_out,
+                                           unsigned long long* sh) {
+  unsigned long long mine = 0;
+  for (int64_t i = threadIdx.x; i < b; i += blockDim.x) mine += part[i];
+  const long long base = (long long)block_sum(mine, sh);
+  const int64_t i0 = b * kScanBlock + (int64_t)threadIdx.x * 4;
+  uint32_t c[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) c[j] = (i0 + j < n) ? v[i0 + j] : 0u;
+  const long long s = (long long)c[0] + c[1] + c[2] + c[3];
+  long long incl = s;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const long long u = __shfl_up(incl, off);
+    if (lane >= off) incl += u;
+  }
+  __syncthreads();
+  if (lane == 63) sh[wave] = (unsigned long long)incl;
+  __syncthreads();
+  long long x = base + incl - s;
+  for (int w = 0; w < wave; ++w) x += (long long)sh[w];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (i0 + j < n) out[i0 + j] = x;
+    lds_out[threadIdx.x * 4 + j] = x;
+    x += c[j];
+  }
+  if (threadIdx.x == 255) lds_out[kScanBlock] = x;
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------- k_group_scan
+__global__ __launch_bounds__(256) void k_group_scan(Workspace ws) {
+  __shared__ long long lds_out[kScanBlock + 1];
+  __shared__ unsigned long long sh[4];
+  const int64_t b = blockIdx.x;
+  scan_block(ws.grp_cnt, ws.ngroups, ws.grp_part, b, ws.grp_off, lds_out, sh);
+  const int64_t lo = b * kScanBlock, hi = lo + kScanBlock;
+  for (int t = threadIdx.x; t < ws.T; t += 256) {
+    const int64_t gb = ws.td[t].group_begin;
+    if (gb >= lo && gb < hi) ws.tg_base[t] = lds_out[gb - lo];
+  }
+  if (threadIdx.x == 0 && hi >= ws.ngroups) ws.tg_base[ws.T] = lds_out[min((int64_t)kScanBlock, ws.ngroups - lo)];
+}
+
+// ---------------------------------------------------------------- k_route
+// Per tensor: where the select reads from, how long that source is, and its first chunk in
+// the call-wide numbering of active chunks (4096 entries each).
+__global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
+  __shared__ unsigned long long sh[4];
+  __shared__ long long carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int t0 = 0; t0 < ws.T; t0 += 256) {
+    const int t = t0 + threadIdx.x;
+    long long nch = 0, vlen = 0, M = 0;
+    uint32_t use = 0u;
+    if (t < ws.T) {
+      const TensorDesc d = ws.td[t];
+      vlen = d.n;
+      if (d.mode == kSampled && any_sampled) {
+        M = ws.tg_base[t + 1] - ws.tg_base[t];
+        if (ws.ts[t].overflow == 0u && M >= d.k && M <= d.cand_cap) { use = 1u; vlen = M; }
+      }
+      nch = (vlen + kGroup - 1) / kGroup;
+    }
+    long long incl = nch;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const long long u = __shfl_up(incl, off);
+      if (lane >= off) incl += u;
+    }
     __syncthreads();
-    flush_lds_hist<kSelBins>(lh, ws.hist + (int64_t)t * kSelBins);
+    if (lane == 63) sh[wave] = (unsigned long long)incl;
+    __syncthreads();
+    long long x = carry + incl - nch;
+    for (int w = 0; w < wave; ++w) x += (long long)sh[w];
+    if (t < ws.T) {
+      ws.ts[t].vlen = vlen;
+      ws.ts[t].achunk_begin = x;
+      ws.ts[t].cand_total = M;
+      ws.ts[t].use_cand = use;
+    }
+    __syncthreads();
+    if (threadIdx.x == 255) carry = x + nch;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) ws.totals[0] = carry;
+}
+
+// ---------------------------------------------------------------- k_gather
+// One lane per group: copy the group's candidates to their place in the tensor's dense array.
+__global__ __launch_bounds__(256) void k_gather(Workspace ws) {
+  const int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (grp >= ws.ngroups) return;
+  const int t = find_last_le(ws.T, grp, 0, [&](int i) { return (long long)ws.td[i].group_begin; });
+  if (ws.ts[t].use_cand == 0u) return;
+  const TensorDesc d = ws.td[t];
+  const uint32_t cnt = ws.grp_cnt[grp];
+  if (cnt == 0u) return;
+  const long long dst = d.cand_begin + (ws.grp_off[grp] - ws.tg_base[t]);
+  const long long first = (grp - d.group_begin) * (long long)kGroup;
+  const float* __restrict__ sv = ws.slot_val + grp * (int64_t)ws.cap;
+  const uint32_t* __restrict__ sr = ws.slot_rel + grp * (int64_t)ws.cap;
+  for (uint32_t j = 0; j < cnt; ++j) {
+    ws.cand_val[dst + j] = sv[j];
+    ws.cand_idx[dst + j] = first + sr[j];
   }
 }
 
 // ---------------------------------------------------------------- source of the select passes
-// After k_main an item is read either from its candidate slots (sampled tensor, fast path
-// holds) or from the dense residual, which now holds acc.
-struct ItemSrc {
-  const float* val;     // values, ascending index order
-  const uint32_t* rel;  // offsets inside the item (null: offset = position)
-  uint32_t len;
+// A wavefront reads one sub-chunk (1024 entries) of a tensor's select source: the dense
+// candidate array, or the residual itself (which holds acc after the streaming pass).
+struct SubSrc {
+  const float* val;      // values, ascending index order
+  const long long* idx;  // element index inside the tensor (null: first + position)
+  long long first;
+  int len;
 };
 
-__device__ __forceinline__ ItemSrc item_source(const Workspace& ws, const TensorDesc& d, bool use_cand,
-                                               int64_t item, const float* e) {
-  ItemSrc s;
-  const int64_t li = item - d.item_begin;
-  if (li >= d.nitems) { s.val = nullptr; s.rel = nullptr; s.len = 0; return s; }
-  if (use_cand) {
-    s.val = ws.cand_val + item * (int64_t)ws.cap;
-    s.rel = ws.cand_rel + item * (int64_t)ws.cap;
-    s.len = ws.item_cnt[item];
+__device__ __forceinline__ SubSrc sub_source(const Workspace& ws, const TensorDesc& d, const TensorState& st,
+                                             long long lchunk, int wave, const float* e) {
+  SubSrc s;
+  const long long pos = lchunk * kGroup + (long long)wave * kChunk;
+  s.len = (int)max(0ll, min((long long)kChunk, st.vlen - pos));
+  s.first = pos;
+  if (st.use_cand) {
+    s.val = ws.cand_val + d.cand_begin + pos;
+    s.idx = ws.cand_idx + d.cand_begin + pos;
   } else {
-    const int64_t ioff = li * ws.item_len;
-    s.val = e + d.off + ioff;
-    s.rel = nullptr;
-    s.len = (uint32_t)min((int64_t)ws.item_len, d.n - ioff);
+    s.val = e + d.off + pos;
+    s.idx = nullptr;
   }
   return s;
 }
 
 // ---------------------------------------------------------------- k_hist
-__global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const float* __restrict__ e,
-                                              int64_t ngroups) {
+__global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const float* __restrict__ e) {
   __shared__ uint32_t lh[kSelBins];
   for (int b = threadIdx.x; b < kSelBins; b += 256) lh[b] = 0u;
   __syncthreads();
@@ -339,9 +490,10 @@ __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const flo
   const int shift = sel_shift(level);
   const uint32_t mask = (1u << sel_bits(level)) - 1u;
   const int pshift = shift + sel_bits(level);  // bits above this digit must match the prefix
+  const long long A = ws.totals[0];
   int cur = -1;
-  for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
-    const int t = find_tensor_by_item(ws.td, ws.T, grp * kItemsPerGroup, cur < 0 ? 0 : cur);
+  for (long long a = blockIdx.x; a < A; a += gridDim.x) {
+    const int t = find_last_le(ws.T, a, cur < 0 ? 0 : cur, [&](int i) { return ws.ts[i].achunk_begin; });
     if (t != cur) {
       if (cur >= 0) {
         __syncthreads();
@@ -352,11 +504,9 @@ __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const flo
     }
     const TensorDesc d = ws.td[t];
     const TensorState st = ws.ts[t];
-    const bool use_cand = d.mode == kSampled && !fast_path_failed(st, d);
-    if (level == 0 && d.mode == kDense) continue;  // k_main already built this digit
-    const ItemSrc s = item_source(ws, d, use_cand, grp * kItemsPerGroup + wave, e);
+    const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
     const uint32_t want = (level == 0) ? 0u : (st.prefix >> pshift);
-    for (uint32_t j = lane; j < s.len; j += 64) {
+    for (int j = lane; j < s.len; j += 64) {
       const uint32_t key = key_of(s.val[j]);
       if (level == 0 || (key >> pshift) == want) atomicAdd(&lh[(key >> shift) & mask], 1u);
     }
@@ -387,75 +537,53 @@ __global__ __launch_bounds__(256) void k_select_scan(Workspace ws, int level) {
 // ---------------------------------------------------------------- k_count
 __global__ __launch_bounds__(256) void k_count(Workspace ws, const float* __restrict__ e) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t item = (int64_t)blockIdx.x * kItemsPerGroup + wave;
-  const int t = find_tensor_by_item(ws.td, ws.T, (int64_t)blockIdx.x * kItemsPerGroup, 0);
-  const TensorDesc d = ws.td[t];
-  const TensorState st = ws.ts[t];
-  const bool use_cand = d.mode == kSampled && !fast_path_failed(st, d);
-  const ItemSrc s = item_source(ws, d, use_cand, item, e);
-  const uint32_t thr = st.prefix;
-  uint32_t gt = 0, eq = 0;
-  for (uint32_t j0 = 0; j0 < s.len; j0 += 64) {
-    const uint32_t j = j0 + lane;
-    const bool valid = j < s.len;
-    const uint32_t key = valid ? key_of(s.val[j]) : 0u;
-    gt += (uint32_t)__popcll(__ballot(valid && key > thr));
-    eq += (uint32_t)__popcll(__ballot(valid && key == thr));
-  }
-  if (lane == 0) {
-    ws.item_gt[item] = gt;
-    ws.item_eq[item] = eq;
+  const long long A = ws.totals[0];
+  int cur = 0;
+  for (long long a = blockIdx.x; a < A; a += gridDim.x) {
+    const int t = find_last_le(ws.T, a, cur, [&](int i) { return ws.ts[i].achunk_begin; });
+    cur = t;
+    const TensorDesc d = ws.td[t];
+    const TensorState st = ws.ts[t];
+    const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
+    const uint32_t thr = st.prefix;
+    uint32_t gt = 0, eq = 0;
+    for (int j0 = 0; j0 < s.len; j0 += 64) {
+      const int j = j0 + lane;
+      const bool valid = j < s.len;
+      const uint32_t key = valid ? key_of(s.val[j]) : 0u;
+      gt += (uint32_t)__popcll(__ballot(valid && key > thr));
+      eq += (uint32_t)__popcll(__ballot(valid && key == thr));
+    }
+    if (lane == 0) {
+      const long long ent = a * 4 + wave;
+      ws.ch_gt[ent] = gt;
+      ws.ch_eq[ent] = eq;
+      if (gt) atomicAdd(&ws.ch_part_gt[ent / kScanBlock], (unsigned long long)gt);
+      if (eq) atomicAdd(&ws.ch_part_eq[ent / kScanBlock], (unsigned long long)eq);
+    }
   }
 }
 
-// ---------------------------------------------------------------- k_item_scan
-// Exclusive prefix sums of item_gt / item_eq over the item slots of one tensor.
-constexpr int kScanThreads = 1024;
-constexpr int kScanPer = 8;
-__global__ __launch_bounds__(kScanThreads) void k_item_scan(Workspace ws) {
-  __shared__ long long wsum_g[kScanThreads / 64], wsum_e[kScanThreads / 64];
-  __shared__ long long carry_g, carry_e;
-  const int t = blockIdx.x;
-  const TensorDesc d = ws.td[t];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (threadIdx.x == 0) { carry_g = 0; carry_e = 0; }
-  __syncthreads();
-  const int64_t nslots = d.item_end - d.item_begin;
-  for (int64_t c0 = 0; c0 < nslots; c0 += (int64_t)kScanThreads * kScanPer) {
-    const int64_t first = d.item_begin + c0 + (int64_t)threadIdx.x * kScanPer;
-    uint32_t vg[kScanPer], ve[kScanPer];
-    long long sg = 0, se = 0;
-#pragma unroll
-    for (int j = 0; j < kScanPer; ++j) {
-      const bool in = first + j < d.item_end;
-      vg[j] = in ? ws.item_gt[first + j] : 0u;
-      ve[j] = in ? ws.item_eq[first + j] : 0u;
-      sg += vg[j];
-      se += ve[j];
-    }
-    // inclusive scan across the wavefront
-    long long ig = sg, ie = se;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const long long ug = __shfl_up(ig, off), ue = __shfl_up(ie, off);
-      if (lane >= off) { ig += ug; ie += ue; }
-    }
-    if (lane == 63) { wsum_g[wave] = ig; wsum_e[wave] = ie; }
-    __syncthreads();
-    long long bg = carry_g, be = carry_e;
-    for (int w = 0; w < wave; ++w) { bg += wsum_g[w]; be += wsum_e[w]; }
-    long long xg = bg + ig - sg, xe = be + ie - se;  // exclusive prefix of this thread's first slot
-#pragma unroll
-    for (int j = 0; j < kScanPer; ++j) {
-      if (first + j < d.item_end) {
-        ws.item_goff[first + j] = xg;
-        ws.item_eoff[first + j] = xe;
-      }
-      xg += vg[j];
-      xe += ve[j];
+// ---------------------------------------------------------------- k_chunk_scan
+__global__ __launch_bounds__(256) void k_chunk_scan(Workspace ws) {
+  __shared__ long long lds_out[kScanBlock + 1];
+  __shared__ unsigned long long sh[4];
+  const long long A = ws.totals[0];
+  const long long n = A * 4;
+  const long long nblocks = (n + kScanBlock - 1) / kScanBlock;
+  for (long long b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    const long long lo = b * kScanBlock, hi = lo + kScanBlock;
+    scan_block(ws.ch_gt, n, ws.ch_part_gt, b, ws.ch_goff, lds_out, sh);
+    for (int t = threadIdx.x; t < ws.T; t += 256) {
+      const long long ent = ws.ts[t].achunk_begin * 4;
+      if (ent >= lo && ent < hi) ws.tb_g[t] = lds_out[ent - lo];
     }
     __syncthreads();
-    if (threadIdx.x == kScanThreads - 1) { carry_g = xg; carry_e = xe; }
+    scan_block(ws.ch_eq, n, ws.ch_part_eq, b, ws.ch_eoff, lds_out, sh);
+    for (int t = threadIdx.x; t < ws.T; t += 256) {
+      const long long ent = ws.ts[t].achunk_begin * 4;
+      if (ent >= lo && ent < hi) ws.tb_e[t] = lds_out[ent - lo];
+    }
     __syncthreads();
   }
 }
@@ -465,54 +593,48 @@ template <typename I>
 __global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restrict__ e,
                                               I* __restrict__ out_idx) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t item = (int64_t)blockIdx.x * kItemsPerGroup + wave;
-  const int t = find_tensor_by_item(ws.td, ws.T, (int64_t)blockIdx.x * kItemsPerGroup, 0);
-  const TensorDesc d = ws.td[t];
-  const TensorState st = ws.ts[t];
-  const bool use_cand = d.mode == kSampled && !fast_path_failed(st, d);
-  const ItemSrc s = item_source(ws, d, use_cand, item, e);
-  if (s.len == 0) return;
-  const uint32_t thr = st.prefix;
-  const long long quota = (long long)st.k_rem;
-  long long G = ws.item_goff[item], E = ws.item_eoff[item];
-  const int64_t item_first = d.off + (item - d.item_begin) * ws.item_len;  // flat index of offset 0
-  for (uint32_t j0 = 0; j0 < s.len; j0 += 64) {
-    const uint32_t j = j0 + lane;
-    const bool valid = j < s.len;
-    const float v = valid ? s.val[j] : 0.0f;
-    const uint32_t key = key_of(v);
-    const bool isgt = valid && key > thr, iseq = valid && key == thr;
-    const uint64_t mg = __ballot(isgt), me = __ballot(iseq);
-    const long long grank = G + mbcnt64(mg), erank = E + mbcnt64(me);
-    const bool keep = isgt || (iseq && erank < quota);
-    if (keep) {
-      const long long pos = d.kprefix + grank + (erank < quota ? erank : quota);
-      const uint32_t rel = s.rel ? s.rel[j] : j;
-      out_idx[pos] = (I)(item_first + rel);
-      ws.kept_val[pos] = v;
+  const long long A = ws.totals[0];
+  int cur = 0;
+  for (long long a = blockIdx.x; a < A; a += gridDim.x) {
+    const int t = find_last_le(ws.T, a, cur, [&](int i) { return ws.ts[i].achunk_begin; });
+    cur = t;
+    const TensorDesc d = ws.td[t];
+    const TensorState st = ws.ts[t];
+    const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
+    if (s.len == 0) continue;
+    const uint32_t thr = st.prefix;
+    const long long quota = (long long)st.k_rem;
+    const long long ent = a * 4 + wave;
+    long long G = ws.ch_goff[ent] - ws.tb_g[t], E = ws.ch_eoff[ent] - ws.tb_e[t];
+    for (int j0 = 0; j0 < s.len; j0 += 64) {
+      const int j = j0 + lane;
+      const bool valid = j < s.len;
+      const float v = valid ? s.val[j] : 0.0f;
+      const uint32_t key = key_of(v);
+      const bool isgt = valid && key > thr, iseq = valid && key == thr;
+      const uint64_t mg = __ballot(isgt), me = __ballot(iseq);
+      const long long grank = G + mbcnt64(mg), erank = E + mbcnt64(me);
+      if (isgt || (iseq && erank < quota)) {
+        const long long pos = d.kprefix + grank + (erank < quota ? erank : quota);
+        const long long within = s.idx ? s.idx[j] : (s.first + j);
+        out_idx[pos] = (I)(d.off + within);
+        ws.kept_val[pos] = v;
+      }
+      G += __popcll(mg);
+      E += __popcll(me);
     }
-    G += __popcll(mg);
-    E += __popcll(me);
   }
 }
 
 // ---------------------------------------------------------------- k_quant
 // One workgroup per block of `block` consecutive kept entries of one tensor.
 template <typename I>
-__global__ __launch_bounds__(256) void k_quant(Workspace ws, float* __restrict__ e,
-                                               const I* __restrict__ idx, int8_t* __restrict__ q,
-                                               float* __restrict__ scales, int32_t block) {
+__global__ __launch_bounds__(1024) void k_quant(Workspace ws, float* __restrict__ e,
+                                                const I* __restrict__ idx, int8_t* __restrict__ q,
+                                                float* __restrict__ scales, int32_t block) {
   __shared__ uint32_t s_amax;
   const int64_t gb = blockIdx.x;
-  int t = 0;
-  if (ws.T > 1) {  // largest t with sprefix <= gb
-    int lo = 0, hi = ws.T - 1;
-    while (lo < hi) {
-      int mid = (lo + hi + 1) >> 1;
-      if (ws.td[mid].sprefix <= gb) lo = mid; else hi = mid - 1;
-    }
-    t = lo;
-  }
+  const int t = find_last_le(ws.T, gb, 0, [&](int i) { return (long long)ws.td[i].sprefix; });
   const TensorDesc d = ws.td[t];
   const int64_t j0 = d.kprefix + (gb - d.sprefix) * block;
   const int64_t j1 = min(d.kprefix + d.k, j0 + block);
@@ -549,7 +671,6 @@ __global__ __launch_bounds__(256) void k_quant(Workspace ws, float* __restrict__
 }
 
 inline int clamp_grid(int64_t want, int64_t cap) { return (int)(want < 1 ? 1 : (want > cap ? cap : want)); }
-inline int64_t ngroups_of(const Workspace& ws) { return ws.nitem_slots / kItemsPerGroup; }
 
 }  // namespace
 
@@ -559,12 +680,11 @@ void launch_init(const Workspace& ws, hipStream_t s) {
 }
 
 void launch_sample(const Workspace& ws, const void* g, int dtype, const float* e, hipStream_t s) {
-  const int64_t ng = ngroups_of(ws);
-  const dim3 grid(clamp_grid(ng, 2048));
+  const dim3 grid(clamp_grid((ws.nsgran + 3) / 4, 2048));
   if (dtype == 0)
-    hipLaunchKernelGGL(k_sample<float>, grid, dim3(256), 0, s, ws, (const float*)g, e, ng);
+    hipLaunchKernelGGL(k_sample<float>, grid, dim3(256), 0, s, ws, (const float*)g, e);
   else
-    hipLaunchKernelGGL(k_sample<uint16_t>, grid, dim3(256), 0, s, ws, (const uint16_t*)g, e, ng);
+    hipLaunchKernelGGL(k_sample<uint16_t>, grid, dim3(256), 0, s, ws, (const uint16_t*)g, e);
 }
 
 void launch_sample_thresh(const Workspace& ws, hipStream_t s) {
@@ -572,16 +692,28 @@ void launch_sample_thresh(const Workspace& ws, hipStream_t s) {
 }
 
 void launch_main(const Workspace& ws, const void* g, int dtype, float* e, hipStream_t s) {
-  const dim3 grid((unsigned)ngroups_of(ws));
+  const dim3 grid((unsigned)ws.ngroups);
+  const size_t pad = (size_t)ws.main_lds_pad;
   if (dtype == 0)
-    hipLaunchKernelGGL(k_main<float>, grid, dim3(256), 0, s, ws, (const float*)g, e);
+    hipLaunchKernelGGL(k_main<float>, grid, dim3(256), pad, s, ws, (const float*)g, e);
   else
-    hipLaunchKernelGGL(k_main<uint16_t>, grid, dim3(256), 0, s, ws, (const uint16_t*)g, e);
+    hipLaunchKernelGGL(k_main<uint16_t>, grid, dim3(256), pad, s, ws, (const uint16_t*)g, e);
+}
+
+void launch_group_scan(const Workspace& ws, hipStream_t s) {
+  hipLaunchKernelGGL(k_group_scan, dim3((unsigned)((ws.ngroups + kScanBlock - 1) / kScanBlock)), dim3(256), 0, s, ws);
+}
+
+void launch_route(const Workspace& ws, hipStream_t s) {
+  hipLaunchKernelGGL(k_route, dim3(1), dim3(256), 0, s, ws, ws.nsgran > 0 ? 1 : 0);
+}
+
+void launch_gather(const Workspace& ws, hipStream_t s) {
+  hipLaunchKernelGGL(k_gather, dim3((unsigned)((ws.ngroups + 255) / 256)), dim3(256), 0, s, ws);
 }
 
 void launch_hist(const Workspace& ws, int level, const float* e, hipStream_t s) {
-  const int64_t ng = ngroups_of(ws);
-  hipLaunchKernelGGL(k_hist, dim3(clamp_grid(ng, 2048)), dim3(256), 0, s, ws, level, e, ng);
+  hipLaunchKernelGGL(k_hist, dim3(clamp_grid((ws.est_chunk_wgs + 1) / 2, 1024)), dim3(256), 0, s, ws, level, e);
 }
 
 void launch_select_scan(const Workspace& ws, int level, hipStream_t s) {
@@ -589,15 +721,16 @@ void launch_select_scan(const Workspace& ws, int level, hipStream_t s) {
 }
 
 void launch_count(const Workspace& ws, const float* e, hipStream_t s) {
-  hipLaunchKernelGGL(k_count, dim3((unsigned)ngroups_of(ws)), dim3(256), 0, s, ws, e);
+  hipLaunchKernelGGL(k_count, dim3(clamp_grid(ws.est_chunk_wgs, 2048)), dim3(256), 0, s, ws, e);
 }
 
-void launch_item_scan(const Workspace& ws, hipStream_t s) {
-  hipLaunchKernelGGL(k_item_scan, dim3(ws.T), dim3(kScanThreads), 0, s, ws);
+void launch_chunk_scan(const Workspace& ws, hipStream_t s) {
+  const int64_t blocks = ((int64_t)ws.est_chunk_wgs * 4 + kScanBlock - 1) / kScanBlock;
+  hipLaunchKernelGGL(k_chunk_scan, dim3(clamp_grid(blocks, 512)), dim3(256), 0, s, ws);
 }
 
 void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStream_t s) {
-  const dim3 grid((unsigned)ngroups_of(ws));
+  const dim3 grid(clamp_grid(ws.est_chunk_wgs, 2048));
   if (out.index_bits == 32)
     hipLaunchKernelGGL(k_emit<uint32_t>, grid, dim3(256), 0, s, ws, e, (uint32_t*)out.indices);
   else
@@ -606,7 +739,7 @@ void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStre
 }
 
 void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t total_blocks, hipStream_t s) {
-  int threads = out.block >= 256 ? 256 : ((out.block + 63) / 64) * 64;
+  int threads = out.block >= 1024 ? 1024 : ((out.block + 63) / 64) * 64;
   const dim3 grid((unsigned)total_blocks);
   if (out.index_bits == 32)
     hipLaunchKernelGGL(k_quant<uint32_t>, grid, dim3(threads), 0, s, ws, e, (const uint32_t*)out.indices,

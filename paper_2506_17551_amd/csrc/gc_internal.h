@@ -19,37 +19,48 @@ __host__ __device__ constexpr int sel_bits(int level) { return level == 2 ? 9 : 
 constexpr int kSampleBits = 13;
 constexpr int kSampleBins = 1 << kSampleBits;
 constexpr int kSampleShift = 31 - kSampleBits;
+constexpr int kSampleGranule = 256;  // one wavefront, one 128-bit load per lane and array
 
-constexpr int kWaveTile = 1024;   // elements one wave moves per iteration of the streaming pass
-constexpr int kSampleGranule = 256;
-constexpr int kItemsPerGroup = 4; // one workgroup (4 waves) owns 4 consecutive items of one tensor
+// Streaming pass: one workgroup of 4 wavefronts streams one GROUP of 4096 consecutive
+// elements once (1024 per wavefront) and exits.
+constexpr int kGroup = 4096;
+constexpr int kWaveTile = 1024;
+// Select / compaction passes read their source in CHUNKS of 1024 entries per wavefront.
+constexpr int kChunk = 1024;
+// Prefix sums over per-group / per-chunk counts are cut into blocks of 1024 counts.
+constexpr int kScanBlock = 1024;
 
 enum Mode : int32_t { kDense = 0, kSampled = 1 };
 
 // Immutable per-tensor plan, built on the host, read by every kernel.
 struct TensorDesc {
-  int64_t off;         // first element in the flat gradient / residual
-  int64_t n;           // elements
-  int64_t k;           // entries to keep
-  int64_t kprefix;     // first output pair of this tensor
-  int64_t sprefix;     // first output scale of this tensor
-  int64_t item_begin;  // first item (multiple of kItemsPerGroup)
-  int64_t item_end;    // one past the last item slot (padded to a multiple of kItemsPerGroup)
-  int64_t nitems;      // items that hold elements: ceil(n / item_len)
-  int32_t mode;        // Mode
-  int32_t sample_len;  // elements sampled from each item (multiple of kSampleGranule)
+  int64_t off;          // first element in the flat gradient / residual
+  int64_t n;            // elements
+  int64_t k;            // entries to keep
+  int64_t kprefix;      // first output pair of this tensor
+  int64_t sprefix;      // first output scale of this tensor
+  int64_t group_begin;  // first group slot of this tensor
+  int64_t ngroups;      // ceil(n / kGroup)
+  int64_t cand_begin;   // first entry of this tensor's region in the dense candidate arrays
+  int64_t cand_cap;     // entries in that region
+  int64_t sgran_begin;  // first sampled-granule work item of this tensor
+  int64_t nsgran;       // sampled granules
+  int32_t mode;         // Mode
+  int32_t sample_stride;   // one granule out of this many is sampled
   uint32_t sample_target;  // sample count that the candidate threshold must cover
   uint32_t pad_;
 };
 
 // Per-tensor state of one compress call, zeroed by the first kernel of the call.
 struct TensorState {
-  unsigned long long cand_total;  // candidates gathered by the streaming pass
-  unsigned long long k_rem;       // rank still to resolve inside `prefix`; after the last level: tie quota
-  uint32_t t_lo;                  // candidate threshold key (sampled tensors)
-  uint32_t overflow;              // some item ran out of candidate slots
-  uint32_t prefix;                // resolved high bits of the threshold key; after the last level: T
-  uint32_t pad_;
+  unsigned long long k_rem;  // rank still to resolve inside `prefix`; after the last level: tie quota
+  long long vlen;            // entries of the select source: candidates, or n on the dense route
+  long long achunk_begin;    // first active chunk of this tensor in the call-wide chunk numbering
+  long long cand_total;      // candidates gathered by the streaming pass
+  uint32_t t_lo;             // candidate threshold key (sampled tensors)
+  uint32_t overflow;         // some group ran out of candidate slots
+  uint32_t prefix;           // resolved high bits of the threshold key; after the last level: T
+  uint32_t use_cand;         // 1: select from the gathered candidates, 0: from the dense residual
 };
 
 struct Workspace {  // device pointers into the context's scratch
@@ -57,20 +68,35 @@ struct Workspace {  // device pointers into the context's scratch
   TensorState* ts;
   unsigned long long* shist;  // [T][kSampleBins]
   unsigned long long* hist;   // [T][kSelBins]
-  uint32_t* item_cnt;         // candidates per item
-  uint32_t* item_gt;          // per item: entries above the threshold
-  uint32_t* item_eq;          // per item: entries equal to the threshold
-  long long* item_goff;       // exclusive prefix of item_gt within the tensor
-  long long* item_eoff;       // exclusive prefix of item_eq within the tensor
-  float* cand_val;            // [items][cap]
-  uint32_t* cand_rel;         // [items][cap] offset of the candidate inside its item
-  float* kept_val;            // [sum k] accumulated values of the kept entries, ascending
-  uint32_t* flags;            // [0] non-finite seen
+  // streaming pass output
+  uint32_t* grp_cnt;                // [groups] candidates of each group
+  unsigned long long* grp_part;     // [ceil(groups / kScanBlock)] block sums of grp_cnt
+  long long* grp_off;               // [groups] exclusive prefix of grp_cnt (call-wide)
+  long long* tg_base;               // [T + 1] grp_off at each tensor's first group; [T] = total
+  float* slot_val;                  // [groups][cap]
+  uint32_t* slot_rel;               // [groups][cap] offset of the candidate inside its group
+  // dense candidate arrays (per-tensor regions)
+  float* cand_val;
+  long long* cand_idx;              // element index inside the tensor
+  // select / compaction over chunks of the source
+  uint32_t* ch_gt;                  // [active chunk] entries above the threshold
+  uint32_t* ch_eq;                  // [active chunk] entries equal to the threshold
+  unsigned long long* ch_part_gt;   // block sums of ch_gt
+  unsigned long long* ch_part_eq;
+  long long* ch_goff;               // exclusive prefixes (call-wide)
+  long long* ch_eoff;
+  long long* tb_g;                  // [T] ch_goff at each tensor's first active chunk
+  long long* tb_e;
+  long long* totals;                // [0] active chunks of the call
+  float* kept_val;                  // [sum k] accumulated values of the kept entries, ascending
+  uint32_t* flags;                  // [0] non-finite seen
   int32_t T;
-  int32_t item_len;
-  int32_t cap;
-  int32_t pad_;
-  int64_t nitem_slots;        // padded item slots over all tensors
+  int32_t cap;                      // candidate slots per group
+  int64_t ngroups;                  // group slots over all tensors
+  int64_t nsgran;                   // sampled granules over all tensors
+  int64_t max_chunks;               // capacity of the per-chunk arrays
+  int32_t est_chunk_wgs;            // grid of the chunk kernels (host estimate; kernels grid-stride)
+  int32_t main_lds_pad;             // dynamic LDS bytes of the streaming pass (occupancy control)
 };
 
 struct OutBuf {
@@ -83,8 +109,8 @@ struct OutBuf {
 
 // kernel ids for profiling
 enum KernelId : int32_t {
-  kKInit = 0, kKSample, kKSampleThresh, kKMain, kKHist, kKSelectScan, kKCount, kKItemScan,
-  kKEmit, kKQuant, kKDecBounds, kKDecTiles, kKNum
+  kKInit = 0, kKSample, kKSampleThresh, kKMain, kKGroupScan, kKRoute, kKGather, kKHist, kKSelectScan,
+  kKCount, kKChunkScan, kKEmit, kKQuant, kKDecBounds, kKDecTiles, kKNum
 };
 
 // launchers (defined in the .hip files next to their kernels)
@@ -92,10 +118,13 @@ void launch_init(const Workspace& ws, hipStream_t s);
 void launch_sample(const Workspace& ws, const void* g, int dtype, const float* e, hipStream_t s);
 void launch_sample_thresh(const Workspace& ws, hipStream_t s);
 void launch_main(const Workspace& ws, const void* g, int dtype, float* e, hipStream_t s);
+void launch_group_scan(const Workspace& ws, hipStream_t s);
+void launch_route(const Workspace& ws, hipStream_t s);
+void launch_gather(const Workspace& ws, hipStream_t s);
 void launch_hist(const Workspace& ws, int level, const float* e, hipStream_t s);
 void launch_select_scan(const Workspace& ws, int level, hipStream_t s);
 void launch_count(const Workspace& ws, const float* e, hipStream_t s);
-void launch_item_scan(const Workspace& ws, hipStream_t s);
+void launch_chunk_scan(const Workspace& ws, hipStream_t s);
 void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStream_t s);
 void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t total_blocks, hipStream_t s);
 
