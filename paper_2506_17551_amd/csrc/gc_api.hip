@@ -23,9 +23,11 @@ struct Plan {  // everything that depends only on (offsets, k, block)
   int32_t block = 0;
   std::vector<TensorDesc> td;
   int32_t cap = 0;            // candidate slots per group
+  int32_t slot_stride = 16;   // records per group incl. the header, multiple of 16
   int64_t ngroups = 0, nsgran = 0, cand_total_cap = 0, ktotal = 0, stotal = 0;
   int64_t n_sampled = 0, est_chunks = 0;
-  DevBuf td_dev;
+  std::vector<GroupRec> recs;  // one per group, only when there are several tensors
+  DevBuf td_dev, recs_dev;
 };
 
 struct DecPlan {  // per-tensor prefix tables for multi-tensor decompress
@@ -46,7 +48,7 @@ struct gc_ctx {
   std::vector<Plan*> plans;
   std::vector<DecPlan*> dplans;
   // workspace (sized for the largest plan seen)
-  DevBuf ts, shist, hist, grp_cnt, grp_part, grp_off, tg_base, slot_val, slot_rel, cand_val, cand_idx, ch_gt,
+  DevBuf ts, shist, hist, grp_cnt, grp_part, grp_off, tg_base, slots, cand_val, cand_idx, ch_gt,
       ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, flags, bounds;
   uint32_t* host_flags = nullptr;  // pinned
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
@@ -128,10 +130,10 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
     const bool sampled = d.n >= kMinSampledN && d.k >= kMinSampledK && d.k * kMaxDensityInv <= d.n;
     d.mode = sampled ? kSampled : kDense;
     if (sampled) {
-      // sample about 256 expected winners, between 1/64 and 1/4 of the data
-      double f = 256.0 / (double)d.k;
-      f = std::min(0.25, std::max(1.0 / 64.0, f));
-      const int64_t stride = std::max<int64_t>(4, std::min<int64_t>(64, (int64_t)std::floor(1.0 / f)));
+      // sample about 1024 expected winners, between 1/256 and 1/4 of the data
+      double f = 1024.0 / (double)d.k;
+      f = std::min(0.25, std::max(1.0 / 256.0, f));
+      const int64_t stride = std::max<int64_t>(4, std::min<int64_t>(256, (int64_t)std::floor(1.0 / f)));
       d.sample_stride = (int32_t)stride;
       d.nsgran = (d.n / kSampleGranule) / stride;  // whole granules only; >= 8 since n >= 2^17
       sg += round_up(d.nsgran, 4);
@@ -150,6 +152,18 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
       est += d.ngroups;
     }
   }
+  if (T > 1) {
+    P->recs.resize((size_t)grp);
+    for (int32_t t = 0; t < T; ++t) {
+      const TensorDesc& d = P->td[t];
+      for (int64_t lg = 0; lg < d.ngroups; ++lg) {
+        GroupRec& r = P->recs[(size_t)(d.group_begin + lg)];
+        r.start = d.off + lg * kGroup;
+        r.len = (int32_t)std::min<int64_t>(kGroup, d.n - lg * kGroup);
+        r.tensor = (uint32_t)t | (d.mode == kSampled ? 0x80000000u : 0u);
+      }
+    }
+  }
   P->ngroups = grp;
   P->nsgran = sg;
   P->cand_total_cap = cb;
@@ -159,6 +173,8 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
   const double cap = std::ceil(3.0 * max_lambda + 8.0 * std::sqrt(max_lambda) + 16.0);
   P->cap = (int32_t)std::min<double>(round_up((int64_t)cap, 16), (double)kGroup);
   if (P->n_sampled == 0) P->cap = 1;
+  P->cap = std::min(P->cap, 4080);  // header + cap records must fit the 32 KB LDS staging
+  P->slot_stride = (int32_t)round_up(P->cap + 1, 16);
   return P;
 }
 
@@ -186,6 +202,13 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
   gc_status st = ensure(P->td_dev, sizeof(TensorDesc) * T);
   if (st == GC_OK && hipMemcpy(P->td_dev.p, P->td.data(), sizeof(TensorDesc) * T, hipMemcpyHostToDevice) != hipSuccess)
     st = GC_ERR_DEVICE;
+  if (st == GC_OK && !P->recs.empty()) {
+    st = ensure(P->recs_dev, sizeof(GroupRec) * P->recs.size());
+    if (st == GC_OK && hipMemcpy(P->recs_dev.p, P->recs.data(), sizeof(GroupRec) * P->recs.size(),
+                                 hipMemcpyHostToDevice) != hipSuccess)
+      st = GC_ERR_DEVICE;
+    std::vector<GroupRec>().swap(P->recs);
+  }
   const size_t ng = (size_t)P->ngroups, nent = ng * 4;
   const size_t ngp = (ng + kScanBlock - 1) / kScanBlock, ncp = (nent + kScanBlock - 1) / kScanBlock;
   if (st == GC_OK) st = ensure(ctx->ts, sizeof(TensorState) * T);
@@ -196,8 +219,7 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
   if (st == GC_OK) st = ensure(ctx->grp_off, sizeof(long long) * ng);
   if (st == GC_OK) st = ensure(ctx->tg_base, sizeof(long long) * (T + 1));
   if (P->n_sampled > 0) {
-    if (st == GC_OK) st = ensure(ctx->slot_val, sizeof(float) * ng * P->cap);
-    if (st == GC_OK) st = ensure(ctx->slot_rel, sizeof(uint32_t) * ng * P->cap);
+    if (st == GC_OK) st = ensure(ctx->slots, sizeof(uint2) * ng * (size_t)P->slot_stride);
     if (st == GC_OK) st = ensure(ctx->cand_val, sizeof(float) * (size_t)P->cand_total_cap);
     if (st == GC_OK) st = ensure(ctx->cand_idx, sizeof(long long) * (size_t)P->cand_total_cap);
   }
@@ -222,6 +244,7 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
   }
   if (st != GC_OK) {
     release(P->td_dev);
+    release(P->recs_dev);
     delete P;
     return st;
   }
@@ -232,6 +255,7 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
     if (ctx->last_plan == old) ctx->last_plan = nullptr;
     (void)hipDeviceSynchronize();
     release(old->td_dev);
+    release(old->recs_dev);
     delete old;
   }
   *out = P;
@@ -299,6 +323,8 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   Workspace ws;
   std::memset(&ws, 0, sizeof(ws));
   ws.td = (const TensorDesc*)P->td_dev.p;
+  ws.recs = (const GroupRec*)P->recs_dev.p;
+  ws.n_single = offsets[T];
   ws.ts = (TensorState*)ctx->ts.p;
   ws.shist = (unsigned long long*)ctx->shist.p;
   ws.hist = (unsigned long long*)ctx->hist.p;
@@ -306,8 +332,8 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   ws.grp_part = (unsigned long long*)ctx->grp_part.p;
   ws.grp_off = (long long*)ctx->grp_off.p;
   ws.tg_base = (long long*)ctx->tg_base.p;
-  ws.slot_val = (float*)ctx->slot_val.p;
-  ws.slot_rel = (uint32_t*)ctx->slot_rel.p;
+  ws.slots = (uint2*)ctx->slots.p;
+  ws.slot_stride = P->slot_stride;
   ws.cand_val = (float*)ctx->cand_val.p;
   ws.cand_idx = (long long*)ctx->cand_idx.p;
   ws.ch_gt = (uint32_t*)ctx->ch_gt.p;
@@ -338,7 +364,10 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
     { Scope sc(ctx, kKSampleThresh, s); launch_sample_thresh(ws, s); }
   }
   { Scope sc(ctx, kKMain, s); launch_main(ws, grad, (int)dtype, residual, s); }
-  if (any_sampled) { Scope sc(ctx, kKGroupScan, s); launch_group_scan(ws, s); }
+  if (any_sampled) {
+    { Scope sc(ctx, kKGroupSums, s); launch_group_sums(ws, s); }
+    { Scope sc(ctx, kKGroupScan, s); launch_group_scan(ws, s); }
+  }
   { Scope sc(ctx, kKRoute, s); launch_route(ws, s); }
   if (any_sampled) { Scope sc(ctx, kKGather, s); launch_gather(ws, s); }
   for (int level = 0; level < kSelLevels; ++level) {
@@ -346,6 +375,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
     { Scope sc(ctx, kKSelectScan, s); launch_select_scan(ws, level, s); }
   }
   { Scope sc(ctx, kKCount, s); launch_count(ws, residual, s); }
+  { Scope sc(ctx, kKChunkSums, s); launch_chunk_sums(ws, s); }
   { Scope sc(ctx, kKChunkScan, s); launch_chunk_scan(ws, s); }
   { Scope sc(ctx, kKEmit, s); launch_emit(ws, residual, ob, s); }
   { Scope sc(ctx, kKQuant, s); launch_quant(ws, residual, ob, P->stotal, s); }
@@ -443,9 +473,9 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   return launch_status();
 }
 
-const char* const kKernelNames[kKNum] = {"k_init", "k_sample", "k_sample_thresh", "k_main", "k_group_scan",
+const char* const kKernelNames[kKNum] = {"k_init", "k_sample", "k_sample_thresh", "k_main", "k_group_sums", "k_group_scan",
                                          "k_route", "k_gather", "k_hist", "k_select_scan", "k_count",
-                                         "k_chunk_scan", "k_emit", "k_quant", "k_dec_bounds", "k_dec_tiles"};
+                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_bounds", "k_dec_tiles"};
 
 }  // namespace
 
@@ -481,10 +511,10 @@ gc_status gc_destroy(gc_ctx* c) {
   if (!c) return GC_ERR_INVALID_ARG;
   (void)hipSetDevice(c->device);
   (void)hipDeviceSynchronize();
-  for (Plan* P : c->plans) { release(P->td_dev); delete P; }
+  for (Plan* P : c->plans) { release(P->td_dev); release(P->recs_dev); delete P; }
   for (DecPlan* D : c->dplans) { release(D->kprefix); release(D->sprefix); delete D; }
   DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
-                   &c->slot_val, &c->slot_rel, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
+                   &c->slots, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
                    &c->ch_part_gt, &c->ch_part_eq, &c->ch_goff, &c->ch_eoff, &c->tb_g, &c->tb_e,
                    &c->totals, &c->kept_val, &c->flags, &c->bounds};
   for (DevBuf* b : all) release(*b);

@@ -23,6 +23,8 @@
 //   acc after step 2). A sampled tensor whose candidates turn out too few, too many, or too
 //   clustered for their slots takes that same dense route, decided on the device; the result
 //   never depends on the sample, only the time does.
+#include <algorithm>
+
 #include "gc_internal.h"
 
 namespace gc {
@@ -93,12 +95,8 @@ __global__ __launch_bounds__(256) void k_init(Workspace ws) {
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   const int64_t ns = (int64_t)ws.T * kSampleBins, nh = (int64_t)ws.T * kSelBins;
-  const int64_t ngp = (ws.ngroups + kScanBlock - 1) / kScanBlock;
-  const int64_t ncp = (ws.max_chunks * 4 + kScanBlock - 1) / kScanBlock;
   for (int64_t i = tid; i < ns; i += stride) ws.shist[i] = 0ull;
   for (int64_t i = tid; i < nh; i += stride) ws.hist[i] = 0ull;
-  for (int64_t i = tid; i < ngp; i += stride) ws.grp_part[i] = 0ull;
-  for (int64_t i = tid; i < ncp; i += stride) { ws.ch_part_gt[i] = 0ull; ws.ch_part_eq[i] = 0ull; }
   for (int64_t i = tid; i < ws.T; i += stride) {
     TensorState z;
     z.k_rem = 0ull; z.vlen = 0; z.achunk_begin = 0; z.cand_total = 0;
@@ -225,22 +223,45 @@ __global__ __launch_bounds__(256) void k_sample_thresh(Workspace ws) {
 }
 
 // ---------------------------------------------------------------- k_main
+// The prologue is kept short on purpose: a workgroup lives for one group only, so every
+// dependent load in front of its first streaming load shows up in the achieved bandwidth. A
+// single tensor needs kernel arguments only; several tensors cost one 16-byte record per group.
 template <typename G>
-__global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict__ g, float* __restrict__ e) {
-  extern __shared__ char lds_pad[];  // dynamic LDS only limits how many workgroups share a CU
+__global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict__ g, float* __restrict__ e,
+                                              const GroupRec* __restrict__ recs, long long n_single,
+                                              int sampled_single) {
+  // dynamic LDS: staging for the group's candidates; its size also bounds how many workgroups
+  // share a CU (the launcher asks for more than the staging needs on purpose)
+  extern __shared__ __align__(16) char lds_dyn[];
   __shared__ uint32_t wcnt[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t grp = blockIdx.x;
-  const int t = find_last_le(ws.T, grp, 0, [&](int i) { return (long long)ws.td[i].group_begin; });
-  const TensorDesc d = ws.td[t];
-  const int64_t goff = (grp - d.group_begin) * kGroup;
-  const int64_t glen = min((int64_t)kGroup, d.n - goff);  // >= 1 by construction of the plan
+  long long gstart;  // first element of the group in the flat arrays
+  int glen, t;
+  bool sampled;
+  if (recs == nullptr) {
+    gstart = grp * (long long)kGroup;
+    glen = (int)min((long long)kGroup, n_single - gstart);
+    t = 0;
+    sampled = sampled_single != 0;
+  } else {
+    const GroupRec r = recs[grp];
+    gstart = r.start;
+    glen = r.len;
+    t = (int)(r.tensor & 0x7FFFFFFFu);
+    sampled = (r.tensor >> 31) != 0u;
+  }
   const int wstart = wave * kWaveTile;
-  const int wlen = (int)max((int64_t)0, min((int64_t)kWaveTile, glen - wstart));
-  const bool sampled = d.mode == kSampled;
-  const uint32_t t_lo = sampled ? ws.ts[t].t_lo : 0xFFFFFFFFu;  // no key reaches 0xFFFFFFFF
-  const G* gp = g + d.off + goff + wstart;
-  float* ep = e + d.off + goff + wstart;
+  const int wlen = max(0, min(kWaveTile, glen - wstart));
+  // The candidate threshold is fetched with a vector load issued AFTER the streaming loads, so
+  // that its latency hides behind theirs instead of delaying them (a scalar load would be
+  // waited for first). The zero offset is opaque to the compiler on purpose.
+  uint32_t lane_zero;
+  asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+  const uint32_t* t_lo_ptr = &ws.ts[t].t_lo + lane_zero;
+  uint32_t t_lo = 0xFFFFFFFFu;  // no key reaches 0xFFFFFFFF: a dense tensor gathers no candidates
+  const G* gp = g + gstart + wstart;
+  float* ep = e + gstart + wstart;
   const bool vec = wlen == kWaveTile && ((reinterpret_cast<uintptr_t>(gp) & GradVec<G>::kAlignMask) == 0) &&
                    ((reinterpret_cast<uintptr_t>(ep) & 15u) == 0);
   f32x4 a[4];
@@ -252,6 +273,7 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
     for (int u = 0; u < 4; ++u) gv[u] = GradVec<G>::load(gp + u * 256 + lane * 4);
 #pragma unroll
     for (int u = 0; u < 4; ++u) ev[u] = *reinterpret_cast<const f32x4*>(ep + u * 256 + lane * 4);
+    if (sampled) t_lo = *t_lo_ptr;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       a[u].x = __fadd_rn(gv[u].x, ev[u].x);
@@ -268,6 +290,7 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
     }
   } else {
     // tail group of a tensor, or addresses that are not 16-byte aligned: one element per lane
+    if (sampled) t_lo = *t_lo_ptr;
     for (int j0 = 0; j0 < wlen; j0 += 64) {
       const int j = j0 + lane;
       bool c = false;
@@ -279,10 +302,7 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
       mycnt += (uint32_t)__popcll(__ballot(c));
     }
   }
-  if (!sampled) {  // uniform over the workgroup: a dense tensor gathers no candidates
-    if (threadIdx.x == 0) ws.grp_cnt[grp] = 0u;
-    return;
-  }
+  if (!sampled) return;  // uniform over the workgroup: a dense tensor gathers no candidates
   if (lane == 0) wcnt[wave] = mycnt;
   __syncthreads();
   uint32_t before = 0u, tot = 0u;
@@ -292,10 +312,13 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
     if (w < wave) before += c;
     tot += c;
   }
+  // Candidates are staged in LDS in ascending index order and leave the workgroup as whole
+  // 128-byte lines (a header record with the count, then the candidates, padded with zero
+  // records): scattered 4-byte stores would turn into read-modify-write cycles in HBM and
+  // cost more than the bytes they carry.
   const uint32_t cap = (uint32_t)ws.cap;
+  uint2* stage = reinterpret_cast<uint2*>(lds_dyn);
   if (tot) {
-    float* __restrict__ cv = ws.slot_val + grp * (int64_t)cap;
-    uint32_t* __restrict__ cr = ws.slot_rel + grp * (int64_t)cap;
     if (vec) {
       if (flags) {
 #pragma unroll
@@ -304,10 +327,10 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
           if (f) {
             uint32_t r = before + rank[u];
             const uint32_t rel = (uint32_t)(wstart + u * 256 + lane * 4);
-            if (f & 1u) { if (r < cap) { cv[r] = a[u].x; cr[r] = rel; } ++r; }
-            if (f & 2u) { if (r < cap) { cv[r] = a[u].y; cr[r] = rel + 1u; } ++r; }
-            if (f & 4u) { if (r < cap) { cv[r] = a[u].z; cr[r] = rel + 2u; } ++r; }
-            if (f & 8u) { if (r < cap) { cv[r] = a[u].w; cr[r] = rel + 3u; } }
+            if (f & 1u) { if (r < cap) stage[r] = make_uint2(__float_as_uint(a[u].x), rel); ++r; }
+            if (f & 2u) { if (r < cap) stage[r] = make_uint2(__float_as_uint(a[u].y), rel + 1u); ++r; }
+            if (f & 4u) { if (r < cap) stage[r] = make_uint2(__float_as_uint(a[u].z), rel + 2u); ++r; }
+            if (f & 8u) { if (r < cap) stage[r] = make_uint2(__float_as_uint(a[u].w), rel + 3u); }
           }
         }
       }
@@ -324,17 +347,22 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
         }
         const uint64_t m = __ballot(c);
         const uint32_t r = r0 + mbcnt64(m);
-        if (c && r < cap) { cv[r] = acc; cr[r] = (uint32_t)(wstart + j); }
+        if (c && r < cap) stage[r] = make_uint2(__float_as_uint(acc), (uint32_t)(wstart + j));
         r0 += (uint32_t)__popcll(m);
       }
     }
+    __syncthreads();  // tot is uniform over the workgroup
   }
-  if (threadIdx.x == 0) {
-    const uint32_t kept = min(tot, cap);
-    ws.grp_cnt[grp] = kept;
-    if (kept) atomicAdd(&ws.grp_part[grp / kScanBlock], (unsigned long long)kept);
-    if (tot > cap) ws.ts[t].overflow = 1u;
+  const uint32_t kept = min(tot, cap);
+  const uint32_t nout = (kept + 1u + 15u) & ~15u;  // header + candidates, in whole 128-byte lines
+  uint2* __restrict__ dst = ws.slots + grp * (int64_t)ws.slot_stride;
+  for (uint32_t j = threadIdx.x; j < nout; j += 256) {
+    uint2 rec = make_uint2(0u, 0u);
+    if (j == 0u) rec = make_uint2(kept, tot > cap ? 1u : 0u);
+    else if (j - 1u < kept) rec = stage[j - 1u];
+    dst[j] = rec;
   }
+  if (threadIdx.x == 0 && tot > cap) ws.ts[t].overflow = 1u;
 }
 
 // ---------------------------------------------------------------- block-wise exclusive scan
@@ -373,6 +401,50 @@ __device__ __forceinline__ void scan_block(const uint32_t* __restrict__ v, int64
   }
   if (threadIdx.x == 255) lds_out[kScanBlock] = x;
   __syncthreads();
+}
+
+// ---------------------------------------------------------------- block sums
+// part[b] = sum of v[b * kScanBlock .. (b + 1) * kScanBlock) (entries at or past n count as 0).
+// No atomics: consecutive groups finish at the same moment, and same-address atomics from all
+// of them would serialise the streaming pass.
+__device__ __forceinline__ void block_sums_one(const uint32_t* __restrict__ v, long long n, long long b,
+                                               unsigned long long* __restrict__ part, unsigned long long* sh) {
+  const long long i0 = b * kScanBlock + (long long)threadIdx.x * 4;
+  unsigned long long s = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) s += (i0 + j < n) ? v[i0 + j] : 0u;
+  const unsigned long long tot = block_sum(s, sh);
+  if (threadIdx.x == 0) part[b] = tot;
+}
+
+// Reads each group's header record, leaves the counts in a compact array and their block sums.
+__global__ __launch_bounds__(256) void k_group_sums(Workspace ws) {
+  __shared__ unsigned long long sh[4];
+  const long long b = blockIdx.x;
+  const long long i0 = b * kScanBlock + (long long)threadIdx.x * 4;
+  unsigned long long s = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const long long grp = i0 + j;
+    if (grp < ws.ngroups) {
+      const bool sampled = ws.recs ? (ws.recs[grp].tensor >> 31) != 0u : true;
+      const uint32_t c = sampled ? ws.slots[grp * (long long)ws.slot_stride].x : 0u;
+      ws.grp_cnt[grp] = c;
+      s += c;
+    }
+  }
+  const unsigned long long tot = block_sum(s, sh);
+  if (threadIdx.x == 0) ws.grp_part[b] = tot;
+}
+
+__global__ __launch_bounds__(256) void k_chunk_sums(Workspace ws) {
+  __shared__ unsigned long long sh[4];
+  const long long n = ws.totals[0] * 4;
+  const long long nblocks = (n + kScanBlock - 1) / kScanBlock;
+  for (long long b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    block_sums_one(ws.ch_gt, n, b, ws.ch_part_gt, sh);
+    block_sums_one(ws.ch_eq, n, b, ws.ch_part_eq, sh);
+  }
 }
 
 // ---------------------------------------------------------------- k_group_scan
@@ -447,11 +519,18 @@ __global__ __launch_bounds__(256) void k_gather(Workspace ws) {
   if (cnt == 0u) return;
   const long long dst = d.cand_begin + (ws.grp_off[grp] - ws.tg_base[t]);
   const long long first = (grp - d.group_begin) * (long long)kGroup;
-  const float* __restrict__ sv = ws.slot_val + grp * (int64_t)ws.cap;
-  const uint32_t* __restrict__ sr = ws.slot_rel + grp * (int64_t)ws.cap;
-  for (uint32_t j = 0; j < cnt; ++j) {
-    ws.cand_val[dst + j] = sv[j];
-    ws.cand_idx[dst + j] = first + sr[j];
+  const uint2* __restrict__ rec = ws.slots + grp * (int64_t)ws.slot_stride + 1;
+  for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {  // all loads of a round are issued before the stores
+    uint2 r[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) r[u] = (j0 + u < cnt) ? rec[j0 + u] : make_uint2(0u, 0u);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (j0 + u < cnt) {
+        ws.cand_val[dst + j0 + u] = __uint_as_float(r[u].x);
+        ws.cand_idx[dst + j0 + u] = first + r[u].y;
+      }
+    }
   }
 }
 
@@ -547,19 +626,25 @@ __global__ __launch_bounds__(256) void k_count(Workspace ws, const float* __rest
     const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
     const uint32_t thr = st.prefix;
     uint32_t gt = 0, eq = 0;
-    for (int j0 = 0; j0 < s.len; j0 += 64) {
-      const int j = j0 + lane;
-      const bool valid = j < s.len;
-      const uint32_t key = valid ? key_of(s.val[j]) : 0u;
-      gt += (uint32_t)__popcll(__ballot(valid && key > thr));
-      eq += (uint32_t)__popcll(__ballot(valid && key == thr));
+    for (int j0 = 0; j0 < s.len; j0 += 256) {
+      uint32_t key[4];
+      bool valid[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int j = j0 + u * 64 + lane;
+        valid[u] = j < s.len;
+        key[u] = valid[u] ? key_of(s.val[j]) : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        gt += (uint32_t)__popcll(__ballot(valid[u] && key[u] > thr));
+        eq += (uint32_t)__popcll(__ballot(valid[u] && key[u] == thr));
+      }
     }
     if (lane == 0) {
       const long long ent = a * 4 + wave;
       ws.ch_gt[ent] = gt;
       ws.ch_eq[ent] = eq;
-      if (gt) atomicAdd(&ws.ch_part_gt[ent / kScanBlock], (unsigned long long)gt);
-      if (eq) atomicAdd(&ws.ch_part_eq[ent / kScanBlock], (unsigned long long)eq);
     }
   }
 }
@@ -693,11 +778,24 @@ void launch_sample_thresh(const Workspace& ws, hipStream_t s) {
 
 void launch_main(const Workspace& ws, const void* g, int dtype, float* e, hipStream_t s) {
   const dim3 grid((unsigned)ws.ngroups);
-  const size_t pad = (size_t)ws.main_lds_pad;
+  const size_t pad = (size_t)std::max<int64_t>(ws.main_lds_pad, (int64_t)ws.cap * 8);
+  const long long n_single = ws.recs ? 0 : ws.n_single;
+  const int sampled_single = ws.nsgran > 0 ? 1 : 0;
   if (dtype == 0)
-    hipLaunchKernelGGL(k_main<float>, grid, dim3(256), pad, s, ws, (const float*)g, e);
+    hipLaunchKernelGGL(k_main<float>, grid, dim3(256), pad, s, ws, (const float*)g, e, ws.recs, n_single,
+                       sampled_single);
   else
-    hipLaunchKernelGGL(k_main<uint16_t>, grid, dim3(256), pad, s, ws, (const uint16_t*)g, e);
+    hipLaunchKernelGGL(k_main<uint16_t>, grid, dim3(256), pad, s, ws, (const uint16_t*)g, e, ws.recs,
+                       n_single, sampled_single);
+}
+
+void launch_group_sums(const Workspace& ws, hipStream_t s) {
+  hipLaunchKernelGGL(k_group_sums, dim3((unsigned)((ws.ngroups + kScanBlock - 1) / kScanBlock)), dim3(256), 0, s, ws);
+}
+
+void launch_chunk_sums(const Workspace& ws, hipStream_t s) {
+  const int64_t blocks = ((int64_t)ws.est_chunk_wgs * 4 + kScanBlock - 1) / kScanBlock;
+  hipLaunchKernelGGL(k_chunk_sums, dim3(clamp_grid(blocks, 512)), dim3(256), 0, s, ws);
 }
 
 void launch_group_scan(const Workspace& ws, hipStream_t s) {

@@ -63,8 +63,16 @@ struct TensorState {
   uint32_t use_cand;         // 1: select from the gathered candidates, 0: from the dense residual
 };
 
+// One record per group of the streaming pass (only built when a call has several tensors).
+struct GroupRec {
+  long long start;   // first element of the group in the flat arrays
+  int32_t len;       // elements in the group (1..kGroup)
+  uint32_t tensor;   // tensor index; bit 31 set when the tensor is sampled
+};
+
 struct Workspace {  // device pointers into the context's scratch
   const TensorDesc* td;
+  const GroupRec* recs;       // null when the call has a single tensor
   TensorState* ts;
   unsigned long long* shist;  // [T][kSampleBins]
   unsigned long long* hist;   // [T][kSelBins]
@@ -73,8 +81,8 @@ struct Workspace {  // device pointers into the context's scratch
   unsigned long long* grp_part;     // [ceil(groups / kScanBlock)] block sums of grp_cnt
   long long* grp_off;               // [groups] exclusive prefix of grp_cnt (call-wide)
   long long* tg_base;               // [T + 1] grp_off at each tensor's first group; [T] = total
-  float* slot_val;                  // [groups][cap]
-  uint32_t* slot_rel;               // [groups][cap] offset of the candidate inside its group
+  uint2* slots;                     // [groups][slot_stride] records: [0] = {count, overflowed},
+                                    // then {acc bits, offset inside the group} per candidate
   // dense candidate arrays (per-tensor regions)
   float* cand_val;
   long long* cand_idx;              // element index inside the tensor
@@ -92,9 +100,12 @@ struct Workspace {  // device pointers into the context's scratch
   uint32_t* flags;                  // [0] non-finite seen
   int32_t T;
   int32_t cap;                      // candidate slots per group
+  int32_t slot_stride;              // records per group: header + cap, rounded up to 16
+  int32_t pad0_;
   int64_t ngroups;                  // group slots over all tensors
   int64_t nsgran;                   // sampled granules over all tensors
   int64_t max_chunks;               // capacity of the per-chunk arrays
+  int64_t n_single;                 // elements of the only tensor (single-tensor calls)
   int32_t est_chunk_wgs;            // grid of the chunk kernels (host estimate; kernels grid-stride)
   int32_t main_lds_pad;             // dynamic LDS bytes of the streaming pass (occupancy control)
 };
@@ -109,8 +120,8 @@ struct OutBuf {
 
 // kernel ids for profiling
 enum KernelId : int32_t {
-  kKInit = 0, kKSample, kKSampleThresh, kKMain, kKGroupScan, kKRoute, kKGather, kKHist, kKSelectScan,
-  kKCount, kKChunkScan, kKEmit, kKQuant, kKDecBounds, kKDecTiles, kKNum
+  kKInit = 0, kKSample, kKSampleThresh, kKMain, kKGroupSums, kKGroupScan, kKRoute, kKGather, kKHist,
+  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecBounds, kKDecTiles, kKNum
 };
 
 // launchers (defined in the .hip files next to their kernels)
@@ -118,6 +129,8 @@ void launch_init(const Workspace& ws, hipStream_t s);
 void launch_sample(const Workspace& ws, const void* g, int dtype, const float* e, hipStream_t s);
 void launch_sample_thresh(const Workspace& ws, hipStream_t s);
 void launch_main(const Workspace& ws, const void* g, int dtype, float* e, hipStream_t s);
+void launch_group_sums(const Workspace& ws, hipStream_t s);
+void launch_chunk_sums(const Workspace& ws, hipStream_t s);
 void launch_group_scan(const Workspace& ws, hipStream_t s);
 void launch_route(const Workspace& ws, hipStream_t s);
 void launch_gather(const Workspace& ws, hipStream_t s);
