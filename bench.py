@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="library tuning knob (gc_set_option), e.g. item_len=16384")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device-to-device copy of 4 GiB three times: the reference that "
+                         "scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--verify", action="store_true", help="check invariants of the last step on the device")
     return ap.parse_args()
 
@@ -252,6 +255,17 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
+    if args.calibrate_copy:
+        nbytes = 4 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(3)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"bytes_read_per_copy": nbytes, "bytes_written_per_copy": nbytes,
+                                             "copies": 3}}))
+        return
     wl = inputs.workload(args.workload, args.scale)
     ctx = gc.Context(0)
     for opt in args.option:

@@ -454,7 +454,7 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   }
   GC_HIP(hipSetDevice(ctx->device));
   const int64_t ntiles = (n + kDecTile - 1) / kDecTile;
-  if ((ntiles + 3) / 4 >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
+  if (ntiles >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
   gc_status st = ensure(ctx->bounds, sizeof(uint32_t) * (size_t)(ntiles + 1) * W);
   if (st != GC_OK) return st;
   DecPlan* D = nullptr;

@@ -142,7 +142,10 @@ void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStre
 void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t total_blocks, hipStream_t s);
 
 constexpr int kMaxWorkers = 64;
-constexpr int kDecTile = 2048;  // output floats per wave-tile of decompress_sum
+#ifndef GC_DEC_TILE
+#define GC_DEC_TILE 2048
+#endif
+constexpr int kDecTile = GC_DEC_TILE;  // output floats per wave-tile of decompress_sum
 struct DecArgs {
   const void* indices[kMaxWorkers];
   const int8_t* q[kMaxWorkers];
