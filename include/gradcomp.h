@@ -123,7 +123,8 @@ gc_status gc_sync_status(gc_ctx* ctx, void* hip_stream);
 gc_status gc_last_stats(gc_ctx* ctx, gc_stats* stats);
 
 /* Per-kernel timing with HIP events recorded on the caller's stream around each
- * launch. gc_profile_enable(ctx, 1) starts a fresh recording; gc_profile_read
+ * launch. gc_profile_enable(ctx, 1) starts a fresh recording of every kernel, 2 of the
+ * streaming pass of gc_compress only (two event records per call), 0 stops; gc_profile_read
  * waits for the recorded events and returns, for kernel `id` in
  * [0, gc_profile_num_kernels()), the summed duration in milliseconds and the
  * number of launches since recording started. */

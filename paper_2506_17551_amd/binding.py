@@ -132,8 +132,9 @@ class Context:
         _check(lib().gc_set_option(self.handle, name.encode(), int(value)), "gc_set_option")
 
     # ---- profiling helpers (gc_profile_*) ----
-    def profile_enable(self, on: bool = True) -> None:
-        _check(lib().gc_profile_enable(self.handle, 1 if on else 0), "gc_profile_enable")
+    def profile_enable(self, mode=1) -> None:
+        """0/False: off, 1/True: every kernel, 2: only the streaming pass of compress."""
+        _check(lib().gc_profile_enable(self.handle, int(mode)), "gc_profile_enable")
 
     def profile_read(self) -> dict:
         """{kernel name: (total ms, launches)} since profile_enable(True)."""

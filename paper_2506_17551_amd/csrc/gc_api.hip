@@ -49,14 +49,14 @@ struct gc_ctx {
   std::vector<DecPlan*> dplans;
   // workspace (sized for the largest plan seen)
   DevBuf ts, shist, hist, grp_cnt, grp_part, grp_off, tg_base, slots, cand_val, cand_idx, ch_gt,
-      ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, flags, bounds;
+      ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, blk_amax, flags, bounds;
   uint32_t* host_flags = nullptr;  // pinned
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
   size_t host_ts_cap = 0;
   const Plan* last_plan = nullptr;
   int64_t opt_main_lds_pad = 49152;  // dynamic LDS of the streaming pass: 3 workgroups per CU
   // profiling
-  bool prof = false;
+  int prof = 0;  // 0 off, 1 every kernel, 2 only the streaming pass
   std::vector<EventPair> ev_used, ev_free;
 };
 
@@ -130,8 +130,9 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
     const bool sampled = d.n >= kMinSampledN && d.k >= kMinSampledK && d.k * kMaxDensityInv <= d.n;
     d.mode = sampled ? kSampled : kDense;
     if (sampled) {
-      // sample about 1024 expected winners, between 1/256 and 1/4 of the data
-      double f = 1024.0 / (double)d.k;
+      // sample about 64 expected winners, between 1/256 and 1/4 of the data: a thin sample only
+      // makes the candidate list a little longer, and candidates are cheap
+      double f = 64.0 / (double)d.k;
       f = std::min(0.25, std::max(1.0 / 256.0, f));
       const int64_t stride = std::max<int64_t>(4, std::min<int64_t>(256, (int64_t)std::floor(1.0 / f)));
       d.sample_stride = (int32_t)stride;
@@ -233,6 +234,7 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
   if (st == GC_OK) st = ensure(ctx->tb_e, sizeof(long long) * T);
   if (st == GC_OK) st = ensure(ctx->totals, sizeof(long long) * 4);
   if (st == GC_OK) st = ensure(ctx->kept_val, sizeof(float) * (size_t)P->ktotal);
+  if (st == GC_OK) st = ensure(ctx->blk_amax, sizeof(uint32_t) * (size_t)P->stotal);
   if (st == GC_OK && ctx->host_ts_cap < (size_t)T) {
     if (ctx->host_ts) (void)hipHostFree(ctx->host_ts);
     ctx->host_ts = nullptr;
@@ -268,7 +270,8 @@ struct Scope {  // records an event pair around one launch when profiling is on
   hipStream_t s;
   EventPair ev;
   bool on;
-  Scope(gc_ctx* ctx, int32_t id, hipStream_t st) : c(ctx), s(st), on(ctx->prof) {
+  Scope(gc_ctx* ctx, int32_t id, hipStream_t st)
+      : c(ctx), s(st), on(ctx->prof == 1 || (ctx->prof == 2 && id == kKMain)) {
     if (!on) return;
     if (!c->ev_free.empty()) {
       ev = c->ev_free.back();
@@ -346,6 +349,8 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   ws.tb_e = (long long*)ctx->tb_e.p;
   ws.totals = (long long*)ctx->totals.p;
   ws.kept_val = (float*)ctx->kept_val.p;
+  ws.blk_amax = (uint32_t*)ctx->blk_amax.p;
+  ws.nblocks = P->stotal;
   ws.flags = (uint32_t*)ctx->flags.p;
   ws.T = T;
   ws.cap = P->cap;
@@ -378,7 +383,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   { Scope sc(ctx, kKChunkSums, s); launch_chunk_sums(ws, s); }
   { Scope sc(ctx, kKChunkScan, s); launch_chunk_scan(ws, s); }
   { Scope sc(ctx, kKEmit, s); launch_emit(ws, residual, ob, s); }
-  { Scope sc(ctx, kKQuant, s); launch_quant(ws, residual, ob, P->stotal, s); }
+  { Scope sc(ctx, kKQuant, s); launch_quant(ws, residual, ob, P->ktotal, s); }
   ctx->last_plan = P;
   return launch_status();
 }
@@ -516,7 +521,7 @@ gc_status gc_destroy(gc_ctx* c) {
   DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
                    &c->slots, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
                    &c->ch_part_gt, &c->ch_part_eq, &c->ch_goff, &c->ch_eoff, &c->tb_g, &c->tb_e,
-                   &c->totals, &c->kept_val, &c->flags, &c->bounds};
+                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->bounds};
   for (DevBuf* b : all) release(*b);
   if (c->host_flags) (void)hipHostFree(c->host_flags);
   if (c->host_ts) (void)hipHostFree(c->host_ts);
@@ -602,7 +607,7 @@ gc_status gc_profile_enable(gc_ctx* ctx, int32_t on) {
   GC_HIP(hipDeviceSynchronize());
   for (auto& e : ctx->ev_used) ctx->ev_free.push_back(e);
   ctx->ev_used.clear();
-  ctx->prof = on != 0;
+  ctx->prof = (on == 2) ? 2 : (on != 0 ? 1 : 0);
   return GC_OK;
 }
 

@@ -97,6 +97,7 @@ __global__ __launch_bounds__(256) void k_init(Workspace ws) {
   const int64_t ns = (int64_t)ws.T * kSampleBins, nh = (int64_t)ws.T * kSelBins;
   for (int64_t i = tid; i < ns; i += stride) ws.shist[i] = 0ull;
   for (int64_t i = tid; i < nh; i += stride) ws.hist[i] = 0ull;
+  for (int64_t i = tid; i < ws.nblocks; i += stride) ws.blk_amax[i] = 0u;
   for (int64_t i = tid; i < ws.T; i += stride) {
     TensorState z;
     z.k_rem = 0ull; z.vlen = 0; z.achunk_begin = 0; z.cand_total = 0;
@@ -135,7 +136,10 @@ __global__ __launch_bounds__(256) void k_sample(Workspace ws, const G* __restric
   // A workgroup takes 4 consecutive sampled-granule slots per iteration, one per wavefront. Every
   // tensor's slots start at a multiple of 4 and are padded to a multiple of 4, so one iteration
   // never mixes tensors and the LDS histogram can be flushed when the tensor changes.
-  for (int64_t s0 = (int64_t)blockIdx.x * 4; s0 < ws.nsgran; s0 += (int64_t)gridDim.x * 4) {
+  // each workgroup takes one contiguous run of slots, so it meets few tensors
+  const int64_t per = ((ws.nsgran / 4 + gridDim.x - 1) / gridDim.x) * 4;
+  const int64_t s_end = min(ws.nsgran, ((int64_t)blockIdx.x + 1) * per);
+  for (int64_t s0 = (int64_t)blockIdx.x * per; s0 < s_end; s0 += 4) {
     const int t = find_last_le(ws.T, s0, cur < 0 ? 0 : cur, [&](int i) { return (long long)ws.td[i].sgran_begin; });
     if (t != cur) {
       if (cur >= 0) {
@@ -570,8 +574,10 @@ __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const flo
   const uint32_t mask = (1u << sel_bits(level)) - 1u;
   const int pshift = shift + sel_bits(level);  // bits above this digit must match the prefix
   const long long A = ws.totals[0];
+  const long long per = (A + gridDim.x - 1) / gridDim.x;  // one contiguous run of chunks per workgroup
+  const long long a_end = min(A, ((long long)blockIdx.x + 1) * per);
   int cur = -1;
-  for (long long a = blockIdx.x; a < A; a += gridDim.x) {
+  for (long long a = (long long)blockIdx.x * per; a < a_end; ++a) {
     const int t = find_last_le(ws.T, a, cur < 0 ? 0 : cur, [&](int i) { return ws.ts[i].achunk_begin; });
     if (t != cur) {
       if (cur >= 0) {
@@ -676,7 +682,7 @@ __global__ __launch_bounds__(256) void k_chunk_scan(Workspace ws) {
 // ---------------------------------------------------------------- k_emit
 template <typename I>
 __global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restrict__ e,
-                                              I* __restrict__ out_idx) {
+                                              I* __restrict__ out_idx, int32_t block) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const long long A = ws.totals[0];
   int cur = 0;
@@ -699,11 +705,33 @@ __global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restr
       const bool isgt = valid && key > thr, iseq = valid && key == thr;
       const uint64_t mg = __ballot(isgt), me = __ballot(iseq);
       const long long grank = G + mbcnt64(mg), erank = E + mbcnt64(me);
-      if (isgt || (iseq && erank < quota)) {
-        const long long pos = d.kprefix + grank + (erank < quota ? erank : quota);
+      const bool keep = isgt || (iseq && erank < quota);
+      uint32_t blk = 0u, bkey = 0u;  // quantization block of this lane's kept entry, and its key
+      if (keep) {
+        const long long rel = grank + (erank < quota ? erank : quota);  // position inside the tensor
+        const long long pos = d.kprefix + rel;
         const long long within = s.idx ? s.idx[j] : (s.first + j);
         out_idx[pos] = (I)(d.off + within);
         ws.kept_val[pos] = v;
+        blk = (uint32_t)(d.sprefix + rel / block) + 1u;  // +1 so that 0 means "no entry"
+        bkey = key;
+      }
+      // Per-block amax for the quantizer: kept positions ascend with the lane, so the lanes of
+      // one block form a contiguous run; a segmented max-scan leaves each run's maximum in its
+      // last lane, which alone touches memory (one atomic per block and wavefront iteration).
+      if (mg | me) {
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {  // lanes without an entry inherit the block to their left
+          const uint32_t ob = __shfl_up(blk, off);
+          if (lane >= off && blk == 0u) blk = ob;
+        }
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const uint32_t ok = __shfl_up(bkey, off), ob = __shfl_up(blk, off);
+          if (lane >= off && ob == blk) bkey = max(bkey, ok);
+        }
+        const uint32_t nb = __shfl_down(blk, 1);
+        if (blk != 0u && (lane == 63 || nb != blk) && bkey != 0u) atomicMax(&ws.blk_amax[blk - 1u], bkey);
       }
       G += __popcll(mg);
       E += __popcll(me);
@@ -712,47 +740,34 @@ __global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restr
 }
 
 // ---------------------------------------------------------------- k_quant
-// One workgroup per block of `block` consecutive kept entries of one tensor.
+// One thread per kept entry: scale of its block from the block's amax key (left by k_emit),
+// int8 code, and the residual at the kept position, e' = acc - fl32(q * s) (Eq. 11).
 template <typename I>
-__global__ __launch_bounds__(1024) void k_quant(Workspace ws, float* __restrict__ e,
-                                                const I* __restrict__ idx, int8_t* __restrict__ q,
-                                                float* __restrict__ scales, int32_t block) {
-  __shared__ uint32_t s_amax;
-  const int64_t gb = blockIdx.x;
-  const int t = find_last_le(ws.T, gb, 0, [&](int i) { return (long long)ws.td[i].sprefix; });
-  const TensorDesc d = ws.td[t];
-  const int64_t j0 = d.kprefix + (gb - d.sprefix) * block;
-  const int64_t j1 = min(d.kprefix + d.k, j0 + block);
-  if (threadIdx.x == 0) s_amax = 0u;
-  __syncthreads();
-  uint32_t m = 0;
-  for (int64_t j = j0 + threadIdx.x; j < j1; j += blockDim.x) m = max(m, key_of(ws.kept_val[j]));
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
-  if ((threadIdx.x & 63) == 0) atomicMax(&s_amax, m);
-  __syncthreads();
-  const uint32_t akey = s_amax;
+__global__ __launch_bounds__(256) void k_quant(Workspace ws, float* __restrict__ e,
+                                               const I* __restrict__ idx, int8_t* __restrict__ q,
+                                               float* __restrict__ scales, int32_t block, long long ktotal) {
+  const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (j >= ktotal) return;
+  const int t = find_last_le(ws.T, j, 0, [&](int i) { return (long long)ws.td[i].kprefix; });
+  const long long rel = j - ws.td[t].kprefix;
+  const long long blk = ws.td[t].sprefix + rel / block;
+  const uint32_t akey = ws.blk_amax[blk];
   const bool finite = akey < 0x7F800000u;
   float s = __fdiv_rn(__uint_as_float(akey), 127.0f);
   if (!finite || !(s >= 1.17549435e-38f)) s = 0.0f;
-  if (threadIdx.x == 0) {
-    scales[gb] = s;
+  if (rel % block == 0) {
+    scales[blk] = s;
     if (!finite) ws.flags[0] = 1u;
   }
-  for (int64_t j = j0 + threadIdx.x; j < j1; j += blockDim.x) {
-    const float v = ws.kept_val[j];
-    int code = 0;
-    if (s != 0.0f) {
-      float r = rintf(__fdiv_rn(v, s));
-      r = fminf(fmaxf(r, -127.0f), 127.0f);
-      code = (int)r;
-    }
-    q[j] = (int8_t)code;
-    if (finite) {
-      const float dq = __fmul_rn((float)code, s);
-      e[(int64_t)idx[j]] = __fsub_rn(v, dq);
-    }
+  const float v = ws.kept_val[j];
+  int code = 0;
+  if (s != 0.0f) {
+    float r = rintf(__fdiv_rn(v, s));
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    code = (int)r;
   }
+  q[j] = (int8_t)code;
+  if (finite) e[(int64_t)idx[j]] = __fsub_rn(v, __fmul_rn((float)code, s));
 }
 
 inline int clamp_grid(int64_t want, int64_t cap) { return (int)(want < 1 ? 1 : (want > cap ? cap : want)); }
@@ -830,21 +845,20 @@ void launch_chunk_scan(const Workspace& ws, hipStream_t s) {
 void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStream_t s) {
   const dim3 grid(clamp_grid(ws.est_chunk_wgs, 2048));
   if (out.index_bits == 32)
-    hipLaunchKernelGGL(k_emit<uint32_t>, grid, dim3(256), 0, s, ws, e, (uint32_t*)out.indices);
+    hipLaunchKernelGGL(k_emit<uint32_t>, grid, dim3(256), 0, s, ws, e, (uint32_t*)out.indices, out.block);
   else
     hipLaunchKernelGGL(k_emit<unsigned long long>, grid, dim3(256), 0, s, ws, e,
-                       (unsigned long long*)out.indices);
+                       (unsigned long long*)out.indices, out.block);
 }
 
-void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t total_blocks, hipStream_t s) {
-  int threads = out.block >= 1024 ? 1024 : ((out.block + 63) / 64) * 64;
-  const dim3 grid((unsigned)total_blocks);
+void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktotal, hipStream_t s) {
+  const dim3 grid((unsigned)((ktotal + 255) / 256));
   if (out.index_bits == 32)
-    hipLaunchKernelGGL(k_quant<uint32_t>, grid, dim3(threads), 0, s, ws, e, (const uint32_t*)out.indices,
-                       out.q, out.scales, out.block);
+    hipLaunchKernelGGL(k_quant<uint32_t>, grid, dim3(256), 0, s, ws, e, (const uint32_t*)out.indices, out.q,
+                       out.scales, out.block, (long long)ktotal);
   else
-    hipLaunchKernelGGL(k_quant<unsigned long long>, grid, dim3(threads), 0, s, ws, e,
-                       (const unsigned long long*)out.indices, out.q, out.scales, out.block);
+    hipLaunchKernelGGL(k_quant<unsigned long long>, grid, dim3(256), 0, s, ws, e,
+                       (const unsigned long long*)out.indices, out.q, out.scales, out.block, (long long)ktotal);
 }
 
 }  // namespace gc

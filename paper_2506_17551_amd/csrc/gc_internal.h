@@ -97,6 +97,7 @@ struct Workspace {  // device pointers into the context's scratch
   long long* tb_e;
   long long* totals;                // [0] active chunks of the call
   float* kept_val;                  // [sum k] accumulated values of the kept entries, ascending
+  uint32_t* blk_amax;               // [sum ceil(k/block)] largest key of each quantization block
   uint32_t* flags;                  // [0] non-finite seen
   int32_t T;
   int32_t cap;                      // candidate slots per group
@@ -106,6 +107,7 @@ struct Workspace {  // device pointers into the context's scratch
   int64_t nsgran;                   // sampled granules over all tensors
   int64_t max_chunks;               // capacity of the per-chunk arrays
   int64_t n_single;                 // elements of the only tensor (single-tensor calls)
+  int64_t nblocks;                  // quantization blocks over all tensors
   int32_t est_chunk_wgs;            // grid of the chunk kernels (host estimate; kernels grid-stride)
   int32_t main_lds_pad;             // dynamic LDS bytes of the streaming pass (occupancy control)
 };
@@ -139,7 +141,7 @@ void launch_select_scan(const Workspace& ws, int level, hipStream_t s);
 void launch_count(const Workspace& ws, const float* e, hipStream_t s);
 void launch_chunk_scan(const Workspace& ws, hipStream_t s);
 void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStream_t s);
-void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t total_blocks, hipStream_t s);
+void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktotal, hipStream_t s);
 
 constexpr int kMaxWorkers = 64;
 #ifndef GC_DEC_TILE

@@ -377,3 +377,49 @@ def test_argument_errors_write_nothing(gc, ctx):
         gc.compress_multi(ctx, g, e, [0, 500, 400], [5, 5], 4)
     with pytest.raises(ValueError):
         gc.compress(ctx, g.cpu(), e, 10, 4)
+
+
+def test_calls_can_be_captured_in_a_hip_graph(gc, ctx, oracle):
+    """compress + decompress_sum queue only kernels on the caller's stream (no host wait, no
+    allocation once the shape has been seen, no memset nodes), so a caller may capture them.
+    Replays are interleaved with eager work and each one is compared with the oracle."""
+    n, k, block = 700_000, 7000, 128
+    g = torch.empty(n, device=DEV)
+    e = torch.zeros(n, device=DEV)
+    buf = gc.CompressedBuf.allocate(n, k, gc.num_scales(k, block), block, 32, DEV)
+    out = torch.empty(n, device=DEV)
+    g.copy_(inputs.normal(n, 1.0, 1))
+    gc.compress(ctx, g, e.clone(), k, block, out=buf)      # warm-up: builds the plan, sizes the workspace
+    gc.decompress_sum(ctx, [buf, buf], n, out=out)
+    gc.sync_status(ctx)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            gc.compress(ctx, g, e, k, block, out=buf)
+            gc.decompress_sum(ctx, [buf, buf], n, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    e_ref = np.zeros(n, np.float32)
+    for step in range(4):
+        g_cpu = inputs.normal(n, 1.0, 100 + step)
+        g.copy_(g_cpu)                                     # eager work between replays
+        junk = torch.randn(1 << 20, device=DEV).sum().item()
+        graph.replay()
+        torch.cuda.synchronize()
+        rc, idx, q, s = oracle.compress(g_cpu.numpy(), e_ref, k, block)
+        assert rc == 0
+        assert np.array_equal(buf.indices_numpy(), idx), step
+        assert np.array_equal(buf.q.cpu().numpy(), q), step
+        assert np.array_equal(bits(e.cpu().numpy()), bits(e_ref)), step
+        rc, want = oracle.decompress_sum([(idx, q, s)] * 2, n, block)
+        assert np.array_equal(bits(out.cpu().numpy()), bits(want)), step
+        assert junk == junk
+    assert gc.sync_status(ctx, raise_on_error=False) == 0
+
+
+def test_many_small_tensors(gc, ctx, oracle):
+    rng = np.random.Generator(np.random.Philox(key=7))
+    sizes = [int(x) for x in rng.integers(1, 6000, size=3000)] + [400_000, 1, 4096, 4097, 262_144]
+    st = _multi_case(gc, ctx, oracle, sizes, 0.02, 16, W=2, seed=900)
+    assert st["tensors"] == len(sizes)
