@@ -114,7 +114,18 @@ def run_flat(args, gc, inputs, torch, wl, ctx):
     ctx.profile_enable(0)
     prof["k_main"] = main_prof
     stats = gc.last_stats(ctx)
-    info = {"n": n, "k": k, "block": block, "W": W, "index_bits": wl.index_bits,
+    # the aggregation variants on the same buffers (outside the timed steps): staleness-damped
+    # sum (Eq. 12) and the fused update of a parameter vector (Eq. 8-9); `out` doubles as theta
+    tw, ta = Timer(torch), Timer(torch)
+    for _ in range(2):
+        tw.reset()
+        ta.reset()
+        with tw:
+            gc.decompress_sum_weighted(ctx, bufs, [w % 4 for w in range(W)], n, out=out)
+        with ta:
+            gc.decompress_apply(ctx, bufs, out, 1.0 / W)
+    variants = {"decompress_sum_weighted_ms": round(tw.total_ms(), 4), "decompress_apply_ms": round(ta.total_ms(), 4)}
+    info = {"n": n, "k": k, "block": block, "W": W, "index_bits": wl.index_bits, **variants,
             "compress_ms_per_worker": ms_c / W, "decompress_sum_ms": ms_d,
             "residuals_resident": resident, "fallback_tensors": stats["tensors_fallback"],
             "candidates_last_call": stats["candidates"]}

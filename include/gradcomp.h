@@ -115,6 +115,23 @@ gc_status gc_decompress_sum(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* o
 gc_status gc_decompress_sum_multi(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k,
                                   int32_t T, float* out, int64_t n, void* hip_stream);
 
+/* Staleness-damped aggregate (Sec. III.B, Eq. 12: a gradient that is tau steps late enters the
+ * update divided by 1 + tau): out[i] = sum over w, in worker order and in fp32, of
+ * fl32(d_w[i] / (1 + staleness[w])), d_w the decoded value of worker w. staleness: W host
+ * entries in [0, 2^24]. With every staleness 0 the result equals gc_decompress_sum bit for bit.
+ * k/T as in gc_decompress_sum_multi, or k = NULL, T = 0 for single-tensor buffers. */
+gc_status gc_decompress_sum_weighted(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
+                                     const int32_t* staleness, float* out, int64_t n, void* hip_stream);
+
+/* Fused aggregate-and-apply (Eq. 8 and Eq. 9): theta[i] <- theta[i] - fl32(step * S[i]), where
+ * S is the aggregate gc_decompress_sum (staleness == NULL) or gc_decompress_sum_weighted would
+ * write, and `step` stands for eta / P (0 <= step, finite). Only positions named by some
+ * buffer are read and written: where S[i] is +0 the update leaves theta[i] unchanged, so the
+ * dense aggregate is never materialised. theta: n fp32, updated in place. */
+gc_status gc_decompress_apply(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
+                              const int32_t* staleness, float* theta, float step, int64_t n,
+                              void* hip_stream);
+
 /* Wait for `hip_stream` and return GC_ERR_NONFINITE if any compress call since
  * the last gc_sync_status() saw Inf/NaN among its kept entries, else GC_OK. */
 gc_status gc_sync_status(gc_ctx* ctx, void* hip_stream);

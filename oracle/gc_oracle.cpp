@@ -220,17 +220,23 @@ int gco_compress_multi(const void* g, int dtype, float* e, const int64_t* offset
   return status;
 }
 
-// Sum of W decompressed buffers into a dense vector (Eq. 8 without the 1/P).
+// Sum of W decompressed buffers into a dense vector (Eq. 8 without the 1/P). If `staleness`
+// is not null, worker w's decoded value is divided by (1 + staleness[w]) before it is added:
+// the damping that Eq. 12 applies to a gradient that is staleness[w] steps late (reading: one
+// IEEE fp32 division per entry by the exactly representable 1 + tau, then the fp32 add).
 // Buffer w holds kcount[w] entries. If T > 0 the buffers came from
 // gco_compress_multi with per-tensor counts ktensor[T] (identical for every
 // worker) and the scale of entry j is found per tensor; with T == 0 the scale
 // of entry j is scales[j / block].
-int gco_decompress_sum(int32_t W, const void* const* idx, const int8_t* const* q,
-                       const float* const* scales, const int64_t* kcount, int32_t block,
-                       int32_t index_bits, const int64_t* ktensor, int32_t T, float* out,
-                       int64_t n) {
+int gco_decompress_sum_weighted(int32_t W, const void* const* idx, const int8_t* const* q,
+                                const float* const* scales, const int64_t* kcount, int32_t block,
+                                int32_t index_bits, const int64_t* ktensor, int32_t T,
+                                const int32_t* staleness, float* out, int64_t n) {
   if (W < 1 || !idx || !q || !scales || !kcount || !out || n <= 0 || block < 1)
     return GCO_ERR_INVALID_ARG;
+  if (staleness)
+    for (int32_t w = 0; w < W; ++w)
+      if (staleness[w] < 0 || staleness[w] > (1 << 24)) return GCO_ERR_INVALID_ARG;
   for (int64_t i = 0; i < n; ++i) out[i] = 0.0f;
   for (int32_t w = 0; w < W; ++w) {
     int64_t t = 0, t_end = (T > 0) ? ktensor[0] : kcount[w], t_begin = 0, s_base = 0;
@@ -247,8 +253,32 @@ int gco_decompress_sum(int32_t W, const void* const* idx, const int8_t* const* q
                                       : static_cast<const uint64_t*>(idx[w])[j];
       if (i >= static_cast<uint64_t>(n)) return GCO_ERR_INVALID_ARG;
       volatile float d = static_cast<float>(q[w][j]) * s;
+      if (staleness) {
+        const float denom = 1.0f + static_cast<float>(staleness[w]);
+        volatile float damped = d / denom;
+        d = damped;
+      }
       out[i] = out[i] + d;
     }
+  }
+  return GCO_OK;
+}
+
+int gco_decompress_sum(int32_t W, const void* const* idx, const int8_t* const* q,
+                       const float* const* scales, const int64_t* kcount, int32_t block,
+                       int32_t index_bits, const int64_t* ktensor, int32_t T, float* out,
+                       int64_t n) {
+  return gco_decompress_sum_weighted(W, idx, q, scales, kcount, block, index_bits, ktensor, T, nullptr, out,
+                                     n);
+}
+
+// Parameter update with the aggregate (Eq. 9 with g from Eq. 8): theta <- theta - step * S,
+// `step` standing for eta / P; two fp32 roundings per entry (product, then difference).
+int gco_apply(float* theta, const float* S, float step, int64_t n) {
+  if (!theta || !S || n <= 0 || !(step >= 0.0f)) return GCO_ERR_INVALID_ARG;
+  for (int64_t i = 0; i < n; ++i) {
+    volatile float upd = step * S[i];
+    theta[i] = theta[i] - upd;
   }
   return GCO_OK;
 }

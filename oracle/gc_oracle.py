@@ -52,6 +52,13 @@ def lib() -> ctypes.CDLL:
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
                                          ctypes.c_void_p, ctypes.c_int64]
+        L.gco_decompress_sum_weighted.restype = ctypes.c_int
+        L.gco_decompress_sum_weighted.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                                  ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        L.gco_apply.restype = ctypes.c_int
+        L.gco_apply.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_int64]
         _lib = L
     return _lib
 
@@ -107,8 +114,9 @@ def compress_multi(g: np.ndarray, e: np.ndarray, offsets, ks, block: int, index_
     return rc, idx, q, s
 
 
-def decompress_sum(bufs, n: int, block: int, ktensor=None):
-    """bufs: list of (idx, q, scales) numpy triples, one per worker. Returns (status, out)."""
+def decompress_sum(bufs, n: int, block: int, ktensor=None, staleness=None):
+    """bufs: list of (idx, q, scales) numpy triples, one per worker. Returns (status, out).
+    staleness: optional per-worker integers (Eq. 12 damping)."""
     W = len(bufs)
     index_bits = 32 if bufs[0][0].dtype == np.uint32 else 64
     PA = ctypes.c_void_p * W
@@ -122,7 +130,19 @@ def decompress_sum(bufs, n: int, block: int, ktensor=None):
         ktp, T = _ptr(kt), kt.shape[0]
     else:
         ktp, T = None, 0
-    rc = lib().gco_decompress_sum(W, ctypes.addressof(ia), ctypes.addressof(qa),
-                                  ctypes.addressof(sa), _ptr(kc), int(block), index_bits, ktp, T,
-                                  _ptr(out), int(n))
+    if staleness is not None:
+        st = np.ascontiguousarray(staleness, dtype=np.int32)
+        assert st.shape[0] == W
+        stp = _ptr(st)
+    else:
+        stp = None
+    rc = lib().gco_decompress_sum_weighted(W, ctypes.addressof(ia), ctypes.addressof(qa),
+                                           ctypes.addressof(sa), _ptr(kc), int(block), index_bits, ktp, T,
+                                           stp, _ptr(out), int(n))
     return rc, out
+
+
+def apply(theta: np.ndarray, S: np.ndarray, step: float) -> int:
+    """theta <- theta - step * S in place (Eq. 9 with eta / P = step)."""
+    assert theta.dtype == np.float32 and S.dtype == np.float32 and theta.shape == S.shape
+    return lib().gco_apply(_ptr(theta), _ptr(S), float(step), theta.shape[0])

@@ -36,7 +36,8 @@ class _GcStats(ctypes.Structure):
 
 
 EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_compress",
-           "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_multi", "gc_sync_status",
+           "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_multi", "gc_decompress_sum_weighted",
+           "gc_decompress_apply", "gc_sync_status",
            "gc_last_stats", "gc_profile_enable", "gc_profile_num_kernels", "gc_profile_kernel_name",
            "gc_profile_read", "gc_set_option", "gc_status_string"]
 
@@ -61,6 +62,8 @@ def lib() -> ctypes.CDLL:
     L.gc_compress_multi.argtypes = [vp, vp, ctypes.c_int, vp, vp, vp, i32, i32, ctypes.POINTER(_GcBuf), vp]
     L.gc_decompress_sum.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i64, vp]
     L.gc_decompress_sum_multi.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, i64, vp]
+    L.gc_decompress_sum_weighted.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, i64, vp]
+    L.gc_decompress_apply.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, ctypes.c_float, i64, vp]
     L.gc_sync_status.argtypes = [vp, vp]
     L.gc_last_stats.argtypes = [vp, ctypes.POINTER(_GcStats)]
     L.gc_profile_enable.argtypes = [vp, i32]
@@ -73,7 +76,8 @@ def lib() -> ctypes.CDLL:
     L.gc_status_string.argtypes = [ctypes.c_int]
     L.gc_status_string.restype = ctypes.c_char_p
     for name in ("gc_create", "gc_destroy", "gc_compress", "gc_compress_multi", "gc_decompress_sum",
-                 "gc_decompress_sum_multi", "gc_sync_status", "gc_last_stats", "gc_profile_enable",
+                 "gc_decompress_sum_multi", "gc_decompress_sum_weighted", "gc_decompress_apply",
+                 "gc_sync_status", "gc_last_stats", "gc_profile_enable",
                  "gc_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -276,6 +280,47 @@ def decompress_sum_multi(ctx: Context, bufs: List[CompressedBuf], ks: Sequence[i
                                        int(n), _stream_ptr(stream, dev))
     _check(rc, "gc_decompress_sum_multi")
     return out
+
+
+def _kt(ks):
+    if ks is None:
+        return None, 0, None
+    kk = np.ascontiguousarray(ks, dtype=np.int64)
+    return kk.ctypes.data, kk.shape[0], kk
+
+
+def decompress_sum_weighted(ctx: Context, bufs: List[CompressedBuf], staleness: Sequence[int], n: int,
+                            out: Optional[torch.Tensor] = None, ks: Optional[Sequence[int]] = None,
+                            stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """gc_decompress_sum_weighted: worker w's contribution divided by 1 + staleness[w] (Eq. 12)."""
+    dev = bufs[0].q.device
+    if out is None:
+        out = torch.empty(int(n), dtype=torch.float32, device=dev)
+    _check_dev(out, "out", torch.float32)
+    st = np.ascontiguousarray(staleness, dtype=np.int32)
+    if st.shape[0] != len(bufs):
+        raise ValueError("one staleness per buffer")
+    kp, T, _keep = _kt(ks)
+    rc = lib().gc_decompress_sum_weighted(ctx.handle, _buf_array(bufs), len(bufs), kp, T, st.ctypes.data,
+                                          out.data_ptr(), int(n), _stream_ptr(stream, dev))
+    _check(rc, "gc_decompress_sum_weighted")
+    return out
+
+
+def decompress_apply(ctx: Context, bufs: List[CompressedBuf], theta: torch.Tensor, step: float,
+                     staleness: Optional[Sequence[int]] = None, ks: Optional[Sequence[int]] = None,
+                     stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """gc_decompress_apply: theta -= step * aggregate, touching only the positions the buffers name."""
+    _check_dev(theta, "theta", torch.float32)
+    st = None if staleness is None else np.ascontiguousarray(staleness, dtype=np.int32)
+    if st is not None and st.shape[0] != len(bufs):
+        raise ValueError("one staleness per buffer")
+    kp, T, _keep = _kt(ks)
+    rc = lib().gc_decompress_apply(ctx.handle, _buf_array(bufs), len(bufs), kp, T,
+                                   None if st is None else st.ctypes.data, theta.data_ptr(), float(step),
+                                   theta.numel(), _stream_ptr(stream, theta.device))
+    _check(rc, "gc_decompress_apply")
+    return theta
 
 
 def sync_status(ctx: Context, stream: Optional[torch.cuda.Stream] = None, raise_on_error: bool = True) -> int:

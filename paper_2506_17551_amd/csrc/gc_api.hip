@@ -429,8 +429,10 @@ gc_status get_dec_plan(gc_ctx* ctx, const int64_t* k, int32_t T, int32_t block, 
 }
 
 gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
-                          float* out, int64_t n, void* hip_stream) {
+                          const int32_t* staleness, bool apply, float c_apply, float* out, int64_t n,
+                          void* hip_stream) {
   if (!ctx || !bufs || !out || W < 1 || n <= 0) return GC_ERR_INVALID_ARG;
+  if (apply && !(c_apply >= 0.0f && c_apply <= 3.0e38f)) return GC_ERR_INVALID_ARG;
   if (W > kMaxWorkers) return GC_ERR_UNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(out) % 4) return GC_ERR_INVALID_ARG;
   const int32_t block = bufs[0].block, ib = bufs[0].index_bits;
@@ -456,6 +458,11 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     a.q[w] = b.q;
     a.scales[w] = b.scales;
     a.k[w] = (uint32_t)b.k;
+    a.denom[w] = 1.0f;
+    if (staleness) {
+      if (staleness[w] < 0 || staleness[w] > (1 << 24)) return GC_ERR_INVALID_ARG;  // 1 + tau exact in fp32
+      a.denom[w] = 1.0f + (float)staleness[w];
+    }
   }
   GC_HIP(hipSetDevice(ctx->device));
   const int64_t ntiles = (n + kDecTile - 1) / kDecTile;
@@ -473,7 +480,7 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     Scope sc(ctx, kKDecTiles, s);
     launch_dec_tiles(a, W, ib, block, n, ntiles, (const uint32_t*)ctx->bounds.p,
                      D ? (const long long*)D->kprefix.p : nullptr, D ? (const long long*)D->sprefix.p : nullptr,
-                     D ? T : 1, out, s);
+                     D ? T : 1, out, staleness ? 1 : 0, apply ? 1 : 0, c_apply, s);
   }
   return launch_status();
 }
@@ -559,13 +566,26 @@ gc_status gc_compress_multi(gc_ctx* ctx, const void* grad, gc_dtype dtype, float
 
 gc_status gc_decompress_sum(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* out, int64_t n,
                             void* hip_stream) {
-  return decompress_impl(ctx, bufs, W, nullptr, 0, out, n, hip_stream);
+  return decompress_impl(ctx, bufs, W, nullptr, 0, nullptr, false, 0.0f, out, n, hip_stream);
+}
+
+gc_status gc_decompress_sum_weighted(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
+                                     const int32_t* staleness, float* out, int64_t n, void* hip_stream) {
+  if (!staleness || T < 0) return GC_ERR_INVALID_ARG;
+  return decompress_impl(ctx, bufs, W, k, T, staleness, false, 0.0f, out, n, hip_stream);
+}
+
+gc_status gc_decompress_apply(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
+                              const int32_t* staleness, float* theta, float step, int64_t n,
+                              void* hip_stream) {
+  if (T < 0) return GC_ERR_INVALID_ARG;
+  return decompress_impl(ctx, bufs, W, k, T, staleness, true, step, theta, n, hip_stream);
 }
 
 gc_status gc_decompress_sum_multi(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
                                   float* out, int64_t n, void* hip_stream) {
   if (T < 1) return GC_ERR_INVALID_ARG;
-  return decompress_impl(ctx, bufs, W, k, T, out, n, hip_stream);
+  return decompress_impl(ctx, bufs, W, k, T, nullptr, false, 0.0f, out, n, hip_stream);
 }
 
 gc_status gc_sync_status(gc_ctx* ctx, void* hip_stream) {

@@ -56,98 +56,133 @@ __global__ __launch_bounds__(256) void k_dec_bounds(DecArgs a, int W, int64_t nt
 #define GC_DEC_WAVES 8
 #endif
 constexpr int kDecWaves = GC_DEC_WAVES;  // wavefronts (= tiles) per workgroup
+#ifndef GC_DEC_GRID
+#define GC_DEC_GRID 512
+#endif
+constexpr int kDecGrid = GC_DEC_GRID;    // persistent workgroups (2 per CU)
 
-template <typename I>
+// What one lane decodes in one round of a tile: a pair of some worker, or nothing.
+struct LanePair {
+  bool active;
+  int w;         // worker
+  uint32_t j;    // pair index in that worker's buffer
+};
+
+// Pair number (s0 + lane) of the tile, counting the workers' pairs in worker order.
+__device__ __forceinline__ LanePair locate_pair(uint32_t s0, int lane, uint32_t total, int W, uint32_t excl,
+                                                uint32_t cnt, uint32_t lo) {
+  LanePair p;
+  const uint32_t sidx = s0 + lane;
+  p.active = sidx < total;
+  p.w = 0;
+  p.j = 0;
+  for (int w = 0; w < W; ++w) {  // w is wave-uniform: scalar lane reads
+    const uint32_t ex = (uint32_t)__builtin_amdgcn_readlane((int)excl, w);
+    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)cnt, w);
+    const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)lo, w);
+    if (c != 0u && sidx >= ex) { p.w = w; p.j = l + (sidx - ex); }
+  }
+  return p;
+}
+
+constexpr uint32_t kClaimed = 0x7FC0DEADu;  // a NaN pattern no finite sum can produce
+
+// MODE 0: out[tile] = sum (dense write).  MODE 1: theta[i] -= c * sum[i] at the touched i only.
+template <typename I, int MODE>
 __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(DecArgs a, int W, int32_t block, int64_t n,
                                                    int64_t ntiles, const uint32_t* __restrict__ bounds,
                                                    const long long* __restrict__ kprefix,
                                                    const long long* __restrict__ sprefix, int T,
-                                                   float* __restrict__ out) {
+                                                   float* __restrict__ out, int weighted, float c_apply) {
   __shared__ float tile_mem[kDecWaves][kDecTile];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float* lt = tile_mem[wave];
   // wavefronts walk the tiles with a grid stride; no workgroup barrier is used in the loop
   for (int64_t tile = (int64_t)blockIdx.x * kDecWaves + wave; tile < ntiles;
        tile += (int64_t)gridDim.x * kDecWaves) {
-  const int64_t base = tile * kDecTile;
-  const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-  for (int i = 0; i < kDecTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
-
-  // lane w holds worker w's pair range for this tile
-  uint32_t lo = 0, cnt = 0;
-  if (lane < W) {
-    lo = bounds[tile * W + lane];
-    cnt = bounds[(tile + 1) * W + lane] - lo;
-  }
-  uint32_t incl = cnt;  // inclusive scan over lanes
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t u = __shfl_up(incl, off);
-    if (lane >= off) incl += u;
-  }
-  const uint32_t total = __shfl(incl, 63);
-  const uint32_t excl = incl - cnt;
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-
-  for (uint32_t s0 = 0; s0 < total; s0 += 64) {
-    const uint32_t sidx = s0 + lane;
-    const bool active = sidx < total;
-    // owner worker of slot sidx: the last w with excl[w] <= sidx among workers that have pairs
-    int myw = 0;
-    uint32_t myj = 0;
-    for (int w = 0; w < W; ++w) {  // w is wave-uniform: scalar lane reads
-      const uint32_t ex = (uint32_t)__builtin_amdgcn_readlane((int)excl, w);
-      const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)cnt, w);
-      const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)lo, w);
-      if (c != 0u && sidx >= ex) { myw = w; myj = l + (sidx - ex); }
+    const int64_t base = tile * kDecTile;
+    // lane w holds worker w's pair range for this tile
+    uint32_t lo = 0, cnt = 0;
+    if (lane < W) {
+      lo = bounds[tile * W + lane];
+      cnt = bounds[(tile + 1) * W + lane] - lo;
     }
-    float val = 0.0f;
-    uint32_t pos = 0;
-    if (active) {
-      const I* idx = static_cast<const I*>(a.indices[myw]);
-      pos = (uint32_t)((unsigned long long)idx[myj] - (unsigned long long)base);
-      const int code = a.q[myw][myj];
-      long long sj = (long long)myj / block;
-      if (T > 1) {  // scales restart at every tensor: find the tensor that owns pair myj
-        int tl = 0, th = T - 1;
-        while (tl < th) {
-          const int mid = (tl + th + 1) >> 1;
-          if (kprefix[mid] <= (long long)myj) tl = mid; else th = mid - 1;
+    uint32_t incl = cnt;  // inclusive scan over lanes
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t u = __shfl_up(incl, off);
+      if (lane >= off) incl += u;
+    }
+    const uint32_t total = __shfl(incl, 63);
+    const uint32_t excl = incl - cnt;
+    if (MODE == 1 && total == 0u) continue;  // nothing to apply in this tile
+    const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int i = 0; i < kDecTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    for (uint32_t s0 = 0; s0 < total; s0 += 64) {
+      const LanePair p = locate_pair(s0, lane, total, W, excl, cnt, lo);
+      float val = 0.0f;
+      uint32_t pos = 0;
+      if (p.active) {
+        const I* idx = static_cast<const I*>(a.indices[p.w]);
+        pos = (uint32_t)((unsigned long long)idx[p.j] - (unsigned long long)base);
+        const int code = a.q[p.w][p.j];
+        long long sj = (long long)p.j / block;
+        if (T > 1) {  // scales restart at every tensor: find the tensor that owns pair j
+          int tl = 0, th = T - 1;
+          while (tl < th) {
+            const int mid = (tl + th + 1) >> 1;
+            if (kprefix[mid] <= (long long)p.j) tl = mid; else th = mid - 1;
+          }
+          sj = sprefix[tl] + ((long long)p.j - kprefix[tl]) / block;
         }
-        sj = sprefix[tl] + ((long long)myj - kprefix[tl]) / block;
+        val = __fmul_rn((float)code, a.scales[p.w][sj]);
+        if (weighted) val = __fdiv_rn(val, a.denom[p.w]);  // Eq. 12: a stale worker counts for less
       }
-      val = __fmul_rn((float)code, a.scales[myw][sj]);
+      // add worker by worker so that equal indices of different workers keep ascending order
+      const uint64_t act = __ballot(p.active);
+      const int w_first = __shfl(p.w, __ffsll((unsigned long long)act) - 1);
+      const int w_last = __shfl(p.w, 63 - __clzll((unsigned long long)act));
+      for (int w = w_first; w <= w_last; ++w) {
+        if (p.active && p.w == w && pos < (uint32_t)kDecTile) lt[pos] = __fadd_rn(lt[pos], val);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
     }
-    // add worker by worker so that equal indices of different workers keep ascending order
-    const uint64_t act = __ballot(active);
-    const int w_first = __shfl(myw, __ffsll((unsigned long long)act) - 1);
-    const int w_last = __shfl(myw, 63 - __clzll((unsigned long long)act));
-    for (int w = w_first; w <= w_last; ++w) {
-      if (active && myw == w && pos < (uint32_t)kDecTile) lt[pos] = __fadd_rn(lt[pos], val);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-    }
-  }
 
-  const int64_t remain = n - base;
-  if (remain >= kDecTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
+    if (MODE == 0) {
+      const int64_t remain = n - base;
+      if (remain >= kDecTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
 #pragma unroll
-    for (int i = 0; i < kDecTile / 256; ++i) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
-#if defined(GC_DEC_PLAIN_STORE)
-      *reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4) = v;
-#else
-      __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
-#endif
+        for (int i = 0; i < kDecTile / 256; ++i) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
+          __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
+        }
+      } else {
+        const int lim = (int)(remain < kDecTile ? remain : kDecTile);
+        for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
+      }
+    } else {
+      // every touched position is claimed once (LDS exchange with a marker) and updated in place:
+      // theta - fl32(c * sum). Untouched positions have sum +0 and would not change anyway.
+      for (uint32_t s0 = 0; s0 < total; s0 += 64) {
+        const LanePair p = locate_pair(s0, lane, total, W, excl, cnt, lo);
+        if (p.active) {
+          const I* idx = static_cast<const I*>(a.indices[p.w]);
+          const unsigned long long gi = (unsigned long long)idx[p.j];
+          const uint32_t pos = (uint32_t)(gi - (unsigned long long)base);
+          if (pos < (uint32_t)kDecTile && gi < (unsigned long long)n) {
+            const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + pos, kClaimed);
+            if (old != kClaimed) out[gi] = __fsub_rn(out[gi], __fmul_rn(c_apply, __uint_as_float(old)));
+          }
+        }
+      }
     }
-  } else {
-    const int lim = (int)(remain < kDecTile ? remain : kDecTile);
-    for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   }  // tile loop
 }
 
@@ -164,22 +199,18 @@ void launch_dec_bounds(const DecArgs& a, int W, int index_bits, int64_t ntiles, 
 
 void launch_dec_tiles(const DecArgs& a, int W, int index_bits, int32_t block, int64_t n, int64_t ntiles,
                       const uint32_t* bounds, const long long* kprefix, const long long* sprefix, int T,
-                      float* out, hipStream_t s) {
-#ifndef GC_DEC_GRID
-#define GC_DEC_GRID 512
-#endif
-#if GC_DEC_GRID > 0
+                      float* out, int weighted, int apply, float c_apply, hipStream_t s) {
   const int64_t want = (ntiles + kDecWaves - 1) / kDecWaves;
-  const dim3 grid((unsigned)(want < GC_DEC_GRID ? want : GC_DEC_GRID));
-#else
-  const dim3 grid((unsigned)((ntiles + kDecWaves - 1) / kDecWaves));
-#endif
-  if (index_bits == 32)
-    hipLaunchKernelGGL(k_dec_tiles<uint32_t>, grid, dim3(kDecWaves * 64), 0, s, a, W, block, n, ntiles, bounds,
-                       kprefix, sprefix, T, out);
-  else
-    hipLaunchKernelGGL(k_dec_tiles<unsigned long long>, grid, dim3(kDecWaves * 64), 0, s, a, W, block, n, ntiles,
-                       bounds, kprefix, sprefix, T, out);
+  const dim3 grid((unsigned)(want < kDecGrid ? want : kDecGrid)), blk(kDecWaves * 64);
+#define GC_LAUNCH_TILES(ITYPE, MODE)                                                                        \
+  hipLaunchKernelGGL((k_dec_tiles<ITYPE, MODE>), grid, blk, 0, s, a, W, block, n, ntiles, bounds, kprefix, \
+                     sprefix, T, out, weighted, c_apply)
+  if (index_bits == 32) {
+    if (apply) GC_LAUNCH_TILES(uint32_t, 1); else GC_LAUNCH_TILES(uint32_t, 0);
+  } else {
+    if (apply) GC_LAUNCH_TILES(unsigned long long, 1); else GC_LAUNCH_TILES(unsigned long long, 0);
+  }
+#undef GC_LAUNCH_TILES
 }
 
 }  // namespace gc

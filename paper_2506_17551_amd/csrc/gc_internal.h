@@ -153,11 +153,13 @@ struct DecArgs {
   const int8_t* q[kMaxWorkers];
   const float* scales[kMaxWorkers];
   uint32_t k[kMaxWorkers];
+  float denom[kMaxWorkers];  // 1 + staleness of the worker (weighted aggregate)
 };
 void launch_dec_bounds(const DecArgs& a, int W, int index_bits, int64_t ntiles, uint32_t* bounds,
                        hipStream_t s);
 void launch_dec_tiles(const DecArgs& a, int W, int index_bits, int32_t block, int64_t n,
                       int64_t ntiles, const uint32_t* bounds, const long long* kprefix,
-                      const long long* sprefix, int T, float* out, hipStream_t s);
+                      const long long* sprefix, int T, float* out, int weighted, int apply, float c_apply,
+                      hipStream_t s);
 
 }  // namespace gc

@@ -423,3 +423,82 @@ def test_many_small_tensors(gc, ctx, oracle):
     sizes = [int(x) for x in rng.integers(1, 6000, size=3000)] + [400_000, 1, 4096, 4097, 262_144]
     st = _multi_case(gc, ctx, oracle, sizes, 0.02, 16, W=2, seed=900)
     assert st["tensors"] == len(sizes)
+
+
+# ---------------------------------------------------------------------------------- Eq. 12 / Eq. 9
+def _workers(gc, ctx, oracle, n, k, block, W, seed, bits=32):
+    bufs, refs = [], []
+    hot = inputs.normal(n, 1.0, seed + 999)
+    for w in range(W):
+        g = inputs.normal(n, 1.0, seed + w) + 1.5 * hot
+        buf, ref, _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, block, index_bits=bits, tag=f"w{w}")
+        bufs.append(buf)
+        refs.append(ref)
+    return bufs, refs
+
+
+@pytest.mark.parametrize("bits_", [32, 64])
+def test_staleness_weighted_aggregate(gc, ctx, oracle, bits_):
+    n, k, block, W = 600_011, 9000, 128, 9
+    bufs, refs = _workers(gc, ctx, oracle, n, k, block, W, 40, bits_)
+    for taus in ([0] * W, [3] * W, [0, 1, 2, 5, 9, 30, 0, 7, 100], [1 << 24] + [0] * (W - 1)):
+        out = gc.decompress_sum_weighted(ctx, bufs, taus, n)
+        torch.cuda.synchronize()
+        rc, want = oracle.decompress_sum(refs, n, block, staleness=taus)
+        assert rc == 0 and np.array_equal(bits(out.cpu().numpy()), bits(want)), taus
+    plain = gc.decompress_sum(ctx, bufs, n)
+    same = gc.decompress_sum_weighted(ctx, bufs, [0] * W, n)
+    torch.cuda.synchronize()
+    assert torch.equal(plain.view(torch.int32), same.view(torch.int32))
+    with pytest.raises(gc.GradCompError):
+        gc.decompress_sum_weighted(ctx, bufs, [-1] + [0] * (W - 1), n)
+
+
+@pytest.mark.parametrize("weighted", [False, True])
+def test_fused_aggregate_and_apply(gc, ctx, oracle, weighted):
+    n, k, block, W = 1_000_003, 15000, 256, 16
+    bufs, refs = _workers(gc, ctx, oracle, n, k, block, W, 70)
+    taus = [w % 5 for w in range(W)] if weighted else None
+    theta0 = inputs.normal(n, 1.0, 5)
+    theta0[::7] = -0.0                                   # signed zeros must survive untouched
+    for step in (0.0, 0.01, 1.0 / W):
+        theta = theta0.to(DEV).clone()
+        gc.decompress_apply(ctx, bufs, theta, step, staleness=taus)
+        torch.cuda.synchronize()
+        rc, S = oracle.decompress_sum(refs, n, block, staleness=taus)
+        want = theta0.numpy().copy()
+        assert oracle.apply(want, S, step) == 0
+        assert np.array_equal(bits(theta.cpu().numpy()), bits(want)), step
+    # the separate route gives the same parameters: dense aggregate, then the update
+    theta = theta0.to(DEV).clone()
+    gc.decompress_apply(ctx, bufs, theta, 0.03, staleness=taus)
+    S_dev = gc.decompress_sum_weighted(ctx, bufs, taus, n) if weighted else gc.decompress_sum(ctx, bufs, n)
+    ref = theta0.to(DEV) - 0.03 * S_dev
+    torch.cuda.synchronize()
+    assert torch.equal(theta.view(torch.int32), ref.view(torch.int32))
+    with pytest.raises(gc.GradCompError):
+        gc.decompress_apply(ctx, bufs, theta, -0.1)
+
+
+def test_apply_multi_tensor(gc, ctx, oracle):
+    sizes = [768, 5, 300001, 2304, 262144]
+    off = inputs.offsets_of(sizes)
+    n = int(off[-1])
+    ks = np.array([gc.k_from_density(int(s), 0.01) for s in sizes], dtype=np.int64)
+    bufs, refs = [], []
+    for w in range(3):
+        g = inputs.normal(n, 0.02, 500 + w)
+        e = torch.zeros(n)
+        e_ref = e.numpy().copy()
+        rc, idx, q, s = oracle.compress_multi(g.numpy(), e_ref, off, ks, 8)
+        bufs.append(gc.compress_multi(ctx, g.to(DEV), e.to(DEV), off, ks, 8))
+        refs.append((idx, q, s))
+    gc.sync_status(ctx)
+    theta0 = inputs.normal(n, 1.0, 6)
+    theta = theta0.to(DEV).clone()
+    gc.decompress_apply(ctx, bufs, theta, 0.25, staleness=[0, 2, 1], ks=ks)
+    torch.cuda.synchronize()
+    rc, S = oracle.decompress_sum(refs, n, 8, ktensor=ks, staleness=[0, 2, 1])
+    want = theta0.numpy().copy()
+    oracle.apply(want, S, 0.25)
+    assert np.array_equal(bits(theta.cpu().numpy()), bits(want))

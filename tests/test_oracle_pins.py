@@ -397,3 +397,74 @@ def test_threshold_matches_closed_form_quantile(oracle):
     rc, idx, q, s = oracle.compress(g, np.zeros(n, np.float32), k, 2048)
     thr = np.abs(g[idx]).min()
     assert abs(thr / (0.1 * stats.norm.isf(0.05)) - 1) < 0.05
+
+
+# ----------------------------------------------------------------- Eq. 12 damping and Eq. 9 update
+def test_golden_staleness_and_apply(oracle):
+    G = read_golden("staleness_apply.txt")
+    bufs = [(np.array([int(x) for x in G[f"idx{w}"]], dtype=np.uint32),
+             np.array([int(x) for x in G[f"q{w}"]], dtype=np.int8), f32(G[f"s{w}"])) for w in range(2)]
+    n, block = int(G["n"][0]), int(G["block"][0])
+    rc, S = oracle.decompress_sum(bufs, n, block, staleness=[int(x) for x in G["staleness"]])
+    assert rc == 0 and S.tolist() == f32(G["S"]).tolist()
+    theta = f32(G["theta"])
+    assert oracle.apply(theta, S, float(G["step"][0])) == 0
+    assert theta.tolist() == f32(G["theta_new"]).tolist()
+
+
+def test_staleness_properties(oracle):
+    n, k, block, W = 20000, 800, 32, 6
+    bufs = [_compress_worker(oracle, n, k, block, 300 + w) for w in range(W)]
+    rc, plain = oracle.decompress_sum(bufs, n, block)
+    # no staleness anywhere: bit-identical to the plain aggregate (d / 1 == d)
+    rc, s0 = oracle.decompress_sum(bufs, n, block, staleness=[0] * W)
+    assert rc == 0 and np.array_equal(s0.view(np.uint32), plain.view(np.uint32))
+    # a single worker that is tau late: its decoded vector divided by (1 + tau), Eq. 12 with eta = 1
+    for tau in (1, 2, 3, 10, 1000):
+        rc, s1 = oracle.decompress_sum(bufs[:1], n, block, staleness=[tau])
+        d = np.zeros(n, np.float32)
+        d[bufs[0][0]] = dequant(bufs[0][1], bufs[0][2], block)
+        assert np.array_equal(s1, (d / np.float32(1 + tau)).astype(np.float32))
+    # power-of-two denominators are exact scalings, so damping everyone by 4 quarters the aggregate
+    rc, s3 = oracle.decompress_sum(bufs, n, block, staleness=[3] * W)
+    assert np.array_equal(s3, plain * np.float32(0.25))
+    # general case against float64 with the fp32 error bound (one division and W-1 adds)
+    taus = [0, 1, 2, 5, 9, 30]
+    rc, sw = oracle.decompress_sum(bufs, n, block, staleness=taus)
+    ref = np.zeros(n, np.float64)
+    mag = np.zeros(n, np.float64)
+    for (idx, q, s), tau in zip(bufs, taus):
+        d = dequant(q, s, block).astype(np.float64) / (1 + tau)
+        ref[idx] += d
+        mag[idx] += np.abs(d)
+    assert np.all(np.abs(sw - ref) <= W * 2.0 ** -24 * mag + 1e-300)
+    assert oracle.decompress_sum(bufs, n, block, staleness=[-1] + [0] * (W - 1))[0] == oracle.ERR_INVALID_ARG
+
+
+def test_apply_properties(oracle):
+    n = 5000
+    theta0 = inputs.normal(n, 1.0, 1).numpy()
+    S = inputs.normal(n, 1.0, 2).numpy()
+    S[::3] = 0.0
+    th = theta0.copy()
+    assert oracle.apply(th, S, 0.0) == 0 and np.array_equal(th.view(np.uint32), theta0.view(np.uint32))
+    th = theta0.copy()
+    oracle.apply(th, S, 0.125)
+    assert np.array_equal(th[::3].view(np.uint32), theta0[::3].view(np.uint32))   # zero aggregate: untouched
+    want = (theta0 - (np.float32(0.125) * S).astype(np.float32)).astype(np.float32)
+    assert np.array_equal(th.view(np.uint32), want.view(np.uint32))
+    # Eq. 8 + Eq. 9 with P workers at density 1 and a power-of-two block scale: theta - eta * mean(g)
+    P, eta = 4, 0.5
+    gs = [np.round(inputs.normal(256, 8.0, 10 + p).numpy()).clip(-127, 127).astype(np.float32) for p in range(P)]
+    for g in gs:
+        g[0] = 127.0                                     # amax 127 -> scale exactly 1 -> codes are g itself
+    bufs = []
+    for g in gs:
+        rc, idx, q, s = oracle.compress(g, np.zeros(256, np.float32), 256, 256)
+        assert s[0] == 1.0
+        bufs.append((idx, q, s))
+    rc, agg = oracle.decompress_sum(bufs, 256, 256)
+    th = np.ones(256, np.float32)
+    oracle.apply(th, agg, eta / P)
+    assert np.array_equal(th, (1.0 - eta * np.mean(np.stack(gs), axis=0)).astype(np.float32))
+    assert oracle.apply(th, agg, -1.0) == oracle.ERR_INVALID_ARG
