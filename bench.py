@@ -125,6 +125,19 @@ def run_flat(args, gc, inputs, torch, wl, ctx):
         with ta:
             gc.decompress_apply(ctx, bufs, out, 1.0 / W)
     variants = {"decompress_sum_weighted_ms": round(tw.total_ms(), 4), "decompress_apply_ms": round(ta.total_ms(), 4)}
+    # the paper's own 1-bit value code (Eq. 10) on the last worker's inputs, same selection path
+    sbuf = gc.CompressedBuf.allocate(n, k, nsc, block, wl.index_bits, dev, gc.GC_CODEC_SIGN1)
+    ts_, tds = Timer(torch), Timer(torch)
+    for _ in range(2):
+        ts_.reset()
+        tds.reset()
+        with ts_:
+            gc.compress(ctx, g, e, k, block, out=sbuf)
+        with tds:
+            gc.decompress_sum(ctx, [sbuf] * W, n, out=out)
+    gc.sync_status(ctx)
+    variants["compress_sign1_ms_per_worker"] = round(ts_.total_ms(), 4)
+    variants["decompress_sum_sign1_ms"] = round(tds.total_ms(), 4)
     info = {"n": n, "k": k, "block": block, "W": W, "index_bits": wl.index_bits, **variants,
             "compress_ms_per_worker": ms_c / W, "decompress_sum_ms": ms_d,
             "residuals_resident": resident, "fallback_tensors": stats["tensors_fallback"],

@@ -40,6 +40,16 @@ typedef enum {
 
 typedef enum { GC_F32 = 0, GC_BF16 = 1 } gc_dtype;
 
+/* How the kept values are coded.
+ * GC_CODEC_INT8:  one int8 per pair and one fp32 scale per block, s = amax / 127,
+ *                 q = rint(v / s); decodes to fl32(q * s).
+ * GC_CODEC_SIGN1: the paper's 1-bit quantizer (Sec. III.B, Eq. 10): one sign bit per pair (set when
+ *                 v >= 0) and one fp32 scale per block, the block's mean magnitude ||v||_1 / len
+ *                 (l1 sum in fp64 over a balanced binary tree, then one division, one rounding);
+ *                 decodes to +s or -s. Bits are packed 8 per byte, least significant first, every
+ *                 block starting a new byte. Needs block <= 8192. */
+typedef enum { GC_CODEC_INT8 = 0, GC_CODEC_SIGN1 = 1 } gc_codec;
+
 typedef struct gc_ctx gc_ctx; /* opaque; owns scratch workspace on one device */
 
 /* A compressed gradient: k (index, code) pairs in ascending index order plus one
@@ -50,12 +60,14 @@ typedef struct gc_ctx gc_ctx; /* opaque; owns scratch workspace on one device */
  * tensor boundary (scales are concatenated the same way). */
 typedef struct {
   void* indices;      /* k entries; uint32_t if index_bits == 32, uint64_t if 64 */
-  int8_t* q;          /* k codes in [-127, 127] */
+  int8_t* q;          /* gc_num_code_bytes(k, block, codec) bytes: k codes in [-127, 127], or sign bits */
   float* scales;      /* gc_num_scales(k, block) entries (multi: sum over tensors) */
   int64_t n;          /* length of the dense vector the indices point into */
   int64_t k;          /* number of pairs */
   int32_t block;      /* pairs per scale */
   int32_t index_bits; /* 32 or 64; must be 64 when n > 2^32 */
+  int32_t codec;      /* gc_codec of the values */
+  int32_t reserved_;  /* must be 0 */
 } gc_buf;
 
 /* Counters of the last compress call, valid after gc_sync_status(). */
@@ -78,6 +90,11 @@ int64_t gc_k_from_density(int64_t n, double density);
 /* ceil(k / block): number of scales for k pairs. Pure host function. */
 int64_t gc_num_scales(int64_t k, int32_t block);
 
+/* Bytes of `q` for k pairs of ONE tensor (multi-tensor buffers: the sum over tensors): k for
+ * GC_CODEC_INT8; for GC_CODEC_SIGN1 every full block takes ceil(block / 8) bytes and the last,
+ * shorter block ceil(len / 8). Pure host function; 0 on invalid arguments. */
+int64_t gc_num_code_bytes(int64_t k, int32_t block, gc_codec codec);
+
 /* One error-feedback step of one worker on one flat tensor (Sec. III.B, Eq. 11):
  *   acc = residual + grad            (one fp32 add per entry; bf16 grad is widened exactly)
  *   kept = the k entries of largest |acc| (31-bit magnitude pattern; ties to the lower index)
@@ -85,8 +102,10 @@ int64_t gc_num_scales(int64_t k, int32_t block);
  *          of `block` consecutive kept entries (a zero or subnormal s sends the block as zeros)
  *   residual = acc - fl32(q * s) at kept entries, acc elsewhere          (updated in place)
  * grad: n entries of `dtype`, read only. residual: n fp32. 1 <= k <= n, block >= 1,
- * k < 2^32. out->indices/q/scales must hold k / k / gc_num_scales(k, block) entries;
- * out->n, out->k, out->block must equal n, k, block. */
+ * k < 2^32. out->indices/q/scales must hold k / gc_num_code_bytes(k, block, codec) /
+ * gc_num_scales(k, block) entries; out->n, out->k, out->block must equal n, k, block.
+ * out->codec chooses the value code (the description above is GC_CODEC_INT8; with GC_CODEC_SIGN1
+ * the residual at a kept entry is acc -/+ s). */
 gc_status gc_compress(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual, int64_t n,
                       int64_t k, int32_t block, const gc_buf* out, void* hip_stream);
 
@@ -104,7 +123,7 @@ gc_status gc_compress_multi(gc_ctx* ctx, const void* grad, gc_dtype dtype, float
  * the 1/P): out[i] = sum over w = 0..W-1, in that order and in fp32, of the
  * decoded value of worker w at i (0 where w sent nothing). `out` (n fp32) is
  * fully overwritten. bufs: W host structs; all must have n == `n` and the same
- * block and index_bits; indices must be ascending and unique within a buffer
+ * block, index_bits and codec; indices must be ascending and unique within a buffer
  * (as gc_compress writes them). 1 <= W <= 64. */
 gc_status gc_decompress_sum(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* out, int64_t n,
                             void* hip_stream);

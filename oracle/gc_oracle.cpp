@@ -31,6 +31,14 @@
 //   R7  Non-finite acc inside a kept block is reported as an error.
 //   R8  The sum over workers is accumulated in fp32 in ascending worker order,
 //       starting from +0.
+//   R9  Alternative value code, the paper's own 1-bit quantizer (Eq. 10): the code of a kept
+//       entry is its sign (+1 if v >= 0, which includes -0; -1 otherwise) and the block's
+//       scale is the mean magnitude ||v||_1 / len ("accompanied by a scaling factor, e.g.
+//       ||g||_1"). To make the scale a fixed number, the l1 sum is accumulated in fp64 by
+//       the balanced binary tree over the block's entries padded with zeros to a power of
+//       two, s = (float)(sum / len) (one fp64 division, one rounding to fp32), zero or
+//       subnormal s sends zeros. ghat = +-s; the residual is fl32(acc - ghat). Signs are
+//       packed 8 per byte, least significant bit first, every block starting a new byte.
 // Parity status: the selection (R1-R3), Eq. (11) and Eq. (8) are pinned by the
 // CPU tests (brute-force sort, exact invariants, closed-form quantiles). The
 // choice of int8 scheme (R4), block semantics and the k rounding rule (R6) are
@@ -79,15 +87,26 @@ int64_t gco_k_from_density(int64_t n, double density) {
   return static_cast<int64_t>(kd);
 }
 
+// Bytes of code for k kept entries: one per entry (int8), or the packed sign bits of each
+// block rounded up to whole bytes (sign code).
+int64_t gco_num_code_bytes(int64_t k, int32_t block, int32_t codec) {
+  if (k <= 0 || block < 1) return 0;
+  if (codec == 0) return k;
+  const int64_t full = k / block, rest = k % block;
+  return full * ((block + 7) / 8) + (rest + 7) / 8;
+}
+
 // One worker, one tensor, one error-feedback step (Sec. III.B, Eq. 11).
 //   g        n gradient entries, dtype 0 = fp32, 1 = bf16            (read only)
 //   e        n fp32 residual entries: r_t on entry, r_{t+1} on return
 //   idx      k kept indices, ascending; uint32 if index_bits == 32 else uint64
 //   q        k int8 codes, same order
 //   scales   ceil(k / block) fp32 scales
-int gco_compress(const void* g, int dtype, float* e, int64_t n, int64_t k, int32_t block,
-                 void* idx, int32_t index_bits, int8_t* q, float* scales) {
+//   codec    0: per-block int8 (R4), 1: per-block sign bit with mean-magnitude scale (R9)
+int gco_compress_codec(const void* g, int dtype, float* e, int64_t n, int64_t k, int32_t block,
+                       void* idx, int32_t index_bits, int8_t* q, float* scales, int32_t codec) {
   if (!g || !e || !idx || !q || !scales) return GCO_ERR_INVALID_ARG;
+  if (codec != 0 && codec != 1) return GCO_ERR_INVALID_ARG;
   if (n <= 0 || k < 1 || k > n || block < 1) return GCO_ERR_INVALID_ARG;
   if (dtype != 0 && dtype != 1) return GCO_ERR_INVALID_ARG;
   if (index_bits != 32 && index_bits != 64) return GCO_ERR_INVALID_ARG;
@@ -147,6 +166,33 @@ int gco_compress(const void* g, int dtype, float* e, int64_t n, int64_t k, int32
       float a = std::fabs(v[j]);
       if (a > amax) amax = a;
     }
+    if (codec == 1) {  // Eq. 10: sign bits and one scale per block
+      const int64_t len = j1 - j0;
+      uint8_t* bytes = reinterpret_cast<uint8_t*>(q) + b * ((block + 7) / 8);
+      for (int64_t r = 0; r < (len + 7) / 8; ++r) bytes[r] = 0;
+      if (!finite) {
+        status = GCO_ERR_NONFINITE;
+        scales[b] = 0.0f;
+        continue;
+      }
+      int64_t P = 1;
+      while (P < len) P <<= 1;
+      std::vector<double> tree(P, 0.0);
+      for (int64_t r = 0; r < len; ++r) tree[r] = std::fabs(static_cast<double>(v[j0 + r]));
+      for (int64_t stride = P / 2; stride >= 1; stride /= 2)
+        for (int64_t r = 0; r < stride; ++r) tree[r] = tree[r] + tree[r + stride];
+      float s1 = static_cast<float>(tree[0] / static_cast<double>(len));
+      if (!(s1 >= FLT_MIN)) s1 = 0.0f;
+      scales[b] = s1;
+      for (int64_t r = 0; r < len; ++r) {
+        const float val = v[j0 + r];
+        const bool plus = val >= 0.0f;
+        if (plus) bytes[r / 8] = static_cast<uint8_t>(bytes[r / 8] | (1u << (r % 8)));
+        const float d = plus ? s1 : -s1;
+        e[kept[j0 + r]] = val - d;
+      }
+      continue;
+    }
     if (!finite) {
       status = GCO_ERR_NONFINITE;
       scales[b] = 0.0f;
@@ -180,6 +226,11 @@ int gco_compress(const void* g, int dtype, float* e, int64_t n, int64_t k, int32
   return status;
 }
 
+int gco_compress(const void* g, int dtype, float* e, int64_t n, int64_t k, int32_t block,
+                 void* idx, int32_t index_bits, int8_t* q, float* scales) {
+  return gco_compress_codec(g, dtype, e, n, k, block, idx, index_bits, q, scales, 0);
+}
+
 // A list of tensors laid out back to back in one flat buffer; each tensor gets
 // its own top-k and its own quantization blocks (blocks never straddle
 // tensors). Outputs are concatenated in tensor order; indices are positions in
@@ -187,12 +238,12 @@ int gco_compress(const void* g, int dtype, float* e, int64_t n, int64_t k, int32
 //   offsets  T+1 element offsets, offsets[0] = 0, non-decreasing
 //   k        T per-tensor counts (k[t] in [1, n_t])
 //   scales   sum_t ceil(k[t]/block) entries
-int gco_compress_multi(const void* g, int dtype, float* e, const int64_t* offsets,
-                       const int64_t* k, int32_t T, int32_t block, void* idx,
-                       int32_t index_bits, int8_t* q, float* scales) {
+int gco_compress_multi_codec(const void* g, int dtype, float* e, const int64_t* offsets,
+                             const int64_t* k, int32_t T, int32_t block, void* idx,
+                             int32_t index_bits, int8_t* q, float* scales, int32_t codec) {
   if (!offsets || !k || T < 1) return GCO_ERR_INVALID_ARG;
   int status = GCO_OK;
-  int64_t kpos = 0, spos = 0;
+  int64_t kpos = 0, spos = 0, qpos = 0;
   for (int32_t t = 0; t < T; ++t) {
     const int64_t off = offsets[t];
     const int64_t n = offsets[t + 1] - off;
@@ -201,8 +252,8 @@ int gco_compress_multi(const void* g, int dtype, float* e, const int64_t* offset
                          ? static_cast<const void*>(static_cast<const float*>(g) + off)
                          : static_cast<const void*>(static_cast<const uint16_t*>(g) + off);
     std::vector<uint64_t> local(k[t] > 0 ? k[t] : 0);
-    int rc = gco_compress(gt, dtype, e + off, n, k[t], block, local.data(), 64, q + kpos,
-                          scales + spos);
+    int rc = gco_compress_codec(gt, dtype, e + off, n, k[t], block, local.data(), 64, q + qpos,
+                                scales + spos, codec);
     if (rc == GCO_ERR_NONFINITE)
       status = rc;
     else if (rc != GCO_OK)
@@ -216,8 +267,15 @@ int gco_compress_multi(const void* g, int dtype, float* e, const int64_t* offset
     }
     kpos += k[t];
     spos += (k[t] + block - 1) / block;
+    qpos += gco_num_code_bytes(k[t], block, codec);
   }
   return status;
+}
+
+int gco_compress_multi(const void* g, int dtype, float* e, const int64_t* offsets,
+                       const int64_t* k, int32_t T, int32_t block, void* idx,
+                       int32_t index_bits, int8_t* q, float* scales) {
+  return gco_compress_multi_codec(g, dtype, e, offsets, k, T, block, idx, index_bits, q, scales, 0);
 }
 
 // Sum of W decompressed buffers into a dense vector (Eq. 8 without the 1/P). If `staleness`
@@ -228,10 +286,11 @@ int gco_compress_multi(const void* g, int dtype, float* e, const int64_t* offset
 // gco_compress_multi with per-tensor counts ktensor[T] (identical for every
 // worker) and the scale of entry j is found per tensor; with T == 0 the scale
 // of entry j is scales[j / block].
-int gco_decompress_sum_weighted(int32_t W, const void* const* idx, const int8_t* const* q,
-                                const float* const* scales, const int64_t* kcount, int32_t block,
-                                int32_t index_bits, const int64_t* ktensor, int32_t T,
-                                const int32_t* staleness, float* out, int64_t n) {
+int gco_decompress_sum_codec(int32_t W, const void* const* idx, const int8_t* const* q,
+                             const float* const* scales, const int64_t* kcount, int32_t block,
+                             int32_t index_bits, const int64_t* ktensor, int32_t T,
+                             const int32_t* staleness, float* out, int64_t n, int32_t codec) {
+  if (codec != 0 && codec != 1) return GCO_ERR_INVALID_ARG;
   if (W < 1 || !idx || !q || !scales || !kcount || !out || n <= 0 || block < 1)
     return GCO_ERR_INVALID_ARG;
   if (staleness)
@@ -239,10 +298,11 @@ int gco_decompress_sum_weighted(int32_t W, const void* const* idx, const int8_t*
       if (staleness[w] < 0 || staleness[w] > (1 << 24)) return GCO_ERR_INVALID_ARG;
   for (int64_t i = 0; i < n; ++i) out[i] = 0.0f;
   for (int32_t w = 0; w < W; ++w) {
-    int64_t t = 0, t_end = (T > 0) ? ktensor[0] : kcount[w], t_begin = 0, s_base = 0;
+    int64_t t = 0, t_end = (T > 0) ? ktensor[0] : kcount[w], t_begin = 0, s_base = 0, q_base = 0;
     for (int64_t j = 0; j < kcount[w]; ++j) {
       while (T > 0 && j >= t_end) {  // advance to the tensor that owns entry j
         s_base += (t_end - t_begin + block - 1) / block;
+        q_base += gco_num_code_bytes(t_end - t_begin, block, codec);
         t_begin = t_end;
         ++t;
         if (t >= T) return GCO_ERR_INVALID_ARG;
@@ -252,7 +312,14 @@ int gco_decompress_sum_weighted(int32_t W, const void* const* idx, const int8_t*
       uint64_t i = (index_bits == 32) ? static_cast<const uint32_t*>(idx[w])[j]
                                       : static_cast<const uint64_t*>(idx[w])[j];
       if (i >= static_cast<uint64_t>(n)) return GCO_ERR_INVALID_ARG;
-      volatile float d = static_cast<float>(q[w][j]) * s;
+      volatile float d;
+      if (codec == 0) {
+        d = static_cast<float>(q[w][j]) * s;
+      } else {  // sign code: +-s, bit r of the block's bytes
+        const int64_t r = (j - t_begin) % block, bb = (j - t_begin) / block;
+        const uint8_t byte = reinterpret_cast<const uint8_t*>(q[w])[q_base + bb * ((block + 7) / 8) + r / 8];
+        d = ((byte >> (r % 8)) & 1u) ? s : -s;
+      }
       if (staleness) {
         const float denom = 1.0f + static_cast<float>(staleness[w]);
         volatile float damped = d / denom;
@@ -264,12 +331,20 @@ int gco_decompress_sum_weighted(int32_t W, const void* const* idx, const int8_t*
   return GCO_OK;
 }
 
+int gco_decompress_sum_weighted(int32_t W, const void* const* idx, const int8_t* const* q,
+                                const float* const* scales, const int64_t* kcount, int32_t block,
+                                int32_t index_bits, const int64_t* ktensor, int32_t T,
+                                const int32_t* staleness, float* out, int64_t n) {
+  return gco_decompress_sum_codec(W, idx, q, scales, kcount, block, index_bits, ktensor, T, staleness, out, n,
+                                  0);
+}
+
 int gco_decompress_sum(int32_t W, const void* const* idx, const int8_t* const* q,
                        const float* const* scales, const int64_t* kcount, int32_t block,
                        int32_t index_bits, const int64_t* ktensor, int32_t T, float* out,
                        int64_t n) {
-  return gco_decompress_sum_weighted(W, idx, q, scales, kcount, block, index_bits, ktensor, T, nullptr, out,
-                                     n);
+  return gco_decompress_sum_codec(W, idx, q, scales, kcount, block, index_bits, ktensor, T, nullptr, out, n,
+                                  0);
 }
 
 // Parameter update with the aggregate (Eq. 9 with g from Eq. 8): theta <- theta - step * S,

@@ -18,6 +18,7 @@ _LIB = os.path.join(_HERE, "libgc_oracle.so")
 
 OK, ERR_INVALID_ARG, ERR_NONFINITE = 0, 1, 4
 F32, BF16 = 0, 1
+INT8, SIGN1 = 0, 1  # value codes
 
 
 def build(force: bool = False) -> str:
@@ -57,6 +58,14 @@ def lib() -> ctypes.CDLL:
                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
                                                   ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
                                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        L.gco_num_code_bytes.restype = ctypes.c_int64
+        L.gco_num_code_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
+        L.gco_compress_codec.restype = ctypes.c_int
+        L.gco_compress_codec.argtypes = L.gco_compress.argtypes + [ctypes.c_int32]
+        L.gco_compress_multi_codec.restype = ctypes.c_int
+        L.gco_compress_multi_codec.argtypes = L.gco_compress_multi.argtypes + [ctypes.c_int32]
+        L.gco_decompress_sum_codec.restype = ctypes.c_int
+        L.gco_decompress_sum_codec.argtypes = L.gco_decompress_sum_weighted.argtypes + [ctypes.c_int32]
         L.gco_apply.restype = ctypes.c_int
         L.gco_apply.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_int64]
         _lib = L
@@ -80,26 +89,31 @@ def _ptr(a: np.ndarray) -> int:
     return a.ctypes.data
 
 
-def compress(g: np.ndarray, e: np.ndarray, k: int, block: int, index_bits: int = 32):
+def num_code_bytes(k: int, block: int, codec: int = INT8) -> int:
+    return int(lib().gco_num_code_bytes(int(k), int(block), int(codec)))
+
+
+def compress(g: np.ndarray, e: np.ndarray, k: int, block: int, index_bits: int = 32, codec: int = INT8):
     """One error-feedback step. `e` (float32) is updated IN PLACE to r_{t+1}.
 
-    Returns (status, idx, q, scales)."""
+    Returns (status, idx, q, scales); with codec=SIGN1 `q` holds the packed sign bytes."""
     n = g.shape[0]
     assert e.dtype == np.float32 and e.shape[0] == n
     kk = max(int(k), 0)
     idx = np.zeros(kk, dtype=np.uint32 if index_bits == 32 else np.uint64)
-    q = np.zeros(kk, dtype=np.int8)
+    q = np.zeros(max(num_code_bytes(kk, max(block, 1), codec), 0), dtype=np.int8)
     nb = (kk + block - 1) // block if block > 0 else 0
     s = np.zeros(max(nb, 1), dtype=np.float32)
     # zero-length arrays still need a non-null pointer for the argument check
     pad = np.zeros(1, dtype=np.uint64)
-    rc = lib().gco_compress(_ptr(g), _grad_dtype(g), _ptr(e), n, int(k), int(block),
-                            _ptr(idx) if kk else _ptr(pad), index_bits,
-                            _ptr(q) if kk else _ptr(pad), _ptr(s))
+    rc = lib().gco_compress_codec(_ptr(g), _grad_dtype(g), _ptr(e), n, int(k), int(block),
+                                  _ptr(idx) if kk else _ptr(pad), index_bits,
+                                  _ptr(q) if q.size else _ptr(pad), _ptr(s), int(codec))
     return rc, idx, q, s[:nb]
 
 
-def compress_multi(g: np.ndarray, e: np.ndarray, offsets, ks, block: int, index_bits: int = 32):
+def compress_multi(g: np.ndarray, e: np.ndarray, offsets, ks, block: int, index_bits: int = 32,
+                   codec: int = INT8):
     """Per-tensor top-k over a flat concatenation. Returns (status, idx, q, scales)."""
     offsets = np.ascontiguousarray(offsets, dtype=np.int64)
     ks = np.ascontiguousarray(ks, dtype=np.int64)
@@ -107,14 +121,14 @@ def compress_multi(g: np.ndarray, e: np.ndarray, offsets, ks, block: int, index_
     ktot = int(ks.sum())
     stot = int(((ks + block - 1) // block).sum())
     idx = np.zeros(ktot, dtype=np.uint32 if index_bits == 32 else np.uint64)
-    q = np.zeros(ktot, dtype=np.int8)
+    q = np.zeros(sum(num_code_bytes(int(x), block, codec) for x in ks), dtype=np.int8)
     s = np.zeros(stot, dtype=np.float32)
-    rc = lib().gco_compress_multi(_ptr(g), _grad_dtype(g), _ptr(e), _ptr(offsets), _ptr(ks), T,
-                                  int(block), _ptr(idx), index_bits, _ptr(q), _ptr(s))
+    rc = lib().gco_compress_multi_codec(_ptr(g), _grad_dtype(g), _ptr(e), _ptr(offsets), _ptr(ks), T,
+                                        int(block), _ptr(idx), index_bits, _ptr(q), _ptr(s), int(codec))
     return rc, idx, q, s
 
 
-def decompress_sum(bufs, n: int, block: int, ktensor=None, staleness=None):
+def decompress_sum(bufs, n: int, block: int, ktensor=None, staleness=None, codec: int = INT8):
     """bufs: list of (idx, q, scales) numpy triples, one per worker. Returns (status, out).
     staleness: optional per-worker integers (Eq. 12 damping)."""
     W = len(bufs)
@@ -136,9 +150,9 @@ def decompress_sum(bufs, n: int, block: int, ktensor=None, staleness=None):
         stp = _ptr(st)
     else:
         stp = None
-    rc = lib().gco_decompress_sum_weighted(W, ctypes.addressof(ia), ctypes.addressof(qa),
-                                           ctypes.addressof(sa), _ptr(kc), int(block), index_bits, ktp, T,
-                                           stp, _ptr(out), int(n))
+    rc = lib().gco_decompress_sum_codec(W, ctypes.addressof(ia), ctypes.addressof(qa),
+                                        ctypes.addressof(sa), _ptr(kc), int(block), index_bits, ktp, T,
+                                        stp, _ptr(out), int(n), int(codec))
     return rc, out
 
 

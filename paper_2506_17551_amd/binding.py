@@ -16,6 +16,7 @@ from . import build as _build
 
 GC_OK, GC_ERR_INVALID_ARG, GC_ERR_UNSUPPORTED, GC_ERR_WORKSPACE, GC_ERR_NONFINITE, GC_ERR_DEVICE = range(6)
 GC_F32, GC_BF16 = 0, 1
+GC_CODEC_INT8, GC_CODEC_SIGN1 = 0, 1
 
 
 class GradCompError(RuntimeError):
@@ -27,7 +28,7 @@ class GradCompError(RuntimeError):
 class _GcBuf(ctypes.Structure):
     _fields_ = [("indices", ctypes.c_void_p), ("q", ctypes.c_void_p), ("scales", ctypes.c_void_p),
                 ("n", ctypes.c_int64), ("k", ctypes.c_int64), ("block", ctypes.c_int32),
-                ("index_bits", ctypes.c_int32)]
+                ("index_bits", ctypes.c_int32), ("codec", ctypes.c_int32), ("reserved_", ctypes.c_int32)]
 
 
 class _GcStats(ctypes.Structure):
@@ -35,7 +36,7 @@ class _GcStats(ctypes.Structure):
                 ("tensors_fallback", ctypes.c_int64), ("candidates", ctypes.c_int64)]
 
 
-EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_compress",
+EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_num_code_bytes", "gc_compress",
            "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_multi", "gc_decompress_sum_weighted",
            "gc_decompress_apply", "gc_sync_status",
            "gc_last_stats", "gc_profile_enable", "gc_profile_num_kernels", "gc_profile_kernel_name",
@@ -58,6 +59,8 @@ def lib() -> ctypes.CDLL:
     L.gc_k_from_density.restype = i64
     L.gc_num_scales.argtypes = [i64, i32]
     L.gc_num_scales.restype = i64
+    L.gc_num_code_bytes.argtypes = [i64, i32, ctypes.c_int]
+    L.gc_num_code_bytes.restype = i64
     L.gc_compress.argtypes = [vp, vp, ctypes.c_int, vp, i64, i64, i32, ctypes.POINTER(_GcBuf), vp]
     L.gc_compress_multi.argtypes = [vp, vp, ctypes.c_int, vp, vp, vp, i32, i32, ctypes.POINTER(_GcBuf), vp]
     L.gc_decompress_sum.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i64, vp]
@@ -99,6 +102,10 @@ def k_from_density(n: int, density: float) -> int:
 
 def num_scales(k: int, block: int) -> int:
     return int(lib().gc_num_scales(int(k), int(block)))
+
+
+def num_code_bytes(k: int, block: int, codec: int = GC_CODEC_INT8) -> int:
+    return int(lib().gc_num_code_bytes(int(k), int(block), int(codec)))
 
 
 def _stream_ptr(stream: Optional[torch.cuda.Stream], device) -> int:
@@ -162,21 +169,26 @@ class CompressedBuf:
     k: int
     block: int
     index_bits: int
+    codec: int = GC_CODEC_INT8
 
     def struct(self) -> _GcBuf:
         return _GcBuf(self.indices.data_ptr(), self.q.data_ptr(), self.scales.data_ptr(), self.n, self.k,
-                      self.block, self.index_bits)
+                      self.block, self.index_bits, self.codec, 0)
 
     def indices_numpy(self) -> np.ndarray:
         a = self.indices.detach().cpu().numpy()
         return a.view(np.uint32) if self.index_bits == 32 else a.view(np.uint64)
 
     @staticmethod
-    def allocate(n: int, k: int, nscales: int, block: int, index_bits: int, device) -> "CompressedBuf":
+    def allocate(n: int, k: int, nscales: int, block: int, index_bits: int, device, codec: int = GC_CODEC_INT8,
+                 code_bytes: Optional[int] = None) -> "CompressedBuf":
         it = torch.int32 if index_bits == 32 else torch.int64
-        return CompressedBuf(torch.empty(k, dtype=it, device=device), torch.empty(k, dtype=torch.int8, device=device),
+        nq = k if codec == GC_CODEC_INT8 else (code_bytes if code_bytes is not None
+                                               else num_code_bytes(k, max(block, 1), codec))
+        return CompressedBuf(torch.empty(k, dtype=it, device=device),
+                             torch.empty(max(nq, 1), dtype=torch.int8, device=device)[:nq],
                              torch.empty(max(nscales, 1), dtype=torch.float32, device=device)[:nscales],
-                             int(n), int(k), int(block), int(index_bits))
+                             int(n), int(k), int(block), int(index_bits), int(codec))
 
 
 def _grad_dtype(grad: torch.Tensor) -> int:
@@ -198,7 +210,7 @@ def _check_dev(t: torch.Tensor, name: str, dtype=None) -> None:
 
 def compress(ctx: Context, grad: torch.Tensor, residual: torch.Tensor, k: int, block: int,
              out: Optional[CompressedBuf] = None, index_bits: Optional[int] = None,
-             stream: Optional[torch.cuda.Stream] = None) -> CompressedBuf:
+             stream: Optional[torch.cuda.Stream] = None, codec: int = GC_CODEC_INT8) -> CompressedBuf:
     """gc_compress: one error-feedback step on one flat tensor; `residual` is updated in place."""
     _check_dev(grad, "grad")
     _check_dev(residual, "residual", torch.float32)
@@ -209,7 +221,7 @@ def compress(ctx: Context, grad: torch.Tensor, residual: torch.Tensor, k: int, b
         index_bits = 64 if n > (1 << 32) else 32
     if out is None:
         kk = max(int(k), 0)
-        out = CompressedBuf.allocate(n, kk, num_scales(kk, block), block, index_bits, grad.device)
+        out = CompressedBuf.allocate(n, kk, num_scales(kk, block), block, index_bits, grad.device, codec)
     st = out.struct()
     rc = lib().gc_compress(ctx.handle, grad.data_ptr(), _grad_dtype(grad), residual.data_ptr(), n, int(k),
                            int(block), ctypes.byref(st), _stream_ptr(stream, grad.device))
@@ -220,7 +232,7 @@ def compress(ctx: Context, grad: torch.Tensor, residual: torch.Tensor, k: int, b
 def compress_multi(ctx: Context, grad: torch.Tensor, residual: torch.Tensor, offsets: Sequence[int],
                    ks: Sequence[int], block: int, out: Optional[CompressedBuf] = None,
                    index_bits: Optional[int] = None,
-                   stream: Optional[torch.cuda.Stream] = None) -> CompressedBuf:
+                   stream: Optional[torch.cuda.Stream] = None, codec: int = GC_CODEC_INT8) -> CompressedBuf:
     """gc_compress_multi: per-tensor top-k over tensors stored back to back in one flat buffer."""
     _check_dev(grad, "grad")
     _check_dev(residual, "residual", torch.float32)
@@ -237,7 +249,8 @@ def compress_multi(ctx: Context, grad: torch.Tensor, residual: torch.Tensor, off
     if out is None:
         ktot = int(kk.clip(min=0).sum())
         stot = int(sum(num_scales(int(x), block) for x in kk))
-        out = CompressedBuf.allocate(n, ktot, stot, block, index_bits, grad.device)
+        qtot = int(sum(num_code_bytes(int(x), block, codec) for x in kk)) if block > 0 else 0
+        out = CompressedBuf.allocate(n, ktot, stot, block, index_bits, grad.device, codec, qtot)
     st = out.struct()
     rc = lib().gc_compress_multi(ctx.handle, grad.data_ptr(), _grad_dtype(grad), residual.data_ptr(),
                                  off.ctypes.data, kk.ctypes.data, T, int(block), ctypes.byref(st),

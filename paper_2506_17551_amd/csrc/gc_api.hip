@@ -20,7 +20,7 @@ struct DevBuf {
 
 struct Plan {  // everything that depends only on (offsets, k, block)
   std::vector<int64_t> offsets, k;
-  int32_t block = 0;
+  int32_t block = 0, codec = 0;
   std::vector<TensorDesc> td;
   int32_t cap = 0;            // candidate slots per group
   int32_t slot_stride = 16;   // records per group incl. the header, multiple of 16
@@ -32,8 +32,8 @@ struct Plan {  // everything that depends only on (offsets, k, block)
 
 struct DecPlan {  // per-tensor prefix tables for multi-tensor decompress
   std::vector<int64_t> k;
-  int32_t block = 0;
-  DevBuf kprefix, sprefix;
+  int32_t block = 0, codec = 0;
+  DevBuf kprefix, sprefix, qprefix;
 };
 
 struct EventPair {
@@ -103,14 +103,21 @@ constexpr int64_t kMinSampledN = 1 << 17;
 constexpr int64_t kMinSampledK = 64;
 constexpr int64_t kMaxDensityInv = 8;  // sampled only if k * 8 <= n
 
-Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t block) {
+int64_t code_bytes(int64_t k, int32_t block, int32_t codec) {
+  if (k <= 0 || block < 1) return 0;
+  if (codec == GC_CODEC_INT8) return k;
+  return (k / block) * ((block + 7) / 8) + (k % block + 7) / 8;
+}
+
+Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t block, int32_t codec) {
   Plan* P = new (std::nothrow) Plan();
   if (!P) return nullptr;
   P->offsets.assign(offsets, offsets + T + 1);
   P->k.assign(k, k + T);
   P->block = block;
+  P->codec = codec;
   P->td.resize(T);
-  int64_t grp = 0, kp = 0, sp = 0, sg = 0, cb = 0, est = 0;
+  int64_t grp = 0, kp = 0, sp = 0, sg = 0, cb = 0, est = 0, qp = 0;
   double max_lambda = 0.0;
   for (int32_t t = 0; t < T; ++t) {
     TensorDesc& d = P->td[t];
@@ -120,6 +127,8 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
     d.k = k[t];
     d.kprefix = kp;
     d.sprefix = sp;
+    d.qprefix = qp;
+    qp += code_bytes(d.k, block, codec);
     d.group_begin = grp;
     d.ngroups = (d.n + kGroup - 1) / kGroup;
     grp += d.ngroups;
@@ -179,16 +188,17 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
   return P;
 }
 
-bool same_plan(const Plan* P, const int64_t* offsets, const int64_t* k, int32_t T, int32_t block) {
-  return P->block == block && (int32_t)P->k.size() == T &&
+bool same_plan(const Plan* P, const int64_t* offsets, const int64_t* k, int32_t T, int32_t block,
+               int32_t codec) {
+  return P->block == block && P->codec == codec && (int32_t)P->k.size() == T &&
          std::memcmp(P->offsets.data(), offsets, sizeof(int64_t) * (T + 1)) == 0 &&
          std::memcmp(P->k.data(), k, sizeof(int64_t) * T) == 0;
 }
 
 gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_t T, int32_t block,
-                   Plan** out) {
+                   int32_t codec, Plan** out) {
   for (size_t i = 0; i < ctx->plans.size(); ++i) {
-    if (same_plan(ctx->plans[i], offsets, k, T, block)) {
+    if (same_plan(ctx->plans[i], offsets, k, T, block, codec)) {
       Plan* P = ctx->plans[i];
       if (i != 0) {  // keep the most recent first
         ctx->plans.erase(ctx->plans.begin() + i);
@@ -198,7 +208,7 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
       return GC_OK;
     }
   }
-  Plan* P = build_plan(offsets, k, T, block);
+  Plan* P = build_plan(offsets, k, T, block, codec);
   if (!P) return GC_ERR_WORKSPACE;
   gc_status st = ensure(P->td_dev, sizeof(TensorDesc) * T);
   if (st == GC_OK && hipMemcpy(P->td_dev.p, P->td.data(), sizeof(TensorDesc) * T, hipMemcpyHostToDevice) != hipSuccess)
@@ -311,6 +321,9 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   if (out->n != n || out->k != ktotal || out->block != block) return GC_ERR_INVALID_ARG;
   if (out->index_bits != 32 && out->index_bits != 64) return GC_ERR_INVALID_ARG;
   if (out->index_bits == 32 && n > (int64_t(1) << 32)) return GC_ERR_INVALID_ARG;
+  if (out->codec != GC_CODEC_INT8 && out->codec != GC_CODEC_SIGN1) return GC_ERR_INVALID_ARG;
+  if (out->reserved_ != 0) return GC_ERR_INVALID_ARG;
+  if (out->codec == GC_CODEC_SIGN1 && block > 8192) return GC_ERR_UNSUPPORTED;
   const size_t gsz = dtype == GC_F32 ? 4 : 2;
   if ((reinterpret_cast<uintptr_t>(grad) % gsz) || (reinterpret_cast<uintptr_t>(residual) % 4) ||
       (reinterpret_cast<uintptr_t>(out->scales) % 4) ||
@@ -319,7 +332,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
 
   GC_HIP(hipSetDevice(ctx->device));
   Plan* P = nullptr;
-  gc_status st = get_plan(ctx, offsets, k, T, block, &P);
+  gc_status st = get_plan(ctx, offsets, k, T, block, out->codec, &P);
   if (st != GC_OK) return st;
   if (P->ngroups >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
 
@@ -359,7 +372,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   ws.max_chunks = P->ngroups;
   ws.est_chunk_wgs = (int32_t)std::min<int64_t>(P->est_chunks, 1 << 20);
   ws.main_lds_pad = (int32_t)ctx->opt_main_lds_pad;
-  OutBuf ob{out->indices, out->q, out->scales, out->index_bits, block};
+  OutBuf ob{out->indices, out->q, out->scales, out->index_bits, block, out->codec};
   hipStream_t s = (hipStream_t)hip_stream;
   const bool any_sampled = P->n_sampled > 0;
 
@@ -388,9 +401,10 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   return launch_status();
 }
 
-gc_status get_dec_plan(gc_ctx* ctx, const int64_t* k, int32_t T, int32_t block, DecPlan** out) {
+gc_status get_dec_plan(gc_ctx* ctx, const int64_t* k, int32_t T, int32_t block, int32_t codec,
+                       DecPlan** out) {
   for (DecPlan* D : ctx->dplans)
-    if (D->block == block && (int32_t)D->k.size() == T && std::memcmp(D->k.data(), k, sizeof(int64_t) * T) == 0) {
+    if (D->block == block && D->codec == codec && (int32_t)D->k.size() == T && std::memcmp(D->k.data(), k, sizeof(int64_t) * T) == 0) {
       *out = D;
       return GC_OK;
     }
@@ -398,20 +412,26 @@ gc_status get_dec_plan(gc_ctx* ctx, const int64_t* k, int32_t T, int32_t block, 
   if (!D) return GC_ERR_WORKSPACE;
   D->k.assign(k, k + T);
   D->block = block;
-  std::vector<long long> kp(T + 1), sp(T + 1);
-  kp[0] = sp[0] = 0;
+  D->codec = codec;
+  std::vector<long long> kp(T + 1), sp(T + 1), qp(T + 1);
+  kp[0] = sp[0] = qp[0] = 0;
   for (int32_t t = 0; t < T; ++t) {
     kp[t + 1] = kp[t] + k[t];
     sp[t + 1] = sp[t] + (k[t] + block - 1) / block;
+    qp[t + 1] = qp[t] + code_bytes(k[t], block, codec);
   }
   gc_status st = ensure(D->kprefix, sizeof(long long) * (T + 1));
   if (st == GC_OK) st = ensure(D->sprefix, sizeof(long long) * (T + 1));
+  if (st == GC_OK) st = ensure(D->qprefix, sizeof(long long) * (T + 1));
+  if (st == GC_OK && hipMemcpy(D->qprefix.p, qp.data(), sizeof(long long) * (T + 1), hipMemcpyHostToDevice) != hipSuccess)
+    st = GC_ERR_DEVICE;
   if (st == GC_OK && (hipMemcpy(D->kprefix.p, kp.data(), sizeof(long long) * (T + 1), hipMemcpyHostToDevice) != hipSuccess ||
                       hipMemcpy(D->sprefix.p, sp.data(), sizeof(long long) * (T + 1), hipMemcpyHostToDevice) != hipSuccess))
     st = GC_ERR_DEVICE;
   if (st != GC_OK) {
     release(D->kprefix);
     release(D->sprefix);
+    release(D->qprefix);
     delete D;
     return st;
   }
@@ -422,6 +442,7 @@ gc_status get_dec_plan(gc_ctx* ctx, const int64_t* k, int32_t T, int32_t block, 
     (void)hipDeviceSynchronize();
     release(old->kprefix);
     release(old->sprefix);
+    release(old->qprefix);
     delete old;
   }
   *out = D;
@@ -435,8 +456,9 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   if (apply && !(c_apply >= 0.0f && c_apply <= 3.0e38f)) return GC_ERR_INVALID_ARG;
   if (W > kMaxWorkers) return GC_ERR_UNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(out) % 4) return GC_ERR_INVALID_ARG;
-  const int32_t block = bufs[0].block, ib = bufs[0].index_bits;
+  const int32_t block = bufs[0].block, ib = bufs[0].index_bits, codec = bufs[0].codec;
   if (block < 1 || (ib != 32 && ib != 64)) return GC_ERR_INVALID_ARG;
+  if (codec != GC_CODEC_INT8 && codec != GC_CODEC_SIGN1) return GC_ERR_INVALID_ARG;
   if (ib == 32 && n > (int64_t(1) << 32)) return GC_ERR_INVALID_ARG;
   int64_t ksum = 0;
   if (T > 0) {
@@ -450,7 +472,8 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   std::memset(&a, 0, sizeof(a));
   for (int32_t w = 0; w < W; ++w) {
     const gc_buf& b = bufs[w];
-    if (b.n != n || b.block != block || b.index_bits != ib || b.k < 0) return GC_ERR_INVALID_ARG;
+    if (b.n != n || b.block != block || b.index_bits != ib || b.codec != codec || b.k < 0 || b.reserved_ != 0)
+      return GC_ERR_INVALID_ARG;
     if (b.k >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
     if (b.k > 0 && (!b.indices || !b.q || !b.scales)) return GC_ERR_INVALID_ARG;
     if (T > 0 && b.k != ksum) return GC_ERR_INVALID_ARG;
@@ -471,7 +494,7 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   if (st != GC_OK) return st;
   DecPlan* D = nullptr;
   if (T > 1) {
-    st = get_dec_plan(ctx, k, T, block, &D);
+    st = get_dec_plan(ctx, k, T, block, codec, &D);
     if (st != GC_OK) return st;
   }
   hipStream_t s = (hipStream_t)hip_stream;
@@ -480,7 +503,7 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     Scope sc(ctx, kKDecTiles, s);
     launch_dec_tiles(a, W, ib, block, n, ntiles, (const uint32_t*)ctx->bounds.p,
                      D ? (const long long*)D->kprefix.p : nullptr, D ? (const long long*)D->sprefix.p : nullptr,
-                     D ? T : 1, out, staleness ? 1 : 0, apply ? 1 : 0, c_apply, s);
+                     D ? (const long long*)D->qprefix.p : nullptr, D ? T : 1, codec, out, staleness ? 1 : 0, apply ? 1 : 0, c_apply, s);
   }
   return launch_status();
 }
@@ -524,7 +547,7 @@ gc_status gc_destroy(gc_ctx* c) {
   (void)hipSetDevice(c->device);
   (void)hipDeviceSynchronize();
   for (Plan* P : c->plans) { release(P->td_dev); release(P->recs_dev); delete P; }
-  for (DecPlan* D : c->dplans) { release(D->kprefix); release(D->sprefix); delete D; }
+  for (DecPlan* D : c->dplans) { release(D->kprefix); release(D->sprefix); release(D->qprefix); delete D; }
   DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
                    &c->slots, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
                    &c->ch_part_gt, &c->ch_part_eq, &c->ch_goff, &c->ch_eoff, &c->tb_g, &c->tb_e,
@@ -544,6 +567,11 @@ int64_t gc_k_from_density(int64_t n, double density) {
   if (!(kd >= 1.0)) return 1;
   if (kd >= (double)n) return n;
   return (int64_t)kd;
+}
+
+int64_t gc_num_code_bytes(int64_t k, int32_t block, gc_codec codec) {
+  if (codec != GC_CODEC_INT8 && codec != GC_CODEC_SIGN1) return 0;
+  return code_bytes(k, block, (int32_t)codec);
 }
 
 int64_t gc_num_scales(int64_t k, int32_t block) {

@@ -770,6 +770,68 @@ __global__ __launch_bounds__(256) void k_quant(Workspace ws, float* __restrict__
   if (finite) e[(int64_t)idx[j]] = __fsub_rn(v, __fmul_rn((float)code, s));
 }
 
+// ---------------------------------------------------------------- k_quant_sign
+// The 1-bit code of Eq. 10: one workgroup per block of kept entries. The block's l1 norm is
+// accumulated in fp64 over the balanced binary tree a[i] += a[i + stride], stride = P/2 .. 1, on the
+// entries padded with zeros to a power of two P (levels with stride >= 256 stay inside a thread's
+// registers, the rest goes through LDS; padding with +0 is exact, so P = max(256, pow2(len)) gives
+// the same sum as pow2(len)). s = (float)(sum / len); bits are packed through wavefront ballots.
+constexpr int kSignMaxPerThread = 32;  // block <= 8192
+template <typename I>
+__global__ __launch_bounds__(256) void k_quant_sign(Workspace ws, float* __restrict__ e,
+                                                    const I* __restrict__ idx, uint8_t* __restrict__ q,
+                                                    float* __restrict__ scales, int32_t block) {
+  __shared__ double sh[256];
+  const int64_t gb = blockIdx.x;
+  const int t = find_last_le(ws.T, gb, 0, [&](int i) { return (long long)ws.td[i].sprefix; });
+  const TensorDesc d = ws.td[t];
+  const int64_t lb = gb - d.sprefix;
+  const int64_t j0 = d.kprefix + lb * block;
+  const int len = (int)min((int64_t)block, d.k - lb * block);
+  int per = 1;  // entries per thread: P / 256
+  while (per * 256 < len) per <<= 1;
+  double r[kSignMaxPerThread];
+#pragma unroll
+  for (int m = 0; m < kSignMaxPerThread; ++m) {
+    const int i = threadIdx.x + m * 256;
+    r[m] = (m < per && i < len) ? fabs((double)ws.kept_val[j0 + i]) : 0.0;
+  }
+#pragma unroll
+  for (int half = kSignMaxPerThread / 2; half >= 1; half >>= 1) {  // stride = half * 256
+    if (half < per) {
+#pragma unroll
+      for (int m = 0; m < kSignMaxPerThread / 2; ++m)
+        if (m < half) r[m] = r[m] + r[m + half];
+    }
+  }
+  sh[threadIdx.x] = r[0];
+  __syncthreads();
+  for (int stride = 128; stride >= 1; stride >>= 1) {
+    if ((int)threadIdx.x < stride) sh[threadIdx.x] = sh[threadIdx.x] + sh[threadIdx.x + stride];
+    __syncthreads();
+  }
+  const uint32_t akey = ws.blk_amax[gb];
+  const bool finite = akey < 0x7F800000u;
+  float s = (float)(sh[0] / (double)len);
+  if (!finite || !(s >= 1.17549435e-38f)) s = 0.0f;
+  if (threadIdx.x == 0) {
+    scales[gb] = s;
+    if (!finite) ws.flags[0] = 1u;
+  }
+  // this block's bytes: blocks before it in the tensor are full
+  uint8_t* qb = q + d.qprefix + lb * ((block + 7) / 8);
+  const int lane = threadIdx.x & 63;
+  for (int i0 = (threadIdx.x >> 6) * 64; i0 < len; i0 += 256) {  // i0 is wave-uniform
+    const int i = i0 + lane;
+    const bool valid = i < len;
+    const float v = valid ? ws.kept_val[j0 + i] : 0.0f;
+    const bool plus = valid && v >= 0.0f;
+    const uint64_t m = __ballot(plus);
+    if (lane < 8 && i0 + lane * 8 < len) qb[i0 / 8 + lane] = (uint8_t)(finite ? (m >> (8 * lane)) & 0xFFull : 0ull);
+    if (valid && finite) e[(int64_t)idx[j0 + i]] = __fsub_rn(v, plus ? s : -s);
+  }
+}
+
 inline int clamp_grid(int64_t want, int64_t cap) { return (int)(want < 1 ? 1 : (want > cap ? cap : want)); }
 
 }  // namespace
@@ -852,6 +914,16 @@ void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStre
 }
 
 void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktotal, hipStream_t s) {
+  if (out.codec == 1) {  // sign code: one workgroup per block
+    const dim3 gridb((unsigned)ws.nblocks);
+    if (out.index_bits == 32)
+      hipLaunchKernelGGL(k_quant_sign<uint32_t>, gridb, dim3(256), 0, s, ws, e, (const uint32_t*)out.indices,
+                         (uint8_t*)out.q, out.scales, out.block);
+    else
+      hipLaunchKernelGGL(k_quant_sign<unsigned long long>, gridb, dim3(256), 0, s, ws, e,
+                         (const unsigned long long*)out.indices, (uint8_t*)out.q, out.scales, out.block);
+    return;
+  }
   const dim3 grid((unsigned)((ktotal + 255) / 256));
   if (out.index_bits == 32)
     hipLaunchKernelGGL(k_quant<uint32_t>, grid, dim3(256), 0, s, ws, e, (const uint32_t*)out.indices, out.q,

@@ -92,7 +92,8 @@ template <typename I, int MODE>
 __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(DecArgs a, int W, int32_t block, int64_t n,
                                                    int64_t ntiles, const uint32_t* __restrict__ bounds,
                                                    const long long* __restrict__ kprefix,
-                                                   const long long* __restrict__ sprefix, int T,
+                                                   const long long* __restrict__ sprefix,
+                                                   const long long* __restrict__ qprefix, int T, int codec,
                                                    float* __restrict__ out, int weighted, float c_apply) {
   __shared__ float tile_mem[kDecWaves][kDecTile];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -129,17 +130,26 @@ __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(DecArgs a, int W, 
       if (p.active) {
         const I* idx = static_cast<const I*>(a.indices[p.w]);
         pos = (uint32_t)((unsigned long long)idx[p.j] - (unsigned long long)base);
-        const int code = a.q[p.w][p.j];
-        long long sj = (long long)p.j / block;
-        if (T > 1) {  // scales restart at every tensor: find the tensor that owns pair j
+        long long rel = (long long)p.j, sbase = 0, qbase = 0;  // pair inside its tensor; tensor's scales, bytes
+        if (T > 1) {  // blocks restart at every tensor: find the tensor that owns pair j
           int tl = 0, th = T - 1;
           while (tl < th) {
             const int mid = (tl + th + 1) >> 1;
             if (kprefix[mid] <= (long long)p.j) tl = mid; else th = mid - 1;
           }
-          sj = sprefix[tl] + ((long long)p.j - kprefix[tl]) / block;
+          rel -= kprefix[tl];
+          sbase = sprefix[tl];
+          qbase = qprefix[tl];
         }
-        val = __fmul_rn((float)code, a.scales[p.w][sj]);
+        const long long blk = rel / block;
+        const float s = a.scales[p.w][sbase + blk];
+        if (codec == 0) {
+          val = __fmul_rn((float)a.q[p.w][T > 1 ? qbase + rel : rel], s);
+        } else {  // sign code (Eq. 10): bit r of the block's bytes, +s or -s
+          const int r = (int)(rel - blk * block);
+          const uint32_t byte = (uint8_t)a.q[p.w][qbase + blk * ((block + 7) / 8) + (r >> 3)];
+          val = ((byte >> (r & 7)) & 1u) ? s : -s;
+        }
         if (weighted) val = __fdiv_rn(val, a.denom[p.w]);  // Eq. 12: a stale worker counts for less
       }
       // add worker by worker so that equal indices of different workers keep ascending order
@@ -198,13 +208,14 @@ void launch_dec_bounds(const DecArgs& a, int W, int index_bits, int64_t ntiles, 
 }
 
 void launch_dec_tiles(const DecArgs& a, int W, int index_bits, int32_t block, int64_t n, int64_t ntiles,
-                      const uint32_t* bounds, const long long* kprefix, const long long* sprefix, int T,
-                      float* out, int weighted, int apply, float c_apply, hipStream_t s) {
+                      const uint32_t* bounds, const long long* kprefix, const long long* sprefix,
+                      const long long* qprefix, int T, int codec, float* out, int weighted, int apply,
+                      float c_apply, hipStream_t s) {
   const int64_t want = (ntiles + kDecWaves - 1) / kDecWaves;
   const dim3 grid((unsigned)(want < kDecGrid ? want : kDecGrid)), blk(kDecWaves * 64);
 #define GC_LAUNCH_TILES(ITYPE, MODE)                                                                        \
   hipLaunchKernelGGL((k_dec_tiles<ITYPE, MODE>), grid, blk, 0, s, a, W, block, n, ntiles, bounds, kprefix, \
-                     sprefix, T, out, weighted, c_apply)
+                     sprefix, qprefix, T, codec, out, weighted, c_apply)
   if (index_bits == 32) {
     if (apply) GC_LAUNCH_TILES(uint32_t, 1); else GC_LAUNCH_TILES(uint32_t, 0);
   } else {

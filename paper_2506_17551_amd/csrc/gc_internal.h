@@ -39,6 +39,7 @@ struct TensorDesc {
   int64_t k;            // entries to keep
   int64_t kprefix;      // first output pair of this tensor
   int64_t sprefix;      // first output scale of this tensor
+  int64_t qprefix;      // first code byte of this tensor (sign code; equals kprefix for int8)
   int64_t group_begin;  // first group slot of this tensor
   int64_t ngroups;      // ceil(n / kGroup)
   int64_t cand_begin;   // first entry of this tensor's region in the dense candidate arrays
@@ -118,6 +119,7 @@ struct OutBuf {
   float* scales;
   int32_t index_bits;
   int32_t block;
+  int32_t codec;
 };
 
 // kernel ids for profiling
@@ -159,7 +161,7 @@ void launch_dec_bounds(const DecArgs& a, int W, int index_bits, int64_t ntiles, 
                        hipStream_t s);
 void launch_dec_tiles(const DecArgs& a, int W, int index_bits, int32_t block, int64_t n,
                       int64_t ntiles, const uint32_t* bounds, const long long* kprefix,
-                      const long long* sprefix, int T, float* out, int weighted, int apply, float c_apply,
-                      hipStream_t s);
+                      const long long* sprefix, const long long* qprefix, int T, int codec, float* out,
+                      int weighted, int apply, float c_apply, hipStream_t s);
 
 }  // namespace gc

@@ -35,12 +35,12 @@ def _idx64(buf):
     return (i & 0xFFFFFFFF) if buf.index_bits == 32 else i
 
 
-def check_one_step(gc, oracle, ctx, g, e0, k, block, index_bits, tag):
+def check_one_step(gc, oracle, ctx, g, e0, k, block, index_bits, tag, codec=0):
     """compress(g, e0.clone()) at full size; returns (buf, new residual, kept values)."""
     n = g.numel()
-    print(f"[case] {tag}: n={n} k={k} block={block} bits={index_bits} dtype={g.dtype}", flush=True)
+    print(f"[case] {tag}: n={n} k={k} block={block} bits={index_bits} dtype={g.dtype} codec={codec}", flush=True)
     e = e0.clone()
-    buf = gc.compress(ctx, g, e, k, block, index_bits=index_bits)
+    buf = gc.compress(ctx, g, e, k, block, index_bits=index_bits, codec=codec)
     gc.sync_status(ctx)
     st = gc.last_stats(ctx)
     assert st["tensors_fallback"] == 0, st          # the timed configuration is the sampled route
@@ -73,7 +73,7 @@ def check_one_step(gc, oracle, ctx, g, e0, k, block, index_bits, tag):
     # the oracle on the kept values, as a tensor of their own with every entry kept
     v_np = v.cpu().numpy()
     e_small = np.zeros(k, dtype=np.float32)
-    rc, oi, oq, osc = oracle.compress(v_np, e_small, k, block)
+    rc, oi, oq, osc = oracle.compress(v_np, e_small, k, block, codec=codec)
     assert rc == 0 and np.array_equal(oi, np.arange(k, dtype=np.uint32))
     assert np.array_equal(buf.q.cpu().numpy(), oq), "codes differ from the oracle's"
     assert np.array_equal(buf.scales.cpu().numpy().view(np.uint32), osc.view(np.uint32)), "scales differ"
@@ -81,7 +81,7 @@ def check_one_step(gc, oracle, ctx, g, e0, k, block, index_bits, tag):
     return buf, e, (oq, osc)
 
 
-def check_aggregate(gc, oracle, ctx, bufs, n, block):
+def check_aggregate(gc, oracle, ctx, bufs, n, block, codec=0):
     """decompress_sum at full size against the oracle on the union of indices."""
     out = gc.decompress_sum(ctx, bufs, n)
     torch.cuda.synchronize()
@@ -91,7 +91,7 @@ def check_aggregate(gc, oracle, ctx, bufs, n, block):
     for b in bufs:
         pos = torch.searchsorted(union, _idx64(b)).cpu().numpy().astype(np.uint32)
         refs.append((pos, b.q.cpu().numpy(), b.scales.cpu().numpy()))
-    rc, want = oracle.decompress_sum(refs, U, block)
+    rc, want = oracle.decompress_sum(refs, U, block, codec=codec)
     assert rc == 0
     assert np.array_equal(out[union].cpu().numpy().view(np.uint32), want.view(np.uint32)), "aggregate differs"
     nz = 0
@@ -126,7 +126,12 @@ def test_config5_7b_fp32(gc, oracle):
     g = wl.grad(0, 0, DEV)
     e0 = wl.residual0(0, DEV)
     buf, e, _ = check_one_step(gc, oracle, ctx, g, e0, k, wl.block, 64, "config5")
-    del e0
+    del e
+    # the same step with the 1-bit sign code (Eq. 10): same kept set, other codes and residuals
+    buf1, e, _ = check_one_step(gc, oracle, ctx, g, e0, k, wl.block, 64, "config5 sign code", codec=1)
+    assert torch.equal(buf1.indices, buf.indices)
+    out1, _ = check_aggregate(gc, oracle, ctx, [buf1, buf1, buf1], wl.n, wl.block, codec=1)
+    del out1, e0
     # three "workers": the real one, itself again (every index collides), and a shifted copy
     bufs = [buf, shifted(gc, buf, 0, wl.n), shifted(gc, buf, 1, wl.n), buf]
     out, multi = check_aggregate(gc, oracle, ctx, bufs, wl.n, wl.block)

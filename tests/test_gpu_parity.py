@@ -502,3 +502,97 @@ def test_apply_multi_tensor(gc, ctx, oracle):
     want = theta0.numpy().copy()
     oracle.apply(want, S, 0.25)
     assert np.array_equal(bits(theta.cpu().numpy()), bits(want))
+
+
+# ---------------------------------------------------------------------------------- Eq. 10: sign code
+def check_compress_sign(gc, ctx, oracle, g_cpu, e_cpu, k, block, index_bits=32, tag=""):
+    n = g_cpu.numel()
+    print(f"[case] sign {tag} n={n} k={k} block={block} bits={index_bits} dtype={g_cpu.dtype}", flush=True)
+    e_ref = e_cpu.numpy().copy()
+    rc, idx, q, s = oracle.compress(_np_grad(g_cpu), e_ref, k, block, index_bits=index_bits, codec=oracle.SIGN1)
+    assert rc == 0
+    e = e_cpu.to(DEV).clone()
+    buf = gc.compress(ctx, g_cpu.to(DEV), e, k, block, index_bits=index_bits, codec=gc.GC_CODEC_SIGN1)
+    gc.sync_status(ctx)
+    assert buf.q.numel() == q.size == gc.num_code_bytes(k, block, gc.GC_CODEC_SIGN1)
+    assert np.array_equal(buf.indices_numpy(), idx), f"{tag}: index sets differ"
+    assert np.array_equal(buf.q.cpu().numpy(), q), f"{tag}: sign bytes differ"
+    assert np.array_equal(bits(buf.scales.cpu().numpy()), bits(s)), f"{tag}: scales differ"
+    assert np.array_equal(bits(e.cpu().numpy()), bits(e_ref)), f"{tag}: residuals differ"
+    return buf, (idx, q, s)
+
+
+@pytest.mark.parametrize("n,k,block", [(1, 1, 1), (65, 65, 8), (5000, 777, 100), (300_000, 3000, 256),
+                                       (1_000_003, 10_001, 2048), (1_000_003, 10_001, 8192),
+                                       (700_000, 70_000, 1), (400_000, 399, 7), (2_500_000, 2500, 1000)])
+def test_sign_code_parity(gc, ctx, oracle, n, k, block):
+    g = inputs.normal(n, 1.0, n + block)
+    e = inputs.normal(n, 0.3, n + block + 1)
+    buf, ref = check_compress_sign(gc, ctx, oracle, g, e, k, block, tag="gauss")
+    out = gc.decompress_sum(ctx, [buf, buf, buf], n)
+    torch.cuda.synchronize()
+    rc, want = oracle.decompress_sum([ref] * 3, n, block, codec=oracle.SIGN1)
+    assert rc == 0 and np.array_equal(bits(out.cpu().numpy()), bits(want))
+
+
+def test_sign_code_distributions_and_widths(gc, ctx, oracle):
+    n, k = 500_000, 5000
+    for name, (g, e) in {"t3": (inputs.student_t3(n, 1e-3, 1), inputs.student_t3(n, 1e-3, 2)),
+                         "mix": (inputs.outlier_mixture(n, 1e-3, 0.01, 100.0, 3), inputs.outlier_mixture(n, 1e-3, 0.01, 100.0, 4)),
+                         "huge": (inputs.normal(n, 1e30, 7), inputs.normal(n, 1e30, 8)),
+                         "subnormal": (inputs.normal(n, 3e-39, 9), inputs.normal(n, 1e-39, 10)),
+                         "zeros": (torch.zeros(n), torch.zeros(n)),
+                         "ties": (inputs.tie_alphabet(n, (0.0, -0.0, 1.0, -1.0, 2.0), 5), torch.zeros(n))}.items():
+        check_compress_sign(gc, ctx, oracle, g, e, k, 512, tag=name)
+    gb = inputs.student_t3(n, 1e-3, 11).to(torch.bfloat16)
+    check_compress_sign(gc, ctx, oracle, gb, inputs.normal(n, 1e-4, 12), k, 1024, tag="bf16")
+    check_compress_sign(gc, ctx, oracle, inputs.normal(n, 1.0, 13), torch.zeros(n), k, 64, index_bits=64, tag="u64")
+    with pytest.raises(gc.GradCompError) as ei:
+        gc.compress(ctx, inputs.normal(n, 1.0, 1).to(DEV), torch.zeros(n, device=DEV), k, 8200,
+                    codec=gc.GC_CODEC_SIGN1)
+    assert ei.value.status == 2
+    g = inputs.normal(n, 1.0, 2)
+    g[77] = float("nan")
+    gc.compress(ctx, g.to(DEV), torch.zeros(n, device=DEV), k, 64, codec=gc.GC_CODEC_SIGN1)
+    assert gc.sync_status(ctx, raise_on_error=False) == 4
+
+
+def test_sign_code_multi_tensor_and_aggregation_variants(gc, ctx, oracle):
+    sizes = [768, 5, 300001, 2304, 262144, 1, 4097]
+    off = inputs.offsets_of(sizes)
+    n = int(off[-1])
+    ks = np.array([gc.k_from_density(int(s), 0.02) for s in sizes], dtype=np.int64)
+    block, W = 12, 4
+    bufs, refs = [], []
+    for w in range(W):
+        g = inputs.normal(n, 0.02, 800 + w)
+        e = inputs.normal(n, 0.01, 900 + w)
+        e_ref = e.numpy().copy()
+        rc, idx, q, s = oracle.compress_multi(g.numpy(), e_ref, off, ks, block, codec=oracle.SIGN1)
+        assert rc == 0
+        ed = e.to(DEV)
+        buf = gc.compress_multi(ctx, g.to(DEV), ed, off, ks, block, codec=gc.GC_CODEC_SIGN1)
+        gc.sync_status(ctx)
+        assert np.array_equal(buf.indices_numpy(), idx) and np.array_equal(buf.q.cpu().numpy(), q)
+        assert np.array_equal(bits(buf.scales.cpu().numpy()), bits(s))
+        assert np.array_equal(bits(ed.cpu().numpy()), bits(e_ref))
+        bufs.append(buf)
+        refs.append((idx, q, s))
+    out = gc.decompress_sum_multi(ctx, bufs, ks, n)
+    torch.cuda.synchronize()
+    rc, want = oracle.decompress_sum(refs, n, block, ktensor=ks, codec=oracle.SIGN1)
+    assert np.array_equal(bits(out.cpu().numpy()), bits(want))
+    taus = [0, 3, 1, 6]
+    outw = gc.decompress_sum_weighted(ctx, bufs, taus, n, ks=ks)
+    theta0 = inputs.normal(n, 1.0, 4)
+    theta = theta0.to(DEV).clone()
+    gc.decompress_apply(ctx, bufs, theta, 0.125, staleness=taus, ks=ks)
+    torch.cuda.synchronize()
+    rc, S = oracle.decompress_sum(refs, n, block, ktensor=ks, staleness=taus, codec=oracle.SIGN1)
+    assert np.array_equal(bits(outw.cpu().numpy()), bits(S))
+    tw = theta0.numpy().copy()
+    oracle.apply(tw, S, 0.125)
+    assert np.array_equal(bits(theta.cpu().numpy()), bits(tw))
+    mixed = [bufs[0], gc.CompressedBuf(bufs[1].indices, bufs[1].q, bufs[1].scales, n, bufs[1].k, block, 32, 0)]
+    with pytest.raises(gc.GradCompError):
+        gc.decompress_sum_multi(ctx, mixed, ks, n)

@@ -468,3 +468,94 @@ def test_apply_properties(oracle):
     oracle.apply(th, agg, eta / P)
     assert np.array_equal(th, (1.0 - eta * np.mean(np.stack(gs), axis=0)).astype(np.float32))
     assert oracle.apply(th, agg, -1.0) == oracle.ERR_INVALID_ARG
+
+
+# ----------------------------------------------------------------- Eq. 10: the 1-bit sign code
+def unpack_signs(qbytes, k, block):
+    """+1/-1 per kept entry from the packed bytes (every block starts a new byte, LSB first)."""
+    out = np.empty(k, np.float32)
+    per = (block + 7) // 8
+    b = np.frombuffer(qbytes.tobytes(), dtype=np.uint8)
+    for j in range(k):
+        blk, r = divmod(j, block)
+        out[j] = 1.0 if (b[blk * per + r // 8] >> (r % 8)) & 1 else -1.0
+    return out
+
+
+def test_golden_sign_block(oracle):
+    G = read_golden("sign_block.txt")
+    g = f32(G["g"])
+    e = np.zeros(g.size, np.float32)
+    rc, idx, q, s = oracle.compress(g, e, int(G["k"][0]), int(G["block"][0]), codec=oracle.SIGN1)
+    assert rc == 0 and idx.tolist() == [int(x) for x in G["idx"]]
+    assert q.view(np.uint8).tolist() == [int(G["byte"][0])]
+    want_s = np.float32(float(G["scale_num"][0]) / float(G["scale_den"][0]))
+    assert s.tolist() == [want_s]
+    signs = np.array([1, -1, 1, -1, 1, 1], np.float32)
+    assert np.array_equal(e, (g - signs * want_s).astype(np.float32))
+
+
+def test_sign_code_properties(oracle):
+    import math
+    n, k = 6000, 1000
+    for name, g, r0 in _dists(n, 31):
+        for block in (1, 8, 64, 100, 1000):
+            e = r0.copy()
+            acc = (g + r0).astype(np.float32)
+            rc, idx, q, s = oracle.compress(g, e, k, block, codec=oracle.SIGN1)
+            assert rc == 0 and q.size == oracle.num_code_bytes(k, block, oracle.SIGN1)
+            # the kept set does not depend on the value code
+            rc2, idx2, _, _ = oracle.compress(g, r0.copy(), k, block)
+            assert np.array_equal(idx, idx2)
+            v = acc[idx]
+            sg = unpack_signs(q, k, block)
+            assert np.array_equal(sg > 0, v >= 0), name                                # Eq. 10
+            for b in range(s.size):                                                     # scale = ||v||_1 / len
+                blkv = v[b * block:(b + 1) * block]
+                exact = math.fsum(abs(float(x)) for x in blkv) / blkv.size
+                want = np.float32(exact)
+                if not want >= np.finfo(np.float32).tiny:
+                    want = np.float32(0)
+                assert s[b] == want, (name, block, b)
+            d = sg * np.repeat(s, block)[:k]
+            assert np.array_equal(e[idx], (v - d).astype(np.float32)), name           # Eq. 11, one rounding
+            mask = np.ones(n, bool)
+            mask[idx] = False
+            assert np.array_equal(e[mask].view(np.uint32), acc[mask].view(np.uint32))
+            if block == 1:                                                              # lossless: s = |v|
+                nz = s > 0
+                assert np.array_equal(d[nz], v[nz]) and not e[idx][nz].any()
+    # scaling by 2^m scales s and leaves the bits alone; the aggregate decodes to +-s
+    g = inputs.normal(512, 1.0, 5).numpy()
+    rc, idx, q, s = oracle.compress(g, np.zeros(512, np.float32), 512, 64, codec=oracle.SIGN1)
+    rc, idx2, q2, s2 = oracle.compress(np.ldexp(g, 7).astype(np.float32), np.zeros(512, np.float32), 512, 64,
+                                       codec=oracle.SIGN1)
+    assert np.array_equal(q, q2) and np.array_equal(np.ldexp(s, 7).astype(np.float32), s2)
+    rc, out = oracle.decompress_sum([(idx, q, s)], 512, 64, codec=oracle.SIGN1)
+    assert np.array_equal(out, (unpack_signs(q, 512, 64) * np.repeat(s, 64)).astype(np.float32))
+    rc, out3 = oracle.decompress_sum([(idx, q, s)] * 2, 512, 64, codec=oracle.SIGN1, staleness=[0, 1])
+    assert np.array_equal(out3, (out * np.float32(1.5)).astype(np.float32))
+
+
+def test_sign_code_multi_tensor(oracle):
+    sizes = [100, 7, 300, 1]
+    off = inputs.offsets_of(sizes)
+    n = int(off[-1])
+    g = inputs.normal(n, 1.0, 3).numpy()
+    ks = np.array([10, 7, 33, 1], np.int64)
+    e = np.zeros(n, np.float32)
+    rc, idx, q, s = oracle.compress_multi(g, e, off, ks, 12, codec=oracle.SIGN1)
+    assert rc == 0
+    dense = np.zeros(n, np.float32)
+    kp = qp = sp = 0
+    for t, sz in enumerate(sizes):
+        a, b = int(off[t]), int(off[t + 1])
+        et = np.zeros(sz, np.float32)
+        rc, it, qt, st = oracle.compress(g[a:b].copy(), et, int(ks[t]), 12, codec=oracle.SIGN1)
+        assert np.array_equal(idx[kp:kp + ks[t]], it + a) and np.array_equal(q[qp:qp + qt.size], qt)
+        assert np.array_equal(s[sp:sp + st.size], st) and np.array_equal(e[a:b], et)
+        dense[it + a] = unpack_signs(qt, int(ks[t]), 12) * np.repeat(st, 12)[:ks[t]]
+        kp += int(ks[t]); qp += qt.size; sp += st.size
+    assert qp == q.size
+    rc, out = oracle.decompress_sum([(idx, q, s)], n, 12, ktensor=ks, codec=oracle.SIGN1)
+    assert rc == 0 and np.array_equal(out.view(np.uint32), dense.view(np.uint32))
