@@ -387,7 +387,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
     { Scope sc(ctx, kKGroupScan, s); launch_group_scan(ws, s); }
   }
   { Scope sc(ctx, kKRoute, s); launch_route(ws, s); }
-  if (any_sampled) { Scope sc(ctx, kKGather, s); launch_gather(ws, s); }
+  if (any_sampled) { Scope sc(ctx, kKGather, s); launch_gather(ws, residual, s); }
   for (int level = 0; level < kSelLevels; ++level) {
     { Scope sc(ctx, kKHist, s); launch_hist(ws, level, residual, s); }
     { Scope sc(ctx, kKSelectScan, s); launch_select_scan(ws, level, s); }

@@ -20,9 +20,10 @@
 //   6. k_quant   per block of kept entries: amax, scale, int8 codes, and the residual at the
 //        kept positions, acc - q*s (Eq. 11 with ghat = q*s).
 //   Small or dense tensors skip 1 and 3: steps 4-5 then read the residual itself (it holds
-//   acc after step 2). A sampled tensor whose candidates turn out too few, too many, or too
-//   clustered for their slots takes that same dense route, decided on the device; the result
-//   never depends on the sample, only the time does.
+//   acc after step 2). A sampled tensor whose candidates turn out too few or too many takes
+//   that same dense route, decided on the device; candidates clustered beyond a group's slots
+//   are re-read from the residual by the gather. The result never depends on the sample, only
+//   the time does.
 #include <algorithm>
 
 #include "gc_internal.h"
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(256) void k_init(Workspace ws) {
   for (int64_t i = tid; i < ws.T; i += stride) {
     TensorState z;
     z.k_rem = 0ull; z.vlen = 0; z.achunk_begin = 0; z.cand_total = 0;
-    z.t_lo = 0u; z.overflow = 0u; z.prefix = 0u; z.use_cand = 0u;
+    z.t_lo = 0u; z.spare_ = 0u; z.prefix = 0u; z.use_cand = 0u;
     ws.ts[i] = z;
   }
   if (tid == 0) ws.totals[0] = 0;
@@ -362,11 +363,10 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
   uint2* __restrict__ dst = ws.slots + grp * (int64_t)ws.slot_stride;
   for (uint32_t j = threadIdx.x; j < nout; j += 256) {
     uint2 rec = make_uint2(0u, 0u);
-    if (j == 0u) rec = make_uint2(kept, tot > cap ? 1u : 0u);
+    if (j == 0u) rec = make_uint2(tot, kept);  // all candidates of the group, and how many fit the slots
     else if (j - 1u < kept) rec = stage[j - 1u];
     dst[j] = rec;
   }
-  if (threadIdx.x == 0 && tot > cap) ws.ts[t].overflow = 1u;
 }
 
 // ---------------------------------------------------------------- block-wise exclusive scan
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
       vlen = d.n;
       if (d.mode == kSampled && any_sampled) {
         M = ws.tg_base[t + 1] - ws.tg_base[t];
-        if (ws.ts[t].overflow == 0u && M >= d.k && M <= d.cand_cap) { use = 1u; vlen = M; }
+        if (M >= d.k && M <= d.cand_cap) { use = 1u; vlen = M; }
       }
       nch = (vlen + kGroup - 1) / kGroup;
     }
@@ -513,27 +513,65 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
 
 // ---------------------------------------------------------------- k_gather
 // One lane per group: copy the group's candidates to their place in the tensor's dense array.
-__global__ __launch_bounds__(256) void k_gather(Workspace ws) {
+// A group with more candidates than slots (winners clustered in one stretch of the tensor) is
+// re-read from the residual, which holds acc by now, by the whole wavefront: 64 coalesced loads
+// and ballot-ordered appends. Only the tensor-wide totals can still send a tensor down the
+// dense route.
+__global__ __launch_bounds__(256) void k_gather(Workspace ws, const float* __restrict__ e) {
+  const int lane = threadIdx.x & 63;
   const int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (grp >= ws.ngroups) return;
-  const int t = find_last_le(ws.T, grp, 0, [&](int i) { return (long long)ws.td[i].group_begin; });
-  if (ws.ts[t].use_cand == 0u) return;
-  const TensorDesc d = ws.td[t];
-  const uint32_t cnt = ws.grp_cnt[grp];
-  if (cnt == 0u) return;
-  const long long dst = d.cand_begin + (ws.grp_off[grp] - ws.tg_base[t]);
-  const long long first = (grp - d.group_begin) * (long long)kGroup;
-  const uint2* __restrict__ rec = ws.slots + grp * (int64_t)ws.slot_stride + 1;
-  for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {  // all loads of a round are issued before the stores
-    uint2 r[8];
+  bool big = false;
+  long long dst = 0, first = 0, gbase = 0;
+  int glen = 0;
+  uint32_t t_lo = 0u;
+  if (grp < ws.ngroups) {
+    const int t = find_last_le(ws.T, grp, 0, [&](int i) { return (long long)ws.td[i].group_begin; });
+    if (ws.ts[t].use_cand != 0u) {
+      const TensorDesc d = ws.td[t];
+      const uint32_t cnt = ws.grp_cnt[grp];
+      dst = d.cand_begin + (ws.grp_off[grp] - ws.tg_base[t]);
+      first = (grp - d.group_begin) * (long long)kGroup;
+      if (cnt > (uint32_t)ws.cap) {
+        big = true;
+        gbase = d.off + first;
+        glen = (int)min((long long)kGroup, d.n - first);
+        t_lo = ws.ts[t].t_lo;
+      } else if (cnt != 0u) {
+        const uint2* __restrict__ rec = ws.slots + grp * (int64_t)ws.slot_stride + 1;
+        for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {  // all loads of a round are issued before the stores
+          uint2 r[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) r[u] = (j0 + u < cnt) ? rec[j0 + u] : make_uint2(0u, 0u);
+          for (int u = 0; u < 8; ++u) r[u] = (j0 + u < cnt) ? rec[j0 + u] : make_uint2(0u, 0u);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (j0 + u < cnt) {
-        ws.cand_val[dst + j0 + u] = __uint_as_float(r[u].x);
-        ws.cand_idx[dst + j0 + u] = first + r[u].y;
+          for (int u = 0; u < 8; ++u) {
+            if (j0 + u < cnt) {
+              ws.cand_val[dst + j0 + u] = __uint_as_float(r[u].x);
+              ws.cand_idx[dst + j0 + u] = first + r[u].y;
+            }
+          }
+        }
       }
+    }
+  }
+  uint64_t todo = __ballot(big);
+  while (todo) {  // wave-uniform loop over this wavefront's overflowed groups
+    const int src = __ffsll((unsigned long long)todo) - 1;
+    todo &= todo - 1;
+    const long long o_dst = __shfl(dst, src), o_first = __shfl(first, src), o_base = __shfl(gbase, src);
+    const int o_len = __shfl(glen, src);
+    const uint32_t o_tlo = __shfl(t_lo, src);
+    long long w = o_dst;
+    for (int j0 = 0; j0 < o_len; j0 += 64) {
+      const int j = j0 + lane;
+      const float v = j < o_len ? e[o_base + j] : 0.0f;
+      const bool c = j < o_len && key_of(v) >= o_tlo;
+      const uint64_t m = __ballot(c);
+      if (c) {
+        const long long pos = w + mbcnt64(m);
+        ws.cand_val[pos] = v;
+        ws.cand_idx[pos] = o_first + j;
+      }
+      w += __popcll(m);
     }
   }
 }
@@ -883,8 +921,8 @@ void launch_route(const Workspace& ws, hipStream_t s) {
   hipLaunchKernelGGL(k_route, dim3(1), dim3(256), 0, s, ws, ws.nsgran > 0 ? 1 : 0);
 }
 
-void launch_gather(const Workspace& ws, hipStream_t s) {
-  hipLaunchKernelGGL(k_gather, dim3((unsigned)((ws.ngroups + 255) / 256)), dim3(256), 0, s, ws);
+void launch_gather(const Workspace& ws, const float* e, hipStream_t s) {
+  hipLaunchKernelGGL(k_gather, dim3((unsigned)((ws.ngroups + 255) / 256)), dim3(256), 0, s, ws, e);
 }
 
 void launch_hist(const Workspace& ws, int level, const float* e, hipStream_t s) {

@@ -59,7 +59,7 @@ struct TensorState {
   long long achunk_begin;    // first active chunk of this tensor in the call-wide chunk numbering
   long long cand_total;      // candidates gathered by the streaming pass
   uint32_t t_lo;             // candidate threshold key (sampled tensors)
-  uint32_t overflow;         // some group ran out of candidate slots
+  uint32_t spare_;
   uint32_t prefix;           // resolved high bits of the threshold key; after the last level: T
   uint32_t use_cand;         // 1: select from the gathered candidates, 0: from the dense residual
 };
@@ -82,7 +82,7 @@ struct Workspace {  // device pointers into the context's scratch
   unsigned long long* grp_part;     // [ceil(groups / kScanBlock)] block sums of grp_cnt
   long long* grp_off;               // [groups] exclusive prefix of grp_cnt (call-wide)
   long long* tg_base;               // [T + 1] grp_off at each tensor's first group; [T] = total
-  uint2* slots;                     // [groups][slot_stride] records: [0] = {count, overflowed},
+  uint2* slots;                     // [groups][slot_stride] records: [0] = {candidates, stored},
                                     // then {acc bits, offset inside the group} per candidate
   // dense candidate arrays (per-tensor regions)
   float* cand_val;
@@ -137,7 +137,7 @@ void launch_group_sums(const Workspace& ws, hipStream_t s);
 void launch_chunk_sums(const Workspace& ws, hipStream_t s);
 void launch_group_scan(const Workspace& ws, hipStream_t s);
 void launch_route(const Workspace& ws, hipStream_t s);
-void launch_gather(const Workspace& ws, hipStream_t s);
+void launch_gather(const Workspace& ws, const float* e, hipStream_t s);
 void launch_hist(const Workspace& ws, int level, const float* e, hipStream_t s);
 void launch_select_scan(const Workspace& ws, int level, hipStream_t s);
 void launch_count(const Workspace& ws, const float* e, hipStream_t s);

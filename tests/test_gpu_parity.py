@@ -124,13 +124,22 @@ def test_massive_ties_force_the_dense_route(gc, ctx, oracle):
     assert np.array_equal(buf.indices_numpy(), np.arange(k, dtype=np.uint32))
 
 
-def test_clustered_winners_force_the_dense_route(gc, ctx, oracle):
-    # all winners sit in one short stretch: the sampled threshold is useless there, the result is not
+def test_clustered_winners(gc, ctx, oracle):
+    # all winners sit in one short stretch (more candidates per group than slots): the gather
+    # re-reads those groups from the residual; whatever route is taken, the result is the oracle's
     n, k = 2_000_000, 2000
     g = inputs.normal(n, 1e-3, 41)
     g[777_000:779_000] += 5.0
     e = torch.zeros(n)
     check_compress(gc, ctx, oracle, g, e, k, 256, tag="clustered")
+    # a layer with 30x the scale of the rest takes every winner: stays on the candidate route
+    n, k = 6_000_000, 6000
+    g = inputs.normal(n, 1e-3, 42)
+    g[1_000_001:1_300_003] *= 30.0
+    check_compress(gc, ctx, oracle, g, inputs.normal(n, 1e-4, 43), k, 512, tag="hot layer", expect_fallback=False)
+    g = inputs.normal(n, 1e-3, 44)
+    g[5_990_000:] *= 1000.0
+    check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 512, tag="hot tail", expect_fallback=False)
 
 
 # ---------------------------------------------------------------------------------- distributions
@@ -596,3 +605,20 @@ def test_sign_code_multi_tensor_and_aggregation_variants(gc, ctx, oracle):
     mixed = [bufs[0], gc.CompressedBuf(bufs[1].indices, bufs[1].q, bufs[1].scales, n, bufs[1].k, block, 32, 0)]
     with pytest.raises(gc.GradCompError):
         gc.decompress_sum_multi(ctx, mixed, ks, n)
+
+
+def test_random_shapes(gc, ctx, oracle):
+    """Many small random cases (sizes, densities, blocks, codes, value scales) in one go."""
+    rng = np.random.Generator(np.random.Philox(key=2025))
+    for case in range(60):
+        n = int(rng.integers(1, 400_000))
+        k = int(min(n, max(1, int(n * 10 ** rng.uniform(-4, 0)))))
+        block = int(rng.choice([1, 2, 7, 32, 100, 256, 1000, 2048]))
+        scale = float(10 ** rng.uniform(-6, 3))
+        g = inputs.normal(n, scale, 5000 + case)
+        e = inputs.normal(n, scale * float(rng.uniform(0, 2)), 6000 + case)
+        if case % 3 == 0:
+            check_compress_sign(gc, ctx, oracle, g, e, k, block, tag=f"random {case}")
+        else:
+            check_compress(gc, ctx, oracle, g, e, k, block, index_bits=64 if case % 5 == 0 else 32,
+                           tag=f"random {case}")
