@@ -24,7 +24,7 @@ struct Plan {  // everything that depends only on (offsets, k, block)
   std::vector<TensorDesc> td;
   int32_t cap = 0;            // candidate slots per group
   int32_t slot_stride = 16;   // records per group incl. the header, multiple of 16
-  int64_t ngroups = 0, nsgran = 0, cand_total_cap = 0, ktotal = 0, stotal = 0;
+  int64_t ngroups = 0, nsgran = 0, cand_total_cap = 0, ktotal = 0, stotal = 0, max_chunks = 0;
   int64_t n_sampled = 0, est_chunks = 0;
   std::vector<GroupRec> recs;  // one per group, only when there are several tensors
   DevBuf td_dev, recs_dev;
@@ -132,6 +132,7 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
     d.group_begin = grp;
     d.ngroups = (d.n + kGroup - 1) / kGroup;
     grp += d.ngroups;
+    P->max_chunks += (d.n + kChunkElems - 1) / kChunkElems;
     kp += d.k;
     sp += (d.k + block - 1) / block;
     d.sgran_begin = sg;
@@ -156,10 +157,10 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
       max_lambda = std::max(max_lambda, target / m * (double)kGroup);  // candidates expected per group
       d.cand_cap = std::min<int64_t>(d.n, 4 * d.k + 4096);
       cb += d.cand_cap;
-      est += (std::min<int64_t>(d.cand_cap, 2 * d.k) + kGroup - 1) / kGroup + 1;
+      est += (std::min<int64_t>(d.cand_cap, 2 * d.k) + kChunkElems - 1) / kChunkElems + 1;
       P->n_sampled++;
     } else {
-      est += d.ngroups;
+      est += (d.n + kChunkElems - 1) / kChunkElems;
     }
   }
   if (T > 1) {
@@ -180,11 +181,13 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
   P->ktotal = kp;
   P->stotal = sp;
   P->est_chunks = est;
-  const double cap = std::ceil(3.0 * max_lambda + 8.0 * std::sqrt(max_lambda) + 16.0);
-  P->cap = (int32_t)std::min<double>(round_up((int64_t)cap, 16), (double)kGroup);
+  // a group that gets more candidates than slots is re-read by the gather, so the slots only
+  // need to cover the ordinary spread of the count
+  const double cap = std::ceil(3.0 * max_lambda + 8.0 * std::sqrt(max_lambda) + 8.0) + 1.0;
+  P->cap = (int32_t)std::min<double>(round_up((int64_t)cap, kSlotLine) - 1, (double)kGroup);
   if (P->n_sampled == 0) P->cap = 1;
-  P->cap = std::min(P->cap, 4080);  // header + cap records must fit the 32 KB LDS staging
-  P->slot_stride = (int32_t)round_up(P->cap + 1, 16);
+  P->cap = std::min(P->cap, 4088);  // the LDS staging holds cap records (at most 32 KB)
+  P->slot_stride = (int32_t)round_up(P->cap + 1, kSlotLine);
   return P;
 }
 
@@ -220,7 +223,7 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
       st = GC_ERR_DEVICE;
     std::vector<GroupRec>().swap(P->recs);
   }
-  const size_t ng = (size_t)P->ngroups, nent = ng * 4;
+  const size_t ng = (size_t)P->ngroups, nent = (size_t)P->max_chunks * 4;
   const size_t ngp = (ng + kScanBlock - 1) / kScanBlock, ncp = (nent + kScanBlock - 1) / kScanBlock;
   if (st == GC_OK) st = ensure(ctx->ts, sizeof(TensorState) * T);
   if (st == GC_OK) st = ensure(ctx->shist, sizeof(unsigned long long) * (size_t)T * kSampleBins);
@@ -369,7 +372,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   ws.cap = P->cap;
   ws.ngroups = P->ngroups;
   ws.nsgran = P->nsgran;
-  ws.max_chunks = P->ngroups;
+  ws.max_chunks = P->max_chunks;
   ws.est_chunk_wgs = (int32_t)std::min<int64_t>(P->est_chunks, 1 << 20);
   ws.main_lds_pad = (int32_t)ctx->opt_main_lds_pad;
   OutBuf ob{out->indices, out->q, out->scales, out->index_bits, block, out->codec};

@@ -6,7 +6,7 @@
 //        form acc = g + e there, histogram the top 13 key bits in LDS and pick a candidate
 //        threshold t_lo that, with overwhelming probability, lies below the k-th largest key.
 //   2. k_main   THE streaming pass, the only one that touches every element: a workgroup
-//        streams one group of 4096 consecutive elements with 128-bit loads, writes
+//        streams one group of 2048 consecutive elements with 128-bit loads, writes
 //        acc = g + e over e, and appends every entry with key >= t_lo, in ascending index
 //        order (wavefront ballots + a 4-entry LDS prefix), to the group's candidate slots.
 //        Workgroups are short-lived and few per CU: HBM sees a narrow window of addresses
@@ -269,18 +269,18 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
   float* ep = e + gstart + wstart;
   const bool vec = wlen == kWaveTile && ((reinterpret_cast<uintptr_t>(gp) & GradVec<G>::kAlignMask) == 0) &&
                    ((reinterpret_cast<uintptr_t>(ep) & 15u) == 0);
-  f32x4 a[4];
-  uint32_t rank[4] = {0u, 0u, 0u, 0u};
+  f32x4 a[kRows];
+  uint32_t rank[kRows];
   uint32_t flags = 0u, mycnt = 0u;
   if (vec) {
-    f32x4 gv[4], ev[4];
+    f32x4 gv[kRows], ev[kRows];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) gv[u] = GradVec<G>::load(gp + u * 256 + lane * 4);
+    for (int u = 0; u < kRows; ++u) gv[u] = GradVec<G>::load(gp + u * 256 + lane * 4);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) ev[u] = *reinterpret_cast<const f32x4*>(ep + u * 256 + lane * 4);
+    for (int u = 0; u < kRows; ++u) ev[u] = *reinterpret_cast<const f32x4*>(ep + u * 256 + lane * 4);
     if (sampled) t_lo = *t_lo_ptr;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kRows; ++u) {
       a[u].x = __fadd_rn(gv[u].x, ev[u].x);
       a[u].y = __fadd_rn(gv[u].y, ev[u].y);
       a[u].z = __fadd_rn(gv[u].z, ev[u].z);
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
     if (vec) {
       if (flags) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kRows; ++u) {
           const uint32_t f = (flags >> (4 * u)) & 15u;
           if (f) {
             uint32_t r = before + rank[u];
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
     __syncthreads();  // tot is uniform over the workgroup
   }
   const uint32_t kept = min(tot, cap);
-  const uint32_t nout = (kept + 1u + 15u) & ~15u;  // header + candidates, in whole 128-byte lines
+  const uint32_t nout = (kept + kSlotLine) & ~(uint32_t)(kSlotLine - 1);  // header + candidates, whole lines
   uint2* __restrict__ dst = ws.slots + grp * (int64_t)ws.slot_stride;
   for (uint32_t j = threadIdx.x; j < nout; j += 256) {
     uint2 rec = make_uint2(0u, 0u);
@@ -485,7 +485,7 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
         M = ws.tg_base[t + 1] - ws.tg_base[t];
         if (M >= d.k && M <= d.cand_cap) { use = 1u; vlen = M; }
       }
-      nch = (vlen + kGroup - 1) / kGroup;
+      nch = (vlen + kChunkElems - 1) / kChunkElems;
     }
     long long incl = nch;
 #pragma unroll
@@ -589,7 +589,7 @@ struct SubSrc {
 __device__ __forceinline__ SubSrc sub_source(const Workspace& ws, const TensorDesc& d, const TensorState& st,
                                              long long lchunk, int wave, const float* e) {
   SubSrc s;
-  const long long pos = lchunk * kGroup + (long long)wave * kChunk;
+  const long long pos = lchunk * kChunkElems + (long long)wave * kChunk;
   s.len = (int)max(0ll, min((long long)kChunk, st.vlen - pos));
   s.first = pos;
   if (st.use_cand) {
