@@ -54,7 +54,7 @@ struct gc_ctx {
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
   size_t host_ts_cap = 0;
   const Plan* last_plan = nullptr;
-  int64_t opt_main_lds_pad = 49152;  // dynamic LDS of the streaming pass: 3 workgroups per CU
+  int64_t opt_main_lds_pad = 16384;  // dynamic LDS of the streaming pass: at most 8 workgroups per CU
   // profiling
   int prof = 0;  // 0 off, 1 every kernel, 2 only the streaming pass
   std::vector<EventPair> ev_used, ev_free;

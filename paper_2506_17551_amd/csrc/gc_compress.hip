@@ -6,7 +6,7 @@
 //        form acc = g + e there, histogram the top 13 key bits in LDS and pick a candidate
 //        threshold t_lo that, with overwhelming probability, lies below the k-th largest key.
 //   2. k_main   THE streaming pass, the only one that touches every element: a workgroup
-//        streams one group of 2048 consecutive elements with 128-bit loads, writes
+//        streams one group of 1024 consecutive elements with 128-bit loads, writes
 //        acc = g + e over e, and appends every entry with key >= t_lo, in ascending index
 //        order (wavefront ballots + a 4-entry LDS prefix), to the group's candidate slots.
 //        Workgroups are short-lived and few per CU: HBM sees a narrow window of addresses
@@ -277,7 +277,8 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
 #pragma unroll
     for (int u = 0; u < kRows; ++u) gv[u] = GradVec<G>::load(gp + u * 256 + lane * 4);
 #pragma unroll
-    for (int u = 0; u < kRows; ++u) ev[u] = *reinterpret_cast<const f32x4*>(ep + u * 256 + lane * 4);
+    for (int u = 0; u < kRows; ++u)  // read once, then overwritten: non-temporal like g (measured +4 %)
+      ev[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(ep + u * 256 + lane * 4));
     if (sampled) t_lo = *t_lo_ptr;
 #pragma unroll
     for (int u = 0; u < kRows; ++u) {

@@ -22,10 +22,11 @@ constexpr int kSampleShift = 31 - kSampleBits;
 constexpr int kSampleGranule = 256;  // one wavefront, one 128-bit load per lane and array
 
 // Streaming pass: one workgroup of 4 wavefronts streams one GROUP of consecutive elements once
-// (kRows 128-bit loads per lane and array) and exits. 2048-element groups measured ~6 % faster
-// than 4096-element ones; smaller still gains nothing once the per-group candidate line counts.
+// (kRows 128-bit loads per lane and array) and exits. With non-temporal loads on both inputs,
+// 1024-element groups (one load per lane and array) measured fastest on the 1.3B and 7B
+// workloads, 2048- and 4096-element groups 1-3 % slower overall.
 #ifndef GC_ROWS
-#define GC_ROWS 2
+#define GC_ROWS 1
 #endif
 constexpr int kRows = GC_ROWS;
 constexpr int kWaveTile = kRows * 256;
