@@ -138,6 +138,26 @@ def run_flat(args, gc, inputs, torch, wl, ctx):
     gc.sync_status(ctx)
     variants["compress_sign1_ms_per_worker"] = round(ts_.total_ms(), 4)
     variants["decompress_sum_sign1_ms"] = round(tds.total_ms(), 4)
+    # the dense coders (every entry sent, no selection): Eq. 10 over the whole accumulated gradient
+    dq = dsc = None
+    t1, t2, t3 = Timer(torch), Timer(torch), Timer(torch)
+    for _ in range(2):
+        for t in (t1, t2, t3):
+            t.reset()
+        with t1:
+            dq, dsc = gc.compress_dense(ctx, g, e, block, codec=gc.GC_CODEC_SIGN1, q=dq, scales=dsc)
+        with t2:
+            gc.decompress_sum_dense(ctx, [dq] * W, [dsc] * W, n, block, codec=gc.GC_CODEC_SIGN1, out=out)
+    q8 = None
+    for _ in range(2):
+        t3.reset()
+        with t3:
+            q8, dsc = gc.compress_dense(ctx, g, e, block, codec=gc.GC_CODEC_INT8, q=q8, scales=dsc)
+    gc.sync_status(ctx)
+    del q8, dq
+    variants["compress_dense_sign1_ms"] = round(t1.total_ms(), 4)
+    variants["decompress_sum_dense_sign1_ms"] = round(t2.total_ms(), 4)
+    variants["compress_dense_int8_ms"] = round(t3.total_ms(), 4)
     info = {"n": n, "k": k, "block": block, "W": W, "index_bits": wl.index_bits, **variants,
             "compress_ms_per_worker": ms_c / W, "decompress_sum_ms": ms_d,
             "residuals_resident": resident, "fallback_tensors": stats["tensors_fallback"],

@@ -151,6 +151,32 @@ gc_status gc_decompress_apply(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const 
                               const int32_t* staleness, float* theta, float step, int64_t n,
                               void* hip_stream);
 
+/* Dense codes with error feedback: every entry is sent, so nothing is selected and there is no
+ * index list. With GC_CODEC_SIGN1 this is the paper's 1-bit quantizer (Sec. III.B, Eq. 10: the signs
+ * and one scale derived from the l1 norm) applied to the whole accumulated gradient, with the residual
+ * of Eq. 11 feeding what the signs lose into the next step:
+ *   acc = residual + grad;  per block of `block` consecutive ELEMENTS: scale and codes exactly as
+ *   gc_compress computes them for a block of kept values;  residual = acc - decoded value.
+ * The codes, scales and residual equal, bit for bit, those of gc_compress with k = n.
+ * q: gc_num_code_bytes(n, block, codec) bytes; scales: gc_num_scales(n, block) fp32. block <= 8192
+ * (GC_ERR_UNSUPPORTED beyond). Non-finite input is reported by gc_sync_status(). */
+gc_status gc_compress_dense(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual, int64_t n,
+                            int32_t block, gc_codec codec, void* q, float* scales, void* hip_stream);
+
+/* Aggregate of W workers' dense codes (Eq. 8 without the 1/P): out[i] = sum over w = 0..W-1, in that
+ * order and in fp32, of worker w's decoded value at i; with `staleness` (W host entries in [0, 2^24],
+ * or NULL) each term is first divided by 1 + staleness[w] (Eq. 12). q, scales: host arrays of W device
+ * pointers, laid out as gc_compress_dense writes them. `out` (n fp32) is fully overwritten. */
+gc_status gc_decompress_sum_dense(gc_ctx* ctx, const void* const* q, const float* const* scales, int32_t W,
+                                  int32_t block, gc_codec codec, const int32_t* staleness, float* out,
+                                  int64_t n, void* hip_stream);
+
+/* The same aggregate applied at once (Eq. 9): theta[i] <- theta[i] - fl32(step * S[i]) for every i,
+ * `step` standing for eta / P (0 <= step, finite). theta: n fp32, updated in place. */
+gc_status gc_decompress_apply_dense(gc_ctx* ctx, const void* const* q, const float* const* scales, int32_t W,
+                                    int32_t block, gc_codec codec, const int32_t* staleness, float* theta,
+                                    float step, int64_t n, void* hip_stream);
+
 /* Wait for `hip_stream` and return GC_ERR_NONFINITE if any compress call since
  * the last gc_sync_status() saw Inf/NaN among its kept entries, else GC_OK. */
 gc_status gc_sync_status(gc_ctx* ctx, void* hip_stream);

@@ -38,7 +38,8 @@ class _GcStats(ctypes.Structure):
 
 EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_num_code_bytes", "gc_compress",
            "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_multi", "gc_decompress_sum_weighted",
-           "gc_decompress_apply", "gc_sync_status",
+           "gc_decompress_apply", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
+           "gc_sync_status",
            "gc_last_stats", "gc_profile_enable", "gc_profile_num_kernels", "gc_profile_kernel_name",
            "gc_profile_read", "gc_set_option", "gc_status_string"]
 
@@ -67,6 +68,9 @@ def lib() -> ctypes.CDLL:
     L.gc_decompress_sum_multi.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, i64, vp]
     L.gc_decompress_sum_weighted.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, i64, vp]
     L.gc_decompress_apply.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, ctypes.c_float, i64, vp]
+    L.gc_compress_dense.argtypes = [vp, vp, ctypes.c_int, vp, i64, i32, ctypes.c_int, vp, vp, vp]
+    L.gc_decompress_sum_dense.argtypes = [vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, i64, vp]
+    L.gc_decompress_apply_dense.argtypes = [vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, ctypes.c_float, i64, vp]
     L.gc_sync_status.argtypes = [vp, vp]
     L.gc_last_stats.argtypes = [vp, ctypes.POINTER(_GcStats)]
     L.gc_profile_enable.argtypes = [vp, i32]
@@ -80,6 +84,7 @@ def lib() -> ctypes.CDLL:
     L.gc_status_string.restype = ctypes.c_char_p
     for name in ("gc_create", "gc_destroy", "gc_compress", "gc_compress_multi", "gc_decompress_sum",
                  "gc_decompress_sum_multi", "gc_decompress_sum_weighted", "gc_decompress_apply",
+                 "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
                  "gc_sync_status", "gc_last_stats", "gc_profile_enable",
                  "gc_profile_read"):
         getattr(L, name).restype = ctypes.c_int
@@ -333,6 +338,76 @@ def decompress_apply(ctx: Context, bufs: List[CompressedBuf], theta: torch.Tenso
                                    None if st is None else st.ctypes.data, theta.data_ptr(), float(step),
                                    theta.numel(), _stream_ptr(stream, theta.device))
     _check(rc, "gc_decompress_apply")
+    return theta
+
+
+def compress_dense(ctx: Context, grad: torch.Tensor, residual: torch.Tensor, block: int,
+                   codec: int = GC_CODEC_SIGN1, q: Optional[torch.Tensor] = None,
+                   scales: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """gc_compress_dense: every entry coded (no indices); `residual` is updated in place.
+    Returns (q, scales)."""
+    _check_dev(grad, "grad")
+    _check_dev(residual, "residual", torch.float32)
+    n = grad.numel()
+    if residual.numel() != n:
+        raise ValueError("grad and residual differ in length")
+    if q is None:
+        nq = num_code_bytes(n, max(int(block), 1), codec)
+        q = torch.empty(max(nq, 1), dtype=torch.int8, device=grad.device)[:nq]
+    if scales is None:
+        ns = num_scales(n, block)
+        scales = torch.empty(max(ns, 1), dtype=torch.float32, device=grad.device)[:ns]
+    _check_dev(q, "q", torch.int8)
+    _check_dev(scales, "scales", torch.float32)
+    rc = lib().gc_compress_dense(ctx.handle, grad.data_ptr(), _grad_dtype(grad), residual.data_ptr(), n, int(block),
+                                 int(codec), q.data_ptr(), scales.data_ptr(), _stream_ptr(stream, grad.device))
+    _check(rc, "gc_compress_dense")
+    return q, scales
+
+
+def _ptr_array(tensors: Sequence[torch.Tensor]):
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def decompress_sum_dense(ctx: Context, qs: Sequence[torch.Tensor], scales: Sequence[torch.Tensor], n: int,
+                         block: int, codec: int = GC_CODEC_SIGN1, staleness: Optional[Sequence[int]] = None,
+                         out: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """gc_decompress_sum_dense: fp32 sum, in worker order, of W workers' dense codes."""
+    if len(qs) != len(scales):
+        raise ValueError("one scales tensor per code tensor")
+    dev = qs[0].device
+    if out is None:
+        out = torch.empty(int(n), dtype=torch.float32, device=dev)
+    _check_dev(out, "out", torch.float32)
+    st = None if staleness is None else np.ascontiguousarray(staleness, dtype=np.int32)
+    if st is not None and st.shape[0] != len(qs):
+        raise ValueError("one staleness per worker")
+    rc = lib().gc_decompress_sum_dense(ctx.handle, _ptr_array(qs), _ptr_array(scales), len(qs), int(block),
+                                       int(codec), None if st is None else st.ctypes.data, out.data_ptr(),
+                                       int(n), _stream_ptr(stream, dev))
+    _check(rc, "gc_decompress_sum_dense")
+    return out
+
+
+def decompress_apply_dense(ctx: Context, qs: Sequence[torch.Tensor], scales: Sequence[torch.Tensor],
+                           theta: torch.Tensor, step: float, block: int, codec: int = GC_CODEC_SIGN1,
+                           staleness: Optional[Sequence[int]] = None,
+                           stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """gc_decompress_apply_dense: theta -= step * aggregate of the dense codes (Eq. 9)."""
+    if len(qs) != len(scales):
+        raise ValueError("one scales tensor per code tensor")
+    _check_dev(theta, "theta", torch.float32)
+    st = None if staleness is None else np.ascontiguousarray(staleness, dtype=np.int32)
+    if st is not None and st.shape[0] != len(qs):
+        raise ValueError("one staleness per worker")
+    rc = lib().gc_decompress_apply_dense(ctx.handle, _ptr_array(qs), _ptr_array(scales), len(qs), int(block),
+                                         int(codec), None if st is None else st.ctypes.data, theta.data_ptr(),
+                                         float(step), theta.numel(), _stream_ptr(stream, theta.device))
+    _check(rc, "gc_decompress_apply_dense")
     return theta
 
 

@@ -54,6 +54,7 @@ struct gc_ctx {
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
   size_t host_ts_cap = 0;
   const Plan* last_plan = nullptr;
+  int64_t last_dense_tensors = 0;  // tensors of the last compress call when it took the dense coder
   int64_t opt_main_lds_pad = 16384;  // dynamic LDS of the streaming pass: at most 8 workgroups per CU
   // profiling
   int prof = 0;  // 0 off, 1 every kernel, 2 only the streaming pass
@@ -334,6 +335,19 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
     return GC_ERR_INVALID_ARG;
 
   GC_HIP(hipSetDevice(ctx->device));
+  if (T == 1 && k[0] == n && block <= kDenseMaxBlock) {
+    // every entry is kept: no selection, the one-pass dense coder writes the same result
+    hipStream_t ds = (hipStream_t)hip_stream;
+    {
+      Scope sc(ctx, kKDense, ds);
+      launch_dense(grad, (int)dtype, residual, n, block, out->codec, out->q, out->scales, out->indices,
+                   out->index_bits, (uint32_t*)ctx->flags.p, ds);
+    }
+    ctx->last_plan = nullptr;
+    ctx->last_dense_tensors = 1;
+    return launch_status();
+  }
+  ctx->last_dense_tensors = 0;
   Plan* P = nullptr;
   gc_status st = get_plan(ctx, offsets, k, T, block, out->codec, &P);
   if (st != GC_OK) return st;
@@ -511,9 +525,49 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   return launch_status();
 }
 
+gc_status dense_common_check(gc_ctx* ctx, int64_t n, int32_t block, gc_codec codec) {
+  if (!ctx || n <= 0 || block < 1) return GC_ERR_INVALID_ARG;
+  if (codec != GC_CODEC_INT8 && codec != GC_CODEC_SIGN1) return GC_ERR_INVALID_ARG;
+  if (block > kDenseMaxBlock) return GC_ERR_UNSUPPORTED;
+  if ((n + block - 1) / block >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
+  return GC_OK;
+}
+
+gc_status dense_sum_impl(gc_ctx* ctx, const void* const* q, const float* const* scales, int32_t W, int32_t block,
+                         gc_codec codec, const int32_t* staleness, bool apply, float c_apply, float* out,
+                         int64_t n, void* hip_stream) {
+  gc_status st = dense_common_check(ctx, n, block, codec);
+  if (st != GC_OK) return st;
+  if (!q || !scales || !out || W < 1) return GC_ERR_INVALID_ARG;
+  if (W > kMaxWorkers) return GC_ERR_UNSUPPORTED;
+  if (apply && !(c_apply >= 0.0f && c_apply <= 3.0e38f)) return GC_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(out) % 4) return GC_ERR_INVALID_ARG;
+  if ((n + 1023) / 1024 >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
+  DenseDecArgs a;
+  std::memset(&a, 0, sizeof(a));
+  for (int32_t w = 0; w < W; ++w) {
+    if (!q[w] || !scales[w] || (reinterpret_cast<uintptr_t>(scales[w]) % 4)) return GC_ERR_INVALID_ARG;
+    a.q[w] = static_cast<const int8_t*>(q[w]);
+    a.scales[w] = scales[w];
+    a.denom[w] = 1.0f;
+    if (staleness) {
+      if (staleness[w] < 0 || staleness[w] > (1 << 24)) return GC_ERR_INVALID_ARG;
+      a.denom[w] = 1.0f + (float)staleness[w];
+    }
+  }
+  GC_HIP(hipSetDevice(ctx->device));
+  hipStream_t s = (hipStream_t)hip_stream;
+  {
+    Scope sc(ctx, kKDenseSum, s);
+    launch_dense_sum(a, W, block, n, (int)codec, out, staleness ? 1 : 0, apply ? 1 : 0, c_apply, s);
+  }
+  return launch_status();
+}
+
 const char* const kKernelNames[kKNum] = {"k_init", "k_sample", "k_sample_thresh", "k_main", "k_group_sums", "k_group_scan",
                                          "k_route", "k_gather", "k_hist", "k_select_scan", "k_count",
-                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_bounds", "k_dec_tiles"};
+                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_bounds", "k_dec_tiles",
+                                         "k_dense", "k_dense_sum"};
 
 }  // namespace
 
@@ -619,6 +673,39 @@ gc_status gc_decompress_sum_multi(gc_ctx* ctx, const gc_buf* bufs, int32_t W, co
   return decompress_impl(ctx, bufs, W, k, T, nullptr, false, 0.0f, out, n, hip_stream);
 }
 
+gc_status gc_compress_dense(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual, int64_t n,
+                            int32_t block, gc_codec codec, void* q, float* scales, void* hip_stream) {
+  gc_status st = dense_common_check(ctx, n, block, codec);
+  if (st != GC_OK) return st;
+  if (!grad || !residual || !q || !scales) return GC_ERR_INVALID_ARG;
+  if (dtype != GC_F32 && dtype != GC_BF16) return GC_ERR_INVALID_ARG;
+  const size_t gsz = dtype == GC_F32 ? 4 : 2;
+  if ((reinterpret_cast<uintptr_t>(grad) % gsz) || (reinterpret_cast<uintptr_t>(residual) % 4) ||
+      (reinterpret_cast<uintptr_t>(scales) % 4))
+    return GC_ERR_INVALID_ARG;
+  GC_HIP(hipSetDevice(ctx->device));
+  hipStream_t s = (hipStream_t)hip_stream;
+  {
+    Scope sc(ctx, kKDense, s);
+    launch_dense(grad, (int)dtype, residual, n, block, (int)codec, q, scales, nullptr, 0, (uint32_t*)ctx->flags.p, s);
+  }
+  ctx->last_plan = nullptr;
+  ctx->last_dense_tensors = 1;
+  return launch_status();
+}
+
+gc_status gc_decompress_sum_dense(gc_ctx* ctx, const void* const* q, const float* const* scales, int32_t W,
+                                  int32_t block, gc_codec codec, const int32_t* staleness, float* out,
+                                  int64_t n, void* hip_stream) {
+  return dense_sum_impl(ctx, q, scales, W, block, codec, staleness, false, 0.0f, out, n, hip_stream);
+}
+
+gc_status gc_decompress_apply_dense(gc_ctx* ctx, const void* const* q, const float* const* scales, int32_t W,
+                                    int32_t block, gc_codec codec, const int32_t* staleness, float* theta,
+                                    float step, int64_t n, void* hip_stream) {
+  return dense_sum_impl(ctx, q, scales, W, block, codec, staleness, true, step, theta, n, hip_stream);
+}
+
 gc_status gc_sync_status(gc_ctx* ctx, void* hip_stream) {
   if (!ctx) return GC_ERR_INVALID_ARG;
   GC_HIP(hipSetDevice(ctx->device));
@@ -640,7 +727,10 @@ gc_status gc_last_stats(gc_ctx* ctx, gc_stats* stats) {
   if (!ctx || !stats) return GC_ERR_INVALID_ARG;
   std::memset(stats, 0, sizeof(*stats));
   const Plan* P = ctx->last_plan;
-  if (!P) return GC_OK;
+  if (!P) {
+    stats->tensors = ctx->last_dense_tensors;
+    return GC_OK;
+  }
   stats->tensors = (int64_t)P->td.size();
   for (size_t t = 0; t < P->td.size(); ++t) {
     if (P->td[t].mode != kSampled) continue;

@@ -31,40 +31,6 @@
 namespace gc {
 namespace {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ uint32_t mbcnt64(uint64_t m) {
-  return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-}
-__device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
-
-template <typename G> __device__ __forceinline__ float load_grad(const G* g, int64_t i);
-template <> __device__ __forceinline__ float load_grad<float>(const float* g, int64_t i) { return g[i]; }
-template <> __device__ __forceinline__ float load_grad<uint16_t>(const uint16_t* g, int64_t i) {
-  return __uint_as_float((uint32_t)g[i] << 16);  // bf16 -> fp32 is exact
-}
-
-template <typename G> struct GradVec;
-template <> struct GradVec<float> {
-  static __device__ __forceinline__ f32x4 load(const float* p) {
-    return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-  }
-  static constexpr uint32_t kAlignMask = 15u;
-};
-template <> struct GradVec<uint16_t> {
-  static __device__ __forceinline__ f32x4 load(const uint16_t* p) {
-    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
-    f32x4 r;
-    r.x = __uint_as_float(v.x << 16);
-    r.y = __uint_as_float(v.x & 0xFFFF0000u);
-    r.z = __uint_as_float(v.y << 16);
-    r.w = __uint_as_float(v.y & 0xFFFF0000u);
-    return r;
-  }
-  static constexpr uint32_t kAlignMask = 7u;
-};
-
 // Largest t in [0, T) with begin(t) <= x (begin is non-decreasing, begin(0) <= x).
 template <typename F>
 __device__ __forceinline__ int find_last_le(int T, long long x, int hint, F begin) {

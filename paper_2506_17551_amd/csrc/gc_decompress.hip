@@ -15,7 +15,6 @@
 namespace gc {
 namespace {
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <typename I>
 __device__ __forceinline__ uint32_t lower_bound_idx(const I* __restrict__ idx, uint32_t lo, uint32_t hi,

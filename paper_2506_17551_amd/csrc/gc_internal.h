@@ -139,7 +139,7 @@ struct OutBuf {
 // kernel ids for profiling
 enum KernelId : int32_t {
   kKInit = 0, kKSample, kKSampleThresh, kKMain, kKGroupSums, kKGroupScan, kKRoute, kKGather, kKHist,
-  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecBounds, kKDecTiles, kKNum
+  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecBounds, kKDecTiles, kKDense, kKDenseSum, kKNum
 };
 
 // launchers (defined in the .hip files next to their kernels)
@@ -159,6 +159,41 @@ void launch_chunk_scan(const Workspace& ws, hipStream_t s);
 void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStream_t s);
 void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktotal, hipStream_t s);
 
+// ---- small device helpers shared by the kernels ----------------------------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t mbcnt64(uint64_t m) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+__device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+
+template <typename G> __device__ __forceinline__ float load_grad(const G* g, int64_t i);
+template <> __device__ __forceinline__ float load_grad<float>(const float* g, int64_t i) { return g[i]; }
+template <> __device__ __forceinline__ float load_grad<uint16_t>(const uint16_t* g, int64_t i) {
+  return __uint_as_float((uint32_t)g[i] << 16);  // bf16 -> fp32 is exact
+}
+
+template <typename G> struct GradVec;
+template <> struct GradVec<float> {
+  static __device__ __forceinline__ f32x4 load(const float* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  }
+  static constexpr uint32_t kAlignMask = 15u;
+};
+template <> struct GradVec<uint16_t> {
+  static __device__ __forceinline__ f32x4 load(const uint16_t* p) {
+    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+    f32x4 r;
+    r.x = __uint_as_float(v.x << 16);
+    r.y = __uint_as_float(v.x & 0xFFFF0000u);
+    r.z = __uint_as_float(v.y << 16);
+    r.w = __uint_as_float(v.y & 0xFFFF0000u);
+    return r;
+  }
+  static constexpr uint32_t kAlignMask = 7u;
+};
+
 constexpr int kMaxWorkers = 64;
 #ifndef GC_DEC_TILE
 #define GC_DEC_TILE 2048
@@ -176,6 +211,20 @@ void launch_dec_bounds(const DecArgs& a, int W, int index_bits, int64_t ntiles, 
 void launch_dec_tiles(const DecArgs& a, int W, int index_bits, int32_t block, int64_t n,
                       int64_t ntiles, const uint32_t* bounds, const long long* kprefix,
                       const long long* sprefix, const long long* qprefix, int T, int codec, float* out,
+                      int weighted, int apply, float c_apply, hipStream_t s);
+
+// ---- dense codes (every entry kept, no indices) -----------------------------
+constexpr int kDenseWaveBlock = 1024;  // blocks up to this size are owned by one wavefront
+constexpr int kDenseMaxBlock = 8192;   // larger blocks do not fit one workgroup's registers
+struct DenseDecArgs {
+  const int8_t* q[kMaxWorkers];
+  const float* scales[kMaxWorkers];
+  float denom[kMaxWorkers];
+};
+// idx may be null (no index list); otherwise 0..n-1 is written with `index_bits` wide entries.
+void launch_dense(const void* g, int dtype, float* e, int64_t n, int32_t block, int codec, void* q,
+                  float* scales, void* idx, int index_bits, uint32_t* flags, hipStream_t s);
+void launch_dense_sum(const DenseDecArgs& a, int W, int32_t block, int64_t n, int codec, float* out,
                       int weighted, int apply, float c_apply, hipStream_t s);
 
 }  // namespace gc
