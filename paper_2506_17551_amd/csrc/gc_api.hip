@@ -56,6 +56,8 @@ struct gc_ctx {
   const Plan* last_plan = nullptr;
   int64_t last_dense_tensors = 0;  // tensors of the last compress call when it took the dense coder
   int64_t opt_main_lds_pad = 16384;  // dynamic LDS of the streaming pass: at most 8 workgroups per CU
+  int64_t opt_dense_wave_block = 1024;  // dense coder: blocks up to this size are held by one wavefront
+  int64_t opt_dense_lds_pad = -1;       // dense coder: dynamic LDS per workgroup (occupancy bound); -1: by shape
   // profiling
   int prof = 0;  // 0 off, 1 every kernel, 2 only the streaming pass
   std::vector<EventPair> ev_used, ev_free;
@@ -341,7 +343,8 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
     {
       Scope sc(ctx, kKDense, ds);
       launch_dense(grad, (int)dtype, residual, n, block, out->codec, out->q, out->scales, out->indices,
-                   out->index_bits, (uint32_t*)ctx->flags.p, ds);
+                   out->index_bits, (uint32_t*)ctx->flags.p, (int)ctx->opt_dense_wave_block,
+                   (int)ctx->opt_dense_lds_pad, ds);
     }
     ctx->last_plan = nullptr;
     ctx->last_dense_tensors = 1;
@@ -687,7 +690,8 @@ gc_status gc_compress_dense(gc_ctx* ctx, const void* grad, gc_dtype dtype, float
   hipStream_t s = (hipStream_t)hip_stream;
   {
     Scope sc(ctx, kKDense, s);
-    launch_dense(grad, (int)dtype, residual, n, block, (int)codec, q, scales, nullptr, 0, (uint32_t*)ctx->flags.p, s);
+    launch_dense(grad, (int)dtype, residual, n, block, (int)codec, q, scales, nullptr, 0, (uint32_t*)ctx->flags.p,
+                 (int)ctx->opt_dense_wave_block, (int)ctx->opt_dense_lds_pad, s);
   }
   ctx->last_plan = nullptr;
   ctx->last_dense_tensors = 1;
@@ -757,6 +761,16 @@ gc_status gc_set_option(gc_ctx* ctx, const char* name, int64_t value) {
   if (std::strcmp(name, "main_lds_pad") == 0) {
     if (value < 0 || value > 65536) return GC_ERR_INVALID_ARG;
     ctx->opt_main_lds_pad = value;
+    return GC_OK;
+  }
+  if (std::strcmp(name, "dense_wave_block") == 0) {
+    if (value < 0 || value > 2048) return GC_ERR_INVALID_ARG;
+    ctx->opt_dense_wave_block = value;
+    return GC_OK;
+  }
+  if (std::strcmp(name, "dense_lds_pad") == 0) {
+    if (value < -1 || value > 65536) return GC_ERR_INVALID_ARG;
+    ctx->opt_dense_lds_pad = value;
     return GC_OK;
   }
   return GC_ERR_INVALID_ARG;

@@ -214,7 +214,6 @@ void launch_dec_tiles(const DecArgs& a, int W, int index_bits, int32_t block, in
                       int weighted, int apply, float c_apply, hipStream_t s);
 
 // ---- dense codes (every entry kept, no indices) -----------------------------
-constexpr int kDenseWaveBlock = 1024;  // blocks up to this size are owned by one wavefront
 constexpr int kDenseMaxBlock = 8192;   // larger blocks do not fit one workgroup's registers
 struct DenseDecArgs {
   const int8_t* q[kMaxWorkers];
@@ -222,8 +221,11 @@ struct DenseDecArgs {
   float denom[kMaxWorkers];
 };
 // idx may be null (no index list); otherwise 0..n-1 is written with `index_bits` wide entries.
+// Blocks of up to wave_block (<= 2048) elements are owned by one wavefront, larger ones by the workgroup;
+// lds_pad bytes of dynamic LDS only bound how many workgroups share a compute unit.
 void launch_dense(const void* g, int dtype, float* e, int64_t n, int32_t block, int codec, void* q,
-                  float* scales, void* idx, int index_bits, uint32_t* flags, hipStream_t s);
+                  float* scales, void* idx, int index_bits, uint32_t* flags, int wave_block, int lds_pad,
+                  hipStream_t s);
 void launch_dense_sum(const DenseDecArgs& a, int W, int32_t block, int64_t n, int codec, float* out,
                       int weighted, int apply, float c_apply, hipStream_t s);
 
