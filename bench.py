@@ -248,26 +248,26 @@ def run_multi(args, gc, inputs, torch, wl, ctx):
 
 def run_recsys(args, gc, inputs, torch, wl, ctx):
     """Workload 3: per worker a 100M dense tower gradient plus a row-sparse embedding gradient
-    (touched rows of a 10M x 128 table, compressed on its compacted values). The harness maps
-    compacted positions to table positions between compress and decompress_sum (untimed index
-    bookkeeping); the table aggregate is a dense 10M x 128 fp32 output."""
-    import numpy as np
+    (touched rows of a 10M x 128 table). The embedding step is gc_compress_rows on a table-shaped
+    residual per worker (8 x 5.12 GB), its buffers carry table positions and go straight into
+    decompress_sum; the table aggregate is a dense 10M x 128 fp32 output."""
     dev = "cuda:0"
     W, block, n = wl.W, wl.block, wl.n
     k = gc.k_from_density(n, wl.density)
     ctx_e = gc.Context(0)  # the embedding tensors have per-worker sizes: keep their plans apart
+    R, D = 10_000_000, 128
+    n_table = R * D
     rows, vals, kv = [], [], []
     for w in range(W):
         r, v = inputs.embedding_rows_workload(w, dev)
         rows.append(torch.from_numpy(r).to(dev))
         vals.append(v)
         kv.append(gc.k_from_density(v.numel(), wl.density))
-    n_table = 10_000_000 * 128
     g = [None] * W
     res = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(W)]
-    res_e = [torch.zeros(v.numel(), dtype=torch.float32, device=dev) for v in vals]
+    res_t = [torch.zeros(R, D, dtype=torch.float32, device=dev) for _ in range(W)]
     bufs = [gc.CompressedBuf.allocate(n, k, gc.num_scales(k, block), block, 32, dev) for _ in range(W)]
-    bufs_e = [gc.CompressedBuf.allocate(vals[w].numel(), kv[w], gc.num_scales(kv[w], block), block, 32, dev)
+    bufs_e = [gc.CompressedBuf.allocate(n_table, kv[w], gc.num_scales(kv[w], block), block, 32, dev)
               for w in range(W)]
     out = torch.empty(n, dtype=torch.float32, device=dev)
     out_t = torch.empty(n_table, dtype=torch.float32, device=dev)
@@ -284,21 +284,14 @@ def run_recsys(args, gc, inputs, torch, wl, ctx):
             ctx.profile_enable(1)
         for w in range(W):
             g[w] = wl.grad(w, step, dev, out=g[w])
-            res_e[w].zero_()
         torch.cuda.synchronize()
         with tc:
             for w in range(W):
                 gc.compress(ctx, g[w], res[w], k, block, out=bufs[w])
-                gc.compress(ctx_e, vals[w], res_e[w], kv[w], block, out=bufs_e[w])
-        tbufs = []
-        for w in range(W):  # compacted position -> position in the table
-            pos = bufs_e[w].indices.to(torch.int64) & 0xFFFFFFFF
-            tidx = rows[w][pos // 128] * 128 + pos % 128
-            tbufs.append(gc.CompressedBuf(tidx, bufs_e[w].q, bufs_e[w].scales, n_table, kv[w], block, 64))
-        torch.cuda.synchronize()
+                gc.compress_rows(ctx_e, vals[w], res_t[w], rows[w], kv[w], block, out=bufs_e[w])
         with td:
             gc.decompress_sum(ctx, bufs, n, out=out)
-            gc.decompress_sum(ctx, tbufs, n_table, out=out_t)
+            gc.decompress_sum(ctx, bufs_e, n_table, out=out_t)
         gc.sync_status(ctx)
         gc.sync_status(ctx_e)
     torch.cuda.synchronize()

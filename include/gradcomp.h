@@ -151,6 +151,24 @@ gc_status gc_decompress_apply(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const 
                               const int32_t* staleness, float* theta, float step, int64_t n,
                               void* hip_stream);
 
+/* One error-feedback step on a ROW-SPARSE gradient (the gradient of an embedding table of R rows x D
+ * columns of which this step touched U rows; Sec. III.B, Eq. 11, with the residual kept in the shape
+ * of the table). Only the touched rows take part: acc = vals + residual_table[rows], the k largest
+ * |acc| among those U * D entries are kept and coded as in gc_compress, and residual_table[rows] is
+ * rewritten; every other row of the residual is neither read nor written. The paper does not treat
+ * sparse gradients; this is the reading under which "density applied to the touched rows" means
+ * something, and it makes the step equal to gc_compress on the compacted (U x D) tensor.
+ * vals: U * D entries of `dtype`, row-major, in the order of `rows`. rows: U int64 row ids in DEVICE
+ * memory, ascending, unique, each in [0, R). residual_table: R * D fp32. 1 <= k <= U * D < 2^32.
+ * out->indices receive positions in the table, row * D + column (ascending); out->n must be R * D,
+ * out->index_bits 64 when R * D > 2^32; q and scales as for gc_compress with k pairs. The buffers can
+ * be passed to gc_decompress_sum with n = R * D. A row id that is out of range or out of order is
+ * never dereferenced; the call is then reported by gc_sync_status() as GC_ERR_INVALID_ARG and its
+ * outputs are unspecified. */
+gc_status gc_compress_rows(gc_ctx* ctx, const void* vals, gc_dtype dtype, float* residual_table,
+                           const int64_t* rows, int64_t U, int64_t D, int64_t R, int64_t k, int32_t block,
+                           const gc_buf* out, void* hip_stream);
+
 /* Dense codes with error feedback: every entry is sent, so nothing is selected and there is no
  * index list. With GC_CODEC_SIGN1 this is the paper's 1-bit quantizer (Sec. III.B, Eq. 10: the signs
  * and one scale derived from the l1 norm) applied to the whole accumulated gradient, with the residual
@@ -178,7 +196,8 @@ gc_status gc_decompress_apply_dense(gc_ctx* ctx, const void* const* q, const flo
                                     float step, int64_t n, void* hip_stream);
 
 /* Wait for `hip_stream` and return GC_ERR_NONFINITE if any compress call since
- * the last gc_sync_status() saw Inf/NaN among its kept entries, else GC_OK. */
+ * the last gc_sync_status() saw Inf/NaN among its kept entries (GC_ERR_INVALID_ARG if a
+ * gc_compress_rows call saw a bad row id), else GC_OK. */
 gc_status gc_sync_status(gc_ctx* ctx, void* hip_stream);
 
 /* Counters of the most recent compress call; call after gc_sync_status(). */

@@ -39,6 +39,11 @@
 //       two, s = (float)(sum / len) (one fp64 division, one rounding to fp32), zero or
 //       subnormal s sends zeros. ghat = +-s; the residual is fl32(acc - ghat). Signs are
 //       packed 8 per byte, least significant bit first, every block starting a new byte.
+//   R10 Row-sparse gradients (an embedding table of R rows x D columns of which a step touches
+//       U rows): the residual lives with the table, the step runs on the touched rows only -
+//       acc = vals + residual[rows], top-k over those U*D entries, residual[rows] rewritten -
+//       so untouched rows neither compete nor change, and indices are reported as positions in
+//       the table, row * D + column (ascending, since the rows are given ascending).
 // Parity status: the selection (R1-R3), Eq. (11) and Eq. (8) are pinned by the
 // CPU tests (brute-force sort, exact invariants, closed-form quantiles). The
 // choice of int8 scheme (R4), block semantics and the k rounding rule (R6) are
@@ -270,6 +275,39 @@ int gco_compress_multi_codec(const void* g, int dtype, float* e, const int64_t* 
     qpos += gco_num_code_bytes(k[t], block, codec);
   }
   return status;
+}
+
+// One error-feedback step on the touched rows of a table-shaped residual (R10). vals: U x D
+// gradient values of the touched rows (dtype as in gco_compress), rows: U ascending unique row
+// ids in [0, R), e_table: R x D fp32 residual, updated in place on the touched rows only.
+// idx receives k table positions (index_bits 64 is required when R * D > 2^32).
+int gco_compress_rows(const void* vals, int dtype, float* e_table, const int64_t* rows, int64_t U,
+                      int64_t D, int64_t R, int64_t k, int32_t block, void* idx, int32_t index_bits,
+                      int8_t* q, float* scales, int32_t codec) {
+  if (!vals || !e_table || !rows || !idx) return GCO_ERR_INVALID_ARG;
+  if (U < 1 || D < 1 || R < 1 || U > R) return GCO_ERR_INVALID_ARG;
+  if (index_bits != 32 && index_bits != 64) return GCO_ERR_INVALID_ARG;
+  if (index_bits == 32 && R * D > (int64_t(1) << 32)) return GCO_ERR_INVALID_ARG;
+  for (int64_t u = 0; u < U; ++u) {
+    if (rows[u] < 0 || rows[u] >= R) return GCO_ERR_INVALID_ARG;
+    if (u > 0 && rows[u] <= rows[u - 1]) return GCO_ERR_INVALID_ARG;
+  }
+  const int64_t m = U * D;
+  std::vector<float> ec(static_cast<size_t>(m));
+  for (int64_t u = 0; u < U; ++u)
+    for (int64_t c = 0; c < D; ++c) ec[u * D + c] = e_table[rows[u] * D + c];
+  std::vector<uint64_t> ci(static_cast<size_t>(k > 0 ? k : 1));
+  const int rc = gco_compress_codec(vals, dtype, ec.data(), m, k, block, ci.data(), 64, q, scales, codec);
+  if (rc == GCO_ERR_INVALID_ARG) return rc;
+  for (int64_t j = 0; j < k; ++j) {
+    const int64_t c = static_cast<int64_t>(ci[j]);
+    const uint64_t pos = static_cast<uint64_t>(rows[c / D] * D + c % D);
+    if (index_bits == 32) static_cast<uint32_t*>(idx)[j] = static_cast<uint32_t>(pos);
+    else static_cast<uint64_t*>(idx)[j] = pos;
+  }
+  for (int64_t u = 0; u < U; ++u)
+    for (int64_t c = 0; c < D; ++c) e_table[rows[u] * D + c] = ec[u * D + c];
+  return rc;
 }
 
 int gco_compress_multi(const void* g, int dtype, float* e, const int64_t* offsets,

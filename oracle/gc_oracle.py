@@ -66,6 +66,11 @@ def lib() -> ctypes.CDLL:
         L.gco_compress_multi_codec.argtypes = L.gco_compress_multi.argtypes + [ctypes.c_int32]
         L.gco_decompress_sum_codec.restype = ctypes.c_int
         L.gco_decompress_sum_codec.argtypes = L.gco_decompress_sum_weighted.argtypes + [ctypes.c_int32]
+        L.gco_compress_rows.restype = ctypes.c_int
+        L.gco_compress_rows.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                        ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
+                                        ctypes.c_void_p, ctypes.c_int32]
         L.gco_apply.restype = ctypes.c_int
         L.gco_apply.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_int64]
         _lib = L
@@ -110,6 +115,26 @@ def compress(g: np.ndarray, e: np.ndarray, k: int, block: int, index_bits: int =
                                   _ptr(idx) if kk else _ptr(pad), index_bits,
                                   _ptr(q) if q.size else _ptr(pad), _ptr(s), int(codec))
     return rc, idx, q, s[:nb]
+
+
+def compress_rows(vals: np.ndarray, e_table: np.ndarray, rows: np.ndarray, k: int, block: int,
+                  index_bits: int = 64, codec: int = INT8):
+    """One step on the touched rows of a table-shaped residual. vals: (U*D,) values of the touched
+    rows, e_table: (R, D) float32 updated IN PLACE on those rows, rows: (U,) ascending unique int64.
+    Returns (status, idx, q, scales); idx are positions in the table (row * D + column)."""
+    assert e_table.dtype == np.float32 and e_table.ndim == 2 and e_table.flags["C_CONTIGUOUS"]
+    R, D = e_table.shape
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    U = rows.shape[0]
+    assert vals.shape[0] == U * D
+    kk = max(int(k), 0)
+    idx = np.zeros(max(kk, 1), dtype=np.uint32 if index_bits == 32 else np.uint64)
+    q = np.zeros(max(num_code_bytes(kk, max(block, 1), codec), 1), dtype=np.int8)
+    nb = (kk + block - 1) // block if block > 0 else 0
+    s = np.zeros(max(nb, 1), dtype=np.float32)
+    rc = lib().gco_compress_rows(_ptr(vals), _grad_dtype(vals), _ptr(e_table), _ptr(rows), U, D, R, int(k),
+                                 int(block), _ptr(idx), index_bits, _ptr(q), _ptr(s), int(codec))
+    return rc, idx[:kk], q[:max(num_code_bytes(kk, max(block, 1), codec), 0)], s[:nb]
 
 
 def compress_multi(g: np.ndarray, e: np.ndarray, offsets, ks, block: int, index_bits: int = 32,

@@ -38,7 +38,7 @@ class _GcStats(ctypes.Structure):
 
 EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_num_code_bytes", "gc_compress",
            "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_multi", "gc_decompress_sum_weighted",
-           "gc_decompress_apply", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
+           "gc_decompress_apply", "gc_compress_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
            "gc_sync_status",
            "gc_last_stats", "gc_profile_enable", "gc_profile_num_kernels", "gc_profile_kernel_name",
            "gc_profile_read", "gc_set_option", "gc_status_string"]
@@ -68,6 +68,7 @@ def lib() -> ctypes.CDLL:
     L.gc_decompress_sum_multi.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, i64, vp]
     L.gc_decompress_sum_weighted.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, i64, vp]
     L.gc_decompress_apply.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, ctypes.c_float, i64, vp]
+    L.gc_compress_rows.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, i64, i64, i64, i32, ctypes.POINTER(_GcBuf), vp]
     L.gc_compress_dense.argtypes = [vp, vp, ctypes.c_int, vp, i64, i32, ctypes.c_int, vp, vp, vp]
     L.gc_decompress_sum_dense.argtypes = [vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, i64, vp]
     L.gc_decompress_apply_dense.argtypes = [vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, ctypes.c_float, i64, vp]
@@ -84,7 +85,7 @@ def lib() -> ctypes.CDLL:
     L.gc_status_string.restype = ctypes.c_char_p
     for name in ("gc_create", "gc_destroy", "gc_compress", "gc_compress_multi", "gc_decompress_sum",
                  "gc_decompress_sum_multi", "gc_decompress_sum_weighted", "gc_decompress_apply",
-                 "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
+                 "gc_compress_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
                  "gc_sync_status", "gc_last_stats", "gc_profile_enable",
                  "gc_profile_read"):
         getattr(L, name).restype = ctypes.c_int
@@ -339,6 +340,34 @@ def decompress_apply(ctx: Context, bufs: List[CompressedBuf], theta: torch.Tenso
                                    theta.numel(), _stream_ptr(stream, theta.device))
     _check(rc, "gc_decompress_apply")
     return theta
+
+
+def compress_rows(ctx: Context, vals: torch.Tensor, residual_table: torch.Tensor, rows: torch.Tensor, k: int,
+                  block: int, out: Optional[CompressedBuf] = None, index_bits: Optional[int] = None,
+                  stream: Optional[torch.cuda.Stream] = None, codec: int = GC_CODEC_INT8) -> CompressedBuf:
+    """gc_compress_rows: one step on the touched rows of a table-shaped residual (R x D, updated in place).
+    vals: U*D values, rows: U ascending unique int64 row ids on the device. Indices come out as
+    positions in the table."""
+    _check_dev(vals, "vals")
+    _check_dev(residual_table, "residual_table", torch.float32)
+    _check_dev(rows, "rows", torch.int64)
+    if residual_table.dim() != 2:
+        raise ValueError("residual_table must be (R, D)")
+    R, D = residual_table.shape
+    U = rows.numel()
+    if vals.numel() != U * D:
+        raise ValueError("vals must hold U * D entries")
+    if index_bits is None:
+        index_bits = 64 if R * D > (1 << 32) else 32
+    if out is None:
+        kk = max(int(k), 0)
+        out = CompressedBuf.allocate(R * D, kk, num_scales(kk, block), block, index_bits, vals.device, codec)
+    st = out.struct()
+    rc = lib().gc_compress_rows(ctx.handle, vals.data_ptr(), _grad_dtype(vals), residual_table.data_ptr(),
+                                rows.data_ptr(), U, D, R, int(k), int(block), ctypes.byref(st),
+                                _stream_ptr(stream, vals.device))
+    _check(rc, "gc_compress_rows")
+    return out
 
 
 def compress_dense(ctx: Context, grad: torch.Tensor, residual: torch.Tensor, block: int,

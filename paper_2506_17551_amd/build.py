@@ -8,7 +8,7 @@ import subprocess
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_PKG, "csrc")
 LIB_PATH = os.path.join(_PKG, "libgradcomp.so")
-SOURCES = ["gc_api.hip", "gc_compress.hip", "gc_decompress.hip", "gc_dense.hip"]
+SOURCES = ["gc_api.hip", "gc_compress.hip", "gc_decompress.hip", "gc_dense.hip", "gc_rows.hip"]
 
 # -ffp-contract=off: every fp32 operation of the method rounds on its own (no fused multiply-add),
 # which the bit-exact residual needs. Packed fp32 instructions are disabled for the device pass.

@@ -48,6 +48,7 @@ struct gc_ctx {
   std::vector<Plan*> plans;
   std::vector<DecPlan*> dplans;
   // workspace (sized for the largest plan seen)
+  DevBuf rows_e, rows_idx;  // compact residual and compact positions of a row-sparse step
   DevBuf ts, shist, hist, grp_cnt, grp_part, grp_off, tg_base, slots, cand_val, cand_idx, ch_gt,
       ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, blk_amax, flags, bounds;
   uint32_t* host_flags = nullptr;  // pinned
@@ -570,7 +571,7 @@ gc_status dense_sum_impl(gc_ctx* ctx, const void* const* q, const float* const* 
 const char* const kKernelNames[kKNum] = {"k_init", "k_sample", "k_sample_thresh", "k_main", "k_group_sums", "k_group_scan",
                                          "k_route", "k_gather", "k_hist", "k_select_scan", "k_count",
                                          "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_bounds", "k_dec_tiles",
-                                         "k_dense", "k_dense_sum"};
+                                         "k_dense", "k_dense_sum", "k_rows_gather", "k_rows_finish"};
 
 }  // namespace
 
@@ -611,7 +612,7 @@ gc_status gc_destroy(gc_ctx* c) {
   DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
                    &c->slots, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
                    &c->ch_part_gt, &c->ch_part_eq, &c->ch_goff, &c->ch_eoff, &c->tb_g, &c->tb_e,
-                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->bounds};
+                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->bounds, &c->rows_e, &c->rows_idx};
   for (DevBuf* b : all) release(*b);
   if (c->host_flags) (void)hipHostFree(c->host_flags);
   if (c->host_ts) (void)hipHostFree(c->host_ts);
@@ -676,6 +677,51 @@ gc_status gc_decompress_sum_multi(gc_ctx* ctx, const gc_buf* bufs, int32_t W, co
   return decompress_impl(ctx, bufs, W, k, T, nullptr, false, 0.0f, out, n, hip_stream);
 }
 
+gc_status gc_compress_rows(gc_ctx* ctx, const void* vals, gc_dtype dtype, float* residual_table,
+                           const int64_t* rows, int64_t U, int64_t D, int64_t R, int64_t k, int32_t block,
+                           const gc_buf* out, void* hip_stream) {
+  if (!ctx || !vals || !residual_table || !rows || !out) return GC_ERR_INVALID_ARG;
+  if (U < 1 || D < 1 || R < 1 || U > R || block < 1) return GC_ERR_INVALID_ARG;
+  if (D > (int64_t(1) << 32) || R > (int64_t(1) << 40)) return GC_ERR_UNSUPPORTED;
+  const int64_t m = U * D;                       // compact length: its positions must fit 32 bits
+  if (m >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
+  if (k < 1 || k > m) return GC_ERR_INVALID_ARG;
+  if (out->n != R * D || out->k != k || out->block != block) return GC_ERR_INVALID_ARG;
+  if (out->index_bits != 32 && out->index_bits != 64) return GC_ERR_INVALID_ARG;
+  if (out->index_bits == 32 && R * D > (int64_t(1) << 32)) return GC_ERR_INVALID_ARG;
+  if (!out->indices || !out->q || !out->scales) return GC_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(rows) % 8) || (reinterpret_cast<uintptr_t>(residual_table) % 4) ||
+      (reinterpret_cast<uintptr_t>(out->indices) % (out->index_bits / 8)))
+    return GC_ERR_INVALID_ARG;
+  GC_HIP(hipSetDevice(ctx->device));
+  gc_status st = ensure(ctx->rows_e, sizeof(float) * (size_t)m);
+  if (st == GC_OK) st = ensure(ctx->rows_idx, sizeof(uint32_t) * (size_t)k);
+  if (st != GC_OK) return st;
+  // the flat step on the compact tensor; argument errors surface here, before anything is written
+  gc_buf tmp = *out;
+  tmp.indices = ctx->rows_idx.p;
+  tmp.n = m;
+  tmp.index_bits = 32;
+  hipStream_t s = (hipStream_t)hip_stream;
+  float* ec = (float*)ctx->rows_e.p;
+  const long long* rws = reinterpret_cast<const long long*>(rows);
+  {
+    // the gather only reads caller memory and writes scratch, so running it before the flat
+    // step's own argument check writes nothing the caller can see
+    Scope sc(ctx, kKRowsGather, s);
+    launch_rows_gather(residual_table, rws, U, D, R, ec, (uint32_t*)ctx->flags.p, s);
+  }
+  const int64_t offsets[2] = {0, m};
+  st = compress_impl(ctx, vals, dtype, ec, offsets, &k, 1, block, &tmp, hip_stream);
+  if (st != GC_OK) return st;
+  {
+    Scope sc(ctx, kKRowsFinish, s);
+    launch_rows_finish(residual_table, rws, U, D, R, ec, (const uint32_t*)ctx->rows_idx.p, k, out->indices,
+                       out->index_bits, s);
+  }
+  return launch_status();
+}
+
 gc_status gc_compress_dense(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual, int64_t n,
                             int32_t block, gc_codec codec, void* q, float* scales, void* hip_stream) {
   gc_status st = dense_common_check(ctx, n, block, codec);
@@ -719,11 +765,13 @@ gc_status gc_sync_status(gc_ctx* ctx, void* hip_stream) {
     GC_HIP(hipMemcpyAsync(ctx->host_ts, ctx->ts.p, sizeof(TensorState) * ctx->last_plan->td.size(),
                           hipMemcpyDeviceToHost, s));
   GC_HIP(hipStreamSynchronize(s));
-  const bool bad = ctx->host_flags[0] != 0u;
+  const bool bad_rows = ctx->host_flags[1] != 0u;
+  const bool bad = ctx->host_flags[0] != 0u || bad_rows;
   if (bad) {
     GC_HIP(hipMemsetAsync(ctx->flags.p, 0, sizeof(uint32_t) * 4, s));
     GC_HIP(hipStreamSynchronize(s));
   }
+  if (bad_rows) return GC_ERR_INVALID_ARG;  // a row id out of range or out of order (gc_compress_rows)
   return bad ? GC_ERR_NONFINITE : GC_OK;
 }
 

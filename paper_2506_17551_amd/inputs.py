@@ -183,7 +183,7 @@ def workload(config: int, scale: float = 1.0) -> Workload:
                         note="context length 1024 assumed; per-tensor top-k")
     if config == 3:
         return Workload("recsys-mlp-100M-f32", 3, sc(100_000_000), 0.01, 256, 8,
-                        note="dense MLP tower part; embedding rows are a second compacted tensor")
+                        note="dense MLP tower part; the embedding gradient is row-sparse (touched rows of a 10M x 128 table)")
     if config == 4:
         return Workload("flat-1.3B-bf16", 4, sc(1_300_000_000, 8), 0.005, 1024, 16, steps=10,
                         grad_dtype="bf16")

@@ -1,0 +1,187 @@
+"""Row-sparse step (gc_compress_rows: touched rows of an embedding table, residual kept in the shape
+of the table) against the CPU oracle: table positions, codes, scales and the whole residual table
+must be bit-exact, and rows that were not touched must not change."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2506_17551_amd import inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def gc():
+    import paper_2506_17551_amd as gc_mod
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return gc_mod
+
+
+@pytest.fixture(scope="module")
+def ctx(gc):
+    c = gc.Context(0)
+    yield c
+    c.destroy()
+
+
+def bits(a):
+    return a.view(np.uint32)
+
+
+def _np_grad(g):
+    return inputs.bf16_bits(g) if g.dtype == torch.bfloat16 else g.cpu().numpy()
+
+
+def pick_rows(R, U, seed):
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    return np.sort(rng.choice(R, size=U, replace=False)).astype(np.int64)
+
+
+def check_rows(gc, ctx, oracle, vals_cpu, table_cpu, rows, k, block, index_bits=None, codec=0, tag=""):
+    """One step on both sides from the same bytes; table_cpu (R, D) is the residual before the step.
+    Returns (gpu buf, oracle triple, new table)."""
+    R, D = table_cpu.shape
+    print(f"[case] rows {tag} R={R} D={D} U={rows.size} k={k} block={block} bits={index_bits} codec={codec} "
+          f"dtype={vals_cpu.dtype}", flush=True)
+    ib = index_bits if index_bits is not None else (64 if R * D > (1 << 32) else 32)
+    t_ref = table_cpu.numpy().copy()
+    rc, idx, q, s = oracle.compress_rows(_np_grad(vals_cpu), t_ref, rows, k, block, index_bits=ib, codec=codec)
+    assert rc == 0
+    table = table_cpu.to(DEV).clone()
+    buf = gc.compress_rows(ctx, vals_cpu.to(DEV), table, torch.from_numpy(rows).to(DEV), k, block,
+                           index_bits=ib, codec=codec)
+    gc.sync_status(ctx)
+    assert np.array_equal(buf.indices_numpy(), idx), f"{tag}: table positions differ"
+    assert np.array_equal(buf.q.cpu().numpy(), q), f"{tag}: codes differ"
+    assert np.array_equal(bits(buf.scales.cpu().numpy()), bits(s)), f"{tag}: scales differ"
+    assert np.array_equal(bits(table.cpu().numpy()), bits(t_ref)), f"{tag}: residual tables differ"
+    return buf, (idx, q, s), torch.from_numpy(t_ref)
+
+
+@pytest.mark.parametrize("D", [1, 3, 4, 64, 128, 130])
+@pytest.mark.parametrize("codec", [0, 1])
+def test_rows_shapes(gc, ctx, oracle, D, codec):
+    R, U = 5000, 777
+    rows = pick_rows(R, U, 10 + D)
+    vals = inputs.normal(U * D, 0.01, 100 + D)
+    table = inputs.normal(R * D, 0.01, 200 + D).reshape(R, D)
+    k = gc.k_from_density(U * D, 0.01)
+    check_rows(gc, ctx, oracle, vals, table, rows, k, 256, codec=codec, tag="shapes")
+    check_rows(gc, ctx, oracle, vals, table, rows, k, 256, index_bits=64, codec=codec, tag="shapes 64-bit")
+
+
+def test_rows_chain_of_steps_and_aggregate(gc, ctx, oracle):
+    """Four chained steps of two workers on one table shape, a different row set every step (rows
+    touched earlier keep their residual until they are touched again); the aggregate of the two
+    workers' buffers after every step."""
+    R, D, block = 200_000, 128, 256
+    tables = [torch.zeros(R, D), torch.zeros(R, D)]
+    for step in range(4):
+        bufs, refs = [], []
+        for w in range(2):
+            U = 15_000 + 1000 * w + 37 * step
+            rows = inputs.zipf_unique_rows(4 * U, R, 1.1, inputs.seed_for(3, w, step, 1))
+            vals = inputs.normal(rows.size * D, 0.01, inputs.seed_for(3, w, step, 2))
+            k = gc.k_from_density(rows.size * D, 0.01)
+            buf, ref, tables[w] = check_rows(gc, ctx, oracle, vals, tables[w], rows, k, block, tag=f"chain {step}/{w}")
+            bufs.append(buf)
+            refs.append(ref)
+        out = gc.decompress_sum(ctx, bufs, R * D)
+        torch.cuda.synchronize()
+        rc, want = oracle.decompress_sum(refs, R * D, block)
+        assert rc == 0 and np.array_equal(bits(out.cpu().numpy()), bits(want))
+
+
+def test_rows_every_entry_kept_and_bf16(gc, ctx, oracle):
+    R, D, U = 3000, 32, 100
+    rows = pick_rows(R, U, 5)
+    vals = inputs.student_t3(U * D, 1e-3, 6).to(torch.bfloat16)
+    table = inputs.normal(R * D, 1e-3, 7).reshape(R, D)
+    check_rows(gc, ctx, oracle, vals, table, rows, U * D, 64, tag="all kept bf16")
+    check_rows(gc, ctx, oracle, vals, table, rows, 17, 64, tag="bf16")
+
+
+def test_rows_all_rows_touched_equals_flat_compress(gc, ctx):
+    R, D, k, block = 4000, 64, 2000, 128
+    g = inputs.normal(R * D, 1.0, 31).to(DEV)
+    e1 = inputs.normal(R * D, 1.0, 32).to(DEV)
+    e2 = e1.clone().reshape(R, D)
+    flat = gc.compress(ctx, g, e1, k, block)
+    rowed = gc.compress_rows(ctx, g, e2, torch.arange(R, device=DEV), k, block)
+    gc.sync_status(ctx)
+    assert torch.equal(flat.indices, rowed.indices) and torch.equal(flat.q, rowed.q)
+    assert torch.equal(flat.scales.view(torch.int32), rowed.scales.view(torch.int32))
+    assert torch.equal(e1.view(torch.int32), e2.reshape(-1).view(torch.int32))
+
+
+def test_rows_config3_embedding_table(gc, ctx, oracle):
+    """Config 3's embedding gradient at its real shape: a 10M x 128 residual table (5.12 GB), two
+    workers' Zipf row sets. The oracle runs on the same rows renumbered 0..U-1 (only touched rows
+    matter by definition), and the untouched part of the table is checked on the device."""
+    R, D, block = 10_000_000, 128, 256
+    free, _ = torch.cuda.mem_get_info()
+    if free < 16 * (1 << 30):
+        pytest.skip("needs ~16 GB of free HBM")
+    table = torch.empty(R, D, device=DEV)
+    inputs.normal(R * D, 0.01, 77, DEV, out=table.view(-1))
+    before = table.clone()
+    bufs, refs = [], []
+    for w in range(2):
+        rows, vals = inputs.embedding_rows_workload(w, "cpu")
+        U = rows.size
+        k = gc.k_from_density(U * D, 0.01)
+        rows_d = torch.from_numpy(rows).to(DEV)
+        small = before[rows_d].cpu().numpy().copy()              # the touched rows, renumbered
+        rc, idx, q, s = oracle.compress_rows(vals.numpy(), small, np.arange(U, dtype=np.int64), k, block)
+        assert rc == 0
+        buf = gc.compress_rows(ctx, vals.to(DEV), table, rows_d, k, block)
+        gc.sync_status(ctx)
+        assert buf.index_bits == 32 and R * D < (1 << 32)
+        c = idx.astype(np.int64)
+        want_pos = rows[c // D] * D + c % D
+        assert np.array_equal(buf.indices_numpy().astype(np.int64), want_pos)
+        assert np.array_equal(buf.q.cpu().numpy(), q)
+        assert np.array_equal(bits(buf.scales.cpu().numpy()), bits(s))
+        assert np.array_equal(bits(table[rows_d].cpu().numpy()), bits(small))
+        mask = torch.ones(R, dtype=torch.bool, device=DEV)
+        mask[rows_d] = False
+        assert torch.equal(table[mask].view(torch.int32), before[mask].view(torch.int32)), "an untouched row changed"
+        del mask
+        before[rows_d] = table[rows_d]
+        bufs.append(buf)
+        refs.append((want_pos.astype(np.uint64), q, s))
+    # the aggregate of the two workers over the table; the oracle on the union of positions
+    out = gc.decompress_sum(ctx, bufs, R * D)
+    torch.cuda.synchronize()
+    union = np.unique(np.concatenate([r[0] for r in refs]))
+    comp = [(np.searchsorted(union, r[0]).astype(np.uint32), r[1], r[2]) for r in refs]
+    rc, want = oracle.decompress_sum(comp, union.size, block)
+    got = out[torch.from_numpy(union.astype(np.int64)).to(DEV)].cpu().numpy()
+    assert rc == 0 and np.array_equal(bits(got), bits(want))
+    assert int(torch.count_nonzero(out)) == int(np.count_nonzero(want))
+
+
+def test_rows_bad_ids_are_reported_not_dereferenced(gc, ctx):
+    from paper_2506_17551_amd import binding
+    R, D = 1000, 8
+    vals = inputs.normal(3 * D, 1.0, 1).to(DEV)
+    gc.sync_status(ctx)
+    for bad in ([5, 5, 9], [7, 3, 9], [1, 2, 1000], [-4, 2, 3], [1, 2, 1 << 40]):
+        table = inputs.normal(R * D, 1.0, 2).to(DEV).reshape(R, D)
+        keep = table.clone()
+        gc.compress_rows(ctx, vals, table, torch.tensor(bad, dtype=torch.int64, device=DEV), 4, 4)
+        assert gc.sync_status(ctx, raise_on_error=False) == binding.GC_ERR_INVALID_ARG
+        good = [r for i, r in enumerate(bad) if 0 <= r < R and (i == 0 or bad[i - 1] < r)]
+        mask = torch.ones(R, dtype=torch.bool, device=DEV)
+        mask[torch.tensor(good, dtype=torch.int64, device=DEV)] = False
+        assert torch.equal(table[mask].view(torch.int32), keep[mask].view(torch.int32))
+        assert gc.sync_status(ctx, raise_on_error=False) == binding.GC_OK
+    table = torch.zeros(R, D, device=DEV)
+    rows = torch.tensor([1, 2, 3], dtype=torch.int64, device=DEV)
+    for kwargs, status in [(dict(k=0), binding.GC_ERR_INVALID_ARG), (dict(k=3 * D + 1), binding.GC_ERR_INVALID_ARG),
+                           (dict(k=4, block=0), binding.GC_ERR_INVALID_ARG)]:
+        with pytest.raises(binding.GradCompError) as ei:
+            gc.compress_rows(ctx, vals, table, rows, kwargs.get("k", 4), kwargs.get("block", 4))
+        assert ei.value.status == status
+    assert torch.count_nonzero(table).item() == 0

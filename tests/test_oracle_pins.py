@@ -559,3 +559,100 @@ def test_sign_code_multi_tensor(oracle):
     assert qp == q.size
     rc, out = oracle.decompress_sum([(idx, q, s)], n, 12, ktensor=ks, codec=oracle.SIGN1)
     assert rc == 0 and np.array_equal(out.view(np.uint32), dense.view(np.uint32))
+
+
+# ----------------------------------------------------------------- row-sparse step
+def test_golden_rows_step(oracle):
+    G = read_golden("rows_step.txt")
+    R, D = int(G["R"][0]), int(G["D"][0])
+    e = f32(G["e0"]).reshape(R, D).copy()
+    rows = np.array([int(x) for x in G["rows"]], dtype=np.int64)
+    rc, idx, q, s = oracle.compress_rows(f32(G["vals"]), e, rows, int(G["k"][0]), int(G["block"][0]))
+    assert rc == oracle.OK
+    assert idx.tolist() == [int(x) for x in G["idx"]]
+    assert q.tolist() == [int(x) for x in G["q"]]
+    assert np.array_equal(e.reshape(-1), f32(G["e1"]))
+
+
+@pytest.mark.parametrize("D", [1, 3, 8])
+@pytest.mark.parametrize("alphabet", [(0.0, -0.0, 1.0, -1.0, 2.0), None])
+def test_rows_step_is_the_definition(oracle, D, alphabet):
+    """Against the definition written out with numpy: accumulate on the touched rows, order the
+    touched entries by (magnitude desc, table position asc), keep k; every other row untouched."""
+    rng = np.random.default_rng(10 * D + (0 if alphabet is None else 1))
+    R, U = 37, 11
+    for trial in range(6):
+        rows = np.sort(rng.choice(R, size=U, replace=False)).astype(np.int64)
+        if alphabet is None:
+            vals = rng.standard_normal(U * D).astype(np.float32)
+            e0 = rng.standard_normal((R, D)).astype(np.float32)
+        else:
+            vals = rng.choice(np.array(alphabet, dtype=np.float32), size=U * D)
+            e0 = rng.choice(np.array(alphabet, dtype=np.float32), size=(R, D))
+        k = int(rng.integers(1, U * D + 1))
+        block = int(rng.integers(1, 9))
+        e = e0.copy()
+        rc, idx, q, s = oracle.compress_rows(vals, e, rows, k, block, index_bits=32)
+        assert rc == oracle.OK
+        acc = (vals.reshape(U, D) + e0[rows]).astype(np.float32)            # one fp32 add
+        table_pos = (rows[:, None] * D + np.arange(D)[None, :]).reshape(-1)  # ascending
+        keep = brute_force_topk(acc.reshape(-1), k)
+        assert np.array_equal(idx.astype(np.int64), table_pos[keep])
+        untouched = np.setdiff1d(np.arange(R), rows)
+        assert np.array_equal(e[untouched].view(np.uint32), e0[untouched].view(np.uint32))
+        # Eq. 11 on the touched rows: transmitted + new residual == acc exactly, dropped: residual == acc
+        d = np.zeros(R * D, dtype=np.float32)
+        d[idx.astype(np.int64)] = dequant(q, s, block)
+        got = (d.reshape(R, D)[rows] + e[rows]).astype(np.float32)
+        assert np.array_equal(got, acc)
+        dropped = np.setdiff1d(np.arange(U * D), keep)
+        assert np.array_equal(e[rows].reshape(-1)[dropped].view(np.uint32), acc.reshape(-1)[dropped].view(np.uint32))
+
+
+def test_rows_step_with_every_row_touched_is_the_flat_step(oracle):
+    R, D, k, block = 50, 16, 123, 32
+    g = inputs.normal(R * D, 1.0, 901).numpy()
+    e0 = inputs.normal(R * D, 1.0, 902).numpy()
+    e_flat = e0.copy()
+    rc, idx, q, s = oracle.compress(g, e_flat, k, block)
+    e_tab = e0.reshape(R, D).copy()
+    rc2, idx2, q2, s2 = oracle.compress_rows(g, e_tab, np.arange(R), k, block, index_bits=32)
+    assert rc == rc2 == oracle.OK
+    assert np.array_equal(idx, idx2) and np.array_equal(q, q2)
+    assert np.array_equal(s.view(np.uint32), s2.view(np.uint32))
+    assert np.array_equal(e_flat.view(np.uint32), e_tab.reshape(-1).view(np.uint32))
+
+
+def test_rows_steps_telescope_per_table_entry(oracle):
+    """Eq. 11 summed over steps that touch different row sets: at every table entry,
+    sum of transmitted + final residual == sum of gradients + initial residual."""
+    R, D, block, steps = 40, 8, 16, 6
+    rng = np.random.default_rng(5)
+    e = np.zeros((R, D), dtype=np.float32)
+    sent = np.zeros(R * D, dtype=np.float64)
+    grads = np.zeros((R, D), dtype=np.float64)
+    big = 0.0
+    for t in range(steps):
+        U = int(rng.integers(3, 15))
+        rows = np.sort(rng.choice(R, size=U, replace=False)).astype(np.int64)
+        vals = inputs.normal(U * D, 1.0, 950 + t).numpy()
+        k = oracle.k_from_density(U * D, 0.1)
+        rc, idx, q, s = oracle.compress_rows(vals, e, rows, k, block, index_bits=32)
+        assert rc == oracle.OK
+        grads[rows] += vals.reshape(U, D).astype(np.float64)
+        np.add.at(sent, idx.astype(np.int64), dequant(q, s, block).astype(np.float64))
+        big = max(big, float(np.abs(e).max()), float(np.abs(vals).max()))
+    err = np.abs(sent.reshape(R, D) + e.astype(np.float64) - grads)
+    assert err.max() <= steps * 2.0 ** -23 * 2 * big
+
+
+def test_rows_argument_errors(oracle):
+    e = np.zeros((8, 4), dtype=np.float32)
+    v = np.ones(8, dtype=np.float32)
+    bad = [np.array([3, 3]), np.array([5, 2]), np.array([1, 8]), np.array([-1, 2])]
+    for rows in bad:
+        rc, *_ = oracle.compress_rows(v, e, rows.astype(np.int64), 2, 4, index_bits=32)
+        assert rc == oracle.ERR_INVALID_ARG
+    rc, *_ = oracle.compress_rows(v, e, np.array([1, 2], dtype=np.int64), 9, 4, index_bits=32)
+    assert rc == oracle.ERR_INVALID_ARG
+    assert not e.any()
