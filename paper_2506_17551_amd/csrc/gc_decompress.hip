@@ -86,7 +86,112 @@ __device__ __forceinline__ LanePair locate_pair(uint32_t s0, int lane, uint32_t 
 
 constexpr uint32_t kClaimed = 0x7FC0DEADu;  // a NaN pattern no finite sum can produce
 
+// The pair range of every worker inside one tile: lane w holds worker w's first pair and count,
+// `excl` the number of pairs of the workers before it, `total` the tile's pairs over all workers.
+struct TileBounds {
+  uint32_t lo, cnt, excl, total;
+};
+
+__device__ __forceinline__ void load_bounds(const uint32_t* __restrict__ bounds, int64_t tile, int W, int lane,
+                                            uint32_t& lo, uint32_t& hi) {
+  lo = 0u;
+  hi = 0u;
+  if (lane < W) {
+    lo = bounds[tile * W + lane];
+    hi = bounds[(tile + 1) * W + lane];
+  }
+}
+
+__device__ __forceinline__ TileBounds scan_bounds(uint32_t lo, uint32_t hi, int lane) {
+  TileBounds b;
+  b.lo = lo;
+  b.cnt = hi - lo;
+  uint32_t incl = b.cnt;  // inclusive scan over lanes
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t u = __shfl_up(incl, off);
+    if (lane >= off) incl += u;
+  }
+  b.total = __shfl(incl, 63);
+  b.excl = incl - b.cnt;
+  return b;
+}
+
+// The pair a lane decodes in one round, as loaded: index, scale and raw code.
+struct PairLoad {
+  LanePair p;
+  unsigned long long gi;  // index in the dense vector
+  float s;                // scale of the pair's block
+  uint32_t code;          // int8 code (low byte), or the sign byte << 8 | bit number
+};
+
+// Issues the loads of round s0 of a tile together; nothing here consumes their results, so the
+// index, scale and code of a pair cost one round trip to memory, not three.
+template <typename I>
+__device__ __forceinline__ PairLoad load_pairs(const DecArgs& a, uint32_t s0, int lane, int W, const TileBounds& b,
+                                              int32_t block, const long long* __restrict__ kprefix,
+                                              const long long* __restrict__ sprefix,
+                                              const long long* __restrict__ qprefix, int T, int codec) {
+  PairLoad c;
+  c.p = locate_pair(s0, lane, b.total, W, b.excl, b.cnt, b.lo);
+  c.gi = 0ull;
+  c.s = 0.0f;
+  c.code = 0u;
+  if (c.p.active) {
+    const I* idx = static_cast<const I*>(a.indices[c.p.w]);
+    const float* sc = a.scales[c.p.w];
+    const int8_t* qw = a.q[c.p.w];
+    c.gi = (unsigned long long)idx[c.p.j];
+    long long rel = (long long)c.p.j, sbase = 0, qbase = 0;  // pair inside its tensor; tensor's scales, bytes
+    if (T > 1) {  // blocks restart at every tensor: find the tensor that owns pair j
+      int tl = 0, th = T - 1;
+      while (tl < th) {
+        const int mid = (tl + th + 1) >> 1;
+        if (kprefix[mid] <= (long long)c.p.j) tl = mid; else th = mid - 1;
+      }
+      rel -= kprefix[tl];
+      sbase = sprefix[tl];
+      qbase = qprefix[tl];
+    }
+    const long long blk = rel / block;
+    c.s = sc[sbase + blk];
+    if (codec == 0) {
+      c.code = (uint8_t)qw[T > 1 ? qbase + rel : rel];
+    } else {  // sign code (Eq. 10): bit r of the block's bytes
+      c.code = (uint32_t)(rel - blk * block);  // r; the byte is loaded below, the bit taken at use
+      c.code = (c.code & 7u) | ((uint32_t)(uint8_t)qw[qbase + blk * ((block + 7) / 8) + (c.code >> 3)] << 8);
+    }
+  }
+  return c;
+}
+
+// Adds one round of pairs into the wavefront's LDS tile, worker by worker, so that equal indices
+// of different workers are added in ascending worker order.
+__device__ __forceinline__ void add_pairs(const DecArgs& a, const PairLoad& c, int64_t base, int codec,
+                                          int weighted, float* lt) {
+  float val = 0.0f;
+  uint32_t pos = 0xFFFFFFFFu;
+  if (c.p.active) {
+    pos = (uint32_t)(c.gi - (unsigned long long)base);
+    if (codec == 0) val = __fmul_rn((float)(int8_t)c.code, c.s);
+    else val = ((c.code >> (8 + (c.code & 7u))) & 1u) ? c.s : -c.s;
+    if (weighted) val = __fdiv_rn(val, a.denom[c.p.w]);  // Eq. 12: a stale worker counts for less
+  }
+  const uint64_t act = __ballot(c.p.active);
+  if (act == 0ull) return;
+  const int w_first = __shfl(c.p.w, __ffsll((unsigned long long)act) - 1);
+  const int w_last = __shfl(c.p.w, 63 - __clzll((unsigned long long)act));
+  for (int w = w_first; w <= w_last; ++w) {
+    if (c.p.active && c.p.w == w && pos < (uint32_t)kDecTile) lt[pos] = __fadd_rn(lt[pos], val);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
 // MODE 0: out[tile] = sum (dense write).  MODE 1: theta[i] -= c * sum[i] at the touched i only.
+// Wavefronts walk the tiles with a grid stride, without workgroup barriers. Fetching a
+// wavefront's next tile ahead of time (its bounds, or its pairs) measured slower on the 7B workload
+// than this plain order, as did keeping the workers' pointers in LDS.
 template <typename I, int MODE>
 __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(DecArgs a, int W, int32_t block, int64_t n,
                                                    int64_t ntiles, const uint32_t* __restrict__ bounds,
@@ -97,102 +202,62 @@ __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(DecArgs a, int W, 
   __shared__ float tile_mem[kDecWaves][kDecTile];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float* lt = tile_mem[wave];
-  // wavefronts walk the tiles with a grid stride; no workgroup barrier is used in the loop
-  for (int64_t tile = (int64_t)blockIdx.x * kDecWaves + wave; tile < ntiles;
-       tile += (int64_t)gridDim.x * kDecWaves) {
+  const int64_t stride = (int64_t)gridDim.x * kDecWaves;
+  int64_t tile = (int64_t)blockIdx.x * kDecWaves + wave;
+  if (tile >= ntiles) return;
+
+  for (; tile < ntiles; tile += stride) {
     const int64_t base = tile * kDecTile;
-    // lane w holds worker w's pair range for this tile
-    uint32_t lo = 0, cnt = 0;
-    if (lane < W) {
-      lo = bounds[tile * W + lane];
-      cnt = bounds[(tile + 1) * W + lane] - lo;
-    }
-    uint32_t incl = cnt;  // inclusive scan over lanes
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t u = __shfl_up(incl, off);
-      if (lane >= off) incl += u;
-    }
-    const uint32_t total = __shfl(incl, 63);
-    const uint32_t excl = incl - cnt;
-    if (MODE == 1 && total == 0u) continue;  // nothing to apply in this tile
-    const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-    for (int i = 0; i < kDecTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    uint32_t lo, hi;
+    load_bounds(bounds, tile, W, lane, lo, hi);
+    const TileBounds cur = scan_bounds(lo, hi, lane);
 
-    for (uint32_t s0 = 0; s0 < total; s0 += 64) {
-      const LanePair p = locate_pair(s0, lane, total, W, excl, cnt, lo);
-      float val = 0.0f;
-      uint32_t pos = 0;
-      if (p.active) {
-        const I* idx = static_cast<const I*>(a.indices[p.w]);
-        pos = (uint32_t)((unsigned long long)idx[p.j] - (unsigned long long)base);
-        long long rel = (long long)p.j, sbase = 0, qbase = 0;  // pair inside its tensor; tensor's scales, bytes
-        if (T > 1) {  // blocks restart at every tensor: find the tensor that owns pair j
-          int tl = 0, th = T - 1;
-          while (tl < th) {
-            const int mid = (tl + th + 1) >> 1;
-            if (kprefix[mid] <= (long long)p.j) tl = mid; else th = mid - 1;
+    if (!(MODE == 1 && cur.total == 0u)) {  // MODE 1: nothing to apply in an empty tile
+      const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int i = 0; i < kDecTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+
+      const PairLoad first = load_pairs<I>(a, 0u, lane, W, cur, block, kprefix, sprefix, qprefix, T, codec);
+      add_pairs(a, first, base, codec, weighted, lt);
+      for (uint32_t s0 = 64; s0 < cur.total; s0 += 64) {
+        const PairLoad c = load_pairs<I>(a, s0, lane, W, cur, block, kprefix, sprefix, qprefix, T, codec);
+        add_pairs(a, c, base, codec, weighted, lt);
+      }
+
+      if (MODE == 0) {
+        const int64_t remain = n - base;
+        if (remain >= kDecTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
+#pragma unroll
+          for (int i = 0; i < kDecTile / 256; ++i) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
           }
-          rel -= kprefix[tl];
-          sbase = sprefix[tl];
-          qbase = qprefix[tl];
-        }
-        const long long blk = rel / block;
-        const float s = a.scales[p.w][sbase + blk];
-        if (codec == 0) {
-          val = __fmul_rn((float)a.q[p.w][T > 1 ? qbase + rel : rel], s);
-        } else {  // sign code (Eq. 10): bit r of the block's bytes, +s or -s
-          const int r = (int)(rel - blk * block);
-          const uint32_t byte = (uint8_t)a.q[p.w][qbase + blk * ((block + 7) / 8) + (r >> 3)];
-          val = ((byte >> (r & 7)) & 1u) ? s : -s;
-        }
-        if (weighted) val = __fdiv_rn(val, a.denom[p.w]);  // Eq. 12: a stale worker counts for less
-      }
-      // add worker by worker so that equal indices of different workers keep ascending order
-      const uint64_t act = __ballot(p.active);
-      const int w_first = __shfl(p.w, __ffsll((unsigned long long)act) - 1);
-      const int w_last = __shfl(p.w, 63 - __clzll((unsigned long long)act));
-      for (int w = w_first; w <= w_last; ++w) {
-        if (p.active && p.w == w && pos < (uint32_t)kDecTile) lt[pos] = __fadd_rn(lt[pos], val);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-      }
-    }
-
-    if (MODE == 0) {
-      const int64_t remain = n - base;
-      if (remain >= kDecTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
-#pragma unroll
-        for (int i = 0; i < kDecTile / 256; ++i) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
-          __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
+        } else {
+          const int lim = (int)(remain < kDecTile ? remain : kDecTile);
+          for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
         }
       } else {
-        const int lim = (int)(remain < kDecTile ? remain : kDecTile);
-        for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
-      }
-    } else {
-      // every touched position is claimed once (LDS exchange with a marker) and updated in place:
-      // theta - fl32(c * sum). Untouched positions have sum +0 and would not change anyway.
-      for (uint32_t s0 = 0; s0 < total; s0 += 64) {
-        const LanePair p = locate_pair(s0, lane, total, W, excl, cnt, lo);
-        if (p.active) {
-          const I* idx = static_cast<const I*>(a.indices[p.w]);
-          const unsigned long long gi = (unsigned long long)idx[p.j];
-          const uint32_t pos = (uint32_t)(gi - (unsigned long long)base);
-          if (pos < (uint32_t)kDecTile && gi < (unsigned long long)n) {
-            const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + pos, kClaimed);
-            if (old != kClaimed) out[gi] = __fsub_rn(out[gi], __fmul_rn(c_apply, __uint_as_float(old)));
+        // every touched position is claimed once (LDS exchange with a marker) and updated in place:
+        // theta - fl32(c * sum). Untouched positions have sum +0 and would not change anyway.
+        for (uint32_t s0 = 0; s0 < cur.total; s0 += 64) {
+          const LanePair p = locate_pair(s0, lane, cur.total, W, cur.excl, cur.cnt, cur.lo);
+          if (p.active) {
+            const I* idx = static_cast<const I*>(a.indices[p.w]);
+            const unsigned long long gi = (unsigned long long)idx[p.j];
+            const uint32_t pos = (uint32_t)(gi - (unsigned long long)base);
+            if (pos < (uint32_t)kDecTile && gi < (unsigned long long)n) {
+              const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + pos, kClaimed);
+              if (old != kClaimed) out[gi] = __fsub_rn(out[gi], __fmul_rn(c_apply, __uint_as_float(old)));
+            }
           }
         }
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-  }  // tile loop
+  }
 }
 
 }  // namespace
