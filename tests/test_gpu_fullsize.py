@@ -206,3 +206,65 @@ def test_config3_recsys_mlp_tower_and_embedding_rows(gc, oracle):
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
     assert int(torch.count_nonzero(out)) == int(np.count_nonzero(want))
     ctx.destroy()
+
+
+def _check_dense_blocks(gc, oracle, g, e0, e, q, s, block, codec, blocks):
+    """The dense coder is block-local: codes, scale and residual of block b depend only on the
+    elements of block b, so the oracle checks any block on its own."""
+    n = g.numel()
+    bpb = (block + 7) // 8 if codec == 1 else block
+    for b in blocks:
+        a, z = b * block, min(n, (b + 1) * block)
+        gb = g[a:z]
+        g_np = inputs.bf16_bits(gb) if gb.dtype == torch.bfloat16 else gb.cpu().numpy()
+        e_np = e0[a:z].cpu().numpy().copy()
+        rc, oi, oq, osc = oracle.compress(g_np, e_np, z - a, block, codec=codec)
+        assert rc == 0
+        assert np.array_equal(q[b * bpb:b * bpb + oq.size].cpu().numpy(), oq), f"codes of block {b}"
+        assert np.array_equal(s[b:b + 1].cpu().numpy().view(np.uint32), osc.view(np.uint32)), f"scale of block {b}"
+        assert np.array_equal(e[a:z].cpu().numpy().view(np.uint32), e_np.view(np.uint32)), f"residual of block {b}"
+
+
+@pytest.mark.parametrize("config", [4, 5])
+def test_dense_sign_coder_at_benchmark_shapes(gc, oracle, config):
+    """gc_compress_dense with the 1-bit code (Eq. 10 over every entry) on the 1.3B bf16 and 7B fp32
+    gradients: sampled blocks against the oracle, and the identity d + e' == acc on every element."""
+    wl = inputs.workload(config)
+    free, _ = torch.cuda.mem_get_info()
+    need = wl.n * (12 if config == 5 else 10) + (8 << 30)
+    if free < need:
+        pytest.skip("not enough free HBM")
+    ctx = gc.Context(0)
+    g = wl.grad(0, 0, DEV)
+    e0 = wl.residual0(0, DEV)
+    if config == 4:
+        e0 = inputs.normal(wl.n, 1e-3, 4242, DEV)       # a built-up residual rather than zeros
+    e = e0.clone()
+    print(f"[case] dense sign coder config {config}: n={wl.n} block={wl.block} dtype={g.dtype}", flush=True)
+    q, s = gc.compress_dense(ctx, g, e, wl.block, codec=1)
+    gc.sync_status(ctx)
+    nblocks = (wl.n + wl.block - 1) // wl.block
+    assert s.numel() == nblocks and q.numel() == gc.num_code_bytes(wl.n, wl.block, 1)
+    rng = np.random.Generator(np.random.Philox(key=config))
+    blocks = sorted(set([0, 1, nblocks - 1, nblocks - 2] + rng.integers(0, nblocks, 60).tolist()))
+    _check_dense_blocks(gc, oracle, g, e0, e, q, s, wl.block, 1, blocks)
+    # every element: the sign sent is the sign of acc, and acc - (+-s) == e' in one fp32 subtraction
+    for a in range(0, wl.n, CH):
+        b = min(wl.n, a + CH)
+        assert a % wl.block == 0 and a % 8 == 0
+        acc = g[a:b].float() + e0[a:b]
+        sc = s[a // wl.block:(b + wl.block - 1) // wl.block].repeat_interleave(wl.block)[:b - a]
+        d = torch.where(acc >= 0, sc, -sc)
+        assert torch.equal((acc - d).view(torch.int32), e[a:b].view(torch.int32)), "residual != acc - sign * s"
+        del acc, sc, d
+    # aggregate of three copies (worker order) on a sampled range: 3 ordered fp32 adds of +-s
+    out = gc.decompress_sum_dense(ctx, [q, q, q], [s, s, s], wl.n, wl.block, codec=1)
+    torch.cuda.synchronize()
+    for b in blocks[:12]:
+        a, z = b * wl.block, min(wl.n, (b + 1) * wl.block)
+        acc = g[a:z].float() + e0[a:z]
+        d = torch.where(acc >= 0, s[b], -s[b])
+        want = (d + d) + d
+        assert torch.equal(out[a:z].view(torch.int32), want.view(torch.int32))
+    del out, g, e, e0
+    ctx.destroy()
