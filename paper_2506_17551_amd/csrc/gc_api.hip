@@ -187,11 +187,11 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
   P->est_chunks = est;
   // a group that gets more candidates than slots is re-read by the gather, so the slots only
   // need to cover the ordinary spread of the count
-  const double cap = std::ceil(3.0 * max_lambda + 6.0 * std::sqrt(max_lambda) + 4.0) + 1.0;
-  P->cap = (int32_t)std::min<double>(round_up((int64_t)cap, kSlotLine) - 1, (double)kGroup);
-  if (P->n_sampled == 0) P->cap = 1;
-  P->cap = std::min(P->cap, 4088);  // the LDS staging holds cap records (at most 32 KB)
-  P->slot_stride = (int32_t)round_up(P->cap + 1, kSlotLine);
+  const double cap = std::ceil(3.0 * max_lambda + 6.0 * std::sqrt(max_lambda) + 4.0);
+  P->cap = (int32_t)std::min<double>((double)round_up((int64_t)cap, kSlotLine), (double)kGroup);
+  if (P->n_sampled == 0) P->cap = kSlotLine;
+  P->cap = std::min(P->cap, 4096);  // the LDS staging holds cap records (at most 32 KB)
+  P->slot_stride = P->cap;           // whole 128-byte lines of records
   return P;
 }
 

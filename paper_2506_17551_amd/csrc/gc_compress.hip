@@ -285,9 +285,8 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
     tot += c;
   }
   // Candidates are staged in LDS in ascending index order and leave the workgroup as whole
-  // 128-byte lines (a header record with the count, then the candidates, padded with zero
-  // records): scattered 4-byte stores would turn into read-modify-write cycles in HBM and
-  // cost more than the bytes they carry.
+  // 128-byte lines of records, padded with zero records: scattered 8-byte stores would become
+  // partial-line writes in HBM and cost more than the bytes they carry.
   const uint32_t cap = (uint32_t)ws.cap;
   uint2* stage = reinterpret_cast<uint2*>(lds_dyn);
   if (tot) {
@@ -325,15 +324,13 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
     }
     __syncthreads();  // tot is uniform over the workgroup
   }
+  // The group's count goes to a compact array (plain 4-byte stores of neighbouring workgroups
+  // combine in L2); a group without candidates writes no records at all.
+  if (threadIdx.x == 0) ws.grp_cnt[grp] = tot;
   const uint32_t kept = min(tot, cap);
-  const uint32_t nout = (kept + kSlotLine) & ~(uint32_t)(kSlotLine - 1);  // header + candidates, whole lines
+  const uint32_t nout = (kept + kSlotLine - 1) & ~(uint32_t)(kSlotLine - 1);  // whole lines
   uint2* __restrict__ dst = ws.slots + grp * (int64_t)ws.slot_stride;
-  for (uint32_t j = threadIdx.x; j < nout; j += 256) {
-    uint2 rec = make_uint2(0u, 0u);
-    if (j == 0u) rec = make_uint2(tot, kept);  // all candidates of the group, and how many fit the slots
-    else if (j - 1u < kept) rec = stage[j - 1u];
-    dst[j] = rec;
-  }
+  for (uint32_t j = threadIdx.x; j < nout; j += 256) dst[j] = j < kept ? stage[j] : make_uint2(0u, 0u);
 }
 
 // ---------------------------------------------------------------- block-wise exclusive scan
@@ -388,7 +385,7 @@ __device__ __forceinline__ void block_sums_one(const uint32_t* __restrict__ v, l
   if (threadIdx.x == 0) part[b] = tot;
 }
 
-// Reads each group's header record, leaves the counts in a compact array and their block sums.
+// Block sums of the groups' candidate counts (groups of dense tensors count as zero).
 __global__ __launch_bounds__(256) void k_group_sums(Workspace ws) {
   __shared__ unsigned long long sh[4];
   const long long b = blockIdx.x;
@@ -399,8 +396,8 @@ __global__ __launch_bounds__(256) void k_group_sums(Workspace ws) {
     const long long grp = i0 + j;
     if (grp < ws.ngroups) {
       const bool sampled = ws.recs ? (ws.recs[grp].tensor >> 31) != 0u : true;
-      const uint32_t c = sampled ? ws.slots[grp * (long long)ws.slot_stride].x : 0u;
-      ws.grp_cnt[grp] = c;
+      const uint32_t c = sampled ? ws.grp_cnt[grp] : 0u;
+      if (!sampled) ws.grp_cnt[grp] = 0u;
       s += c;
     }
   }
@@ -504,7 +501,7 @@ __global__ __launch_bounds__(256) void k_gather(Workspace ws, const float* __res
         glen = (int)min((long long)kGroup, d.n - first);
         t_lo = ws.ts[t].t_lo;
       } else if (cnt != 0u) {
-        const uint2* __restrict__ rec = ws.slots + grp * (int64_t)ws.slot_stride + 1;
+        const uint2* __restrict__ rec = ws.slots + grp * (int64_t)ws.slot_stride;
         for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {  // all loads of a round are issued before the stores
           uint2 r[8];
 #pragma unroll

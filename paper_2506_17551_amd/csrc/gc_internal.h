@@ -92,12 +92,12 @@ struct Workspace {  // device pointers into the context's scratch
   unsigned long long* shist;  // [T][kSampleBins]
   unsigned long long* hist;   // [T][kSelBins]
   // streaming pass output
-  uint32_t* grp_cnt;                // [groups] candidates of each group
+  uint32_t* grp_cnt;                // [groups] candidates of each group (may exceed cap)
   unsigned long long* grp_part;     // [ceil(groups / kScanBlock)] block sums of grp_cnt
   long long* grp_off;               // [groups] exclusive prefix of grp_cnt (call-wide)
   long long* tg_base;               // [T + 1] grp_off at each tensor's first group; [T] = total
-  uint2* slots;                     // [groups][slot_stride] records: [0] = {candidates, stored},
-                                    // then {acc bits, offset inside the group} per candidate
+  uint2* slots;                     // [groups][slot_stride] records {acc bits, offset inside the group};
+                                    // a group writes min(count, cap) of them, none when it has none
   // dense candidate arrays (per-tensor regions)
   float* cand_val;
   long long* cand_idx;              // element index inside the tensor
@@ -116,7 +116,7 @@ struct Workspace {  // device pointers into the context's scratch
   uint32_t* flags;                  // [0] non-finite seen
   int32_t T;
   int32_t cap;                      // candidate slots per group
-  int32_t slot_stride;              // records per group: header + cap, rounded up to 16
+  int32_t slot_stride;              // records reserved per group (= cap, a multiple of 16)
   int32_t pad0_;
   int64_t ngroups;                  // group slots over all tensors
   int64_t nsgran;                   // sampled granules over all tensors
