@@ -476,14 +476,17 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
 }
 
 // ---------------------------------------------------------------- k_gather
-// One lane per group: copy the group's candidates to their place in the tensor's dense array.
-// A group with more candidates than slots (winners clustered in one stretch of the tensor) is
-// re-read from the residual, which holds acc by now, by the whole wavefront: 64 coalesced loads
-// and ballot-ordered appends. Only the tensor-wide totals can still send a tensor down the
-// dense route.
+// TEAM lanes per group copy the group's candidates to their place in the tensor's dense array:
+// one lane when a group holds at most one line of records (low density: most groups have one or
+// two), 16 lanes with coalesced loads and stores when it holds more. A group with more
+// candidates than slots (winners clustered in one stretch of the tensor) is re-read from the
+// residual, which holds acc by now, by the whole wavefront: 64 coalesced loads and ballot-ordered
+// appends. Only the tensor-wide totals can still send a tensor down the dense route.
+template <int TEAM>
 __global__ __launch_bounds__(256) void k_gather(Workspace ws, const float* __restrict__ e) {
   const int lane = threadIdx.x & 63;
-  const int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int sub = threadIdx.x % TEAM;  // lane inside the team
+  const int64_t grp = ((int64_t)blockIdx.x * 256 + threadIdx.x) / TEAM;
   bool big = false;
   long long dst = 0, first = 0, gbase = 0;
   int glen = 0;
@@ -496,22 +499,32 @@ __global__ __launch_bounds__(256) void k_gather(Workspace ws, const float* __res
       dst = d.cand_begin + (ws.grp_off[grp] - ws.tg_base[t]);
       first = (grp - d.group_begin) * (long long)kGroup;
       if (cnt > (uint32_t)ws.cap) {
-        big = true;
-        gbase = d.off + first;
-        glen = (int)min((long long)kGroup, d.n - first);
-        t_lo = ws.ts[t].t_lo;
+        if (sub == 0) {
+          big = true;
+          gbase = d.off + first;
+          glen = (int)min((long long)kGroup, d.n - first);
+          t_lo = ws.ts[t].t_lo;
+        }
       } else if (cnt != 0u) {
         const uint2* __restrict__ rec = ws.slots + grp * (int64_t)ws.slot_stride;
-        for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {  // all loads of a round are issued before the stores
-          uint2 r[8];
+        if (TEAM == 1) {
+          for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {  // all loads of a round are issued before the stores
+            uint2 r[8];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) r[u] = (j0 + u < cnt) ? rec[j0 + u] : make_uint2(0u, 0u);
+            for (int u = 0; u < 8; ++u) r[u] = (j0 + u < cnt) ? rec[j0 + u] : make_uint2(0u, 0u);
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            if (j0 + u < cnt) {
-              ws.cand_val[dst + j0 + u] = __uint_as_float(r[u].x);
-              ws.cand_idx[dst + j0 + u] = first + r[u].y;
+            for (int u = 0; u < 8; ++u) {
+              if (j0 + u < cnt) {
+                ws.cand_val[dst + j0 + u] = __uint_as_float(r[u].x);
+                ws.cand_idx[dst + j0 + u] = first + r[u].y;
+              }
             }
+          }
+        } else {
+          for (uint32_t j = sub; j < cnt; j += TEAM) {
+            const uint2 r = rec[j];
+            ws.cand_val[dst + j] = __uint_as_float(r.x);
+            ws.cand_idx[dst + j] = first + r.y;
           }
         }
       }
@@ -886,7 +899,10 @@ void launch_route(const Workspace& ws, hipStream_t s) {
 }
 
 void launch_gather(const Workspace& ws, const float* e, hipStream_t s) {
-  hipLaunchKernelGGL(k_gather, dim3((unsigned)((ws.ngroups + 255) / 256)), dim3(256), 0, s, ws, e);
+  const int team = ws.cap <= kSlotLine ? 1 : 16;  // 64 lanes per group measured no faster than 16
+  const dim3 grid((unsigned)((ws.ngroups * team + 255) / 256));
+  if (team == 1) hipLaunchKernelGGL(k_gather<1>, grid, dim3(256), 0, s, ws, e);
+  else hipLaunchKernelGGL(k_gather<16>, grid, dim3(256), 0, s, ws, e);
 }
 
 void launch_hist(const Workspace& ws, int level, const float* e, hipStream_t s) {

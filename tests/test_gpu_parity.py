@@ -94,7 +94,7 @@ def test_block_sizes(gc, ctx, oracle, block):
     assert np.array_equal(bits(out.cpu().numpy()), bits(want))
 
 
-@pytest.mark.parametrize("density", [1.0, 0.5, 0.126, 0.124, 0.05, 1e-4, 1e-6])
+@pytest.mark.parametrize("density", [1.0, 0.5, 0.126, 0.124, 0.05, 0.02, 0.01, 0.003, 1e-4, 1e-6])
 def test_densities(gc, ctx, oracle, density):
     n = 1_500_000
     k = gc.k_from_density(n, density)
