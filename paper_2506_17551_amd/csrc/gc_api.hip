@@ -160,7 +160,7 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
       d.sample_target = (uint32_t)std::min<double>(target, 4.0e9);
       max_lambda = std::max(max_lambda, target / m * (double)kGroup);  // candidates expected per group
       d.cand_cap = std::min<int64_t>(d.n, 4 * d.k + 4096);
-      cb += d.cand_cap;
+      cb += round_up(d.cand_cap, 4);  // every region starts 16-byte aligned (128-bit loads)
       est += (std::min<int64_t>(d.cand_cap, 2 * d.k) + kChunkElems - 1) / kChunkElems + 1;
       P->n_sampled++;
     } else {

@@ -606,9 +606,23 @@ __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const flo
     const TensorState st = ws.ts[t];
     const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
     const uint32_t want = (level == 0) ? 0u : (st.prefix >> pshift);
-    for (int j = lane; j < s.len; j += 64) {
-      const uint32_t key = key_of(s.val[j]);
-      if (level == 0 || (key >> pshift) == want) atomicAdd(&lh[(key >> shift) & mask], 1u);
+    if (s.len == kChunk && (reinterpret_cast<uintptr_t>(s.val) & 15u) == 0) {
+      // a full sub-chunk: four 128-bit loads per lane, all in flight before the first is used
+      f32x4 x[kChunk / 256];
+#pragma unroll
+      for (int u = 0; u < kChunk / 256; ++u) x[u] = *reinterpret_cast<const f32x4*>(s.val + u * 256 + lane * 4);
+#pragma unroll
+      for (int u = 0; u < kChunk / 256; ++u) {
+        const uint32_t key[4] = {key_of(x[u].x), key_of(x[u].y), key_of(x[u].z), key_of(x[u].w)};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (level == 0 || (key[c] >> pshift) == want) atomicAdd(&lh[(key[c] >> shift) & mask], 1u);
+      }
+    } else {
+      for (int j = lane; j < s.len; j += 64) {
+        const uint32_t key = key_of(s.val[j]);
+        if (level == 0 || (key >> pshift) == want) atomicAdd(&lh[(key >> shift) & mask], 1u);
+      }
     }
   }
   if (cur >= 0) {
@@ -647,6 +661,28 @@ __global__ __launch_bounds__(256) void k_count(Workspace ws, const float* __rest
     const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
     const uint32_t thr = st.prefix;
     uint32_t gt = 0, eq = 0;
+    if (s.len == kChunk && (reinterpret_cast<uintptr_t>(s.val) & 15u) == 0) {
+      f32x4 x[kChunk / 256];
+#pragma unroll
+      for (int u = 0; u < kChunk / 256; ++u) x[u] = *reinterpret_cast<const f32x4*>(s.val + u * 256 + lane * 4);
+      uint32_t g4 = 0, e4 = 0;  // per lane; only the sub-chunk's totals are needed here
+#pragma unroll
+      for (int u = 0; u < kChunk / 256; ++u) {
+        const uint32_t key[4] = {key_of(x[u].x), key_of(x[u].y), key_of(x[u].z), key_of(x[u].w)};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          g4 += key[c] > thr ? 1u : 0u;
+          e4 += key[c] == thr ? 1u : 0u;
+        }
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        g4 += __shfl_xor(g4, off);
+        e4 += __shfl_xor(e4, off);
+      }
+      gt = g4;
+      eq = e4;
+    } else
     for (int j0 = 0; j0 < s.len; j0 += 256) {
       uint32_t key[4];
       bool valid[4];
@@ -712,10 +748,24 @@ __global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restr
     const long long quota = (long long)st.k_rem;
     const long long ent = a * 4 + wave;
     long long G = ws.ch_goff[ent] - ws.tb_g[t], E = ws.ch_eoff[ent] - ws.tb_e[t];
-    for (int j0 = 0; j0 < s.len; j0 += 64) {
+    uint32_t run_blk = 0u, run_max = 0u;  // block whose maximum is being carried (0: none), wave-uniform
+    // the whole sub-chunk is requested before the first entry is used
+    constexpr int kIter = kChunk / 64;
+    float vals[kIter];
+    long long idxs[kIter];
+#pragma unroll
+    for (int u = 0; u < kIter; ++u) {
+      const int j = u * 64 + lane;
+      vals[u] = j < s.len ? s.val[j] : 0.0f;
+      idxs[u] = (s.idx && j < s.len) ? s.idx[j] : (s.first + j);
+    }
+#pragma unroll
+    for (int u = 0; u < kIter; ++u) {
+      const int j0 = u * 64;
+      if (j0 >= s.len) continue;  // uniform over the wavefront
       const int j = j0 + lane;
       const bool valid = j < s.len;
-      const float v = valid ? s.val[j] : 0.0f;
+      const float v = vals[u];
       const uint32_t key = key_of(v);
       const bool isgt = valid && key > thr, iseq = valid && key == thr;
       const uint64_t mg = __ballot(isgt), me = __ballot(iseq);
@@ -725,32 +775,52 @@ __global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restr
       if (keep) {
         const long long rel = grank + (erank < quota ? erank : quota);  // position inside the tensor
         const long long pos = d.kprefix + rel;
-        const long long within = s.idx ? s.idx[j] : (s.first + j);
-        out_idx[pos] = (I)(d.off + within);
+        out_idx[pos] = (I)(d.off + idxs[u]);
         ws.kept_val[pos] = v;
-        blk = (uint32_t)(d.sprefix + rel / block) + 1u;  // +1 so that 0 means "no entry"
+        // rel < k < 2^32, so the block number comes from one 32-bit division
+        blk = (uint32_t)d.sprefix + (uint32_t)rel / (uint32_t)block + 1u;  // +1 so that 0 means "no entry"
         bkey = key;
       }
-      // Per-block amax for the quantizer: kept positions ascend with the lane, so the lanes of
-      // one block form a contiguous run; a segmented max-scan leaves each run's maximum in its
-      // last lane, which alone touches memory (one atomic per block and wavefront iteration).
-      if (mg | me) {
+      // Per-block amax for the quantizer: one atomic per block and wavefront iteration. Kept
+      // positions ascend with the lane, so the lanes of one block form a contiguous run. Nearly
+      // always the whole iteration falls into one block: a plain wavefront maximum then does.
+      // Otherwise a segmented max-scan leaves each run's maximum in its last lane.
+      const uint64_t mk = __ballot(keep);
+      if (mk) {
+        const uint32_t blk_first = __shfl(blk, __ffsll((unsigned long long)mk) - 1);
+        if (__ballot(keep && blk != blk_first) == 0ull) {
+          uint32_t m = bkey;
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {  // lanes without an entry inherit the block to their left
-          const uint32_t ob = __shfl_up(blk, off);
-          if (lane >= off && blk == 0u) blk = ob;
-        }
+          for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+          // the maximum is carried over the iterations of the sub-chunk while the block stays
+          if (blk_first != run_blk) {
+            if (lane == 0 && run_blk != 0u && run_max != 0u) atomicMax(&ws.blk_amax[run_blk - 1u], run_max);
+            run_blk = blk_first;
+            run_max = 0u;
+          }
+          run_max = max(run_max, m);
+        } else {
+          if (lane == 0 && run_blk != 0u && run_max != 0u) atomicMax(&ws.blk_amax[run_blk - 1u], run_max);
+          run_blk = 0u;
+          run_max = 0u;
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-          const uint32_t ok = __shfl_up(bkey, off), ob = __shfl_up(blk, off);
-          if (lane >= off && ob == blk) bkey = max(bkey, ok);
+          for (int off = 1; off < 64; off <<= 1) {  // lanes without an entry inherit the block to their left
+            const uint32_t ob = __shfl_up(blk, off);
+            if (lane >= off && blk == 0u) blk = ob;
+          }
+#pragma unroll
+          for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t ok = __shfl_up(bkey, off), ob = __shfl_up(blk, off);
+            if (lane >= off && ob == blk) bkey = max(bkey, ok);
+          }
+          const uint32_t nb = __shfl_down(blk, 1);
+          if (blk != 0u && (lane == 63 || nb != blk) && bkey != 0u) atomicMax(&ws.blk_amax[blk - 1u], bkey);
         }
-        const uint32_t nb = __shfl_down(blk, 1);
-        if (blk != 0u && (lane == 63 || nb != blk) && bkey != 0u) atomicMax(&ws.blk_amax[blk - 1u], bkey);
       }
       G += __popcll(mg);
       E += __popcll(me);
     }
+    if (lane == 0 && run_blk != 0u && run_max != 0u) atomicMax(&ws.blk_amax[run_blk - 1u], run_max);
   }
 }
 
@@ -764,13 +834,14 @@ __global__ __launch_bounds__(256) void k_quant(Workspace ws, float* __restrict__
   const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
   if (j >= ktotal) return;
   const int t = find_last_le(ws.T, j, 0, [&](int i) { return (long long)ws.td[i].kprefix; });
-  const long long rel = j - ws.td[t].kprefix;
-  const long long blk = ws.td[t].sprefix + rel / block;
+  const uint32_t rel = (uint32_t)(j - ws.td[t].kprefix);  // < k < 2^32: 32-bit division
+  const uint32_t rblk = rel / (uint32_t)block;
+  const long long blk = ws.td[t].sprefix + rblk;
   const uint32_t akey = ws.blk_amax[blk];
   const bool finite = akey < 0x7F800000u;
   float s = __fdiv_rn(__uint_as_float(akey), 127.0f);
   if (!finite || !(s >= 1.17549435e-38f)) s = 0.0f;
-  if (rel % block == 0) {
+  if (rel == rblk * (uint32_t)block) {
     scales[blk] = s;
     if (!finite) ws.flags[0] = 1u;
   }
