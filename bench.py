@@ -9,7 +9,11 @@ workers' gradients at once (the 7B workload), each worker's gradient and residua
 are regenerated in place between the timed intervals, and a step's time is the sum
 of its W compress intervals and its decompress_sum interval.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric / value / unit (GB/s of gradient processed, whole job), ms_per_step,
+config (workload, sizes, per-phase times, variants), roofline (the streaming kernel k_main:
+algorithmic 12 B/element over its HIP-event time, against the 8 TB/s HBM peak, with the measured
+traffic from the committed counter summary), kernels (per-kernel HIP-event times of one extra step)
+and cpu_baseline (the CPU oracle on a bounded sample of the same workload).
 """
 from __future__ import annotations
 
