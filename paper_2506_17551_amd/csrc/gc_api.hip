@@ -355,7 +355,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   Plan* P = nullptr;
   gc_status st = get_plan(ctx, offsets, k, T, block, out->codec, &P);
   if (st != GC_OK) return st;
-  if (P->ngroups >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
+  if (xcd_run_grid(P->ngroups) >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
 
   Workspace ws;
   std::memset(&ws, 0, sizeof(ws));

@@ -206,7 +206,11 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
   extern __shared__ __align__(16) char lds_dyn[];
   __shared__ uint32_t wcnt[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t grp = blockIdx.x;
+  // Consecutive workgroups are dispatched to different compute dies (8 of them, round robin).
+  // Each die is given runs of kXcdRun consecutive groups, so the lines (and pages) one die's L2
+  // and TLB see are contiguous, while all dies together still move one window through memory.
+  const int64_t grp = xcd_run_index(blockIdx.x);
+  if (grp >= ws.ngroups) return;  // the grid is padded to whole rounds of runs
   long long gstart;  // first element of the group in the flat arrays
   int glen, t;
   bool sampled;
@@ -940,7 +944,7 @@ void launch_sample_thresh(const Workspace& ws, hipStream_t s) {
 }
 
 void launch_main(const Workspace& ws, const void* g, int dtype, float* e, hipStream_t s) {
-  const dim3 grid((unsigned)ws.ngroups);
+  const dim3 grid((unsigned)xcd_run_grid(ws.ngroups));
   const size_t pad = (size_t)std::max<int64_t>(ws.main_lds_pad, (int64_t)ws.cap * 8);
   const long long n_single = ws.recs ? 0 : ws.n_single;
   const int sampled_single = ws.nsgran > 0 ? 1 : 0;
@@ -970,7 +974,9 @@ void launch_route(const Workspace& ws, hipStream_t s) {
 }
 
 void launch_gather(const Workspace& ws, const float* e, hipStream_t s) {
-  const int team = ws.cap <= kSlotLine ? 1 : 16;  // 64 lanes per group measured no faster than 16
+  // measured: one lane per group is faster up to ~6 candidates per group (cap 48), 16 lanes from ~11
+  // (cap 64) on; 64 lanes per group are no faster than 16
+  const int team = ws.cap < 4 * kSlotLine ? 1 : 16;
   const dim3 grid((unsigned)((ws.ngroups * team + 255) / 256));
   if (team == 1) hipLaunchKernelGGL(k_gather<1>, grid, dim3(256), 0, s, ws, e);
   else hipLaunchKernelGGL(k_gather<16>, grid, dim3(256), 0, s, ws, e);
