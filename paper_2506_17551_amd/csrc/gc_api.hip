@@ -533,7 +533,7 @@ gc_status dense_common_check(gc_ctx* ctx, int64_t n, int32_t block, gc_codec cod
   if (!ctx || n <= 0 || block < 1) return GC_ERR_INVALID_ARG;
   if (codec != GC_CODEC_INT8 && codec != GC_CODEC_SIGN1) return GC_ERR_INVALID_ARG;
   if (block > kDenseMaxBlock) return GC_ERR_UNSUPPORTED;
-  if ((n + block - 1) / block >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
+  if ((n + block - 1) / block >= (int64_t(1) << 31) - (int64_t(1) << 20)) return GC_ERR_UNSUPPORTED;  // padded grid
   return GC_OK;
 }
 

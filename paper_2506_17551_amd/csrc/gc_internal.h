@@ -169,13 +169,18 @@ void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktot
 #endif
 constexpr int kXcds = 8;
 constexpr int kXcdRun = GC_XCD_RUN;
-__host__ __device__ inline int64_t xcd_run_grid(int64_t items) {
-  const int64_t round = (int64_t)kXcds * kXcdRun;
+__host__ __device__ inline int64_t xcd_run_grid(int64_t items, int64_t run = kXcdRun) {
+  const int64_t round = (int64_t)kXcds * run;
   return (items + round - 1) / round * round;
 }
-__device__ __forceinline__ int64_t xcd_run_index(int64_t b) {
+__device__ __forceinline__ int64_t xcd_run_index(int64_t b, int64_t run = kXcdRun) {
   const int64_t x = b % kXcds, l = b / kXcds;
-  return ((l / kXcdRun) * kXcds + x) * kXcdRun + (l % kXcdRun);
+  return ((l / run) * kXcds + x) * run + (l % run);
+}
+// Run length that gives a die about kXcdRun * 1024 consecutive elements at a time.
+__host__ __device__ inline int xcd_run_for(int64_t elems_per_item) {
+  const int64_t r = (int64_t)kXcdRun * 1024 / (elems_per_item > 0 ? elems_per_item : 1);
+  return (int)(r < 1 ? 1 : r);
 }
 
 // ---- small device helpers shared by the kernels ----------------------------
