@@ -932,7 +932,9 @@ void launch_init(const Workspace& ws, hipStream_t s) {
 }
 
 void launch_sample(const Workspace& ws, const void* g, int dtype, const float* e, hipStream_t s) {
-  const dim3 grid(clamp_grid((ws.nsgran + 3) / 4, 2048));
+  // every workgroup clears and flushes an 8192-bin histogram: 1024 workgroups measured best (256: the
+  // per-workgroup chain of loads gets long; 8192: the flushes dominate)
+  const dim3 grid(clamp_grid((ws.nsgran + 3) / 4, 1024));
   if (dtype == 0)
     hipLaunchKernelGGL(k_sample<float>, grid, dim3(256), 0, s, ws, (const float*)g, e);
   else
