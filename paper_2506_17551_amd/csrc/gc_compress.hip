@@ -976,9 +976,7 @@ void launch_route(const Workspace& ws, hipStream_t s) {
 }
 
 void launch_gather(const Workspace& ws, const float* e, hipStream_t s) {
-  // measured: one lane per group is faster up to ~6 candidates per group (cap 48), 16 lanes from ~11
-  // (cap 64) on; 64 lanes per group are no faster than 16
-  const int team = ws.cap < 4 * kSlotLine ? 1 : 16;
+  const int team = ws.gather_team;  // chosen by the plan from the expected candidates per group
   const dim3 grid((unsigned)((ws.ngroups * team + 255) / 256));
   if (team == 1) hipLaunchKernelGGL(k_gather<1>, grid, dim3(256), 0, s, ws, e);
   else hipLaunchKernelGGL(k_gather<16>, grid, dim3(256), 0, s, ws, e);
