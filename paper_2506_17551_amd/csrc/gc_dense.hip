@@ -228,10 +228,9 @@ __global__ __launch_bounds__(256) void k_dense(const G* __restrict__ g, float* _
 // multiple of 4 they share a block (one scale, one code word or one nibble per worker).
 // MODE 0: out = sum. MODE 1: theta -= fl32(step * sum) (Eq. 9).
 template <int CODEC, int MODE>
-__global__ __launch_bounds__(256) void k_dense_sum(DenseDecArgs a, int W, int32_t block, long long start,
-                                                   long long n, float* __restrict__ out, int weighted,
-                                                   float c_apply) {
-  const long long i0 = start + ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+__device__ __forceinline__ void dense_sum_quad(const DenseDecArgs& a, int W, int32_t block, long long i0,
+                                               long long n, float* __restrict__ out, int weighted,
+                                               float c_apply) {
   if (i0 >= n) return;
   const int bytes_per_block = (block + 7) >> 3;
   float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -316,6 +315,20 @@ __global__ __launch_bounds__(256) void k_dense_sum(DenseDecArgs a, int W, int32_
       if (MODE == 0) op[c] = sum[c];
       else op[c] = __fsub_rn(op[c], __fmul_rn(c_apply, sum[c]));
     }
+  }
+}
+
+// A workgroup covers kDenseSumIter * 1024 consecutive elements, 1024 at a time: larger contiguous
+// pieces per workgroup raise the store rate of this write-dominated kernel.
+constexpr int kDenseSumIter = 4;
+template <int CODEC, int MODE>
+__global__ __launch_bounds__(256) void k_dense_sum(DenseDecArgs a, int W, int32_t block, long long start,
+                                                   long long n, float* __restrict__ out, int weighted,
+                                                   float c_apply) {
+#pragma unroll 1
+  for (int it = 0; it < kDenseSumIter; ++it) {
+    const long long i0 = start + (((long long)blockIdx.x * kDenseSumIter + it) * 256 + threadIdx.x) * 4;
+    dense_sum_quad<CODEC, MODE>(a, W, block, i0, n, out, weighted, c_apply);
   }
 }
 
@@ -468,7 +481,7 @@ void launch_dense_sum(const DenseDecArgs& a, int W, int32_t block, int64_t n, in
       if (start >= n) return;
     }
   }
-  const dim3 grid((unsigned)((n - start + 1023) / 1024));
+  const dim3 grid((unsigned)((n - start + 1024 * kDenseSumIter - 1) / (1024 * kDenseSumIter)));
 #define GC_DSUM(C, M) \
   hipLaunchKernelGGL((k_dense_sum<C, M>), grid, dim3(256), 0, s, a, W, block, start, (long long)n, out, weighted, c_apply)
   if (codec == 0) {
