@@ -145,9 +145,10 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
     const bool sampled = d.n >= kMinSampledN && d.k >= kMinSampledK && d.k * kMaxDensityInv <= d.n;
     d.mode = sampled ? kSampled : kDense;
     if (sampled) {
-      // sample about 64 expected winners, between 1/256 and 1/4 of the data: a thin sample only
-      // makes the candidate list a little longer, and candidates are cheap
-      double f = 64.0 / (double)d.k;
+      // sample about 32 expected winners, between 1/256 and 1/4 of the data: a thin sample only
+      // makes the candidate list a little longer, and candidates are cheap (and a sample that
+      // undershoots only sends the tensor down the dense route, never changes the result)
+      double f = 32.0 / (double)d.k;
       f = std::min(0.25, std::max(1.0 / 256.0, f));
       const int64_t stride = std::max<int64_t>(4, std::min<int64_t>(256, (int64_t)std::floor(1.0 / f)));
       d.sample_stride = (int32_t)stride;
