@@ -135,7 +135,12 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
     d.qprefix = qp;
     qp += code_bytes(d.k, block, codec);
     d.group_begin = grp;
-    d.ngroups = (d.n + kGroup - 1) / kGroup;
+    // Groups lie on the grid of the FLAT buffer (boundaries at multiples of 4 elements from its
+    // start), so that only a tensor's first group can start unaligned: one odd-sized tensor must
+    // not push every later tensor onto the scalar path. With several tensors the first group is
+    // shortened by `group_shift` = off % 4 elements.
+    d.group_shift = T > 1 ? (int32_t)(d.off % 4) : 0;
+    d.ngroups = (d.group_shift + d.n + kGroup - 1) / kGroup;
     grp += d.ngroups;
     P->max_chunks += (d.n + kChunkElems - 1) / kChunkElems;
     kp += d.k;
@@ -175,8 +180,10 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
       const TensorDesc& d = P->td[t];
       for (int64_t lg = 0; lg < d.ngroups; ++lg) {
         GroupRec& r = P->recs[(size_t)(d.group_begin + lg)];
-        r.start = d.off + lg * kGroup;
-        r.len = (int32_t)std::min<int64_t>(kGroup, d.n - lg * kGroup);
+        const int64_t first = std::max<int64_t>(0, lg * kGroup - d.group_shift);  // inside the tensor
+        const int64_t next = std::min<int64_t>(d.n, (lg + 1) * kGroup - d.group_shift);
+        r.start = d.off + first;
+        r.len = (int32_t)(next - first);
         r.tensor = (uint32_t)t | (d.mode == kSampled ? 0x80000000u : 0u);
       }
     }

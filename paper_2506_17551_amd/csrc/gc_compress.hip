@@ -501,12 +501,13 @@ __global__ __launch_bounds__(256) void k_gather(Workspace ws, const float* __res
       const TensorDesc d = ws.td[t];
       const uint32_t cnt = ws.grp_cnt[grp];
       dst = d.cand_begin + (ws.grp_off[grp] - ws.tg_base[t]);
-      first = (grp - d.group_begin) * (long long)kGroup;
+      const long long lg = grp - d.group_begin;
+      first = max(0ll, lg * (long long)kGroup - d.group_shift);  // first element of the group in the tensor
       if (cnt > (uint32_t)ws.cap) {
         if (sub == 0) {
           big = true;
           gbase = d.off + first;
-          glen = (int)min((long long)kGroup, d.n - first);
+          glen = (int)(min((long long)d.n, (lg + 1) * (long long)kGroup - d.group_shift) - first);
           t_lo = ws.ts[t].t_lo;
         }
       } else if (cnt != 0u) {

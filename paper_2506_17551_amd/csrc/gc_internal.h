@@ -63,7 +63,7 @@ struct TensorDesc {
   int32_t mode;         // Mode
   int32_t sample_stride;   // one granule out of this many is sampled
   uint32_t sample_target;  // sample count that the candidate threshold must cover
-  uint32_t pad_;
+  int32_t group_shift;     // elements by which the tensor's first group is shortened (0..3)
 };
 
 // Per-tensor state of one compress call, zeroed by the first kernel of the call.
