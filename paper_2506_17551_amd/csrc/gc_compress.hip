@@ -92,6 +92,51 @@ __device__ __forceinline__ uint32_t mix_hash(uint64_t x) {
   return (uint32_t)(x >> 33);
 }
 
+// One sampled granule as a wavefront sees it: where it lies, and its 256 values once loaded.
+template <typename G>
+struct SampleItem {
+  int t;          // tensor (uniform over the workgroup), -1: no slot
+  bool active;    // this wavefront has a granule in the slot quadruple
+  float gv[4], ev[4];  // the lane's 4 gradient and residual values, as loaded (added when consumed)
+};
+
+template <typename G>
+__device__ __forceinline__ SampleItem<G> sample_fetch(const Workspace& ws, const G* __restrict__ g,
+                                                      const float* __restrict__ e, int64_t s0, int64_t s_end,
+                                                      int hint, int lane, int wave) {
+  SampleItem<G> it;
+  it.t = -1;
+  it.active = false;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) it.gv[c] = it.ev[c] = 0.0f;
+  if (s0 >= s_end) return it;
+  it.t = find_last_le(ws.T, s0, hint < 0 ? 0 : hint, [&](int i) { return (long long)ws.td[i].sgran_begin; });
+  const TensorDesc d = ws.td[it.t];
+  const int64_t ls = s0 + wave - d.sgran_begin;  // sgran_begin is a multiple of 4 and nsgran padded
+  if (ls >= d.nsgran) return it;
+  it.active = true;
+  const int64_t gran = ls * d.sample_stride + (int64_t)(mix_hash((uint64_t)ls) % (uint32_t)d.sample_stride);
+  const int64_t base = d.off + gran * kSampleGranule;
+  const G* gp = g + base;
+  const float* ep = e + base;
+  const bool aligned = ((reinterpret_cast<uintptr_t>(gp) & GradVec<G>::kAlignMask) == 0) &&
+                       ((reinterpret_cast<uintptr_t>(ep) & 15u) == 0);
+  if (aligned) {
+    const f32x4 gv = GradVec<G>::load(gp + lane * 4);
+    const f32x4 ev = *reinterpret_cast<const f32x4*>(ep + lane * 4);
+    it.gv[0] = gv.x; it.gv[1] = gv.y; it.gv[2] = gv.z; it.gv[3] = gv.w;
+    it.ev[0] = ev.x; it.ev[1] = ev.y; it.ev[2] = ev.z; it.ev[3] = ev.w;
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int j = c * 64 + lane;
+      it.gv[c] = load_grad<G>(gp, j);
+      it.ev[c] = ep[j];
+    }
+  }
+  return it;
+}
+
 template <typename G>
 __global__ __launch_bounds__(256) void k_sample(Workspace ws, const G* __restrict__ g,
                                                 const float* __restrict__ e) {
@@ -100,45 +145,33 @@ __global__ __launch_bounds__(256) void k_sample(Workspace ws, const G* __restric
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int cur = -1;
-  // A workgroup takes 4 consecutive sampled-granule slots per iteration, one per wavefront. Every
-  // tensor's slots start at a multiple of 4 and are padded to a multiple of 4, so one iteration
-  // never mixes tensors and the LDS histogram can be flushed when the tensor changes.
-  // each workgroup takes one contiguous run of slots, so it meets few tensors
+  // A workgroup takes 4 consecutive sampled-granule slots per step, one per wavefront. Every
+  // tensor's slots start at a multiple of 4 and are padded to a multiple of 4, so one step never
+  // mixes tensors and the LDS histogram can be flushed when the tensor changes. Each workgroup
+  // takes one contiguous run of slots, so it meets few tensors. Two steps are fetched before the
+  // first is histogrammed: the run is a chain of dependent round trips to memory otherwise.
   const int64_t per = ((ws.nsgran / 4 + gridDim.x - 1) / gridDim.x) * 4;
   const int64_t s_end = min(ws.nsgran, ((int64_t)blockIdx.x + 1) * per);
-  for (int64_t s0 = (int64_t)blockIdx.x * per; s0 < s_end; s0 += 4) {
-    const int t = find_last_le(ws.T, s0, cur < 0 ? 0 : cur, [&](int i) { return (long long)ws.td[i].sgran_begin; });
-    if (t != cur) {
+  auto consume = [&](const SampleItem<G>& it) {
+    if (it.t < 0) return;  // uniform over the workgroup
+    if (it.t != cur) {
       if (cur >= 0) {
         __syncthreads();
         flush_lds_hist<kSampleBins>(lh, ws.shist + (int64_t)cur * kSampleBins);
         __syncthreads();
       }
-      cur = t;
+      cur = it.t;
     }
-    const TensorDesc d = ws.td[t];
-    const int64_t ls = s0 + wave - d.sgran_begin;  // sgran_begin is a multiple of 4 and nsgran padded
-    if (ls >= d.nsgran) continue;
-    const int64_t gran = ls * d.sample_stride + (int64_t)(mix_hash((uint64_t)ls) % (uint32_t)d.sample_stride);
-    const int64_t base = d.off + gran * kSampleGranule;
-    const G* gp = g + base;
-    const float* ep = e + base;
-    const bool aligned = ((reinterpret_cast<uintptr_t>(gp) & GradVec<G>::kAlignMask) == 0) &&
-                         ((reinterpret_cast<uintptr_t>(ep) & 15u) == 0);
-    if (aligned) {
-      const f32x4 gv = GradVec<G>::load(gp + lane * 4);
-      const f32x4 ev = *reinterpret_cast<const f32x4*>(ep + lane * 4);
-      atomicAdd(&lh[key_of(__fadd_rn(gv.x, ev.x)) >> kSampleShift], 1u);
-      atomicAdd(&lh[key_of(__fadd_rn(gv.y, ev.y)) >> kSampleShift], 1u);
-      atomicAdd(&lh[key_of(__fadd_rn(gv.z, ev.z)) >> kSampleShift], 1u);
-      atomicAdd(&lh[key_of(__fadd_rn(gv.w, ev.w)) >> kSampleShift], 1u);
-    } else {
+    if (it.active) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int j = c * 64 + lane;
-        atomicAdd(&lh[key_of(__fadd_rn(load_grad<G>(gp, j), ep[j])) >> kSampleShift], 1u);
-      }
+      for (int c = 0; c < 4; ++c) atomicAdd(&lh[key_of(__fadd_rn(it.gv[c], it.ev[c])) >> kSampleShift], 1u);
     }
+  };
+  for (int64_t s0 = (int64_t)blockIdx.x * per; s0 < s_end; s0 += 8) {
+    const SampleItem<G> a = sample_fetch<G>(ws, g, e, s0, s_end, cur, lane, wave);
+    const SampleItem<G> b = sample_fetch<G>(ws, g, e, s0 + 4, s_end, a.t, lane, wave);
+    consume(a);
+    consume(b);
   }
   if (cur >= 0) {
     __syncthreads();
