@@ -142,7 +142,7 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
     d.group_shift = T > 1 ? (int32_t)(d.off % 4) : 0;
     d.ngroups = (d.group_shift + d.n + kGroup - 1) / kGroup;
     grp += d.ngroups;
-    P->max_chunks += (d.n + kChunkElems - 1) / kChunkElems;
+    P->max_chunks += (d.group_shift + d.n + kChunkElems - 1) / kChunkElems;
     kp += d.k;
     sp += (d.k + block - 1) / block;
     d.sgran_begin = sg;
@@ -171,7 +171,7 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
       est += (std::min<int64_t>(d.cand_cap, 2 * d.k) + kChunkElems - 1) / kChunkElems + 1;
       P->n_sampled++;
     } else {
-      est += (d.n + kChunkElems - 1) / kChunkElems;
+      est += (d.group_shift + d.n + kChunkElems - 1) / kChunkElems;
     }
   }
   if (T > 1) {

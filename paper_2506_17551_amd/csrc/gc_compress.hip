@@ -486,7 +486,7 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
         M = ws.tg_base[t + 1] - ws.tg_base[t];
         if (M >= d.k && M <= d.cand_cap) { use = 1u; vlen = M; }
       }
-      nch = (vlen + kChunkElems - 1) / kChunkElems;
+      nch = (vlen + (use ? 0 : d.group_shift) + kChunkElems - 1) / kChunkElems;
     }
     long long incl = nch;
 #pragma unroll
@@ -604,13 +604,19 @@ struct SubSrc {
 __device__ __forceinline__ SubSrc sub_source(const Workspace& ws, const TensorDesc& d, const TensorState& st,
                                              long long lchunk, int wave, const float* e) {
   SubSrc s;
-  const long long pos = lchunk * kChunkElems + (long long)wave * kChunk;
-  s.len = (int)max(0ll, min((long long)kChunk, st.vlen - pos));
-  s.first = pos;
+  const long long grid_pos = lchunk * kChunkElems + (long long)wave * kChunk;
   if (st.use_cand) {
-    s.val = ws.cand_val + d.cand_begin + pos;
-    s.idx = ws.cand_idx + d.cand_begin + pos;
+    s.len = (int)max(0ll, min((long long)kChunk, st.vlen - grid_pos));
+    s.first = grid_pos;
+    s.val = ws.cand_val + d.cand_begin + grid_pos;
+    s.idx = ws.cand_idx + d.cand_begin + grid_pos;
   } else {
+    // the residual is cut on the flat buffer's 16-byte grid (as the groups are): only the
+    // tensor's first sub-chunk can start unaligned
+    const long long pos = max(0ll, grid_pos - d.group_shift);
+    const long long end = min((long long)st.vlen, grid_pos + kChunk - d.group_shift);
+    s.len = (int)max(0ll, end - pos);
+    s.first = pos;
     s.val = e + d.off + pos;
     s.idx = nullptr;
   }
