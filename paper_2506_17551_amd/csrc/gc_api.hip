@@ -104,8 +104,8 @@ int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 // ---- plan ------------------------------------------------------------------
 // Tensors large and sparse enough get their candidates from a sampled threshold in
 // the single streaming pass; the rest are selected from the dense residual.
-constexpr int64_t kMinSampledN = 1 << 17;
-constexpr int64_t kMinSampledK = 64;
+constexpr int64_t kMinSampledN = 1 << 15;
+constexpr int64_t kMinSampledK = 32;
 constexpr int64_t kMaxDensityInv = 8;  // sampled only if k * 8 <= n
 
 int64_t code_bytes(int64_t k, int32_t block, int32_t codec) {
@@ -157,7 +157,7 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
       f = std::min(0.25, std::max(1.0 / 256.0, f));
       const int64_t stride = std::max<int64_t>(4, std::min<int64_t>(256, (int64_t)std::floor(1.0 / f)));
       d.sample_stride = (int32_t)stride;
-      d.nsgran = (d.n / kSampleGranule) / stride;  // whole granules only; >= 8 since n >= 2^17
+      d.nsgran = (d.n / kSampleGranule) / stride;  // whole granules only; >= 1: k * 8 <= n bounds the stride by n / 256
       sg += round_up(d.nsgran, 4);
       const double m = (double)d.nsgran * kSampleGranule;
       const double ks = (double)d.k * m / (double)d.n;

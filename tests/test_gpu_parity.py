@@ -74,7 +74,8 @@ def test_config1_three_error_feedback_steps(gc, ctx, oracle):
 
 # ---------------------------------------------------------------------------------- sizes and tails
 @pytest.mark.parametrize("n,k", [(1, 1), (2, 1), (63, 5), (64, 64), (65, 1), (1023, 100), (1024, 1024),
-                                 (1025, 7), (4097, 4097), (131071, 131), (131072, 1311), (131073, 64),
+                                 (1025, 7), (4097, 4097), (32767, 33), (32768, 32), (32768, 31), (32769, 330), (65536, 66),
+                                 (131071, 131), (131072, 1311), (131073, 64),
                                  (200003, 2001), (1 << 20, 1), (1048583, 10486), (3000017, 3001)])
 def test_ragged_sizes(gc, ctx, oracle, n, k):
     g = inputs.normal(n, 1.0, n + k)
