@@ -623,3 +623,45 @@ def test_random_shapes(gc, ctx, oracle):
         else:
             check_compress(gc, ctx, oracle, g, e, k, block, index_bits=64 if case % 5 == 0 else 32,
                            tag=f"random {case}")
+
+
+# ---------------------------------------------------------------------------------- closed loop
+@pytest.mark.parametrize("codec", [0, 1])
+def test_closed_loop_sgd_with_error_feedback(gc, ctx, oracle, codec):
+    """Eq. 11 (compress with residual), Eq. 8/12 (damped aggregate) and Eq. 9 (update) chained for 12
+    steps of data-parallel SGD on a least-squares problem with three workers. The workers' gradients
+    are computed once per step (on the device, from the device's parameters) and the same bytes go
+    to both sides, so the parameters must stay bit-identical step after step; the loss must fall."""
+    torch.manual_seed(1234)
+    d, rows, W, block, density, step = 40_000, 64, 3, 128, 0.02, 0.25
+    k = gc.k_from_density(d, density)
+    A = [torch.randn(rows, d, device=DEV) / d ** 0.5 for _ in range(W)]
+    x_true = torch.randn(d, device=DEV)
+    b = [a @ x_true for a in A]
+    theta = torch.zeros(d, device=DEV)
+    theta_ref = theta.cpu().numpy().copy()
+    res = [torch.zeros(d, device=DEV) for _ in range(W)]
+    res_ref = [np.zeros(d, np.float32) for _ in range(W)]
+    stale = [0, 1, 0]
+
+    def loss():
+        return float(sum(((a @ theta - bb) ** 2).sum() for a, bb in zip(A, b)))
+
+    first = loss()
+    for it in range(12):
+        bufs, refs = [], []
+        for w in range(W):
+            g = (A[w].t() @ (A[w] @ theta - b[w])).contiguous()
+            buf = gc.compress(ctx, g, res[w], k, block, codec=codec)
+            rc, idx, q, s = oracle.compress(g.cpu().numpy(), res_ref[w], k, block, codec=codec)
+            assert rc == 0
+            bufs.append(buf)
+            refs.append((idx, q, s))
+        gc.decompress_apply(ctx, bufs, theta, step / W, staleness=stale)
+        gc.sync_status(ctx)
+        rc, S = oracle.decompress_sum(refs, d, block, staleness=stale, codec=codec)
+        assert rc == 0 and oracle.apply(theta_ref, S, np.float32(step / W)) == 0
+        assert np.array_equal(bits(theta.cpu().numpy()), bits(theta_ref)), f"parameters diverge at step {it}"
+        for w in range(W):
+            assert np.array_equal(bits(res[w].cpu().numpy()), bits(res_ref[w])), f"residual {w} at step {it}"
+    assert loss() < 0.8 * first
