@@ -242,7 +242,12 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
   const size_t ngp = (ng + kScanBlock - 1) / kScanBlock, ncp = (nent + kScanBlock - 1) / kScanBlock;
   if (st == GC_OK) st = ensure(ctx->ts, sizeof(TensorState) * T);
   if (st == GC_OK) st = ensure(ctx->shist, sizeof(unsigned long long) * (size_t)T * kSampleBins);
-  if (st == GC_OK) st = ensure(ctx->hist, sizeof(unsigned long long) * (size_t)T * kSelBins);
+  if (st == GC_OK) {  // the select histograms must start zeroed; every call leaves them zeroed again
+    const void* before = ctx->hist.p;
+    st = ensure(ctx->hist, sizeof(unsigned long long) * (size_t)T * kSelBins);
+    if (st == GC_OK && ctx->hist.p != before && hipMemset(ctx->hist.p, 0, ctx->hist.bytes) != hipSuccess)
+      st = GC_ERR_DEVICE;
+  }
   if (st == GC_OK) st = ensure(ctx->grp_cnt, sizeof(uint32_t) * ng);
   if (st == GC_OK) st = ensure(ctx->grp_part, sizeof(unsigned long long) * ngp);
   if (st == GC_OK) st = ensure(ctx->grp_off, sizeof(long long) * ng);

@@ -61,9 +61,11 @@ __device__ __forceinline__ unsigned long long block_sum(unsigned long long v, un
 __global__ __launch_bounds__(256) void k_init(Workspace ws) {
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  const int64_t ns = (int64_t)ws.T * kSampleBins, nh = (int64_t)ws.T * kSelBins;
-  for (int64_t i = tid; i < ns; i += stride) ws.shist[i] = 0ull;
-  for (int64_t i = tid; i < nh; i += stride) ws.hist[i] = 0ull;
+  const int64_t ns = ws.nsgran > 0 ? (int64_t)ws.T * kSampleBins : 0;
+  // sample histograms of the sampled tensors only; the select histograms are left zeroed by the
+  // last digit's scan of the previous call (and are zero-filled when they are allocated)
+  for (int64_t i = tid; i < ns; i += stride)
+    if (ws.td[i / kSampleBins].mode == kSampled) ws.shist[i] = 0ull;
   for (int64_t i = tid; i < ws.nblocks; i += stride) ws.blk_amax[i] = 0u;
   for (int64_t i = tid; i < ws.T; i += stride) {
     TensorState z;
