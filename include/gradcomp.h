@@ -217,7 +217,7 @@ gc_status gc_profile_read(gc_ctx* ctx, int32_t id, double* total_ms, int64_t* la
 /* Tuning knobs; the defaults are chosen for MI355X and results never depend on them.
  *   "main_lds_pad"  bytes of dynamic LDS requested by the streaming pass, used only to bound how
  *                   many of its workgroups share a compute unit (0..65536; default 16384).
- *   "dense_lds_pad" the same for the dense coder (0..65536; default -1: chosen by block size).
+ *   "dense_lds_pad" the same for the dense coder (0..65536, or -1: chosen by block size and code; default -1).
  *   "dense_wave_block"  dense coder: blocks of up to this many elements are held by one wavefront,
  *                   larger ones by a workgroup (0..2048; default 1024).
  * Unknown names or out-of-range values return GC_ERR_INVALID_ARG. */
