@@ -369,6 +369,38 @@ int gco_decompress_sum_codec(int32_t W, const void* const* idx, const int8_t* co
   return GCO_OK;
 }
 
+// Aggregate of W workers' row-sparse buffers over a given set of rows (R10): urows holds Ru
+// ascending unique row ids that contain every row any buffer touches; out is Ru x D and
+// out[r * D + c] is the worker-ordered fp32 sum of the decoded values at table position
+// urows[r] * D + c, exactly as the dense aggregate would hold there. A pair whose row is not
+// in urows is an error.
+int gco_decompress_sum_rows(int32_t W, const void* const* idx, const int8_t* const* q,
+                            const float* const* scales, const int64_t* kcount, int32_t block,
+                            int32_t index_bits, const int64_t* urows, int64_t Ru, int64_t D,
+                            const int32_t* staleness, float* out, int32_t codec) {
+  if (W < 1 || !idx || !kcount || !urows || Ru < 1 || D < 1) return GCO_ERR_INVALID_ARG;
+  if (index_bits != 32 && index_bits != 64) return GCO_ERR_INVALID_ARG;
+  for (int64_t r = 1; r < Ru; ++r)
+    if (urows[r] <= urows[r - 1]) return GCO_ERR_INVALID_ARG;
+  std::vector<std::vector<uint64_t>> compact(static_cast<size_t>(W));
+  std::vector<const void*> cptr(static_cast<size_t>(W));
+  for (int32_t w = 0; w < W; ++w) {
+    compact[w].resize(static_cast<size_t>(kcount[w] > 0 ? kcount[w] : 1));
+    for (int64_t j = 0; j < kcount[w]; ++j) {
+      const uint64_t pos = (index_bits == 32) ? static_cast<const uint32_t*>(idx[w])[j]
+                                              : static_cast<const uint64_t*>(idx[w])[j];
+      const int64_t row = static_cast<int64_t>(pos / static_cast<uint64_t>(D));
+      const int64_t col = static_cast<int64_t>(pos % static_cast<uint64_t>(D));
+      const int64_t* it = std::lower_bound(urows, urows + Ru, row);
+      if (it == urows + Ru || *it != row) return GCO_ERR_INVALID_ARG;
+      compact[w][j] = static_cast<uint64_t>((it - urows) * D + col);
+    }
+    cptr[w] = compact[w].data();
+  }
+  return gco_decompress_sum_codec(W, cptr.data(), q, scales, kcount, block, 64, nullptr, 0, staleness, out,
+                                  Ru * D, codec);
+}
+
 int gco_decompress_sum_weighted(int32_t W, const void* const* idx, const int8_t* const* q,
                                 const float* const* scales, const int64_t* kcount, int32_t block,
                                 int32_t index_bits, const int64_t* ktensor, int32_t T,

@@ -71,6 +71,11 @@ def lib() -> ctypes.CDLL:
                                         ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                         ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_int32]
+        L.gco_decompress_sum_rows.restype = ctypes.c_int
+        L.gco_decompress_sum_rows.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                              ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.c_int32]
         L.gco_apply.restype = ctypes.c_int
         L.gco_apply.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_int64]
         _lib = L
@@ -178,6 +183,30 @@ def decompress_sum(bufs, n: int, block: int, ktensor=None, staleness=None, codec
     rc = lib().gco_decompress_sum_codec(W, ctypes.addressof(ia), ctypes.addressof(qa),
                                         ctypes.addressof(sa), _ptr(kc), int(block), index_bits, ktp, T,
                                         stp, _ptr(out), int(n), int(codec))
+    return rc, out
+
+
+def decompress_sum_rows(bufs, urows, D: int, block: int, staleness=None, codec: int = INT8):
+    """bufs: (idx, q, scales) triples whose idx are table positions (row * D + column); urows:
+    ascending unique rows containing every touched row. Returns (status, out) with out (len(urows), D)."""
+    W = len(bufs)
+    index_bits = 32 if bufs[0][0].dtype == np.uint32 else 64
+    PA = ctypes.c_void_p * W
+    ia = PA(*[_ptr(b[0]) for b in bufs])
+    qa = PA(*[_ptr(b[1]) for b in bufs])
+    sa = PA(*[_ptr(b[2]) for b in bufs])
+    kc = np.array([b[0].shape[0] for b in bufs], dtype=np.int64)
+    ur = np.ascontiguousarray(urows, dtype=np.int64)
+    out = np.empty((ur.shape[0], int(D)), dtype=np.float32)
+    if staleness is not None:
+        st = np.ascontiguousarray(staleness, dtype=np.int32)
+        assert st.shape[0] == W
+        stp = _ptr(st)
+    else:
+        stp = None
+    rc = lib().gco_decompress_sum_rows(W, ctypes.addressof(ia), ctypes.addressof(qa), ctypes.addressof(sa),
+                                       _ptr(kc), int(block), index_bits, _ptr(ur), ur.shape[0], int(D), stp,
+                                       _ptr(out), int(codec))
     return rc, out
 
 

@@ -656,3 +656,51 @@ def test_rows_argument_errors(oracle):
     rc, *_ = oracle.compress_rows(v, e, np.array([1, 2], dtype=np.int64), 9, 4, index_bits=32)
     assert rc == oracle.ERR_INVALID_ARG
     assert not e.any()
+
+
+def _pow2_buf(idx, vals):
+    """A buffer whose entries decode exactly to `vals` (powers of two): block 1, q = +-127."""
+    vals = f32(vals)
+    q = np.where(vals >= 0, 127, -127).astype(np.int8)
+    s = (np.abs(vals) / np.float32(127.0)).astype(np.float32)
+    return np.array(idx, dtype=np.uint32), q, s
+
+
+def test_golden_rows_aggregate(oracle):
+    G = read_golden("rows_step.txt")
+    b0 = _pow2_buf([int(x) for x in G["idx"]], [1.0, -1.0, 0.5])
+    b1 = _pow2_buf([int(x) for x in G["agg_idx1"]], G["agg_val1"])
+    assert np.array_equal(dequant(b0[1], b0[2], 1), f32([1.0, -1.0, 0.5]))      # the premise of the fixture
+    urows = np.array([int(x) for x in G["agg_urows"]], dtype=np.int64)
+    rc, out = oracle.decompress_sum_rows([b0, b1], urows, int(G["D"][0]), 1)
+    assert rc == oracle.OK
+    assert np.array_equal(out.reshape(-1), f32(G["agg_out"]))
+
+
+@pytest.mark.parametrize("codec", [0, 1])
+def test_rows_aggregate_is_the_dense_aggregate_on_those_rows(oracle, codec):
+    rng = np.random.default_rng(77 + codec)
+    R, D, block, W = 60, 8, 16, 4
+    bufs, touched = [], []
+    for w in range(W):
+        U = int(rng.integers(2, 20))
+        rows = np.sort(rng.choice(R, size=U, replace=False)).astype(np.int64)
+        vals = inputs.normal(U * D, 1.0, 700 + w).numpy()
+        e = np.zeros((R, D), np.float32)
+        k = int(rng.integers(1, U * D + 1))
+        rc, idx, q, s = oracle.compress_rows(vals, e, rows, k, block, index_bits=32, codec=codec)
+        assert rc == oracle.OK
+        bufs.append((idx, q, s))
+        touched.append(rows)
+    urows = np.union1d(np.concatenate(touched), np.array([0, R - 1]))          # two rows nobody may have sent
+    stale = [0, 2, 0, 5]
+    rc, dense = oracle.decompress_sum(bufs, R * D, block, staleness=stale, codec=codec)
+    rc2, out = oracle.decompress_sum_rows(bufs, urows, D, block, staleness=stale, codec=codec)
+    assert rc == rc2 == oracle.OK
+    assert np.array_equal(out.view(np.uint32), dense.reshape(R, D)[urows].view(np.uint32))
+    rest = np.setdiff1d(np.arange(R), urows)
+    assert not dense.reshape(R, D)[rest].any()                                   # nothing lies outside the union
+    # a row that is missing from the list is an error, not a silent drop
+    missing = np.setdiff1d(urows, touched[0][:1])
+    rc3, _ = oracle.decompress_sum_rows(bufs, missing, D, block, codec=codec)
+    assert rc3 == oracle.ERR_INVALID_ARG
