@@ -169,6 +169,17 @@ gc_status gc_compress_rows(gc_ctx* ctx, const void* vals, gc_dtype dtype, float*
                            const int64_t* rows, int64_t U, int64_t D, int64_t R, int64_t k, int32_t block,
                            const gc_buf* out, void* hip_stream);
 
+/* Aggregate of W workers' row-sparse buffers (as gc_compress_rows writes them: indices are table
+ * positions row * D + column) over a given list of rows instead of the whole table: urows holds Ru
+ * ascending unique row ids (DEVICE memory, int64) that contain every row any buffer touches, and
+ * out (Ru * D fp32, fully overwritten) receives out[r * D + c] = sum over w, in worker order and in
+ * fp32, of worker w's decoded value at table position urows[r] * D + c - what gc_decompress_sum
+ * would leave in those rows of the dense table. staleness: W host entries or NULL (Eq. 12, as in
+ * gc_decompress_sum_weighted). Ru * D < 2^32. A pair whose row is missing from urows is reported by
+ * gc_sync_status() as GC_ERR_INVALID_ARG (the output is then unspecified). */
+gc_status gc_decompress_sum_rows(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* urows, int64_t Ru,
+                                 int64_t D, const int32_t* staleness, float* out, void* hip_stream);
+
 /* Dense codes with error feedback: every entry is sent, so nothing is selected and there is no
  * index list. With GC_CODEC_SIGN1 this is the paper's 1-bit quantizer (Sec. III.B, Eq. 10: the signs
  * and one scale derived from the l1 norm) applied to the whole accumulated gradient, with the residual

@@ -38,7 +38,7 @@ class _GcStats(ctypes.Structure):
 
 EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_num_code_bytes", "gc_compress",
            "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_multi", "gc_decompress_sum_weighted",
-           "gc_decompress_apply", "gc_compress_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
+           "gc_decompress_apply", "gc_compress_rows", "gc_decompress_sum_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
            "gc_sync_status",
            "gc_last_stats", "gc_profile_enable", "gc_profile_num_kernels", "gc_profile_kernel_name",
            "gc_profile_read", "gc_set_option", "gc_status_string"]
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
     L.gc_decompress_sum_weighted.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, i64, vp]
     L.gc_decompress_apply.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, ctypes.c_float, i64, vp]
     L.gc_compress_rows.argtypes = [vp, vp, ctypes.c_int, vp, vp, i64, i64, i64, i64, i32, ctypes.POINTER(_GcBuf), vp]
+    L.gc_decompress_sum_rows.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i64, i64, vp, vp, vp]
     L.gc_compress_dense.argtypes = [vp, vp, ctypes.c_int, vp, i64, i32, ctypes.c_int, vp, vp, vp]
     L.gc_decompress_sum_dense.argtypes = [vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, i64, vp]
     L.gc_decompress_apply_dense.argtypes = [vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, ctypes.c_float, i64, vp]
@@ -85,7 +86,7 @@ def lib() -> ctypes.CDLL:
     L.gc_status_string.restype = ctypes.c_char_p
     for name in ("gc_create", "gc_destroy", "gc_compress", "gc_compress_multi", "gc_decompress_sum",
                  "gc_decompress_sum_multi", "gc_decompress_sum_weighted", "gc_decompress_apply",
-                 "gc_compress_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
+                 "gc_compress_rows", "gc_decompress_sum_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
                  "gc_sync_status", "gc_last_stats", "gc_profile_enable",
                  "gc_profile_read"):
         getattr(L, name).restype = ctypes.c_int
@@ -367,6 +368,26 @@ def compress_rows(ctx: Context, vals: torch.Tensor, residual_table: torch.Tensor
                                 rows.data_ptr(), U, D, R, int(k), int(block), ctypes.byref(st),
                                 _stream_ptr(stream, vals.device))
     _check(rc, "gc_compress_rows")
+    return out
+
+
+def decompress_sum_rows(ctx: Context, bufs: List[CompressedBuf], urows: torch.Tensor, D: int,
+                        staleness: Optional[Sequence[int]] = None, out: Optional[torch.Tensor] = None,
+                        stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """gc_decompress_sum_rows: the aggregate of row-sparse buffers on the rows `urows` (ascending unique
+    int64 on the device, containing every touched row). Returns (len(urows), D) fp32."""
+    _check_dev(urows, "urows", torch.int64)
+    Ru = urows.numel()
+    if out is None:
+        out = torch.empty((Ru, int(D)), dtype=torch.float32, device=urows.device)
+    _check_dev(out, "out", torch.float32)
+    st = None if staleness is None else np.ascontiguousarray(staleness, dtype=np.int32)
+    if st is not None and st.shape[0] != len(bufs):
+        raise ValueError("one staleness per buffer")
+    rc = lib().gc_decompress_sum_rows(ctx.handle, _buf_array(bufs), len(bufs), urows.data_ptr(), Ru, int(D),
+                                      None if st is None else st.ctypes.data, out.data_ptr(),
+                                      _stream_ptr(stream, urows.device))
+    _check(rc, "gc_decompress_sum_rows")
     return out
 
 

@@ -50,6 +50,7 @@ struct gc_ctx {
   std::vector<DecPlan*> dplans;
   // workspace (sized for the largest plan seen)
   DevBuf rows_e, rows_idx;  // compact residual and compact positions of a row-sparse step
+  DevBuf rows_cidx;         // compact positions of all workers' pairs (aggregate over a row list)
   DevBuf ts, shist, hist, grp_cnt, grp_part, grp_off, tg_base, slots, cand_val, cand_idx, ch_gt,
       ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, blk_amax, flags, bounds;
   uint32_t* host_flags = nullptr;  // pinned
@@ -588,7 +589,7 @@ gc_status dense_sum_impl(gc_ctx* ctx, const void* const* q, const float* const* 
 const char* const kKernelNames[kKNum] = {"k_init", "k_sample", "k_sample_thresh", "k_main", "k_group_sums", "k_group_scan",
                                          "k_route", "k_gather", "k_hist", "k_select_scan", "k_count",
                                          "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_bounds", "k_dec_tiles",
-                                         "k_dense", "k_dense_sum", "k_rows_gather", "k_rows_finish"};
+                                         "k_dense", "k_dense_sum", "k_rows_gather", "k_rows_finish", "k_rows_remap"};
 
 }  // namespace
 
@@ -629,7 +630,7 @@ gc_status gc_destroy(gc_ctx* c) {
   DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
                    &c->slots, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
                    &c->ch_part_gt, &c->ch_part_eq, &c->ch_goff, &c->ch_eoff, &c->tb_g, &c->tb_e,
-                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->bounds, &c->rows_e, &c->rows_idx};
+                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->bounds, &c->rows_e, &c->rows_idx, &c->rows_cidx};
   for (DevBuf* b : all) release(*b);
   if (c->host_flags) (void)hipHostFree(c->host_flags);
   if (c->host_ts) (void)hipHostFree(c->host_ts);
@@ -737,6 +738,39 @@ gc_status gc_compress_rows(gc_ctx* ctx, const void* vals, gc_dtype dtype, float*
                        out->index_bits, s);
   }
   return launch_status();
+}
+
+gc_status gc_decompress_sum_rows(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* urows, int64_t Ru,
+                                 int64_t D, const int32_t* staleness, float* out, void* hip_stream) {
+  if (!ctx || !bufs || !urows || !out || W < 1 || Ru < 1 || D < 1) return GC_ERR_INVALID_ARG;
+  if (W > kMaxWorkers) return GC_ERR_UNSUPPORTED;
+  if (D > (int64_t(1) << 32) || Ru > (int64_t(1) << 32) || Ru * D >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(urows) % 8) return GC_ERR_INVALID_ARG;
+  int64_t ktotal = 0;
+  for (int32_t w = 0; w < W; ++w) {
+    const gc_buf& b = bufs[w];
+    if (b.k < 0 || b.k >= (int64_t(1) << 32) || (b.index_bits != 32 && b.index_bits != 64) || b.reserved_ != 0)
+      return GC_ERR_INVALID_ARG;
+    if (b.k > 0 && (!b.indices || !b.q || !b.scales)) return GC_ERR_INVALID_ARG;
+    ktotal += b.k;
+  }
+  GC_HIP(hipSetDevice(ctx->device));
+  gc_status st = ensure(ctx->rows_cidx, sizeof(uint32_t) * (size_t)std::max<int64_t>(ktotal, 1));
+  if (st != GC_OK) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  std::vector<gc_buf> tmp(bufs, bufs + W);
+  uint32_t* cidx = (uint32_t*)ctx->rows_cidx.p;
+  int64_t at = 0;
+  for (int32_t w = 0; w < W; ++w) {
+    Scope sc(ctx, kKRowsRemap, s);
+    launch_rows_remap(bufs[w].indices, bufs[w].index_bits, bufs[w].k, reinterpret_cast<const long long*>(urows), Ru, D,
+                      cidx + at, (uint32_t*)ctx->flags.p, s);
+    tmp[w].indices = cidx + at;
+    tmp[w].index_bits = 32;
+    tmp[w].n = Ru * D;
+    at += bufs[w].k;
+  }
+  return decompress_impl(ctx, tmp.data(), W, nullptr, 0, staleness, false, 0.0f, out, Ru * D, hip_stream);
 }
 
 gc_status gc_compress_dense(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual, int64_t n,

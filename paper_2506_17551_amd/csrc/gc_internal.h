@@ -139,7 +139,7 @@ struct OutBuf {
 // kernel ids for profiling
 enum KernelId : int32_t {
   kKInit = 0, kKSample, kKSampleThresh, kKMain, kKGroupSums, kKGroupScan, kKRoute, kKGather, kKHist,
-  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecBounds, kKDecTiles, kKDense, kKDenseSum, kKRowsGather, kKRowsFinish, kKNum
+  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecBounds, kKDecTiles, kKDense, kKDenseSum, kKRowsGather, kKRowsFinish, kKRowsRemap, kKNum
 };
 
 // launchers (defined in the .hip files next to their kernels)
@@ -256,6 +256,8 @@ void launch_dense_sum(const DenseDecArgs& a, int W, int32_t block, int64_t n, in
 // ---- row-sparse gradients (touched rows of a table-shaped residual) ----------
 void launch_rows_gather(const float* table, const long long* rows, int64_t U, int64_t D, int64_t R, float* ec,
                         uint32_t* flags, hipStream_t s);
+void launch_rows_remap(const void* idx, int index_bits, int64_t k, const long long* urows, int64_t Ru, int64_t D,
+                       uint32_t* out, uint32_t* flags, hipStream_t s);
 void launch_rows_finish(float* table, const long long* rows, int64_t U, int64_t D, int64_t R, const float* ec,
                         const uint32_t* compact_idx, int64_t k, void* out_idx, int index_bits, hipStream_t s);
 

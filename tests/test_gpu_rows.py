@@ -185,3 +185,53 @@ def test_rows_bad_ids_are_reported_not_dereferenced(gc, ctx):
             gc.compress_rows(ctx, vals, table, rows, kwargs.get("k", 4), kwargs.get("block", 4))
         assert ei.value.status == status
     assert torch.count_nonzero(table).item() == 0
+
+
+@pytest.mark.parametrize("codec", [0, 1])
+def test_rows_aggregate_over_the_union_of_rows(gc, ctx, oracle, codec):
+    """gc_decompress_sum_rows: five workers with overlapping Zipf row sets on one table shape; the
+    output over the union of rows (plus two listed rows nobody touched) against the oracle, with
+    and without staleness, and against the dense aggregate gathered at those rows."""
+    R, D, block, W = 300_000, 128, 256, 5
+    bufs, refs, touched = [], [], []
+    for w in range(W):
+        rows = inputs.zipf_unique_rows(30_000, R, 1.1, inputs.seed_for(3, w, 7, 1))
+        vals = inputs.normal(rows.size * D, 0.01, inputs.seed_for(3, w, 7, 2))
+        k = gc.k_from_density(rows.size * D, 0.01)
+        buf, ref, _ = check_rows(gc, ctx, oracle, vals, torch.zeros(R, D), rows, k, block, codec=codec, tag=f"agg w{w}")
+        bufs.append(buf)
+        refs.append(ref)
+        touched.append(rows)
+    urows = np.union1d(np.concatenate(touched), np.array([R - 2, R - 1]))
+    ur = torch.from_numpy(urows).to(DEV)
+    stale = [0, 1, 4, 0, 2]
+    out = gc.decompress_sum_rows(ctx, bufs, ur, D)
+    outw = gc.decompress_sum_rows(ctx, bufs, ur, D, staleness=stale)
+    dense = gc.decompress_sum(ctx, bufs, R * D)
+    gc.sync_status(ctx)
+    rc, want = oracle.decompress_sum_rows(refs, urows, D, block, codec=codec)
+    rc2, wantw = oracle.decompress_sum_rows(refs, urows, D, block, staleness=stale, codec=codec)
+    assert rc == 0 and rc2 == 0
+    assert np.array_equal(bits(out.cpu().numpy()), bits(want))
+    assert np.array_equal(bits(outw.cpu().numpy()), bits(wantw))
+    assert torch.equal(dense.reshape(R, D)[ur].view(torch.int32), out.view(torch.int32))
+    assert int(torch.count_nonzero(dense)) == int(torch.count_nonzero(out))
+
+
+def test_rows_aggregate_reports_a_missing_row(gc, ctx):
+    from paper_2506_17551_amd import binding
+    R, D = 1000, 8
+    rows = torch.tensor([3, 10, 500], dtype=torch.int64, device=DEV)
+    vals = inputs.normal(3 * D, 1.0, 5).to(DEV)
+    buf = gc.compress_rows(ctx, vals, torch.zeros(R, D, device=DEV), rows, 6, 4)
+    gc.sync_status(ctx)
+    for listed in ([3, 10], [10, 500, 900], [0, 1, 2]):
+        ur = torch.tensor(listed, dtype=torch.int64, device=DEV)
+        out = gc.decompress_sum_rows(ctx, [buf], ur, D)
+        assert gc.sync_status(ctx, raise_on_error=False) == binding.GC_ERR_INVALID_ARG
+        assert out.shape == (len(listed), D)
+    out = gc.decompress_sum_rows(ctx, [buf], rows, D)
+    assert gc.sync_status(ctx, raise_on_error=False) == binding.GC_OK
+    with pytest.raises(binding.GradCompError) as ei:
+        gc.decompress_sum_rows(ctx, [buf] * 65, rows, D)
+    assert ei.value.status == binding.GC_ERR_UNSUPPORTED
