@@ -105,7 +105,9 @@ __device__ __forceinline__ void load_bounds(const uint32_t* __restrict__ bounds,
 __device__ __forceinline__ TileBounds scan_bounds(uint32_t lo, uint32_t hi, int lane) {
   TileBounds b;
   b.lo = lo;
-  b.cnt = hi > lo ? hi - lo : 0u;  // (unsorted indices break the caller's contract; stay in range anyway)
+  // every bound lies in [0, k], so a pair number below lo + cnt is always a valid one; unsorted
+  // indices (which break the caller's contract) can only make hi < lo, and then the tile is skipped
+  b.cnt = hi > lo ? hi - lo : 0u;
   uint32_t incl = b.cnt;  // inclusive scan over lanes
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -134,7 +136,6 @@ __device__ __forceinline__ PairLoad load_pairs(const DecArgs& a, uint32_t s0, in
                                               const long long* __restrict__ qprefix, int T, int codec) {
   PairLoad c;
   c.p = locate_pair(s0, lane, b.total, W, b.excl, b.cnt, b.lo);
-  if (c.p.active && c.p.j >= a.k[c.p.w]) c.p.active = false;  // never read past a worker's pairs
   c.gi = 0ull;
   c.s = 0.0f;
   c.code = 0u;
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(DecArgs a, int W, 
         // theta - fl32(c * sum). Untouched positions have sum +0 and would not change anyway.
         for (uint32_t s0 = 0; s0 < cur.total; s0 += 64) {
           const LanePair p = locate_pair(s0, lane, cur.total, W, cur.excl, cur.cnt, cur.lo);
-          if (p.active && p.j < a.k[p.w]) {
+          if (p.active) {
             const I* idx = static_cast<const I*>(a.indices[p.w]);
             const unsigned long long gi = (unsigned long long)idx[p.j];
             const uint32_t pos = (uint32_t)(gi - (unsigned long long)base);
