@@ -700,13 +700,13 @@ gc_status gc_compress_rows(gc_ctx* ctx, const void* vals, gc_dtype dtype, float*
                            const gc_buf* out, void* hip_stream) {
   if (!ctx || !vals || !residual_table || !rows || !out) return GC_ERR_INVALID_ARG;
   if (U < 1 || D < 1 || R < 1 || U > R || block < 1) return GC_ERR_INVALID_ARG;
-  if (D > (int64_t(1) << 32) || R > (int64_t(1) << 40)) return GC_ERR_UNSUPPORTED;
-  const int64_t m = U * D;                       // compact length: its positions must fit 32 bits
-  if (m >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
+  int64_t m = 0, table = 0;  // compact length (its positions must fit 32 bits) and table length
+  if (__builtin_mul_overflow(U, D, &m) || m >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
+  if (__builtin_mul_overflow(R, D, &table) || table >= (int64_t(1) << 62)) return GC_ERR_UNSUPPORTED;
   if (k < 1 || k > m) return GC_ERR_INVALID_ARG;
-  if (out->n != R * D || out->k != k || out->block != block) return GC_ERR_INVALID_ARG;
+  if (out->n != table || out->k != k || out->block != block) return GC_ERR_INVALID_ARG;
   if (out->index_bits != 32 && out->index_bits != 64) return GC_ERR_INVALID_ARG;
-  if (out->index_bits == 32 && R * D > (int64_t(1) << 32)) return GC_ERR_INVALID_ARG;
+  if (out->index_bits == 32 && table > (int64_t(1) << 32)) return GC_ERR_INVALID_ARG;
   if (!out->indices || !out->q || !out->scales) return GC_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(rows) % 8) || (reinterpret_cast<uintptr_t>(residual_table) % 4) ||
       (reinterpret_cast<uintptr_t>(out->indices) % (out->index_bits / 8)))
@@ -744,7 +744,8 @@ gc_status gc_decompress_sum_rows(gc_ctx* ctx, const gc_buf* bufs, int32_t W, con
                                  int64_t D, const int32_t* staleness, float* out, void* hip_stream) {
   if (!ctx || !bufs || !urows || !out || W < 1 || Ru < 1 || D < 1) return GC_ERR_INVALID_ARG;
   if (W > kMaxWorkers) return GC_ERR_UNSUPPORTED;
-  if (D > (int64_t(1) << 32) || Ru > (int64_t(1) << 32) || Ru * D >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
+  int64_t m = 0;  // length of the compact aggregate: its positions must fit 32 bits
+  if (__builtin_mul_overflow(Ru, D, &m) || m >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(urows) % 8) return GC_ERR_INVALID_ARG;
   int64_t ktotal = 0;
   for (int32_t w = 0; w < W; ++w) {
@@ -767,10 +768,10 @@ gc_status gc_decompress_sum_rows(gc_ctx* ctx, const gc_buf* bufs, int32_t W, con
                       cidx + at, (uint32_t*)ctx->flags.p, s);
     tmp[w].indices = cidx + at;
     tmp[w].index_bits = 32;
-    tmp[w].n = Ru * D;
+    tmp[w].n = m;
     at += bufs[w].k;
   }
-  return decompress_impl(ctx, tmp.data(), W, nullptr, 0, staleness, false, 0.0f, out, Ru * D, hip_stream);
+  return decompress_impl(ctx, tmp.data(), W, nullptr, 0, staleness, false, 0.0f, out, m, hip_stream);
 }
 
 gc_status gc_compress_dense(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* residual, int64_t n,

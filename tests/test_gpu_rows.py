@@ -235,3 +235,24 @@ def test_rows_aggregate_reports_a_missing_row(gc, ctx):
     with pytest.raises(binding.GradCompError) as ei:
         gc.decompress_sum_rows(ctx, [buf] * 65, rows, D)
     assert ei.value.status == binding.GC_ERR_UNSUPPORTED
+
+
+def test_rows_size_products_are_checked_without_overflow(gc, ctx):
+    """U * D, R * D and Ru * D beyond 64 bits are refused by the size checks, before any launch
+    (the pointers only need to be non-null and aligned: nothing is dereferenced)."""
+    import ctypes
+    from paper_2506_17551_amd import binding
+    L = binding.lib()
+    vals = torch.zeros(64, device=DEV)
+    rows = torch.zeros(8, dtype=torch.int64, device=DEV)
+    buf = gc.CompressedBuf.allocate(64, 4, 1, 4, 64, DEV)
+    raw = buf.struct()
+    for U, D, R in [(1 << 33, 1 << 31, 1 << 40), (1 << 20, 1 << 44, 1 << 20), (2, 1 << 31, 1 << 33), (1 << 32, 1 << 32, 1 << 32)]:
+        st = L.gc_compress_rows(ctx.handle, vals.data_ptr(), 0, vals.data_ptr(), rows.data_ptr(), U, D, R, 4, 4,
+                                ctypes.byref(raw), None)
+        assert st == binding.GC_ERR_UNSUPPORTED, (U, D, R, st)
+    arr = (type(raw) * 1)(raw)
+    for Ru, D in [(1 << 32, 1 << 32), (1 << 40, 1 << 30), (3, 1 << 62), (1 << 16, 1 << 16)]:
+        st = L.gc_decompress_sum_rows(ctx.handle, arr, 1, rows.data_ptr(), Ru, D, None, vals.data_ptr(), None)
+        assert st == binding.GC_ERR_UNSUPPORTED, (Ru, D, st)
+    assert gc.sync_status(ctx, raise_on_error=False) == binding.GC_OK
