@@ -167,8 +167,16 @@ __device__ __forceinline__ PairLoad load_pairs(const DecArgs& a, uint32_t s0, in
   return c;
 }
 
-// Adds one round of pairs into the wavefront's LDS tile, worker by worker, so that equal indices
-// of different workers are added in ascending worker order.
+__device__ __forceinline__ void wave_sync() {  // orders the wavefront's own LDS accesses
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// Adds one round of pairs into the wavefront's LDS tile so that equal indices of different workers
+// are added in ascending worker order: one LDS float add (round to nearest even, denormals kept,
+// like the plain fp32 add) per worker present in the round, issued back to back. The LDS executes
+// a wavefront's instructions in the order they were issued, so nothing has to wait in between, and
+// within one worker the indices are unique, so the lanes of one instruction never collide.
 __device__ __forceinline__ void add_pairs(const DecArgs& a, const PairLoad& c, int64_t base, int codec,
                                           int weighted, float* lt) {
   float val = 0.0f;
@@ -179,15 +187,16 @@ __device__ __forceinline__ void add_pairs(const DecArgs& a, const PairLoad& c, i
     else val = ((c.code >> (8 + (c.code & 7u))) & 1u) ? c.s : -c.s;
     if (weighted) val = __fdiv_rn(val, a.denom[c.p.w]);  // Eq. 12: a stale worker counts for less
   }
-  const uint64_t act = __ballot(c.p.active);
-  if (act == 0ull) return;
-  const int w_first = __shfl(c.p.w, __ffsll((unsigned long long)act) - 1);
-  const int w_last = __shfl(c.p.w, 63 - __clzll((unsigned long long)act));
+  const bool act = c.p.active && pos < (uint32_t)kDecTile;
+  const uint64_t am = __ballot(act);
+  if (am == 0ull) return;
+  const int w_first = __shfl(c.p.w, __ffsll((unsigned long long)am) - 1);
+  const int w_last = __shfl(c.p.w, 63 - __clzll((unsigned long long)am));
   for (int w = w_first; w <= w_last; ++w) {
-    if (c.p.active && c.p.w == w && pos < (uint32_t)kDecTile) lt[pos] = __fadd_rn(lt[pos], val);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    if (act && c.p.w == w) (void)__hip_atomic_fetch_add(lt + pos, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    __builtin_amdgcn_wave_barrier();  // keeps the instructions in this order
   }
+  wave_sync();
 }
 
 // MODE 0: out[tile] = sum (dense write).  MODE 1: theta[i] -= c * sum[i] at the touched i only.

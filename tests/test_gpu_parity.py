@@ -285,6 +285,35 @@ def test_decompress_sum_sixteen_workers_with_collisions(gc, ctx, oracle):
     assert np.all(np.abs(got - ref64) <= np.maximum(np.maximum(1e-6 * np.abs(ref64), ulp), (W - 1) * 2.0 ** -24 * mag))
 
 
+@pytest.mark.parametrize("codec", [0, 1])
+def test_decompress_sum_cancellation_down_to_subnormals(gc, ctx, oracle, codec):
+    """Workers that keep the same positions with alternating signs, scaled so that the block scales
+    sit just above the smallest normal fp32: the partial sums cancel into the subnormal range, where
+    a flushed or differently rounded add would show."""
+    n, k, block, W = 300_007, 6000, 64, 6
+    hot = inputs.normal(n, 1.0, 4242)
+    bufs, refs = [], []
+    for w in range(W):
+        g = (inputs.normal(n, 0.3, 70 + w) + 2.0 * hot) * (2e-37 if w % 2 == 0 else -2e-37)
+        if codec == 0:
+            buf, ref, _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, block, tag=f"cancel w{w}")
+        else:
+            buf, ref = check_compress_sign(gc, ctx, oracle, g, torch.zeros(n), k, block, tag=f"cancel w{w}")
+        bufs.append(buf)
+        refs.append(ref)
+    for Wsub in (2, 3, 6):
+        out = gc.decompress_sum(ctx, bufs[:Wsub], n)
+        outw = gc.decompress_sum_weighted(ctx, bufs[:Wsub], [0, 1, 0, 2, 0, 1][:Wsub], n)
+        torch.cuda.synchronize()
+        rc, want = oracle.decompress_sum(refs[:Wsub], n, block, codec=codec)
+        rc2, wantw = oracle.decompress_sum(refs[:Wsub], n, block, staleness=[0, 1, 0, 2, 0, 1][:Wsub], codec=codec)
+        assert rc == 0 and rc2 == 0
+        assert np.array_equal(bits(out.cpu().numpy()), bits(want)), Wsub
+        assert np.array_equal(bits(outw.cpu().numpy()), bits(wantw)), Wsub
+    tiny = np.abs(want[want != 0])
+    assert (tiny < 1.1754944e-38).sum() > 20  # subnormal sums do occur
+
+
 def test_decompress_sum_edge_shapes(gc, ctx, oracle):
     for n, k in ((1, 1), (2047, 3), (2048, 2048), (2049, 1), (10000, 10000), (300000, 1)):
         g = inputs.normal(n, 1.0, n)
