@@ -52,7 +52,8 @@ struct gc_ctx {
   DevBuf rows_e, rows_idx;  // compact residual and compact positions of a row-sparse step
   DevBuf rows_cidx;         // compact positions of all workers' pairs (aggregate over a row list)
   DevBuf ts, shist, hist, grp_cnt, grp_part, grp_off, tg_base, slots, cand_val, cand_idx, ch_gt,
-      ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, blk_amax, flags, bounds;
+      ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, blk_amax, flags;
+  DevBuf dec_brk, dec_rec, dec_tile_start;  // aggregate: range brackets, packed pair records, first record of every tile
   uint32_t* host_flags = nullptr;  // pinned
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
   size_t host_ts_cap = 0;
@@ -509,6 +510,7 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   }
   DecArgs a;
   std::memset(&a, 0, sizeof(a));
+  int64_t nrec = 0;  // pairs of all workers
   for (int32_t w = 0; w < W; ++w) {
     const gc_buf& b = bufs[w];
     if (b.n != n || b.block != block || b.index_bits != ib || b.codec != codec || b.k < 0 || b.reserved_ != 0)
@@ -520,6 +522,7 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     a.q[w] = b.q;
     a.scales[w] = b.scales;
     a.k[w] = (uint32_t)b.k;
+    nrec += b.k;
     a.denom[w] = 1.0f;
     if (staleness) {
       if (staleness[w] < 0 || staleness[w] > (1 << 24)) return GC_ERR_INVALID_ARG;  // 1 + tau exact in fp32
@@ -529,7 +532,11 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   GC_HIP(hipSetDevice(ctx->device));
   const int64_t ntiles = (n + kDecTile - 1) / kDecTile;
   if (ntiles >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
-  gc_status st = ensure(ctx->bounds, sizeof(uint32_t) * (size_t)(ntiles + 1) * W);
+  const int tb = dec_range_tiles(W, nrec, n);
+  const int64_t nranges = (ntiles + tb - 1) / tb;
+  gc_status st = ensure(ctx->dec_brk, sizeof(uint32_t) * (size_t)(nranges + 1) * W);
+  if (st == GC_OK) st = ensure(ctx->dec_rec, sizeof(uint2) * (size_t)std::max<int64_t>(nrec, 1));
+  if (st == GC_OK) st = ensure(ctx->dec_tile_start, sizeof(unsigned long long) * (size_t)(ntiles + 1));
   if (st != GC_OK) return st;
   DecPlan* D = nullptr;
   if (T > 1) {
@@ -537,12 +544,17 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     if (st != GC_OK) return st;
   }
   hipStream_t s = (hipStream_t)hip_stream;
-  { Scope sc(ctx, kKDecBounds, s); launch_dec_bounds(a, W, ib, ntiles, (uint32_t*)ctx->bounds.p, s); }
+  { Scope sc(ctx, kKDecBrackets, s); launch_dec_brackets(a, W, ib, tb, ntiles, (uint32_t*)ctx->dec_brk.p, s); }
+  {
+    Scope sc(ctx, kKDecPack, s);
+    launch_dec_pack(a, W, ib, tb, block, ntiles, (const uint32_t*)ctx->dec_brk.p, D ? (const long long*)D->kprefix.p : nullptr,
+                    D ? (const long long*)D->sprefix.p : nullptr, D ? (const long long*)D->qprefix.p : nullptr,
+                    D ? T : 1, codec, staleness ? 1 : 0, ctx->dec_rec.p, (unsigned long long*)ctx->dec_tile_start.p, s);
+  }
   {
     Scope sc(ctx, kKDecTiles, s);
-    launch_dec_tiles(a, W, ib, block, n, ntiles, (const uint32_t*)ctx->bounds.p,
-                     D ? (const long long*)D->kprefix.p : nullptr, D ? (const long long*)D->sprefix.p : nullptr,
-                     D ? (const long long*)D->qprefix.p : nullptr, D ? T : 1, codec, out, staleness ? 1 : 0, apply ? 1 : 0, c_apply, s);
+    launch_dec_tiles(ctx->dec_rec.p, (const unsigned long long*)ctx->dec_tile_start.p, (uint64_t)nrec, n, ntiles, out,
+                     apply ? 1 : 0, c_apply, s);
   }
   return launch_status();
 }
@@ -588,7 +600,7 @@ gc_status dense_sum_impl(gc_ctx* ctx, const void* const* q, const float* const* 
 
 const char* const kKernelNames[kKNum] = {"k_init", "k_sample", "k_sample_thresh", "k_main", "k_group_sums", "k_group_scan",
                                          "k_route", "k_gather", "k_hist", "k_select_scan", "k_count",
-                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_bounds", "k_dec_tiles",
+                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_brackets", "k_dec_pack", "k_dec_tiles",
                                          "k_dense", "k_dense_sum", "k_rows_gather", "k_rows_finish", "k_rows_remap"};
 
 }  // namespace
@@ -630,7 +642,7 @@ gc_status gc_destroy(gc_ctx* c) {
   DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
                    &c->slots, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
                    &c->ch_part_gt, &c->ch_part_eq, &c->ch_goff, &c->ch_eoff, &c->tb_g, &c->tb_e,
-                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->bounds, &c->rows_e, &c->rows_idx, &c->rows_cidx};
+                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->dec_brk, &c->dec_rec, &c->dec_tile_start, &c->rows_e, &c->rows_idx, &c->rows_cidx};
   for (DevBuf* b : all) release(*b);
   if (c->host_flags) (void)hipHostFree(c->host_flags);
   if (c->host_ts) (void)hipHostFree(c->host_ts);

@@ -1,20 +1,36 @@
 // Decompress-and-sum: the aggregate of W workers' compressed gradients as a dense
 // fp32 vector (paper Sec. III.B, Eq. 8 without the 1/P), for gfx950.
 //
-//   k_dec_bounds  for every output tile and every worker, the first pair whose index falls
-//                 in the tile (bracketed binary search in the worker's ascending index list).
-//   k_dec_tiles   one wavefront per tile of kDecTile output floats held in LDS: the pairs of
-//                 all workers that fall in the tile are decoded in parallel across lanes and
-//                 added into the LDS tile worker by worker (ascending), then the tile is
-//                 written out once with 128-bit stores. Every output byte is written exactly
-//                 once; there is no separate memset and no global atomic. Because indices are
-//                 unique inside one worker's buffer, the adds of one worker never collide, and
-//                 the fixed worker order makes the fp32 sum reproducible bit for bit.
+// The workers' pairs arrive as W separate sorted lists (3 arrays each). Reading them tile by tile
+// means dozens of short reads from as many arrays per tile, which bounds the kernel by memory
+// latency, not by the 4 bytes per element it has to write. So the pairs are first merged into ONE
+// stream that is already in the order the tiles consume it:
+//
+//   k_dec_brackets  for every range of `tb` output tiles and every worker, the first pair whose
+//                   index falls in the range (binary search in the worker's ascending index list).
+//   k_dec_pack      one workgroup per range: finds, in LDS, where every (tile, worker) segment
+//                   starts, decodes the range's pairs (coalesced reads along each worker's list)
+//                   and writes them as 8-byte records {position in tile | worker << 16, value},
+//                   ordered by tile, then worker, then index. tile_start[t] is the first record
+//                   of tile t. All of a range's records lie in one window of the stream.
+//   k_dec_tiles     one wavefront per tile of kDecTile output floats held in LDS: reads the
+//                   tile's run of records with coalesced loads, adds them into the LDS tile worker
+//                   by worker (ascending), then writes the tile once with 128-bit stores. Every
+//                   output byte is written exactly once; there is no separate memset and no global
+//                   atomic. Indices are unique inside one worker's buffer, so the adds of one
+//                   worker never collide, and the fixed worker order makes the fp32 sum
+//                   reproducible bit for bit.
+//
+// Index lists that break the contract (not ascending, duplicates, out of range) give an unspecified
+// sum, but every access stays inside the caller's and the library's arrays: records are only
+// written inside their segment, and positions and workers read back from records are range-checked.
 #include "gc_internal.h"
 
 namespace gc {
 namespace {
 
+static_assert(kDecTile <= 65536, "a record keeps the position in 16 bits");
+static_assert(kMaxWorkers <= 65536, "a record keeps the worker in 16 bits");
 
 template <typename I>
 __device__ __forceinline__ uint32_t lower_bound_idx(const I* __restrict__ idx, uint32_t lo, uint32_t hi,
@@ -26,28 +42,190 @@ __device__ __forceinline__ uint32_t lower_bound_idx(const I* __restrict__ idx, u
   return lo;
 }
 
-// bounds[tile * W + w] = first pair of worker w whose index is >= tile * kDecTile, for tile in
-// [0, ntiles]. A workgroup covers 256 consecutive tiles of all workers: 2W lanes bracket the
-// workgroup's range with full binary searches, then every (tile, worker) is searched inside its
-// worker's bracket (a few hundred pairs that stay in cache). Consecutive threads write
-// consecutive entries, so the table leaves the chip as whole lines.
+// brk[r * W + w] = first pair of worker w whose index is >= r * tb * kDecTile, for r in [0, nranges].
 template <typename I>
-__global__ __launch_bounds__(256) void k_dec_bounds(DecArgs a, int W, int64_t ntiles,
-                                                    uint32_t* __restrict__ bounds) {
-  __shared__ uint32_t s_br[2][kMaxWorkers];
-  const int64_t t0 = (int64_t)blockIdx.x * 256;
-  if ((int)threadIdx.x < 2 * W) {
-    const int w = threadIdx.x % W, side = threadIdx.x / W;
-    s_br[side][w] = lower_bound_idx<I>(static_cast<const I*>(a.indices[w]), 0u, a.k[w],
-                                       (unsigned long long)(t0 + 256 * side) * kDecTile);
+__global__ __launch_bounds__(256) void k_dec_brackets(DecArgs a, int W, int tb, int64_t nranges,
+                                                      uint32_t* __restrict__ brk) {
+  const int64_t flat = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (flat >= (nranges + 1) * W) return;
+  const int w = (int)(flat % W);
+  const int64_t r = flat / W;
+  brk[flat] = lower_bound_idx<I>(static_cast<const I*>(a.indices[w]), 0u, a.k[w],
+                                 (unsigned long long)r * (unsigned long long)tb * kDecTile);
+}
+
+// The wavefronts of a workgroup share out the workers (several wavefronts per worker when there are
+// few workers); every lane issues the loads of a batch of pairs before it uses any of them.
+#ifndef GC_PACK_THREADS
+#define GC_PACK_THREADS 256
+#endif
+#ifndef GC_PACK_BATCH
+#define GC_PACK_BATCH 4
+#endif
+constexpr int kPackThreads = GC_PACK_THREADS, kPackWaves = kPackThreads / 64;
+constexpr int kPackBatch = GC_PACK_BATCH;  // pairs per lane whose loads are issued before any is used
+
+template <typename I>
+__global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int tb, int32_t block, int64_t ntiles,
+                                                           const uint32_t* __restrict__ brk,
+                                                           const long long* __restrict__ kprefix,
+                                                           const long long* __restrict__ sprefix,
+                                                           const long long* __restrict__ qprefix, int T, int codec,
+                                                           int weighted, uint2* __restrict__ rec,
+                                                           unsigned long long* __restrict__ tile_start) {
+  extern __shared__ uint32_t s_dyn[];
+  uint32_t* s_lo = s_dyn;                  // [tb + 1][W]: first pair of worker w at or after local tile t
+  uint32_t* s_off = s_dyn + (tb + 1) * W;  // [tb][W]: first record of segment (t, w) inside the range
+  __shared__ uint32_t s_br0[kMaxWorkers], s_excl[kMaxWorkers + 1], s_wave[kPackThreads / 64];
+  __shared__ unsigned long long s_base;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int team = W >= kPackWaves ? 1 : kPackWaves / W;  // wavefronts that share one worker's pairs
+  const unsigned long long step = 64ull * team;
+  const int64_t r = blockIdx.x, t0 = r * tb;
+
+  if (tid < W) {
+    const uint32_t b0 = brk[r * W + tid], b1 = brk[(r + 1) * W + tid];
+    s_br0[tid] = b0;
+    s_excl[tid + 1] = b1 > b0 ? b1 - b0 : 0u;  // count, turned into a prefix below
   }
   __syncthreads();
-  for (int flat = threadIdx.x; flat < 256 * W; flat += 256) {
-    const int w = flat % W;
-    const int64_t tile = t0 + flat / W;
-    if (tile > ntiles) break;
-    bounds[tile * W + w] = lower_bound_idx<I>(static_cast<const I*>(a.indices[w]), s_br[0][w], s_br[1][w],
-                                              (unsigned long long)tile * kDecTile);
+  if (tid == 0) {
+    unsigned long long base = 0ull;  // records before this range: every worker's pairs before it
+    uint32_t run = 0u;
+    for (int w = 0; w < W; ++w) {
+      const uint32_t c = s_excl[w + 1];
+      base += s_br0[w];
+      s_excl[w] = run;
+      run += c;
+    }
+    s_excl[W] = run;
+    s_base = base;
+  }
+  __syncthreads();
+  const uint32_t total = s_excl[W];
+  for (int i = tid; i < (tb + 1) * W; i += kPackThreads) {  // a tile after a worker's last pair starts at its end
+    const int w = i % W;
+    s_lo[i] = s_br0[w] + (s_excl[w + 1] - s_excl[w]);
+  }
+  __syncthreads();
+
+  // the first pair at or after the start of every tile: pair j opens all tiles after its predecessor's, up to its own
+  for (int w = wave / team; w < W; w += kPackWaves / team) {
+    const I* idx = static_cast<const I*>(a.indices[w]);
+    const unsigned long long j0 = s_br0[w], j1 = j0 + (s_excl[w + 1] - s_excl[w]);  // 64 bits: j1 may sit just below 2^32
+    for (unsigned long long jb = j0 + (unsigned)((wave % team) * 64 + lane); jb < j1; jb += step * kPackBatch) {
+      unsigned long long cur[kPackBatch], prev[kPackBatch];
+#pragma unroll
+      for (int u = 0; u < kPackBatch; ++u) {  // the batch's loads are in flight together
+        const unsigned long long j = jb + u * step;
+        cur[u] = 0ull;
+        prev[u] = 0ull;
+        if (j < j1) {
+          cur[u] = (unsigned long long)idx[j];
+          if (j > j0) prev[u] = (unsigned long long)idx[j - 1];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kPackBatch; ++u) {
+        const unsigned long long j = jb + u * step;
+        const int64_t tc = (int64_t)(cur[u] / kDecTile) - t0;
+        if (j < j1 && tc >= 0 && tc < tb) {  // outside only with indices out of order
+          int64_t tp = -1;
+          if (j > j0) {
+            tp = (int64_t)(prev[u] / kDecTile) - t0;
+            if (tp < -1) tp = -1;
+          }
+          for (int64_t t = tp + 1; t <= tc; ++t) s_lo[t * W + w] = (uint32_t)j;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  // exclusive scan of the segment lengths in (tile, worker) order
+  const int nent = tb * W, per = (nent + kPackThreads - 1) / kPackThreads;
+  const int beg = tid * per, end = beg + per < nent ? beg + per : nent;
+  uint32_t sum = 0u;
+  for (int i = beg; i < end; ++i) {
+    const uint32_t l0 = s_lo[i], l1 = s_lo[i + W];
+    sum += l1 > l0 ? l1 - l0 : 0u;
+  }
+  uint32_t incl = sum;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t u = __shfl_up(incl, off);
+    if (lane >= off) incl += u;
+  }
+  if (lane == 63) s_wave[wave] = incl;
+  __syncthreads();
+  uint32_t run = incl - sum;
+  for (int x = 0; x < wave; ++x) run += s_wave[x];
+  for (int i = beg; i < end; ++i) {
+    const uint32_t l0 = s_lo[i], l1 = s_lo[i + W];
+    s_off[i] = run;
+    run += l1 > l0 ? l1 - l0 : 0u;
+  }
+  __syncthreads();
+
+  for (int t = tid; t < tb; t += kPackThreads)
+    if (t0 + t <= ntiles) tile_start[t0 + t] = s_base + s_off[t * W];
+  if (tid == 0 && t0 + tb == ntiles) tile_start[ntiles] = s_base + total;  // the last range ends at the last tile
+
+  for (int w = wave / team; w < W; w += kPackWaves / team) {
+    const I* idx = static_cast<const I*>(a.indices[w]);
+    const int8_t* qw = a.q[w];
+    const float* scw = a.scales[w];
+    const float denom = a.denom[w];
+    const unsigned long long j0 = s_br0[w], j1 = j0 + (s_excl[w + 1] - s_excl[w]);
+    for (unsigned long long jb = j0 + (unsigned)((wave % team) * 64 + lane); jb < j1; jb += step * kPackBatch) {
+      unsigned long long gi[kPackBatch];
+      float val[kPackBatch];
+#pragma unroll
+      for (int u = 0; u < kPackBatch; ++u) {  // index, scale and code of the whole batch are in flight together
+        const unsigned long long j = jb + u * step;
+        gi[u] = 0ull;
+        val[u] = 0.0f;
+        if (j < j1) {
+          gi[u] = (unsigned long long)idx[j];
+          uint32_t rel = (uint32_t)j;  // pair inside its tensor; sbase, qbase: the tensor's first scale and code byte
+          long long sbase = 0, qbase = 0;
+          if (T > 1) {  // blocks restart at every tensor: find the tensor that owns pair j
+            int tl = 0, th = T - 1;
+            while (tl < th) {
+              const int mid = (tl + th + 1) >> 1;
+              if (kprefix[mid] <= (long long)j) tl = mid; else th = mid - 1;
+            }
+            rel = (uint32_t)((long long)j - kprefix[tl]);
+            sbase = sprefix[tl];
+            qbase = qprefix[tl];
+          }
+          const uint32_t blk = rel / (uint32_t)block;
+          const float sc = scw[sbase + blk];
+          if (codec == 0) {
+            val[u] = __fmul_rn((float)qw[qbase + rel], sc);
+          } else {  // sign code (Eq. 10): bit number rel - blk * block of the block's bytes
+            const uint32_t bit = rel - blk * (uint32_t)block;
+            const uint32_t byte = (uint8_t)qw[qbase + (long long)blk * ((block + 7) / 8) + (bit >> 3)];
+            val[u] = ((byte >> (bit & 7u)) & 1u) ? sc : -sc;
+          }
+          if (weighted) val[u] = __fdiv_rn(val[u], denom);  // Eq. 12: a stale worker counts for less
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kPackBatch; ++u) {
+        const unsigned long long j = jb + u * step;
+        const int64_t tc = (int64_t)(gi[u] / kDecTile) - t0;
+        if (j < j1 && tc >= 0 && tc < tb) {
+          const uint32_t lo = s_lo[tc * W + w], hi = s_lo[(tc + 1) * W + w];
+          const uint32_t dest = s_off[tc * W + w] + ((uint32_t)j - lo);
+          // a record is only written inside its own segment (it always is when the indices ascend)
+          if ((uint32_t)j >= lo && (uint32_t)j < hi && dest < total) {
+            const uint32_t pos = (uint32_t)(gi[u] - (unsigned long long)(t0 + tc) * kDecTile);
+            rec[s_base + dest] = make_uint2(pos | ((uint32_t)w << 16), __float_as_uint(val[u]));
+          }
+        }
+      }
+    }
   }
 }
 
@@ -56,247 +234,152 @@ __global__ __launch_bounds__(256) void k_dec_bounds(DecArgs a, int W, int64_t nt
 #endif
 constexpr int kDecWaves = GC_DEC_WAVES;  // wavefronts (= tiles) per workgroup
 #ifndef GC_DEC_GRID
-#define GC_DEC_GRID 512
+#define GC_DEC_GRID 256
 #endif
-constexpr int kDecGrid = GC_DEC_GRID;    // persistent workgroups (2 per CU)
+constexpr int kDecGrid = GC_DEC_GRID;    // persistent workgroups (1 per CU: 8 tiles of 16 KB in LDS)
+constexpr int kDecRounds = 4;            // rounds of 64 records whose loads are in flight together
 
-// What one lane decodes in one round of a tile: a pair of some worker, or nothing.
-struct LanePair {
-  bool active;
-  int w;         // worker
-  uint32_t j;    // pair index in that worker's buffer
-};
-
-// Pair number (s0 + lane) of the tile, counting the workers' pairs in worker order.
-__device__ __forceinline__ LanePair locate_pair(uint32_t s0, int lane, uint32_t total, int W, uint32_t excl,
-                                                uint32_t cnt, uint32_t lo) {
-  LanePair p;
-  const uint32_t sidx = s0 + lane;
-  p.active = sidx < total;
-  p.w = 0;
-  p.j = 0;
-  for (int w = 0; w < W; ++w) {  // w is wave-uniform: scalar lane reads
-    const uint32_t ex = (uint32_t)__builtin_amdgcn_readlane((int)excl, w);
-    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)cnt, w);
-    const uint32_t l = (uint32_t)__builtin_amdgcn_readlane((int)lo, w);
-    if (c != 0u && sidx >= ex) { p.w = w; p.j = l + (sidx - ex); }
-  }
-  return p;
-}
-
-constexpr uint32_t kClaimed = 0x7FC0DEADu;  // a NaN pattern no finite sum can produce
-
-// The pair range of every worker inside one tile: lane w holds worker w's first pair and count,
-// `excl` the number of pairs of the workers before it, `total` the tile's pairs over all workers.
-struct TileBounds {
-  uint32_t lo, cnt, excl, total;
-};
-
-__device__ __forceinline__ void load_bounds(const uint32_t* __restrict__ bounds, int64_t tile, int W, int lane,
-                                            uint32_t& lo, uint32_t& hi) {
-  lo = 0u;
-  hi = 0u;
-  if (lane < W) {
-    lo = bounds[tile * W + lane];
-    hi = bounds[(tile + 1) * W + lane];
-  }
-}
-
-__device__ __forceinline__ TileBounds scan_bounds(uint32_t lo, uint32_t hi, int lane) {
-  TileBounds b;
-  b.lo = lo;
-  // every bound lies in [0, k], so a pair number below lo + cnt is always a valid one; unsorted
-  // indices (which break the caller's contract) can only make hi < lo, and then the tile is skipped
-  b.cnt = hi > lo ? hi - lo : 0u;
-  uint32_t incl = b.cnt;  // inclusive scan over lanes
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t u = __shfl_up(incl, off);
-    if (lane >= off) incl += u;
-  }
-  b.total = __shfl(incl, 63);
-  b.excl = incl - b.cnt;
-  return b;
-}
-
-// The pair a lane decodes in one round, as loaded: index, scale and raw code.
-struct PairLoad {
-  LanePair p;
-  unsigned long long gi;  // index in the dense vector
-  float s;                // scale of the pair's block
-  uint32_t code;          // int8 code (low byte), or the sign byte << 8 | bit number
-};
-
-// Issues the loads of round s0 of a tile together; nothing here consumes their results, so the
-// index, scale and code of a pair cost one round trip to memory, not three.
-template <typename I>
-__device__ __forceinline__ PairLoad load_pairs(const DecArgs& a, uint32_t s0, int lane, int W, const TileBounds& b,
-                                              int32_t block, const long long* __restrict__ kprefix,
-                                              const long long* __restrict__ sprefix,
-                                              const long long* __restrict__ qprefix, int T, int codec) {
-  PairLoad c;
-  c.p = locate_pair(s0, lane, b.total, W, b.excl, b.cnt, b.lo);
-  c.gi = 0ull;
-  c.s = 0.0f;
-  c.code = 0u;
-  if (c.p.active) {
-    const I* idx = static_cast<const I*>(a.indices[c.p.w]);
-    const float* sc = a.scales[c.p.w];
-    const int8_t* qw = a.q[c.p.w];
-    c.gi = (unsigned long long)idx[c.p.j];
-    long long rel = (long long)c.p.j, sbase = 0, qbase = 0;  // pair inside its tensor; tensor's scales, bytes
-    if (T > 1) {  // blocks restart at every tensor: find the tensor that owns pair j
-      int tl = 0, th = T - 1;
-      while (tl < th) {
-        const int mid = (tl + th + 1) >> 1;
-        if (kprefix[mid] <= (long long)c.p.j) tl = mid; else th = mid - 1;
-      }
-      rel -= kprefix[tl];
-      sbase = sprefix[tl];
-      qbase = qprefix[tl];
-    }
-    const long long blk = rel / block;
-    c.s = sc[sbase + blk];
-    if (codec == 0) {
-      c.code = (uint8_t)qw[T > 1 ? qbase + rel : rel];
-    } else {  // sign code (Eq. 10): bit r of the block's bytes
-      c.code = (uint32_t)(rel - blk * block);  // r; the byte is loaded below, the bit taken at use
-      c.code = (c.code & 7u) | ((uint32_t)(uint8_t)qw[qbase + blk * ((block + 7) / 8) + (c.code >> 3)] << 8);
-    }
-  }
-  return c;
-}
+constexpr uint32_t kClaimed = 0x7FC0DEADu;   // a NaN pattern no finite sum can produce
+constexpr uint32_t kNoRecord = 0xFFFFFFFFu;  // position 0xFFFF: outside every tile
 
 __device__ __forceinline__ void wave_sync() {  // orders the wavefront's own LDS accesses
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
 }
 
-// Adds one round of pairs into the wavefront's LDS tile so that equal indices of different workers
-// are added in ascending worker order: one LDS float add (round to nearest even, denormals kept,
-// like the plain fp32 add) per worker present in the round, issued back to back. The LDS executes
-// a wavefront's instructions in the order they were issued, so nothing has to wait in between, and
-// within one worker the indices are unique, so the lanes of one instruction never collide.
-__device__ __forceinline__ void add_pairs(const DecArgs& a, const PairLoad& c, int64_t base, int codec,
-                                          int weighted, float* lt) {
-  float val = 0.0f;
-  uint32_t pos = 0xFFFFFFFFu;
-  if (c.p.active) {
-    pos = (uint32_t)(c.gi - (unsigned long long)base);
-    if (codec == 0) val = __fmul_rn((float)(int8_t)c.code, c.s);
-    else val = ((c.code >> (8 + (c.code & 7u))) & 1u) ? c.s : -c.s;
-    if (weighted) val = __fdiv_rn(val, a.denom[c.p.w]);  // Eq. 12: a stale worker counts for less
-  }
-  const bool act = c.p.active && pos < (uint32_t)kDecTile;
+// Adds one round of records into the wavefront's LDS tile so that equal positions of different
+// workers are added in ascending worker order (the records of a tile are in worker order): one LDS
+// float add (round to nearest even, denormals kept, like the plain fp32 add) per worker present in
+// the round, issued back to back. The LDS executes a wavefront's instructions in the order they
+// were issued, so nothing has to wait in between, and within one worker the positions are unique,
+// so the lanes of one instruction never collide.
+__device__ __forceinline__ void add_round(uint2 r, float* lt) {
+  const uint32_t pos = r.x & 0xFFFFu;
+  const int w = (int)((r.x >> 16) < (uint32_t)(kMaxWorkers - 1) ? (r.x >> 16) : (uint32_t)(kMaxWorkers - 1));
+  const bool act = pos < (uint32_t)kDecTile;
   const uint64_t am = __ballot(act);
   if (am == 0ull) return;
-  const int w_first = __shfl(c.p.w, __ffsll((unsigned long long)am) - 1);
-  const int w_last = __shfl(c.p.w, 63 - __clzll((unsigned long long)am));
-  for (int w = w_first; w <= w_last; ++w) {
-    if (act && c.p.w == w) (void)__hip_atomic_fetch_add(lt + pos, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+  const int w_first = __shfl(w, __ffsll((unsigned long long)am) - 1);
+  const int w_last = __shfl(w, 63 - __clzll((unsigned long long)am));
+  const float val = __uint_as_float(r.y);
+  for (int x = w_first; x <= w_last; ++x) {
+    if (act && w == x) (void)__hip_atomic_fetch_add(lt + pos, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     __builtin_amdgcn_wave_barrier();  // keeps the instructions in this order
   }
-  wave_sync();
 }
 
 // MODE 0: out[tile] = sum (dense write).  MODE 1: theta[i] -= c * sum[i] at the touched i only.
-// Wavefronts walk the tiles with a grid stride, without workgroup barriers. Fetching a
-// wavefront's next tile ahead of time (its bounds, or its pairs) measured slower on the 7B workload
-// than this plain order, as did keeping the workers' pointers in LDS.
-template <typename I, int MODE>
-__global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(DecArgs a, int W, int32_t block, int64_t n,
-                                                   int64_t ntiles, const uint32_t* __restrict__ bounds,
-                                                   const long long* __restrict__ kprefix,
-                                                   const long long* __restrict__ sprefix,
-                                                   const long long* __restrict__ qprefix, int T, int codec,
-                                                   float* __restrict__ out, int weighted, float c_apply) {
+// Wavefronts walk the tiles with a grid stride, without workgroup barriers.
+template <int MODE>
+__global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(const uint2* __restrict__ rec,
+                                                   const unsigned long long* __restrict__ tile_start,
+                                                   unsigned long long nrec, int64_t n, int64_t ntiles,
+                                                   float* __restrict__ out, float c_apply) {
   __shared__ float tile_mem[kDecWaves][kDecTile];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* lt = tile_mem[wave];
   const int64_t stride = (int64_t)gridDim.x * kDecWaves;
-  int64_t tile = (int64_t)blockIdx.x * kDecWaves + wave;
-  if (tile >= ntiles) return;
 
-  for (; tile < ntiles; tile += stride) {
+  for (int64_t tile = (int64_t)blockIdx.x * kDecWaves + wave; tile < ntiles; tile += stride) {
     const int64_t base = tile * kDecTile;
-    uint32_t lo, hi;
-    load_bounds(bounds, tile, W, lane, lo, hi);
-    const TileBounds cur = scan_bounds(lo, hi, lane);
+    unsigned long long first = tile_start[tile], last = tile_start[tile + 1];
+    if (last > nrec) last = nrec;
+    const unsigned long long total = last > first ? last - first : 0ull;
+    if (MODE == 1 && total == 0ull) continue;  // nothing to apply in an empty tile
 
-    if (!(MODE == 1 && cur.total == 0u)) {  // MODE 1: nothing to apply in an empty tile
-      const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
+    const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-      for (int i = 0; i < kDecTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
+    for (int i = 0; i < kDecTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
+    wave_sync();
 
-      const PairLoad first = load_pairs<I>(a, 0u, lane, W, cur, block, kprefix, sprefix, qprefix, T, codec);
-      add_pairs(a, first, base, codec, weighted, lt);
-      for (uint32_t s0 = 64; s0 < cur.total; s0 += 64) {
-        const PairLoad c = load_pairs<I>(a, s0, lane, W, cur, block, kprefix, sprefix, qprefix, T, codec);
-        add_pairs(a, c, base, codec, weighted, lt);
+    for (unsigned long long s0 = 0; s0 < total; s0 += 64 * kDecRounds) {
+      uint2 r[kDecRounds];
+#pragma unroll
+      for (int i = 0; i < kDecRounds; ++i) {
+        const unsigned long long p = s0 + (unsigned long long)(i * 64 + lane);
+        r[i] = make_uint2(kNoRecord, 0u);
+        if (p < total) r[i] = rec[first + p];
       }
-
-      if (MODE == 0) {
-        const int64_t remain = n - base;
-        if (remain >= kDecTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
 #pragma unroll
-          for (int i = 0; i < kDecTile / 256; ++i) {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
-            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
-          }
-        } else {
-          const int lim = (int)(remain < kDecTile ? remain : kDecTile);
-          for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
+      for (int i = 0; i < kDecRounds; ++i) add_round(r[i], lt);
+    }
+    wave_sync();
+
+    if (MODE == 0) {
+      const int64_t remain = n - base;
+      if (remain >= kDecTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
+#pragma unroll
+        for (int i = 0; i < kDecTile / 256; ++i) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
+          __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
         }
       } else {
-        // every touched position is claimed once (LDS exchange with a marker) and updated in place:
-        // theta - fl32(c * sum). Untouched positions have sum +0 and would not change anyway.
-        for (uint32_t s0 = 0; s0 < cur.total; s0 += 64) {
-          const LanePair p = locate_pair(s0, lane, cur.total, W, cur.excl, cur.cnt, cur.lo);
-          if (p.active) {
-            const I* idx = static_cast<const I*>(a.indices[p.w]);
-            const unsigned long long gi = (unsigned long long)idx[p.j];
-            const uint32_t pos = (uint32_t)(gi - (unsigned long long)base);
-            if (pos < (uint32_t)kDecTile && gi < (unsigned long long)n) {
-              const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + pos, kClaimed);
-              if (old != kClaimed) out[gi] = __fsub_rn(out[gi], __fmul_rn(c_apply, __uint_as_float(old)));
-            }
+        const int lim = (int)(remain < kDecTile ? remain : kDecTile);
+        for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
+      }
+    } else {
+      // every touched position is claimed once (LDS exchange with a marker) and updated in place:
+      // theta - fl32(c * sum). Untouched positions have sum +0 and would not change anyway.
+      for (unsigned long long s0 = 0; s0 < total; s0 += 64) {
+        const unsigned long long p = s0 + (unsigned long long)lane;
+        if (p < total) {
+          const uint32_t pos = rec[first + p].x & 0xFFFFu;
+          const int64_t gi = base + (int64_t)pos;
+          if (pos < (uint32_t)kDecTile && gi < n) {
+            const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + pos, kClaimed);
+            if (old != kClaimed) out[gi] = __fsub_rn(out[gi], __fmul_rn(c_apply, __uint_as_float(old)));
           }
         }
       }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
     }
+    wave_sync();
   }
 }
 
 }  // namespace
 
-void launch_dec_bounds(const DecArgs& a, int W, int index_bits, int64_t ntiles, uint32_t* bounds,
-                       hipStream_t s) {
-  const dim3 grid((unsigned)((ntiles + 1 + 255) / 256));
-  if (index_bits == 32)
-    hipLaunchKernelGGL(k_dec_bounds<uint32_t>, grid, dim3(256), 0, s, a, W, ntiles, bounds);
-  else
-    hipLaunchKernelGGL(k_dec_bounds<unsigned long long>, grid, dim3(256), 0, s, a, W, ntiles, bounds);
+// Tiles per range of the packing pass: 128 (64 with many workers: the LDS tables hold
+// (2 * tiles + 1) * W entries), fewer when the tiles are crowded or the vector is short, so that a
+// range stays a small piece of work and there are enough ranges to fill the chip. A power of two
+// between 8 and 128.
+int dec_range_tiles(int W, int64_t nrec, int64_t n) {
+  const double per_tile = (double)nrec * kDecTile / (double)(n > 0 ? n : 1);
+  const int64_t ntiles = (n + kDecTile - 1) / kDecTile;
+  int tb = W <= 32 ? 128 : 64;
+  while (tb > 8 && (per_tile * tb > 32768.0 || ntiles / tb < 2048)) tb >>= 1;
+  return tb;
 }
 
-void launch_dec_tiles(const DecArgs& a, int W, int index_bits, int32_t block, int64_t n, int64_t ntiles,
-                      const uint32_t* bounds, const long long* kprefix, const long long* sprefix,
-                      const long long* qprefix, int T, int codec, float* out, int weighted, int apply,
-                      float c_apply, hipStream_t s) {
+void launch_dec_brackets(const DecArgs& a, int W, int index_bits, int tb, int64_t ntiles, uint32_t* brk, hipStream_t s) {
+  const int64_t nranges = (ntiles + tb - 1) / tb;
+  const dim3 grid((unsigned)(((nranges + 1) * W + 255) / 256));
+  if (index_bits == 32) hipLaunchKernelGGL(k_dec_brackets<uint32_t>, grid, dim3(256), 0, s, a, W, tb, nranges, brk);
+  else hipLaunchKernelGGL(k_dec_brackets<unsigned long long>, grid, dim3(256), 0, s, a, W, tb, nranges, brk);
+}
+
+void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int32_t block, int64_t ntiles, const uint32_t* brk,
+                     const long long* kprefix, const long long* sprefix, const long long* qprefix, int T,
+                     int codec, int weighted, void* rec, unsigned long long* tile_start, hipStream_t s) {
+  const dim3 grid((unsigned)((ntiles + tb - 1) / tb));
+  const size_t lds = sizeof(uint32_t) * (size_t)(2 * tb + 1) * W;  // at most 33 KB
+  if (index_bits == 32)
+    hipLaunchKernelGGL(k_dec_pack<uint32_t>, grid, dim3(kPackThreads), lds, s, a, W, tb, block, ntiles, brk, kprefix,
+                       sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
+  else
+    hipLaunchKernelGGL(k_dec_pack<unsigned long long>, grid, dim3(kPackThreads), lds, s, a, W, tb, block, ntiles, brk,
+                       kprefix, sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
+}
+
+void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int64_t n,
+                      int64_t ntiles, float* out, int apply, float c_apply, hipStream_t s) {
   const int64_t want = (ntiles + kDecWaves - 1) / kDecWaves;
   const dim3 grid((unsigned)(want < kDecGrid ? want : kDecGrid)), blk(kDecWaves * 64);
-#define GC_LAUNCH_TILES(ITYPE, MODE)                                                                        \
-  hipLaunchKernelGGL((k_dec_tiles<ITYPE, MODE>), grid, blk, 0, s, a, W, block, n, ntiles, bounds, kprefix, \
-                     sprefix, qprefix, T, codec, out, weighted, c_apply)
-  if (index_bits == 32) {
-    if (apply) GC_LAUNCH_TILES(uint32_t, 1); else GC_LAUNCH_TILES(uint32_t, 0);
-  } else {
-    if (apply) GC_LAUNCH_TILES(unsigned long long, 1); else GC_LAUNCH_TILES(unsigned long long, 0);
-  }
-#undef GC_LAUNCH_TILES
+  if (apply)
+    hipLaunchKernelGGL(k_dec_tiles<1>, grid, blk, 0, s, (const uint2*)rec, tile_start, (unsigned long long)nrec, n,
+                       ntiles, out, c_apply);
+  else
+    hipLaunchKernelGGL(k_dec_tiles<0>, grid, blk, 0, s, (const uint2*)rec, tile_start, (unsigned long long)nrec, n,
+                       ntiles, out, c_apply);
 }
 
 }  // namespace gc

@@ -139,7 +139,7 @@ struct OutBuf {
 // kernel ids for profiling
 enum KernelId : int32_t {
   kKInit = 0, kKSample, kKSampleThresh, kKMain, kKGroupSums, kKGroupScan, kKRoute, kKGather, kKHist,
-  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecBounds, kKDecTiles, kKDense, kKDenseSum, kKRowsGather, kKRowsFinish, kKRowsRemap, kKNum
+  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecBrackets, kKDecPack, kKDecTiles, kKDense, kKDenseSum, kKRowsGather, kKRowsFinish, kKRowsRemap, kKNum
 };
 
 // launchers (defined in the .hip files next to their kernels)
@@ -220,7 +220,7 @@ template <> struct GradVec<uint16_t> {
 
 constexpr int kMaxWorkers = 64;
 #ifndef GC_DEC_TILE
-#define GC_DEC_TILE 2048
+#define GC_DEC_TILE 4096
 #endif
 constexpr int kDecTile = GC_DEC_TILE;  // output floats per wave-tile of decompress_sum
 struct DecArgs {
@@ -230,12 +230,15 @@ struct DecArgs {
   uint32_t k[kMaxWorkers];
   float denom[kMaxWorkers];  // 1 + staleness of the worker (weighted aggregate)
 };
-void launch_dec_bounds(const DecArgs& a, int W, int index_bits, int64_t ntiles, uint32_t* bounds,
-                       hipStream_t s);
-void launch_dec_tiles(const DecArgs& a, int W, int index_bits, int32_t block, int64_t n,
-                      int64_t ntiles, const uint32_t* bounds, const long long* kprefix,
-                      const long long* sprefix, const long long* qprefix, int T, int codec, float* out,
-                      int weighted, int apply, float c_apply, hipStream_t s);
+// Tiles per range of the packing pass, from the expected number of records per tile.
+int dec_range_tiles(int W, int64_t nrec, int64_t n);
+// brk: (ranges + 1) * W entries; rec: one 8-byte record per pair of all workers; tile_start: ntiles + 1 entries.
+void launch_dec_brackets(const DecArgs& a, int W, int index_bits, int tb, int64_t ntiles, uint32_t* brk, hipStream_t s);
+void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int32_t block, int64_t ntiles, const uint32_t* brk,
+                     const long long* kprefix, const long long* sprefix, const long long* qprefix, int T,
+                     int codec, int weighted, void* rec, unsigned long long* tile_start, hipStream_t s);
+void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int64_t n,
+                      int64_t ntiles, float* out, int apply, float c_apply, hipStream_t s);
 
 // ---- dense codes (every entry kept, no indices) -----------------------------
 constexpr int kDenseMaxBlock = 8192;   // larger blocks do not fit one workgroup's registers

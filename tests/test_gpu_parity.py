@@ -268,11 +268,18 @@ def test_decompress_sum_sixteen_workers_with_collisions(gc, ctx, oracle):
     for idx, _, _ in refs:
         counts[idx] += 1
     assert (counts >= 3).sum() > 1000  # the order of the fp32 adds matters for these
-    for Wsub in (1, 2, 5, 16):
+    for Wsub in (1, 2, 3, 5, 16):
         out = gc.decompress_sum(ctx, bufs[:Wsub], n)
         torch.cuda.synchronize()
         rc, want = oracle.decompress_sum(refs[:Wsub], n, block)
         assert np.array_equal(bits(out.cpu().numpy()), bits(want)), Wsub
+    for Wbig in (33, 64):  # many workers (the same buffers again and again: every position is shared)
+        pick = [(7 * i) % W for i in range(Wbig)]
+        stale = [i % 3 for i in range(Wbig)]
+        outb = gc.decompress_sum_weighted(ctx, [bufs[i] for i in pick], stale, n)
+        torch.cuda.synchronize()
+        rc, wantb = oracle.decompress_sum([refs[i] for i in pick], n, block, staleness=stale)
+        assert rc == 0 and np.array_equal(bits(outb.cpu().numpy()), bits(wantb)), Wbig
     # tolerance form of the same statement: within 1e-6 relative of the float64 sum (or 1 ulp)
     ref64 = np.zeros(n, np.float64)
     for idx, q, s in refs:
@@ -315,7 +322,8 @@ def test_decompress_sum_cancellation_down_to_subnormals(gc, ctx, oracle, codec):
 
 
 def test_decompress_sum_edge_shapes(gc, ctx, oracle):
-    for n, k in ((1, 1), (2047, 3), (2048, 2048), (2049, 1), (10000, 10000), (300000, 1)):
+    for n, k in ((1, 1), (2047, 3), (2048, 2048), (2049, 1), (4095, 3), (4096, 4096), (4097, 1), (10000, 10000),
+                 (300000, 1), (524287, 100), (524288, 9), (524289, 7), (1_048_577, 11)):  # around tiles and ranges of tiles
         g = inputs.normal(n, 1.0, n)
         buf, ref, _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 8, tag="dec edge")
         out = torch.full((n + 8,), 7.0, device=DEV)
