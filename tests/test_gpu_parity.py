@@ -702,3 +702,71 @@ def test_closed_loop_sgd_with_error_feedback(gc, ctx, oracle, codec):
         for w in range(W):
             assert np.array_equal(bits(res[w].cpu().numpy()), bits(res_ref[w])), f"residual {w} at step {it}"
     assert loss() < 0.8 * first
+
+
+# ------------------------------------------------------------- aggregate on hand-built buffers
+def _random_buffer(rng, gc, n, ks, block, index_bits, codec):
+    """One worker's buffer with random ascending unique indices, random codes and positive scales of
+    mixed magnitude; returns (CompressedBuf, oracle triple)."""
+    k = int(np.sum(ks))
+    idx = np.sort(rng.choice(n, size=k, replace=False)).astype(np.uint32 if index_bits == 32 else np.uint64)
+    nsc = int(sum((int(kt) + block - 1) // block for kt in ks))
+    nq = int(sum(gc.num_code_bytes(int(kt), block, codec) for kt in ks))
+    if codec == 0:
+        q = rng.integers(-127, 128, size=nq, dtype=np.int64).astype(np.int8)
+    else:
+        q = rng.integers(-128, 128, size=nq, dtype=np.int64).astype(np.int8)
+    s = (10.0 ** rng.uniform(-6, 3, size=nsc)).astype(np.float32)
+    it = torch.int32 if index_bits == 32 else torch.int64
+    buf = gc.CompressedBuf(torch.from_numpy(idx.view(np.int32 if index_bits == 32 else np.int64)).to(DEV).to(it),
+                           torch.from_numpy(q).to(DEV), torch.from_numpy(s).to(DEV), n, k, block, index_bits, codec)
+    return buf, (idx, q, s)
+
+
+@pytest.mark.parametrize("seed", [20250617, 7, 99])
+def test_aggregate_random_hand_built_buffers(gc, ctx, oracle, seed):
+    """decompress_sum / weighted / apply on buffers built directly (no compress step): random sizes
+    around tile and range edges, 1 to 64 workers, sparse to fully dense lists, both codes and index
+    widths, single and multi-tensor block layouts."""
+    rng = np.random.default_rng(seed)
+    edges = [1, 2, 4095, 4096, 4097, 8192, 524287, 524288, 524289, 1_048_576 + 3]
+    for case in range(36):
+        n = int(rng.choice(edges)) if case % 3 == 0 else int(rng.integers(1, 1_500_000))
+        W = int(rng.choice([1, 2, 3, 4, 5, 8, 16, 17, 32, 33, 64]))
+        dens = float(rng.choice([1e-4, 1e-3, 0.01, 0.2, 1.0]))
+        if W * n * dens > 6e6:
+            dens = 6e6 / (W * n)
+        k = max(1, min(n, int(np.ceil(n * dens))))
+        block = int(rng.choice([1, 7, 64, 256, 1000, 2048]))
+        bits_ = int(rng.choice([32, 64]))
+        codec = int(rng.choice([0, 1]))
+        T = 1 if (case % 4 or k < 3) else int(rng.integers(2, min(k, 6) + 1))
+        if T == 1:
+            ks = np.array([k], dtype=np.int64)
+        else:
+            cuts = np.sort(rng.choice(np.arange(1, k), size=T - 1, replace=False))
+            ks = np.diff(np.concatenate([[0], cuts, [k]])).astype(np.int64)
+        stale = [int(x) for x in rng.integers(0, 4, size=W)] if case % 2 else None
+        print(f"[case] built n={n} W={W} k={k} block={block} bits={bits_} codec={codec} T={T} stale={stale is not None}",
+              flush=True)
+        pairs = [_random_buffer(rng, gc, n, ks, block, bits_, codec) for _ in range(W)]
+        bufs, refs = [p[0] for p in pairs], [p[1] for p in pairs]
+        kt = ks if T > 1 else None
+        rc, want = oracle.decompress_sum(refs, n, block, ktensor=kt, staleness=stale, codec=codec)
+        assert rc == 0
+        out = torch.full((n + 4,), 9.0, device=DEV)
+        if stale is not None:
+            gc.decompress_sum_weighted(ctx, bufs, stale, n, out=out[:n], ks=kt)
+        elif T > 1:
+            gc.decompress_sum_multi(ctx, bufs, ks, n, out=out[:n])
+        else:
+            gc.decompress_sum(ctx, bufs, n, out=out[:n])
+        theta0 = rng.standard_normal(n).astype(np.float32)
+        theta = torch.from_numpy(theta0).to(DEV)
+        gc.decompress_apply(ctx, bufs, theta, 0.125, staleness=stale, ks=kt)
+        assert gc.sync_status(ctx, raise_on_error=False) == 0
+        assert np.array_equal(bits(out[:n].cpu().numpy()), bits(want)), case
+        assert torch.all(out[n:] == 9.0)
+        exp = theta0.copy()
+        assert oracle.apply(exp, want, 0.125) == 0
+        assert np.array_equal(bits(theta.cpu().numpy()), bits(exp)), case
