@@ -770,3 +770,36 @@ def test_aggregate_random_hand_built_buffers(gc, ctx, oracle, seed):
         exp = theta0.copy()
         assert oracle.apply(exp, want, 0.125) == 0
         assert np.array_equal(bits(theta.cpu().numpy()), bits(exp)), case
+
+
+def test_occupancy_options_never_change_results(gc, oracle):
+    """gc_set_option only moves how many workgroups share a compute unit; outputs stay bit-identical."""
+    n, k, block = 700_001, 7000, 256
+    g = inputs.normal(n, 1.0, 31)
+    e0 = inputs.normal(n, 0.2, 32)
+    e_ref = e0.numpy().copy()
+    rc, idx, q, s = oracle.compress(g.numpy(), e_ref, k, block)
+    e_ref_d = e0.numpy().copy()
+    rc2, idx_d, q_d, s_d = oracle.compress(g.numpy(), e_ref_d, n, block, codec=oracle.SIGN1)
+    assert rc == 0 and rc2 == 0
+    for name, values in (("main_lds_pad", (0, 4096, 16384, 65536)), ("dense_lds_pad", (-1, 0, 32768, 65536)),
+                         ("dense_wave_block", (0, 256, 1024, 2048))):
+        for v in values:
+            c = gc.Context(0)
+            c.set_option(name, v)
+            e = e0.to(DEV).clone()
+            buf = gc.compress(c, g.to(DEV), e, k, block)
+            ed = e0.to(DEV).clone()
+            dq, dsc = gc.compress_dense(c, g.to(DEV), ed, block, codec=gc.GC_CODEC_SIGN1)
+            gc.sync_status(c)
+            assert np.array_equal(buf.indices_numpy(), idx) and np.array_equal(buf.q.cpu().numpy(), q), (name, v)
+            assert np.array_equal(bits(buf.scales.cpu().numpy()), bits(s)), (name, v)
+            assert np.array_equal(bits(e.cpu().numpy()), bits(e_ref)), (name, v)
+            assert np.array_equal(dq.cpu().numpy(), q_d) and np.array_equal(bits(dsc.cpu().numpy()), bits(s_d)), (name, v)
+            assert np.array_equal(bits(ed.cpu().numpy()), bits(e_ref_d)), (name, v)
+            c.destroy()
+    c = gc.Context(0)
+    for name, v in (("main_lds_pad", -1), ("main_lds_pad", 65537), ("dense_wave_block", 4096), ("no_such_option", 1)):
+        with pytest.raises(gc.GradCompError):
+            c.set_option(name, v)
+    c.destroy()
