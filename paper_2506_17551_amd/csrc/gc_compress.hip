@@ -367,7 +367,10 @@ __global__ __launch_bounds__(256) void k_main(Workspace ws, const G* __restrict_
   // combine in L2); a group without candidates writes no records at all.
   if (threadIdx.x == 0) ws.grp_cnt[grp] = tot;
   const uint32_t kept = min(tot, cap);
-  const uint32_t nout = (kept + kSlotLine - 1) & ~(uint32_t)(kSlotLine - 1);  // whole lines
+  // whole lines; with at most 8 slots per group two neighbouring groups share a 128-byte line and
+  // each writes its half (they run on the same die at about the same time, so the halves meet in L2)
+  const uint32_t line = (uint32_t)(ws.slot_stride < kSlotLine ? ws.slot_stride : kSlotLine);
+  const uint32_t nout = (kept + line - 1) & ~(line - 1);
   uint2* __restrict__ dst = ws.slots + grp * (int64_t)ws.slot_stride;
   for (uint32_t j = threadIdx.x; j < nout; j += 256) dst[j] = j < kept ? stage[j] : make_uint2(0u, 0u);
 }

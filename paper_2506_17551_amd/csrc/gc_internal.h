@@ -116,7 +116,7 @@ struct Workspace {  // device pointers into the context's scratch
   uint32_t* flags;                  // [0] non-finite seen
   int32_t T;
   int32_t cap;                      // candidate slots per group
-  int32_t slot_stride;              // records reserved per group (= cap, a multiple of 16)
+  int32_t slot_stride;              // records reserved per group (= cap: 8, or a multiple of 16)
   int32_t gather_team;              // lanes per group in the gather (1 or 16)
   int64_t ngroups;                  // group slots over all tensors
   int64_t nsgran;                   // sampled granules over all tensors
