@@ -34,8 +34,9 @@ constexpr int kGroup = 4 * kWaveTile;
 #ifndef GC_SLOT_LINE
 #define GC_SLOT_LINE 16
 #endif
-// Candidate records leave a workgroup in multiples of 16 (128 bytes, one L2 line). Half lines
-// (8 records) measured ~10 % slower for the whole streaming pass: they are read-modify-written.
+// Candidate records leave a workgroup in multiples of 16 (128 bytes, one L2 line), or of 8 when a
+// group has at most 8 slots: two neighbouring groups then share a line, and under the die-aware
+// order below they run on the same die at about the same time, so their halves meet in L2.
 constexpr int kSlotLine = GC_SLOT_LINE;
 // Select / compaction passes read their source in CHUNKS: 4096 entries per workgroup, 1024 per
 // wavefront.
@@ -162,8 +163,9 @@ void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktot
 // ---- die-aware order of one-shot workgroups ---------------------------------
 // Workgroup b runs on compute die b % 8. Work item number xcd_run_index(b) makes every die walk
 // runs of kXcdRun consecutive items: 256 items (1 MB per fp32 array for 1024-element items)
-// measured best for the streaming pass on the 7B workload (12.7 ms against 13.0 ms for the plain
-// order; runs of 16 items: 14.7 ms). The launch grid must be padded with xcd_run_grid().
+// measured best for the streaming pass on the 7B workload (12.71 ms against 12.80 ms for the plain
+// order with the operands at the same addresses; runs of 64 items: 12.87, of 16: 14.7 ms). The
+// launch grid must be padded with xcd_run_grid().
 #ifndef GC_XCD_RUN
 #define GC_XCD_RUN 256
 #endif
