@@ -226,17 +226,18 @@ def run_flat(args, gc, inputs, torch, wl, ctx):
     if placement is not None:
         info["operand_placement"] = placement
     if args.verify:
-        info["verify"] = verify_flat(gc, torch, wl, ctx, k)
+        info["verify"] = verify_flat(gc, torch, wl, ctx, k, g32, res[0], out)
     return ms_c + ms_d, W * n * gbytes, prof, total_bytes, info
 
 
-def verify_flat(gc, torch, wl, ctx, k):
-    """Size-independent invariants of one compress call, checked on the device."""
+def verify_flat(gc, torch, wl, ctx, k, g32, e_buf, e0_buf):
+    """Size-independent invariants of one compress call, checked on the device (in the bench's own
+    buffers: gradient, residual, and the aggregate's output as the copy of the old residual)."""
     dev = "cuda:0"
     n = wl.n
-    g = wl.grad(0, 0, dev)
-    e0 = wl.residual0(0, dev)
-    e = e0.clone()
+    g = wl.grad(0, 0, dev, out=g32)
+    e0 = wl.residual0(0, dev, out=e0_buf)
+    e = e_buf.copy_(e0)
     buf = gc.compress(ctx, g, e, k, wl.block)
     gc.sync_status(ctx)
     idx = buf.indices.to(torch.int64)
