@@ -109,6 +109,10 @@ int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 constexpr int64_t kMinSampledN = 1 << 15;
 constexpr int64_t kMinSampledK = 32;
 constexpr int64_t kMaxDensityInv = 8;  // sampled only if k * 8 <= n
+#ifndef GC_MAX_SAMPLE_STRIDE
+#define GC_MAX_SAMPLE_STRIDE 1024
+#endif
+constexpr int64_t kMaxSampleStride = GC_MAX_SAMPLE_STRIDE;
 
 int64_t code_bytes(int64_t k, int32_t block, int32_t codec) {
   if (k <= 0 || block < 1) return 0;
@@ -157,7 +161,9 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
       // undershoots only sends the tensor down the dense route, never changes the result)
       double f = 32.0 / (double)d.k;
       f = std::min(0.25, std::max(1.0 / 256.0, f));
-      const int64_t stride = std::max<int64_t>(4, std::min<int64_t>(256, (int64_t)std::floor(1.0 / f)));
+      int64_t stride = std::max<int64_t>(4, std::min<int64_t>(256, (int64_t)std::floor(1.0 / f)));
+      // a very large k leaves thousands of winners in a thinner sample still (at least 4096 expected)
+      if (d.k / 4096 > stride) stride = std::min<int64_t>(kMaxSampleStride, d.k / 4096);
       d.sample_stride = (int32_t)stride;
       d.nsgran = (d.n / kSampleGranule) / stride;  // whole granules only; >= 1: k * 8 <= n bounds the stride by n / 256
       sg += round_up(d.nsgran, 4);
