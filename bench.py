@@ -126,7 +126,14 @@ def run_flat(args, gc, inputs, torch, wl, ctx):
         g32 = torch.empty(n, dtype=torch.float32, device=dev)
         res = [wl.residual0(w, dev) for w in range(W)] if resident else [torch.empty(n, dtype=torch.float32, device=dev)]
     else:
-        g32, e1, out, placement = place_streams(gc, torch, wl, ctx, k, bufs[0], dev, free)
+        try:
+            g32, e1, out, placement = place_streams(gc, torch, wl, ctx, k, bufs[0], dev, free)
+        except torch.OutOfMemoryError:  # the arena did not fit in one piece: take the buffers as they come
+            torch.cuda.empty_cache()
+            out = torch.empty(n, dtype=torch.float32, device=dev)
+            g32 = torch.empty(n, dtype=torch.float32, device=dev)
+            e1 = torch.empty(n, dtype=torch.float32, device=dev)
+            placement = {"arena": "allocation failed; operands placed in allocation order"}
         res = [e1]
     tc, td = Timer(torch), Timer(torch)
     nsteps = args.warmup + args.steps + 1  # the last, extra step records every kernel and is not timed
