@@ -803,3 +803,51 @@ def test_occupancy_options_never_change_results(gc, oracle):
         with pytest.raises(gc.GradCompError):
             c.set_option(name, v)
     c.destroy()
+
+
+def test_two_contexts_on_two_streams_do_not_interfere(gc, oracle):
+    """Each context owns its workspace: calls on two contexts queued on two streams at the same time
+    give the results of the same calls made one after the other."""
+    n, k, block, W = 2_000_003, 20_000, 256, 3
+    ctxs = [gc.Context(0), gc.Context(0)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    data = []
+    for c in range(2):
+        gs = [inputs.normal(n, 1.0, 900 + 10 * c + w) for w in range(W)]
+        es = [inputs.normal(n, 0.3, 950 + 10 * c + w) for w in range(W)]
+        refs = []
+        for w in range(W):
+            e_ref = es[w].numpy().copy()
+            rc, idx, q, s = oracle.compress(gs[w].numpy(), e_ref, k, block)
+            assert rc == 0
+            refs.append((idx, q, s, e_ref))
+        rc, want = oracle.decompress_sum([r[:3] for r in refs], n, block)
+        assert rc == 0
+        data.append((gs, es, refs, want))
+    for c in range(2):  # first use of a shape allocates: keep that out of the concurrent part
+        g0 = data[c][0][0].to(DEV)
+        e0 = data[c][1][0].to(DEV).clone()
+        b0 = gc.compress(ctxs[c], g0, e0, k, block)
+        gc.decompress_sum(ctxs[c], [b0], n)
+        gc.sync_status(ctxs[c])
+    dev_in = [([g.to(DEV) for g in d[0]], [e.to(DEV).clone() for e in d[1]]) for d in data]
+    torch.cuda.synchronize()
+    bufs, outs = [[], []], [None, None]
+    for w in range(W):  # interleave the two contexts' calls
+        for c in range(2):
+            bufs[c].append(gc.compress(ctxs[c], dev_in[c][0][w], dev_in[c][1][w], k, block, stream=streams[c]))
+    for c in range(2):
+        outs[c] = gc.decompress_sum(ctxs[c], bufs[c], n, stream=streams[c])
+    for c in range(2):
+        gc.sync_status(ctxs[c], stream=streams[c])
+    torch.cuda.synchronize()
+    for c in range(2):
+        for w in range(W):
+            idx, q, s, e_ref = data[c][2][w]
+            assert np.array_equal(bufs[c][w].indices_numpy(), idx), (c, w)
+            assert np.array_equal(bufs[c][w].q.cpu().numpy(), q), (c, w)
+            assert np.array_equal(bits(bufs[c][w].scales.cpu().numpy()), bits(s)), (c, w)
+            assert np.array_equal(bits(dev_in[c][1][w].cpu().numpy()), bits(e_ref)), (c, w)
+        assert np.array_equal(bits(outs[c].cpu().numpy()), bits(data[c][3])), c
+    for c in ctxs:
+        c.destroy()
