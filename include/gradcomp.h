@@ -231,6 +231,8 @@ gc_status gc_profile_read(gc_ctx* ctx, int32_t id, double* total_ms, int64_t* la
  *   "dense_lds_pad" the same for the dense coder (0..65536, or -1: chosen by block size and code; default -1).
  *   "dense_wave_block"  dense coder: blocks of up to this many elements are held by one wavefront,
  *                   larger ones by a workgroup (0..2048; default 1024).
+ *   "dec_large_tile"  the aggregate's output tile held in LDS by one wavefront: 16384 floats (1),
+ *                   4096 floats (0), or chosen from the vector's length and filling (-1; default).
  * Unknown names or out-of-range values return GC_ERR_INVALID_ARG. */
 gc_status gc_set_option(gc_ctx* ctx, const char* name, int64_t value);
 

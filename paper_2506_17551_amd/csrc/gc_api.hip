@@ -62,6 +62,7 @@ struct gc_ctx {
   int64_t opt_main_lds_pad = 16384;  // dynamic LDS of the streaming pass: at most 8 workgroups per CU
   int64_t opt_dense_wave_block = 1024;  // dense coder: blocks up to this size are held by one wavefront
   int64_t opt_dense_lds_pad = -1;       // dense coder: dynamic LDS per workgroup (occupancy bound); -1: by shape
+  int64_t opt_dec_large_tile = -1;      // aggregate: 16384-float tiles (1), 4096-float tiles (0), or by shape (-1)
   // profiling
   int prof = 0;  // 0 off, 1 every kernel, 2 only the streaming pass
   std::vector<EventPair> ev_used, ev_free;
@@ -537,9 +538,10 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     }
   }
   GC_HIP(hipSetDevice(ctx->device));
-  const int64_t ntiles = (n + kDecTile - 1) / kDecTile;
+  const int tshift = ctx->opt_dec_large_tile < 0 ? dec_tile_shift(nrec, n) : dec_tile_shift_of(ctx->opt_dec_large_tile != 0);
+  const int64_t ntiles = (n + (int64_t(1) << tshift) - 1) >> tshift;
   if (ntiles >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
-  const int tb = dec_range_tiles(W, nrec, n);
+  const int tb = dec_range_tiles(W, tshift, nrec, n);
   const int64_t nranges = (ntiles + tb - 1) / tb;
   gc_status st = ensure(ctx->dec_brk, sizeof(uint32_t) * (size_t)(nranges + 1) * W);
   if (st == GC_OK) st = ensure(ctx->dec_rec, sizeof(uint2) * (size_t)std::max<int64_t>(nrec, 1));
@@ -551,16 +553,16 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     if (st != GC_OK) return st;
   }
   hipStream_t s = (hipStream_t)hip_stream;
-  { Scope sc(ctx, kKDecBrackets, s); launch_dec_brackets(a, W, ib, tb, ntiles, (uint32_t*)ctx->dec_brk.p, s); }
+  { Scope sc(ctx, kKDecBrackets, s); launch_dec_brackets(a, W, ib, tb, tshift, ntiles, (uint32_t*)ctx->dec_brk.p, s); }
   {
     Scope sc(ctx, kKDecPack, s);
-    launch_dec_pack(a, W, ib, tb, block, ntiles, (const uint32_t*)ctx->dec_brk.p, D ? (const long long*)D->kprefix.p : nullptr,
+    launch_dec_pack(a, W, ib, tb, tshift, block, ntiles, (const uint32_t*)ctx->dec_brk.p, D ? (const long long*)D->kprefix.p : nullptr,
                     D ? (const long long*)D->sprefix.p : nullptr, D ? (const long long*)D->qprefix.p : nullptr,
                     D ? T : 1, codec, staleness ? 1 : 0, ctx->dec_rec.p, (unsigned long long*)ctx->dec_tile_start.p, s);
   }
   {
     Scope sc(ctx, kKDecTiles, s);
-    launch_dec_tiles(ctx->dec_rec.p, (const unsigned long long*)ctx->dec_tile_start.p, (uint64_t)nrec, n, ntiles, out,
+    launch_dec_tiles(ctx->dec_rec.p, (const unsigned long long*)ctx->dec_tile_start.p, (uint64_t)nrec, tshift, n, ntiles, out,
                      apply ? 1 : 0, c_apply, s);
   }
   return launch_status();
@@ -885,6 +887,11 @@ gc_status gc_set_option(gc_ctx* ctx, const char* name, int64_t value) {
   if (std::strcmp(name, "dense_wave_block") == 0) {
     if (value < 0 || value > 2048) return GC_ERR_INVALID_ARG;
     ctx->opt_dense_wave_block = value;
+    return GC_OK;
+  }
+  if (std::strcmp(name, "dec_large_tile") == 0) {
+    if (value < -1 || value > 1) return GC_ERR_INVALID_ARG;
+    ctx->opt_dec_large_tile = value;
     return GC_OK;
   }
   if (std::strcmp(name, "dense_lds_pad") == 0) {

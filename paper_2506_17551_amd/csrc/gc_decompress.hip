@@ -13,7 +13,8 @@
 //                   and writes them as 8-byte records {position in tile | worker << 16, value},
 //                   ordered by tile, then worker, then index. tile_start[t] is the first record
 //                   of tile t. All of a range's records lie in one window of the stream.
-//   k_dec_tiles     one wavefront per tile of kDecTile output floats held in LDS: reads the
+//   k_dec_tiles     one wavefront per tile of output floats held in LDS (4096 floats; 16384 where
+//                   tiles are thinly filled, see dec_tile_shift): reads the
 //                   tile's run of records with coalesced loads, adds them into the LDS tile worker
 //                   by worker (ascending), then writes the tile once with 128-bit stores. Every
 //                   output byte is written exactly once; there is no separate memset and no global
@@ -29,8 +30,6 @@
 namespace gc {
 namespace {
 
-static_assert(kDecTile <= 65536, "a record keeps the position in 16 bits");
-static_assert(kMaxWorkers <= 65536, "a record keeps the worker in 16 bits");
 
 template <typename I>
 __device__ __forceinline__ uint32_t lower_bound_idx(const I* __restrict__ idx, uint32_t lo, uint32_t hi,
@@ -42,16 +41,17 @@ __device__ __forceinline__ uint32_t lower_bound_idx(const I* __restrict__ idx, u
   return lo;
 }
 
-// brk[r * W + w] = first pair of worker w whose index is >= r * tb * kDecTile, for r in [0, nranges].
+// brk[r * W + w] = first pair of worker w whose index is >= r * tb * tile, for r in [0, nranges]
+// (tile = 1 << tshift output floats).
 template <typename I>
-__global__ __launch_bounds__(256) void k_dec_brackets(DecArgs a, int W, int tb, int64_t nranges,
+__global__ __launch_bounds__(256) void k_dec_brackets(DecArgs a, int W, int tb, int tshift, int64_t nranges,
                                                       uint32_t* __restrict__ brk) {
   const int64_t flat = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (flat >= (nranges + 1) * W) return;
   const int w = (int)(flat % W);
   const int64_t r = flat / W;
   brk[flat] = lower_bound_idx<I>(static_cast<const I*>(a.indices[w]), 0u, a.k[w],
-                                 (unsigned long long)r * (unsigned long long)tb * kDecTile);
+                                 ((unsigned long long)r * (unsigned long long)tb) << tshift);
 }
 
 // The wavefronts of a workgroup share out the workers (several wavefronts per worker when there are
@@ -66,7 +66,7 @@ constexpr int kPackThreads = GC_PACK_THREADS, kPackWaves = kPackThreads / 64;
 constexpr int kPackBatch = GC_PACK_BATCH;  // pairs per lane whose loads are issued before any is used
 
 template <typename I>
-__global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int tb, int32_t block, int64_t ntiles,
+__global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int tb, int tshift, int32_t block, int64_t ntiles,
                                                            const uint32_t* __restrict__ brk,
                                                            const long long* __restrict__ kprefix,
                                                            const long long* __restrict__ sprefix,
@@ -128,11 +128,11 @@ __global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int
 #pragma unroll
       for (int u = 0; u < kPackBatch; ++u) {
         const unsigned long long j = jb + u * step;
-        const int64_t tc = (int64_t)(cur[u] / kDecTile) - t0;
+        const int64_t tc = (int64_t)(cur[u] >> tshift) - t0;
         if (j < j1 && tc >= 0 && tc < tb) {  // outside only with indices out of order
           int64_t tp = -1;
           if (j > j0) {
-            tp = (int64_t)(prev[u] / kDecTile) - t0;
+            tp = (int64_t)(prev[u] >> tshift) - t0;
             if (tp < -1) tp = -1;
           }
           for (int64_t t = tp + 1; t <= tc; ++t) s_lo[t * W + w] = (uint32_t)j;
@@ -214,13 +214,13 @@ __global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int
 #pragma unroll
       for (int u = 0; u < kPackBatch; ++u) {
         const unsigned long long j = jb + u * step;
-        const int64_t tc = (int64_t)(gi[u] / kDecTile) - t0;
+        const int64_t tc = (int64_t)(gi[u] >> tshift) - t0;
         if (j < j1 && tc >= 0 && tc < tb) {
           const uint32_t lo = s_lo[tc * W + w], hi = s_lo[(tc + 1) * W + w];
           const uint32_t dest = s_off[tc * W + w] + ((uint32_t)j - lo);
           // a record is only written inside its own segment (it always is when the indices ascend)
           if ((uint32_t)j >= lo && (uint32_t)j < hi && dest < total) {
-            const uint32_t pos = (uint32_t)(gi[u] - (unsigned long long)(t0 + tc) * kDecTile);
+            const uint32_t pos = (uint32_t)(gi[u] - ((unsigned long long)(t0 + tc) << tshift));
             rec[s_base + dest] = make_uint2(pos | ((uint32_t)w << 16), __float_as_uint(val[u]));
           }
         }
@@ -229,14 +229,16 @@ __global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int
   }
 }
 
-#ifndef GC_DEC_WAVES
-#define GC_DEC_WAVES 8
-#endif
-constexpr int kDecWaves = GC_DEC_WAVES;  // wavefronts (= tiles) per workgroup
-#ifndef GC_DEC_GRID
-#define GC_DEC_GRID 256
-#endif
-constexpr int kDecGrid = GC_DEC_GRID;    // persistent workgroups (1 per CU: 8 tiles of 16 KB in LDS)
+// Tiles of 4096 floats (16 KB of LDS per wavefront, 8 wavefronts per workgroup), or of 16384 floats
+// (64 KB, 2 wavefronts) where a tile of 4096 would hold few records: with large tiles the long
+// vectors at low density (7B at 0.1 %, 16 workers: 66 records per 4096 floats) spend less per tile
+// on everything but the write (5.35 against 5.8 ms), while crowded tiles (1.3B at 0.5 %: 330
+// records) do better small (1.2 against 2.0 ms). One persistent workgroup per compute unit.
+constexpr int kDecTileShiftSmall = 12, kDecWavesSmall = 8;
+constexpr int kDecTileShiftLarge = 14, kDecWavesLarge = 2;
+constexpr int kDecGrid = 256;
+static_assert(kDecTileShiftLarge <= 16, "a record keeps the position in 16 bits");
+static_assert(kMaxWorkers <= 65536, "a record keeps the worker in 16 bits");
 constexpr int kDecRounds = 4;            // rounds of 64 records whose loads are in flight together
 
 constexpr uint32_t kClaimed = 0x7FC0DEADu;   // a NaN pattern no finite sum can produce
@@ -253,10 +255,11 @@ __device__ __forceinline__ void wave_sync() {  // orders the wavefront's own LDS
 // the round, issued back to back. The LDS executes a wavefront's instructions in the order they
 // were issued, so nothing has to wait in between, and within one worker the positions are unique,
 // so the lanes of one instruction never collide.
+template <int TILE>
 __device__ __forceinline__ void add_round(uint2 r, float* lt) {
   const uint32_t pos = r.x & 0xFFFFu;
   const int w = (int)((r.x >> 16) < (uint32_t)(kMaxWorkers - 1) ? (r.x >> 16) : (uint32_t)(kMaxWorkers - 1));
-  const bool act = pos < (uint32_t)kDecTile;
+  const bool act = pos < (uint32_t)TILE;
   const uint64_t am = __ballot(act);
   if (am == 0ull) return;
   const int w_first = __shfl(w, __ffsll((unsigned long long)am) - 1);
@@ -270,18 +273,18 @@ __device__ __forceinline__ void add_round(uint2 r, float* lt) {
 
 // MODE 0: out[tile] = sum (dense write).  MODE 1: theta[i] -= c * sum[i] at the touched i only.
 // Wavefronts walk the tiles with a grid stride, without workgroup barriers.
-template <int MODE>
-__global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(const uint2* __restrict__ rec,
+template <int MODE, int TILE, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_dec_tiles(const uint2* __restrict__ rec,
                                                    const unsigned long long* __restrict__ tile_start,
                                                    unsigned long long nrec, int64_t n, int64_t ntiles,
                                                    float* __restrict__ out, float c_apply) {
-  __shared__ float tile_mem[kDecWaves][kDecTile];
+  __shared__ float tile_mem[WAVES][TILE];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* lt = tile_mem[wave];
-  const int64_t stride = (int64_t)gridDim.x * kDecWaves;
+  const int64_t stride = (int64_t)gridDim.x * WAVES;
 
-  for (int64_t tile = (int64_t)blockIdx.x * kDecWaves + wave; tile < ntiles; tile += stride) {
-    const int64_t base = tile * kDecTile;
+  for (int64_t tile = (int64_t)blockIdx.x * WAVES + wave; tile < ntiles; tile += stride) {
+    const int64_t base = tile * TILE;
     unsigned long long first = tile_start[tile], last = tile_start[tile + 1];
     if (last > nrec) last = nrec;
     const unsigned long long total = last > first ? last - first : 0ull;
@@ -289,7 +292,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(const uint2* __res
 
     const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-    for (int i = 0; i < kDecTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
+    for (int i = 0; i < TILE / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
     wave_sync();
 
     for (unsigned long long s0 = 0; s0 < total; s0 += 64 * kDecRounds) {
@@ -301,20 +304,20 @@ __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(const uint2* __res
         if (p < total) r[i] = rec[first + p];
       }
 #pragma unroll
-      for (int i = 0; i < kDecRounds; ++i) add_round(r[i], lt);
+      for (int i = 0; i < kDecRounds; ++i) add_round<TILE>(r[i], lt);
     }
     wave_sync();
 
     if (MODE == 0) {
       const int64_t remain = n - base;
-      if (remain >= kDecTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
+      if (remain >= TILE && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
 #pragma unroll
-        for (int i = 0; i < kDecTile / 256; ++i) {
+        for (int i = 0; i < TILE / 256; ++i) {
           const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
           __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
         }
       } else {
-        const int lim = (int)(remain < kDecTile ? remain : kDecTile);
+        const int lim = (int)(remain < TILE ? remain : TILE);
         for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
       }
     } else {
@@ -325,7 +328,7 @@ __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(const uint2* __res
         if (p < total) {
           const uint32_t pos = rec[first + p].x & 0xFFFFu;
           const int64_t gi = base + (int64_t)pos;
-          if (pos < (uint32_t)kDecTile && gi < n) {
+          if (pos < (uint32_t)TILE && gi < n) {
             const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + pos, kClaimed);
             if (old != kClaimed) out[gi] = __fsub_rn(out[gi], __fmul_rn(c_apply, __uint_as_float(old)));
           }
@@ -338,48 +341,68 @@ __global__ __launch_bounds__(kDecWaves * 64) void k_dec_tiles(const uint2* __res
 
 }  // namespace
 
-// Tiles per range of the packing pass: 128 (64 with many workers: the LDS tables hold
-// (2 * tiles + 1) * W entries), fewer when the tiles are crowded or the vector is short, so that a
-// range stays a small piece of work and there are enough ranges to fill the chip. A power of two
-// between 8 and 128.
-int dec_range_tiles(int W, int64_t nrec, int64_t n) {
-  const double per_tile = (double)nrec * kDecTile / (double)(n > 0 ? n : 1);
-  const int64_t ntiles = (n + kDecTile - 1) / kDecTile;
-  int tb = W <= 32 ? 128 : 64;
+// log2 of the tile size for a call: large tiles for long, thinly filled vectors.
+int dec_tile_shift(int64_t nrec, int64_t n) {
+  const double per_small = (double)nrec * (1 << kDecTileShiftSmall) / (double)(n > 0 ? n : 1);
+  return (n >= (int64_t(1) << 28) && per_small <= 96.0) ? kDecTileShiftLarge : kDecTileShiftSmall;
+}
+
+int dec_tile_shift_of(bool large) { return large ? kDecTileShiftLarge : kDecTileShiftSmall; }
+
+// Tiles per range of the packing pass: as many as make a range 2^19 output floats (128 small
+// tiles; half that with many workers: the LDS tables hold (2 * tiles + 1) * W entries), fewer when
+// the tiles are crowded or the vector is short, so that a range stays a small piece of work and
+// there are enough ranges to fill the chip. A power of two, at least 8.
+int dec_range_tiles(int W, int tshift, int64_t nrec, int64_t n) {
+  const double per_tile = (double)nrec * (double)(int64_t(1) << tshift) / (double)(n > 0 ? n : 1);
+  const int64_t ntiles = (n + (int64_t(1) << tshift) - 1) >> tshift;
+  int tb = (W <= 32 ? (1 << 19) : (1 << 18)) >> tshift;
   while (tb > 8 && (per_tile * tb > 32768.0 || ntiles / tb < 2048)) tb >>= 1;
   return tb;
 }
 
-void launch_dec_brackets(const DecArgs& a, int W, int index_bits, int tb, int64_t ntiles, uint32_t* brk, hipStream_t s) {
+void launch_dec_brackets(const DecArgs& a, int W, int index_bits, int tb, int tshift, int64_t ntiles, uint32_t* brk,
+                         hipStream_t s) {
   const int64_t nranges = (ntiles + tb - 1) / tb;
   const dim3 grid((unsigned)(((nranges + 1) * W + 255) / 256));
-  if (index_bits == 32) hipLaunchKernelGGL(k_dec_brackets<uint32_t>, grid, dim3(256), 0, s, a, W, tb, nranges, brk);
-  else hipLaunchKernelGGL(k_dec_brackets<unsigned long long>, grid, dim3(256), 0, s, a, W, tb, nranges, brk);
+  if (index_bits == 32)
+    hipLaunchKernelGGL(k_dec_brackets<uint32_t>, grid, dim3(256), 0, s, a, W, tb, tshift, nranges, brk);
+  else
+    hipLaunchKernelGGL(k_dec_brackets<unsigned long long>, grid, dim3(256), 0, s, a, W, tb, tshift, nranges, brk);
 }
 
-void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int32_t block, int64_t ntiles, const uint32_t* brk,
-                     const long long* kprefix, const long long* sprefix, const long long* qprefix, int T,
-                     int codec, int weighted, void* rec, unsigned long long* tile_start, hipStream_t s) {
+void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift, int32_t block, int64_t ntiles,
+                     const uint32_t* brk, const long long* kprefix, const long long* sprefix, const long long* qprefix,
+                     int T, int codec, int weighted, void* rec, unsigned long long* tile_start, hipStream_t s) {
   const dim3 grid((unsigned)((ntiles + tb - 1) / tb));
   const size_t lds = sizeof(uint32_t) * (size_t)(2 * tb + 1) * W;  // at most 33 KB
   if (index_bits == 32)
-    hipLaunchKernelGGL(k_dec_pack<uint32_t>, grid, dim3(kPackThreads), lds, s, a, W, tb, block, ntiles, brk, kprefix,
-                       sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
-  else
-    hipLaunchKernelGGL(k_dec_pack<unsigned long long>, grid, dim3(kPackThreads), lds, s, a, W, tb, block, ntiles, brk,
+    hipLaunchKernelGGL(k_dec_pack<uint32_t>, grid, dim3(kPackThreads), lds, s, a, W, tb, tshift, block, ntiles, brk,
                        kprefix, sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
+  else
+    hipLaunchKernelGGL(k_dec_pack<unsigned long long>, grid, dim3(kPackThreads), lds, s, a, W, tb, tshift, block, ntiles,
+                       brk, kprefix, sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
 }
 
-void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int64_t n,
-                      int64_t ntiles, float* out, int apply, float c_apply, hipStream_t s) {
-  const int64_t want = (ntiles + kDecWaves - 1) / kDecWaves;
-  const dim3 grid((unsigned)(want < kDecGrid ? want : kDecGrid)), blk(kDecWaves * 64);
+template <int TSHIFT, int WAVES>
+static void launch_tiles_shape(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int64_t n,
+                               int64_t ntiles, float* out, int apply, float c_apply, hipStream_t s) {
+  const int64_t want = (ntiles + WAVES - 1) / WAVES;
+  const dim3 grid((unsigned)(want < kDecGrid ? want : kDecGrid)), blk(WAVES * 64);
   if (apply)
-    hipLaunchKernelGGL(k_dec_tiles<1>, grid, blk, 0, s, (const uint2*)rec, tile_start, (unsigned long long)nrec, n,
-                       ntiles, out, c_apply);
+    hipLaunchKernelGGL((k_dec_tiles<1, (1 << TSHIFT), WAVES>), grid, blk, 0, s, (const uint2*)rec, tile_start,
+                       (unsigned long long)nrec, n, ntiles, out, c_apply);
   else
-    hipLaunchKernelGGL(k_dec_tiles<0>, grid, blk, 0, s, (const uint2*)rec, tile_start, (unsigned long long)nrec, n,
-                       ntiles, out, c_apply);
+    hipLaunchKernelGGL((k_dec_tiles<0, (1 << TSHIFT), WAVES>), grid, blk, 0, s, (const uint2*)rec, tile_start,
+                       (unsigned long long)nrec, n, ntiles, out, c_apply);
+}
+
+void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int tshift, int64_t n,
+                      int64_t ntiles, float* out, int apply, float c_apply, hipStream_t s) {
+  if (tshift == kDecTileShiftLarge)
+    launch_tiles_shape<kDecTileShiftLarge, kDecWavesLarge>(rec, tile_start, nrec, n, ntiles, out, apply, c_apply, s);
+  else
+    launch_tiles_shape<kDecTileShiftSmall, kDecWavesSmall>(rec, tile_start, nrec, n, ntiles, out, apply, c_apply, s);
 }
 
 }  // namespace gc

@@ -221,10 +221,6 @@ template <> struct GradVec<uint16_t> {
 };
 
 constexpr int kMaxWorkers = 64;
-#ifndef GC_DEC_TILE
-#define GC_DEC_TILE 4096
-#endif
-constexpr int kDecTile = GC_DEC_TILE;  // output floats per wave-tile of decompress_sum
 struct DecArgs {
   const void* indices[kMaxWorkers];
   const int8_t* q[kMaxWorkers];
@@ -232,14 +228,17 @@ struct DecArgs {
   uint32_t k[kMaxWorkers];
   float denom[kMaxWorkers];  // 1 + staleness of the worker (weighted aggregate)
 };
-// Tiles per range of the packing pass, from the expected number of records per tile.
-int dec_range_tiles(int W, int64_t nrec, int64_t n);
+// log2 of the output tile (floats) for a call, and tiles per range of the packing pass.
+int dec_tile_shift(int64_t nrec, int64_t n);
+int dec_tile_shift_of(bool large);
+int dec_range_tiles(int W, int tshift, int64_t nrec, int64_t n);
 // brk: (ranges + 1) * W entries; rec: one 8-byte record per pair of all workers; tile_start: ntiles + 1 entries.
-void launch_dec_brackets(const DecArgs& a, int W, int index_bits, int tb, int64_t ntiles, uint32_t* brk, hipStream_t s);
-void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int32_t block, int64_t ntiles, const uint32_t* brk,
-                     const long long* kprefix, const long long* sprefix, const long long* qprefix, int T,
-                     int codec, int weighted, void* rec, unsigned long long* tile_start, hipStream_t s);
-void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int64_t n,
+void launch_dec_brackets(const DecArgs& a, int W, int index_bits, int tb, int tshift, int64_t ntiles, uint32_t* brk,
+                         hipStream_t s);
+void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift, int32_t block, int64_t ntiles,
+                     const uint32_t* brk, const long long* kprefix, const long long* sprefix, const long long* qprefix,
+                     int T, int codec, int weighted, void* rec, unsigned long long* tile_start, hipStream_t s);
+void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int tshift, int64_t n,
                       int64_t ntiles, float* out, int apply, float c_apply, hipStream_t s);
 
 // ---- dense codes (every entry kept, no indices) -----------------------------

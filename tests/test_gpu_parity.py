@@ -269,10 +269,12 @@ def test_decompress_sum_sixteen_workers_with_collisions(gc, ctx, oracle):
         counts[idx] += 1
     assert (counts >= 3).sum() > 1000  # the order of the fp32 adds matters for these
     for Wsub in (1, 2, 3, 5, 16):
-        out = gc.decompress_sum(ctx, bufs[:Wsub], n)
-        torch.cuda.synchronize()
         rc, want = oracle.decompress_sum(refs[:Wsub], n, block)
-        assert np.array_equal(bits(out.cpu().numpy()), bits(want)), Wsub
+        for tile in (0, 1, -1):  # both tile sizes of the aggregate, then back to the choice by shape
+            ctx.set_option("dec_large_tile", tile)
+            out = gc.decompress_sum(ctx, bufs[:Wsub], n)
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(out.cpu().numpy()), bits(want)), (Wsub, tile)
     for Wbig in (33, 64):  # many workers (the same buffers again and again: every position is shared)
         pick = [(7 * i) % W for i in range(Wbig)]
         stale = [i % 3 for i in range(Wbig)]
@@ -323,15 +325,18 @@ def test_decompress_sum_cancellation_down_to_subnormals(gc, ctx, oracle, codec):
 
 def test_decompress_sum_edge_shapes(gc, ctx, oracle):
     for n, k in ((1, 1), (2047, 3), (2048, 2048), (2049, 1), (4095, 3), (4096, 4096), (4097, 1), (10000, 10000),
+                 (16383, 5), (16384, 16384), (16385, 2),
                  (300000, 1), (524287, 100), (524288, 9), (524289, 7), (1_048_577, 11)):  # around tiles and ranges of tiles
         g = inputs.normal(n, 1.0, n)
         buf, ref, _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 8, tag="dec edge")
-        out = torch.full((n + 8,), 7.0, device=DEV)
-        gc.decompress_sum(ctx, [buf, buf, buf], n, out=out[:n])
-        torch.cuda.synchronize()
         rc, want = oracle.decompress_sum([ref] * 3, n, 8)
-        assert np.array_equal(bits(out[:n].cpu().numpy()), bits(want))
-        assert torch.all(out[n:] == 7.0)  # nothing written past n
+        for tile in (0, 1, -1):
+            ctx.set_option("dec_large_tile", tile)
+            out = torch.full((n + 8,), 7.0, device=DEV)
+            gc.decompress_sum(ctx, [buf, buf, buf], n, out=out[:n])
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(out[:n].cpu().numpy()), bits(want)), (n, k, tile)
+            assert torch.all(out[n:] == 7.0)  # nothing written past n
     # an unaligned output pointer
     n, k = 50001, 500
     g = inputs.normal(n, 1.0, 3)
@@ -508,14 +513,15 @@ def test_fused_aggregate_and_apply(gc, ctx, oracle, weighted):
     taus = [w % 5 for w in range(W)] if weighted else None
     theta0 = inputs.normal(n, 1.0, 5)
     theta0[::7] = -0.0                                   # signed zeros must survive untouched
-    for step in (0.0, 0.01, 1.0 / W):
+    for step, tile in ((0.0, -1), (0.01, 0), (0.01, 1), (1.0 / W, -1)):
+        ctx.set_option("dec_large_tile", tile)
         theta = theta0.to(DEV).clone()
         gc.decompress_apply(ctx, bufs, theta, step, staleness=taus)
         torch.cuda.synchronize()
         rc, S = oracle.decompress_sum(refs, n, block, staleness=taus)
         want = theta0.numpy().copy()
         assert oracle.apply(want, S, step) == 0
-        assert np.array_equal(bits(theta.cpu().numpy()), bits(want)), step
+        assert np.array_equal(bits(theta.cpu().numpy()), bits(want)), (step, tile)
     # the separate route gives the same parameters: dense aggregate, then the update
     theta = theta0.to(DEV).clone()
     gc.decompress_apply(ctx, bufs, theta, 0.03, staleness=taus)
@@ -723,13 +729,24 @@ def _random_buffer(rng, gc, n, ks, block, index_bits, codec):
     return buf, (idx, q, s)
 
 
+@pytest.fixture(params=[-1, 0, 1], ids=["tile-auto", "tile-4096", "tile-16384"])
+def tile_ctx(gc, request):
+    """A context with the aggregate's tile size forced (the large tile is otherwise only chosen
+    for vectors of 2^28 elements and more)."""
+    c = gc.Context(0)
+    c.set_option("dec_large_tile", request.param)
+    yield c
+    c.destroy()
+
+
 @pytest.mark.parametrize("seed", [20250617, 7, 99])
-def test_aggregate_random_hand_built_buffers(gc, ctx, oracle, seed):
+def test_aggregate_random_hand_built_buffers(gc, tile_ctx, oracle, seed):
+    ctx = tile_ctx
     """decompress_sum / weighted / apply on buffers built directly (no compress step): random sizes
     around tile and range edges, 1 to 64 workers, sparse to fully dense lists, both codes and index
     widths, single and multi-tensor block layouts."""
     rng = np.random.default_rng(seed)
-    edges = [1, 2, 4095, 4096, 4097, 8192, 524287, 524288, 524289, 1_048_576 + 3]
+    edges = [1, 2, 4095, 4096, 4097, 8192, 16383, 16384, 16385, 524287, 524288, 524289, 1_048_576 + 3]
     for case in range(36):
         n = int(rng.choice(edges)) if case % 3 == 0 else int(rng.integers(1, 1_500_000))
         W = int(rng.choice([1, 2, 3, 4, 5, 8, 16, 17, 32, 33, 64]))
