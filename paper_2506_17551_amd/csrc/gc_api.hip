@@ -538,7 +538,11 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     }
   }
   GC_HIP(hipSetDevice(ctx->device));
-  const int tshift = ctx->opt_dec_large_tile < 0 ? dec_tile_shift(nrec, n) : dec_tile_shift_of(ctx->opt_dec_large_tile != 0);
+  // the in-place update reads and rewrites scattered words of theta: it needs many wavefronts per
+  // compute unit more than it needs large tiles (7B: 5.0 ms with small tiles, 7.0 ms with large ones)
+  const int tshift = ctx->opt_dec_large_tile >= 0 ? dec_tile_shift_of(ctx->opt_dec_large_tile != 0)
+                     : apply                      ? dec_tile_shift_of(false)
+                                                  : dec_tile_shift(nrec, n);
   const int64_t ntiles = (n + (int64_t(1) << tshift) - 1) >> tshift;
   if (ntiles >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
   const int tb = dec_range_tiles(W, tshift, nrec, n);
