@@ -33,3 +33,13 @@ def oracle():
     from oracle import gc_oracle
     gc_oracle.build()
     return gc_oracle
+
+
+@pytest.fixture
+def progress(capsys):
+    """Prints a line past pytest's capture: the long full-size tests name each step as it starts,
+    so that a run which stops there shows where."""
+    def say(msg):
+        with capsys.disabled():
+            print(f"\n[progress] {msg}", end="", flush=True)
+    return say

@@ -248,10 +248,41 @@ def test_config2_decoder_scaled_eight_workers(gc, ctx, oracle):
     _multi_case(gc, ctx, oracle, w.sizes, w.density, w.block, W=8, seed=200)
 
 
-def test_config2_decoder_full_size(gc, ctx, oracle):
+def test_config2_decoder_full_size_eight_workers(gc, ctx, oracle, progress):
+    """Config 2 as named: 148 tensors, 124,439,808 parameters, 8 workers with independent seeds, each
+    compressed per tensor and checked against the oracle, then Eq. 8 over all 8 buffers."""
     w = inputs.workload(2)
-    st = _multi_case(gc, ctx, oracle, w.sizes, w.density, w.block, W=2, seed=300)
-    assert st["tensors"] == 148 and st["tensors_fallback"] == 0 and st["tensors_sampled"] == 50
+    assert w.W == 8 and len(w.sizes) == 148 and w.n == 124_439_808
+    off = inputs.offsets_of(w.sizes)
+    ks = np.array([gc.k_from_density(int(s), w.density) for s in w.sizes], dtype=np.int64)
+    assert int(ks.sum()) == 124_503
+    bufs, refs = [], []
+    for wk in range(w.W):
+        progress(f"config 2 full size: worker {wk} of {w.W}")
+        g = w.grad(wk, 0, "cpu")
+        e = inputs.normal(w.n, 0.005, inputs.seed_for(2, wk, 0, 0, 1))
+        e_ref = e.numpy().copy()
+        rc, idx, q, s = oracle.compress_multi(g.numpy(), e_ref, off, ks, w.block)
+        assert rc == 0
+        ed = e.to(DEV)
+        buf = gc.compress_multi(ctx, g.to(DEV), ed, off, ks, w.block)
+        gc.sync_status(ctx)
+        st = gc.last_stats(ctx)
+        assert st["tensors"] == 148 and st["tensors_fallback"] == 0 and st["tensors_sampled"] == 50
+        assert np.array_equal(buf.indices_numpy(), idx)
+        assert np.array_equal(buf.q.cpu().numpy(), q)
+        assert np.array_equal(bits(buf.scales.cpu().numpy()), bits(s))
+        assert np.array_equal(bits(ed.cpu().numpy()), bits(e_ref))
+        bufs.append(buf)
+        refs.append((idx, q, s))
+        del g, e, e_ref, ed
+    progress("config 2 full size: decompress_sum_multi(W=8)")
+    out = gc.decompress_sum_multi(ctx, bufs, ks, w.n)
+    torch.cuda.synchronize()
+    rc, want = oracle.decompress_sum(refs, w.n, w.block, ktensor=ks)
+    assert rc == 0 and np.array_equal(bits(out.cpu().numpy()), bits(want))
+    _, hits = np.unique(np.concatenate([r[0] for r in refs]), return_counts=True)
+    assert (hits >= 2).sum() > 100                    # positions named by several workers: the adds meet
 
 
 # ---------------------------------------------------------------------------------- aggregate
