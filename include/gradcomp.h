@@ -128,6 +128,21 @@ gc_status gc_compress_multi(gc_ctx* ctx, const void* grad, gc_dtype dtype, float
 gc_status gc_decompress_sum(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* out, int64_t n,
                             void* hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): gc_decompress_sum for single-tensor buffers, with the
+ * same result bit for bit, that allocates nothing - no hipMalloc, no hipFree, no workspace growth,
+ * no events. Its work arrays (range brackets, the merged record stream, tile starts) live in one
+ * static device array of GC_STATIC_SCRATCH_BYTES that every device the library runs on holds until
+ * the process ends. A call whose arrays would not fit returns GC_ERR_UNSUPPORTED and writes nothing:
+ *   4 * (ceil(n / 32768) + 1) * W + 8 * (ceil(n / 4096) + 1) + 8 * (sum of the buffers' k) + 512
+ * bytes is an upper bound on what a call takes (e.g. n = 2^30 with 3,500,000 pairs of 16 workers).
+ * All calls on one device share that array, and it keeps the last call's contents (every call
+ * rewrites all it reads, nothing has to start at zero): calls that overlap in time on one device,
+ * from any context or stream, race. The context only names the device. */
+#define GC_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+gc_status gc_decompress_sum_static(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* out, int64_t n,
+                                   void* hip_stream);
+
 /* The same for buffers written by gc_compress_multi: k holds the T per-tensor
  * counts (host; identical for every worker), so that scales are looked up per
  * tensor. */

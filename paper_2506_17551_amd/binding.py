@@ -37,7 +37,7 @@ class _GcStats(ctypes.Structure):
 
 
 EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_num_code_bytes", "gc_compress",
-           "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_multi", "gc_decompress_sum_weighted",
+           "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_static", "gc_decompress_sum_multi", "gc_decompress_sum_weighted",
            "gc_decompress_apply", "gc_compress_rows", "gc_decompress_sum_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
            "gc_sync_status",
            "gc_last_stats", "gc_profile_enable", "gc_profile_num_kernels", "gc_profile_kernel_name",
@@ -65,6 +65,7 @@ def lib() -> ctypes.CDLL:
     L.gc_compress.argtypes = [vp, vp, ctypes.c_int, vp, i64, i64, i32, ctypes.POINTER(_GcBuf), vp]
     L.gc_compress_multi.argtypes = [vp, vp, ctypes.c_int, vp, vp, vp, i32, i32, ctypes.POINTER(_GcBuf), vp]
     L.gc_decompress_sum.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i64, vp]
+    L.gc_decompress_sum_static.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i64, vp]
     L.gc_decompress_sum_multi.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, i64, vp]
     L.gc_decompress_sum_weighted.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, i64, vp]
     L.gc_decompress_apply.argtypes = [vp, ctypes.POINTER(_GcBuf), i32, vp, i32, vp, vp, ctypes.c_float, i64, vp]
@@ -85,6 +86,7 @@ def lib() -> ctypes.CDLL:
     L.gc_status_string.argtypes = [ctypes.c_int]
     L.gc_status_string.restype = ctypes.c_char_p
     for name in ("gc_create", "gc_destroy", "gc_compress", "gc_compress_multi", "gc_decompress_sum",
+                 "gc_decompress_sum_static",
                  "gc_decompress_sum_multi", "gc_decompress_sum_weighted", "gc_decompress_apply",
                  "gc_compress_rows", "gc_decompress_sum_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
                  "gc_sync_status", "gc_last_stats", "gc_profile_enable",
@@ -283,6 +285,18 @@ def decompress_sum(ctx: Context, bufs: List[CompressedBuf], n: int, out: Optiona
     arr = _buf_array(bufs)
     rc = lib().gc_decompress_sum(ctx.handle, arr, len(bufs), out.data_ptr(), int(n), _stream_ptr(stream, dev))
     _check(rc, "gc_decompress_sum")
+    return out
+
+
+def decompress_sum_static(ctx: Context, bufs: List[CompressedBuf], n: int, out: torch.Tensor,
+                          stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """gc_decompress_sum_static: the same aggregate without any allocation (static device scratch of
+    GC_STATIC_SCRATCH_BYTES; larger calls raise GC_ERR_UNSUPPORTED). `out` must be given."""
+    _check_dev(out, "out", torch.float32)
+    arr = _buf_array(bufs)
+    rc = lib().gc_decompress_sum_static(ctx.handle, arr, len(bufs), out.data_ptr(), int(n),
+                                        _stream_ptr(stream, out.device))
+    _check(rc, "gc_decompress_sum_static")
     return out
 
 

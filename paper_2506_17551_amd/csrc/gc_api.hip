@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -67,6 +68,17 @@ struct gc_ctx {
   int prof = 0;  // 0 off, 1 every kernel, 2 only the streaming pass
   std::vector<EventPair> ev_used, ev_free;
 };
+
+// ---- scratch of the entry point that allocates nothing --------------------------
+// gc_decompress_sum_static keeps its range brackets, record stream and tile starts in this array
+// instead of the context's workspace. Every device the library runs on holds its own copy at its own
+// address; the name below is only a host-side handle, so host code asks the runtime for the device
+// address once per device (in gc_create, with that device current) and uses that pointer from then on.
+constexpr size_t kStaticScratchBytes = (size_t)GC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, once looked up
+static std::mutex g_scratch_mu;
 
 namespace {
 
@@ -314,7 +326,7 @@ struct Scope {  // records an event pair around one launch when profiling is on
   EventPair ev;
   bool on;
   Scope(gc_ctx* ctx, int32_t id, hipStream_t st)
-      : c(ctx), s(st), on(ctx->prof == 1 || (ctx->prof == 2 && id == kKMain)) {
+      : c(ctx), s(st), on(ctx && (ctx->prof == 1 || (ctx->prof == 2 && id == kKMain))) {
     if (!on) return;
     if (!c->ev_free.empty()) {
       ev = c->ev_free.back();
@@ -497,9 +509,11 @@ gc_status get_dec_plan(gc_ctx* ctx, const int64_t* k, int32_t T, int32_t block, 
   return GC_OK;
 }
 
+// static_scratch: null, or the device address of the file-scope `scratch` array; the call then takes
+// its three work arrays from there instead of the context's workspace and allocates nothing.
 gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
                           const int32_t* staleness, bool apply, float c_apply, float* out, int64_t n,
-                          void* hip_stream) {
+                          void* hip_stream, unsigned char* static_scratch = nullptr) {
   if (!ctx || !bufs || !out || W < 1 || n <= 0) return GC_ERR_INVALID_ARG;
   if (apply && !(c_apply >= 0.0f && c_apply <= 3.0e38f)) return GC_ERR_INVALID_ARG;
   if (W > kMaxWorkers) return GC_ERR_UNSUPPORTED;
@@ -547,27 +561,48 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   if (ntiles >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
   const int tb = dec_range_tiles(W, tshift, nrec, n);
   const int64_t nranges = (ntiles + tb - 1) / tb;
-  gc_status st = ensure(ctx->dec_brk, sizeof(uint32_t) * (size_t)(nranges + 1) * W);
-  if (st == GC_OK) st = ensure(ctx->dec_rec, sizeof(uint2) * (size_t)std::max<int64_t>(nrec, 1));
-  if (st == GC_OK) st = ensure(ctx->dec_tile_start, sizeof(unsigned long long) * (size_t)(ntiles + 1));
-  if (st != GC_OK) return st;
+  const size_t brk_bytes = sizeof(uint32_t) * (size_t)(nranges + 1) * W;
+  const size_t rec_bytes = sizeof(uint2) * (size_t)std::max<int64_t>(nrec, 1);
+  const size_t ts_bytes = sizeof(unsigned long long) * (size_t)(ntiles + 1);
+  uint32_t* brk = nullptr;
+  void* rec = nullptr;
+  unsigned long long* tile_start = nullptr;
+  gc_status st = GC_OK;
   DecPlan* D = nullptr;
-  if (T > 1) {
-    st = get_dec_plan(ctx, k, T, block, codec, &D);
+  if (static_scratch) {
+    // carve the three arrays out of the static array (256-byte pieces); nothing is allocated
+    if (T > 1) return GC_ERR_UNSUPPORTED;
+    const size_t o_ts = (size_t)round_up((int64_t)brk_bytes, 256);
+    const size_t o_rec = o_ts + (size_t)round_up((int64_t)ts_bytes, 256);
+    if (o_rec + rec_bytes > kStaticScratchBytes) return GC_ERR_UNSUPPORTED;
+    brk = reinterpret_cast<uint32_t*>(static_scratch);
+    tile_start = reinterpret_cast<unsigned long long*>(static_scratch + o_ts);
+    rec = static_scratch + o_rec;
+  } else {
+    st = ensure(ctx->dec_brk, brk_bytes);
+    if (st == GC_OK) st = ensure(ctx->dec_rec, rec_bytes);
+    if (st == GC_OK) st = ensure(ctx->dec_tile_start, ts_bytes);
     if (st != GC_OK) return st;
+    if (T > 1) {
+      st = get_dec_plan(ctx, k, T, block, codec, &D);
+      if (st != GC_OK) return st;
+    }
+    brk = (uint32_t*)ctx->dec_brk.p;
+    rec = ctx->dec_rec.p;
+    tile_start = (unsigned long long*)ctx->dec_tile_start.p;
   }
   hipStream_t s = (hipStream_t)hip_stream;
-  { Scope sc(ctx, kKDecBrackets, s); launch_dec_brackets(a, W, ib, tb, tshift, ntiles, (uint32_t*)ctx->dec_brk.p, s); }
+  gc_ctx* pc = static_scratch ? nullptr : ctx;  // event pairs are created on demand: not in the static variant
+  { Scope sc(pc, kKDecBrackets, s); launch_dec_brackets(a, W, ib, tb, tshift, ntiles, brk, s); }
   {
-    Scope sc(ctx, kKDecPack, s);
-    launch_dec_pack(a, W, ib, tb, tshift, block, ntiles, (const uint32_t*)ctx->dec_brk.p, D ? (const long long*)D->kprefix.p : nullptr,
+    Scope sc(pc, kKDecPack, s);
+    launch_dec_pack(a, W, ib, tb, tshift, block, ntiles, brk, D ? (const long long*)D->kprefix.p : nullptr,
                     D ? (const long long*)D->sprefix.p : nullptr, D ? (const long long*)D->qprefix.p : nullptr,
-                    D ? T : 1, codec, staleness ? 1 : 0, ctx->dec_rec.p, (unsigned long long*)ctx->dec_tile_start.p, s);
+                    D ? T : 1, codec, staleness ? 1 : 0, rec, tile_start, s);
   }
   {
-    Scope sc(ctx, kKDecTiles, s);
-    launch_dec_tiles(ctx->dec_rec.p, (const unsigned long long*)ctx->dec_tile_start.p, (uint64_t)nrec, tshift, n, ntiles, out,
-                     apply ? 1 : 0, c_apply, s);
+    Scope sc(pc, kKDecTiles, s);
+    launch_dec_tiles(rec, tile_start, (uint64_t)nrec, tshift, n, ntiles, out, apply ? 1 : 0, c_apply, s);
   }
   return launch_status();
 }
@@ -630,6 +665,17 @@ gc_status gc_create(gc_ctx** out, int device) {
   }
   if (device < 0 || device >= count) return GC_ERR_INVALID_ARG;
   GC_HIP(hipSetDevice(device));
+  if (device < kMaxDevices) {  // this device's copy of the static scratch array: looked up once
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return GC_ERR_DEVICE;
+      }
+      g_scratch_ptr[device] = p;
+    }
+  }
   gc_ctx* c = new (std::nothrow) gc_ctx();
   if (!c) return GC_ERR_WORKSPACE;
   c->device = device;
@@ -699,6 +745,19 @@ gc_status gc_compress_multi(gc_ctx* ctx, const void* grad, gc_dtype dtype, float
 gc_status gc_decompress_sum(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* out, int64_t n,
                             void* hip_stream) {
   return decompress_impl(ctx, bufs, W, nullptr, 0, nullptr, false, 0.0f, out, n, hip_stream);
+}
+
+gc_status gc_decompress_sum_static(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* out, int64_t n,
+                                   void* hip_stream) {
+  if (!ctx) return GC_ERR_INVALID_ARG;
+  if (ctx->device < 0 || ctx->device >= kMaxDevices) return GC_ERR_UNSUPPORTED;
+  unsigned char* sp = nullptr;
+  {
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    sp = static_cast<unsigned char*>(g_scratch_ptr[ctx->device]);  // set by gc_create on this device
+  }
+  if (!sp) return GC_ERR_DEVICE;
+  return decompress_impl(ctx, bufs, W, nullptr, 0, nullptr, false, 0.0f, out, n, hip_stream, sp);
 }
 
 gc_status gc_decompress_sum_weighted(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int64_t* k, int32_t T,
