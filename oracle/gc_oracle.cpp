@@ -33,11 +33,13 @@
 //       starting from +0.
 //   R9  Alternative value code, the paper's own 1-bit quantizer (Eq. 10): the code of a kept
 //       entry is its sign (+1 if v >= 0, which includes -0; -1 otherwise) and the block's
-//       scale is the mean magnitude ||v||_1 / len ("accompanied by a scaling factor, e.g.
-//       ||g||_1"). To make the scale a fixed number, the l1 sum is accumulated in fp64 by
-//       the balanced binary tree over the block's entries padded with zeros to a power of
+//       scale is the mean magnitude ||v||_1 / len (Sec. III.B, Eq. 10: the scale is derived
+//       from the l1 norm). To make the scale a fixed number, the l1 sum is accumulated in fp64
+//       by the balanced binary tree over the block's entries padded with zeros to a power of
 //       two, s = (float)(sum / len) (one fp64 division, one rounding to fp32), zero or
-//       subnormal s sends zeros. ghat = +-s; the residual is fl32(acc - ghat). Signs are
+//       subnormal s sends zeros. The tree is a CHOSEN order, not a plain definition: it is the
+//       order a parallel reduction can reproduce bit for bit. The pins therefore also check the
+//       sent scale against the plain left-to-right fp64 sum and the exactly rounded sum. ghat = +-s; the residual is fl32(acc - ghat). Signs are
 //       packed 8 per byte, least significant bit first, every block starting a new byte.
 //   R10 Row-sparse gradients (an embedding table of R rows x D columns of which a step touches
 //       U rows): the residual lives with the table, the step runs on the touched rows only -

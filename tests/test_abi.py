@@ -44,3 +44,53 @@ def test_product_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "gc_oracle" not in src and "import oracle" not in src and "from oracle" not in src, f
+
+
+def test_code_bytes_table():
+    """gc_num_code_bytes (pure host) against the hand-worked table."""
+    import paper_2506_17551_amd as gc
+    for k, block, codec, want in read_golden("code_bytes.txt")["rows"]:
+        assert gc.num_code_bytes(int(k), int(block), int(codec)) == int(want), (k, block, codec)
+    assert gc.num_code_bytes(10, 4, 7) == 0          # unknown code
+
+
+def test_error_paths_that_need_no_device():
+    """Argument errors that every entry point reports before it touches HIP: a null context, null
+    output pointers of the pure functions. No kernel is launched and no device is needed."""
+    from paper_2506_17551_amd import binding
+    L = binding.lib()
+    INV = binding.GC_ERR_INVALID_ARG
+    buf = binding._GcBuf()
+    stats = binding._GcStats()
+    ms, cnt = ctypes.c_double(), ctypes.c_int64()
+    assert L.gc_create(None, 0) == INV
+    assert L.gc_destroy(None) == INV
+    assert L.gc_compress(None, 1, 0, 1, 16, 1, 4, ctypes.byref(buf), None) == INV
+    assert L.gc_compress_multi(None, 1, 0, 1, 1, 1, 1, 4, ctypes.byref(buf), None) == INV
+    assert L.gc_decompress_sum(None, ctypes.byref(buf), 1, 1, 16, None) == INV
+    assert L.gc_decompress_sum_static(None, ctypes.byref(buf), 1, 1, 16, None) == INV
+    assert L.gc_decompress_sum_multi(None, ctypes.byref(buf), 1, 1, 1, 1, 16, None) == INV
+    assert L.gc_decompress_sum_weighted(None, ctypes.byref(buf), 1, None, 0, 1, 1, 16, None) == INV
+    assert L.gc_decompress_apply(None, ctypes.byref(buf), 1, None, 0, None, 1, 0.5, 16, None) == INV
+    assert L.gc_compress_rows(None, 1, 0, 1, 1, 1, 1, 1, 1, 1, ctypes.byref(buf), None) == INV
+    assert L.gc_decompress_sum_rows(None, ctypes.byref(buf), 1, 1, 1, 1, None, 1, None) == INV
+    assert L.gc_compress_dense(None, 1, 0, 1, 16, 4, 0, 1, 1, None) == INV
+    assert L.gc_decompress_sum_dense(None, 1, 1, 1, 4, 0, None, 1, 16, None) == INV
+    assert L.gc_decompress_apply_dense(None, 1, 1, 1, 4, 0, None, 1, 0.5, 16, None) == INV
+    assert L.gc_sync_status(None, None) == INV
+    assert L.gc_last_stats(None, ctypes.byref(stats)) == INV
+    assert L.gc_profile_enable(None, 1) == INV
+    assert L.gc_profile_read(None, 0, ctypes.byref(ms), ctypes.byref(cnt)) == INV
+    assert L.gc_set_option(None, b"main_lds_pad", 0) == INV
+    assert L.gc_profile_num_kernels() >= 18
+    assert L.gc_profile_kernel_name(-1) == b"" and L.gc_profile_kernel_name(10 ** 6) == b""
+    names = {L.gc_profile_kernel_name(i).decode() for i in range(L.gc_profile_num_kernels())}
+    assert {"k_main", "k_dec_tiles", "k_quant"} <= names
+    for code in range(6):
+        assert binding._status_string(code) not in ("", "unknown status")
+    assert binding._status_string(99) == "unknown status"
+    # pure host size rules at their edges
+    import paper_2506_17551_amd as gc
+    assert gc.k_from_density(0, 0.5) == 0 and gc.k_from_density(10, 0.0) == 1 and gc.k_from_density(10, 2.0) == 10
+    assert gc.k_from_density(10, float("nan")) == 1
+    assert gc.num_scales(5, 0) == 0 and gc.num_scales(-3, 4) == 0

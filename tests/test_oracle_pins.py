@@ -537,6 +537,62 @@ def test_sign_code_properties(oracle):
     assert np.array_equal(out3, (out * np.float32(1.5)).astype(np.float32))
 
 
+def test_golden_code_bytes(oracle):
+    """gco_num_code_bytes against a table worked by hand (both value codes, full and short blocks)."""
+    rows = read_golden("code_bytes.txt")["rows"]
+    assert len(rows) >= 20
+    for k, block, codec, want in rows:
+        assert oracle.num_code_bytes(int(k), int(block), int(codec)) == int(want), (k, block, codec)
+
+
+def _plain_l1_mean(v):
+    """sum |v| left to right in fp64, one division, one rounding to fp32."""
+    acc = 0.0
+    for x in v:
+        acc += abs(float(x))
+    s = np.float32(acc / len(v))
+    return s if s >= np.finfo(np.float32).tiny else np.float32(0)
+
+
+def test_sign_scale_does_not_depend_on_the_summation_order(oracle):
+    """The oracle adds the block's magnitudes in fp64 over a balanced tree (a reading chosen so that
+    a parallel reduction can reproduce the bits). The scale it sends must still be THE mean magnitude:
+    equal, after the rounding to fp32, to the plain left-to-right fp64 sum and to the exactly rounded
+    sum (math.fsum), on every value distribution and block size, and on blocks built to punish a
+    sloppy sum (huge first entry followed by many small ones, alternating signs, a lone tiny tail)."""
+    import math
+    n, k = 6000, 1500
+    for name, g, r0 in _dists(n, 47):
+        for block in (1, 3, 8, 64, 100, 1000, 1500):
+            e = r0.copy()
+            acc = (g + r0).astype(np.float32)
+            rc, idx, q, s = oracle.compress(g, e, k, block, codec=oracle.SIGN1)
+            assert rc == 0
+            v = acc[idx]
+            for b in range(s.size):
+                blkv = v[b * block:(b + 1) * block]
+                assert s[b] == _plain_l1_mean(blkv), (name, block, b)
+    adversarial = [
+        np.array([3e7] + [1.0] * 4095, np.float32),                       # one huge entry, then units
+        np.array([1.0] * 4095 + [3e7], np.float32),
+        np.array([(-1.0) ** i * (1.0 + i * 2.0 ** -20) for i in range(3000)], np.float32),
+        np.array([1e30, -1e30, 1e-30, -1e-30] * 500, np.float32),
+        np.array([2.0 ** -126] * 777 + [2.0 ** -149] * 3, np.float32),    # smallest normals and a subnormal tail
+        np.array([16777216.0, 1.0, 1.0, 1.0, 1.0, 1.0, 1.0], np.float32),  # exact in fp64, not in fp32
+    ]
+    for i, v in enumerate(adversarial):
+        for block in (v.size, 7, 256, 1024):
+            e = np.zeros(v.size, np.float32)
+            rc, idx, q, s = oracle.compress(v, e, v.size, block, codec=oracle.SIGN1)
+            assert rc == 0 and np.array_equal(idx, np.arange(v.size))
+            for b in range(s.size):
+                blkv = v[b * block:(b + 1) * block]
+                exact = np.float32(math.fsum(abs(float(x)) for x in blkv) / blkv.size)
+                if not exact >= np.finfo(np.float32).tiny:
+                    exact = np.float32(0)
+                assert s[b] == exact == _plain_l1_mean(blkv), (i, block, b)
+
+
 def test_sign_code_multi_tensor(oracle):
     sizes = [100, 7, 300, 1]
     off = inputs.offsets_of(sizes)
