@@ -131,11 +131,11 @@ gc_status gc_decompress_sum(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* o
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): gc_decompress_sum for single-tensor buffers, with the
  * same result bit for bit, that allocates nothing - no hipMalloc, no hipFree, no workspace growth,
- * no events. Its work arrays (range brackets, the merged record stream, tile starts) live in one
- * static device array of GC_STATIC_SCRATCH_BYTES that every device the library runs on holds until
- * the process ends. A call whose arrays would not fit returns GC_ERR_UNSUPPORTED and writes nothing:
- *   4 * (ceil(n / 32768) + 1) * W + 8 * (ceil(n / 4096) + 1) + 8 * (sum of the buffers' k) + 512
- * bytes is an upper bound on what a call takes (e.g. n = 2^30 with 3,500,000 pairs of 16 workers).
+ * no events. Its work arrays (the merged record stream, tile starts) live in one static device array
+ * of GC_STATIC_SCRATCH_BYTES that every device the library runs on holds until the process ends. A
+ * call whose arrays would not fit returns GC_ERR_UNSUPPORTED and writes nothing:
+ *   8 * (ceil(n / 4096) + 1) + 8 * (sum of the buffers' k) + 256
+ * bytes is an upper bound on what a call takes (e.g. n = 2^30 with 3,900,000 pairs in all).
  * All calls on one device share that array, and it keeps the last call's contents (every call
  * rewrites all it reads, nothing has to start at zero): calls that overlap in time on one device,
  * from any context or stream, race. The context only names the device. */
@@ -248,6 +248,8 @@ gc_status gc_profile_read(gc_ctx* ctx, int32_t id, double* total_ms, int64_t* la
  *                   larger ones by a workgroup (0..2048; default 1024).
  *   "dec_large_tile"  the aggregate's output tile held in LDS by one wavefront: 16384 floats (1),
  *                   4096 floats (0), or chosen from the vector's length and filling (-1; default).
+ *   "apply_dense_min"  fused apply: an output tile with at least this many pairs per 4096 floats is
+ *                   read and rewritten whole instead of position by position (1..2^30; default 128).
  * Unknown names or out-of-range values return GC_ERR_INVALID_ARG. */
 gc_status gc_set_option(gc_ctx* ctx, const char* name, int64_t value);
 

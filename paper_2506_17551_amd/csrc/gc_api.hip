@@ -54,7 +54,7 @@ struct gc_ctx {
   DevBuf rows_cidx;         // compact positions of all workers' pairs (aggregate over a row list)
   DevBuf ts, shist, hist, grp_cnt, grp_part, grp_off, tg_base, slots, cand_val, cand_idx, ch_gt,
       ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, blk_amax, flags;
-  DevBuf dec_brk, dec_rec, dec_tile_start;  // aggregate: range brackets, packed pair records, first record of every tile
+  DevBuf dec_rec, dec_tile_start;  // aggregate: packed pair records, first record of every tile
   uint32_t* host_flags = nullptr;  // pinned
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
   size_t host_ts_cap = 0;
@@ -64,13 +64,14 @@ struct gc_ctx {
   int64_t opt_dense_wave_block = 1024;  // dense coder: blocks up to this size are held by one wavefront
   int64_t opt_dense_lds_pad = -1;       // dense coder: dynamic LDS per workgroup (occupancy bound); -1: by shape
   int64_t opt_dec_large_tile = -1;      // aggregate: 16384-float tiles (1), 4096-float tiles (0), or by shape (-1)
+  int64_t opt_apply_dense_min = 128;    // fused apply: tiles with at least this many records per 4096 floats are rewritten whole
   // profiling
   int prof = 0;  // 0 off, 1 every kernel, 2 only the streaming pass
   std::vector<EventPair> ev_used, ev_free;
 };
 
 // ---- scratch of the entry point that allocates nothing --------------------------
-// gc_decompress_sum_static keeps its range brackets, record stream and tile starts in this array
+// gc_decompress_sum_static keeps its record stream and tile starts in this array
 // instead of the context's workspace. Every device the library runs on holds its own copy at its own
 // address; the name below is only a host-side handle, so host code asks the runtime for the device
 // address once per device (in gc_create, with that device current) and uses that pointer from then on.
@@ -561,48 +562,42 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   if (ntiles >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
   const int tb = dec_range_tiles(W, tshift, nrec, n);
   const int64_t nranges = (ntiles + tb - 1) / tb;
-  const size_t brk_bytes = sizeof(uint32_t) * (size_t)(nranges + 1) * W;
   const size_t rec_bytes = sizeof(uint2) * (size_t)std::max<int64_t>(nrec, 1);
   const size_t ts_bytes = sizeof(unsigned long long) * (size_t)(ntiles + 1);
-  uint32_t* brk = nullptr;
   void* rec = nullptr;
   unsigned long long* tile_start = nullptr;
   gc_status st = GC_OK;
   DecPlan* D = nullptr;
   if (static_scratch) {
-    // carve the three arrays out of the static array (256-byte pieces); nothing is allocated
+    // carve the two arrays out of the static array (256-byte pieces); nothing is allocated
     if (T > 1) return GC_ERR_UNSUPPORTED;
-    const size_t o_ts = (size_t)round_up((int64_t)brk_bytes, 256);
-    const size_t o_rec = o_ts + (size_t)round_up((int64_t)ts_bytes, 256);
+    const size_t o_rec = (size_t)round_up((int64_t)ts_bytes, 256);
     if (o_rec + rec_bytes > kStaticScratchBytes) return GC_ERR_UNSUPPORTED;
-    brk = reinterpret_cast<uint32_t*>(static_scratch);
-    tile_start = reinterpret_cast<unsigned long long*>(static_scratch + o_ts);
+    tile_start = reinterpret_cast<unsigned long long*>(static_scratch);
     rec = static_scratch + o_rec;
   } else {
-    st = ensure(ctx->dec_brk, brk_bytes);
-    if (st == GC_OK) st = ensure(ctx->dec_rec, rec_bytes);
+    st = ensure(ctx->dec_rec, rec_bytes);
     if (st == GC_OK) st = ensure(ctx->dec_tile_start, ts_bytes);
     if (st != GC_OK) return st;
     if (T > 1) {
       st = get_dec_plan(ctx, k, T, block, codec, &D);
       if (st != GC_OK) return st;
     }
-    brk = (uint32_t*)ctx->dec_brk.p;
     rec = ctx->dec_rec.p;
     tile_start = (unsigned long long*)ctx->dec_tile_start.p;
   }
   hipStream_t s = (hipStream_t)hip_stream;
   gc_ctx* pc = static_scratch ? nullptr : ctx;  // event pairs are created on demand: not in the static variant
-  { Scope sc(pc, kKDecBrackets, s); launch_dec_brackets(a, W, ib, tb, tshift, ntiles, brk, s); }
   {
     Scope sc(pc, kKDecPack, s);
-    launch_dec_pack(a, W, ib, tb, tshift, block, ntiles, brk, D ? (const long long*)D->kprefix.p : nullptr,
+    launch_dec_pack(a, W, ib, tb, tshift, block, ntiles, 0, nranges, D ? (const long long*)D->kprefix.p : nullptr,
                     D ? (const long long*)D->sprefix.p : nullptr, D ? (const long long*)D->qprefix.p : nullptr,
                     D ? T : 1, codec, staleness ? 1 : 0, rec, tile_start, s);
   }
   {
     Scope sc(pc, kKDecTiles, s);
-    launch_dec_tiles(rec, tile_start, (uint64_t)nrec, tshift, n, ntiles, out, apply ? 1 : 0, c_apply, s);
+    launch_dec_tiles(rec, tile_start, (uint64_t)nrec, tshift, n, 0, ntiles, out, apply ? 1 : 0, c_apply,
+                     (unsigned)ctx->opt_apply_dense_min, s);
   }
   return launch_status();
 }
@@ -648,7 +643,7 @@ gc_status dense_sum_impl(gc_ctx* ctx, const void* const* q, const float* const* 
 
 const char* const kKernelNames[kKNum] = {"k_init", "k_sample", "k_sample_thresh", "k_main", "k_group_sums", "k_group_scan",
                                          "k_route", "k_gather", "k_hist", "k_select_scan", "k_count",
-                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_brackets", "k_dec_pack", "k_dec_tiles",
+                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_pack", "k_dec_tiles",
                                          "k_dense", "k_dense_sum", "k_rows_gather", "k_rows_finish", "k_rows_remap"};
 
 }  // namespace
@@ -684,7 +679,9 @@ gc_status gc_create(gc_ctx** out, int device) {
   if (st == GC_OK && hipHostMalloc((void**)&c->host_flags, sizeof(uint32_t) * 4, hipHostMallocDefault) != hipSuccess)
     st = GC_ERR_WORKSPACE;
   if (st != GC_OK) {
+    (void)hipGetLastError();
     release(c->flags);
+    if (c->host_flags) (void)hipHostFree(c->host_flags);
     delete c;
     return st;
   }
@@ -701,7 +698,7 @@ gc_status gc_destroy(gc_ctx* c) {
   DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
                    &c->slots, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
                    &c->ch_part_gt, &c->ch_part_eq, &c->ch_goff, &c->ch_eoff, &c->tb_g, &c->tb_e,
-                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->dec_brk, &c->dec_rec, &c->dec_tile_start, &c->rows_e, &c->rows_idx, &c->rows_cidx};
+                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->dec_rec, &c->dec_tile_start, &c->rows_e, &c->rows_idx, &c->rows_cidx};
   for (DevBuf* b : all) release(*b);
   if (c->host_flags) (void)hipHostFree(c->host_flags);
   if (c->host_ts) (void)hipHostFree(c->host_ts);
@@ -955,6 +952,11 @@ gc_status gc_set_option(gc_ctx* ctx, const char* name, int64_t value) {
   if (std::strcmp(name, "dec_large_tile") == 0) {
     if (value < -1 || value > 1) return GC_ERR_INVALID_ARG;
     ctx->opt_dec_large_tile = value;
+    return GC_OK;
+  }
+  if (std::strcmp(name, "apply_dense_min") == 0) {
+    if (value < 1 || value > (int64_t(1) << 30)) return GC_ERR_INVALID_ARG;
+    ctx->opt_apply_dense_min = value;
     return GC_OK;
   }
   if (std::strcmp(name, "dense_lds_pad") == 0) {

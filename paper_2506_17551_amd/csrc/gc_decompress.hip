@@ -6,13 +6,13 @@
 // latency, not by the 4 bytes per element it has to write. So the pairs are first merged into ONE
 // stream that is already in the order the tiles consume it:
 //
-//   k_dec_brackets  for every range of `tb` output tiles and every worker, the first pair whose
-//                   index falls in the range (binary search in the worker's ascending index list).
-//   k_dec_pack      one workgroup per range: finds, in LDS, where every (tile, worker) segment
-//                   starts, decodes the range's pairs (coalesced reads along each worker's list)
-//                   and writes them as 8-byte records {position in tile | worker << 16, value},
-//                   ordered by tile, then worker, then index. tile_start[t] is the first record
-//                   of tile t. All of a range's records lie in one window of the stream.
+//   k_dec_pack      one workgroup per range of `tb` output tiles: finds every worker's first pair
+//                   in the range and after it (binary search in the worker's ascending index list),
+//                   then, in LDS, where every (tile, worker) segment starts, decodes the range's
+//                   pairs (coalesced reads along each worker's list) and writes them as 8-byte
+//                   records {position in tile | worker << 16, value}, ordered by tile, then worker,
+//                   then index. tile_start[t] is the first record of tile t. All of a range's
+//                   records lie in one window of the stream.
 //   k_dec_tiles     one wavefront per tile of output floats held in LDS (4096 floats; 16384 where
 //                   tiles are thinly filled, see dec_tile_shift): reads the
 //                   tile's run of records with coalesced loads, adds them into the LDS tile worker
@@ -41,19 +41,6 @@ __device__ __forceinline__ uint32_t lower_bound_idx(const I* __restrict__ idx, u
   return lo;
 }
 
-// brk[r * W + w] = first pair of worker w whose index is >= r * tb * tile, for r in [0, nranges]
-// (tile = 1 << tshift output floats).
-template <typename I>
-__global__ __launch_bounds__(256) void k_dec_brackets(DecArgs a, int W, int tb, int tshift, int64_t nranges,
-                                                      uint32_t* __restrict__ brk) {
-  const int64_t flat = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (flat >= (nranges + 1) * W) return;
-  const int w = (int)(flat % W);
-  const int64_t r = flat / W;
-  brk[flat] = lower_bound_idx<I>(static_cast<const I*>(a.indices[w]), 0u, a.k[w],
-                                 ((unsigned long long)r * (unsigned long long)tb) << tshift);
-}
-
 // The wavefronts of a workgroup share out the workers (several wavefronts per worker when there are
 // few workers); every lane issues the loads of a batch of pairs before it uses any of them.
 #ifndef GC_PACK_THREADS
@@ -67,7 +54,7 @@ constexpr int kPackBatch = GC_PACK_BATCH;  // pairs per lane whose loads are iss
 
 template <typename I>
 __global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int tb, int tshift, int32_t block, int64_t ntiles,
-                                                           const uint32_t* __restrict__ brk,
+                                                           int64_t r_first,
                                                            const long long* __restrict__ kprefix,
                                                            const long long* __restrict__ sprefix,
                                                            const long long* __restrict__ qprefix, int T, int codec,
@@ -81,11 +68,20 @@ __global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int team = W >= kPackWaves ? 1 : kPackWaves / W;  // wavefronts that share one worker's pairs
   const unsigned long long step = 64ull * team;
-  const int64_t r = blockIdx.x, t0 = r * tb;
+  const int64_t r = r_first + blockIdx.x, t0 = r * tb;
 
+  // every worker's first pair at or after the start of this range and of the next one: 2 W binary
+  // searches side by side (W <= 64, so they fit the first two wavefronts)
+  __shared__ uint32_t s_br1[kMaxWorkers];
+  if (tid < 2 * W) {
+    const int w = tid < W ? tid : tid - W;
+    const unsigned long long target = ((unsigned long long)(r + (tid < W ? 0 : 1)) * (unsigned long long)tb) << tshift;
+    const uint32_t b = lower_bound_idx<I>(static_cast<const I*>(a.indices[w]), 0u, a.k[w], target);
+    if (tid < W) s_br0[w] = b; else s_br1[w] = b;
+  }
+  __syncthreads();
   if (tid < W) {
-    const uint32_t b0 = brk[r * W + tid], b1 = brk[(r + 1) * W + tid];
-    s_br0[tid] = b0;
+    const uint32_t b0 = s_br0[tid], b1 = s_br1[tid];
     s_excl[tid + 1] = b1 > b0 ? b1 - b0 : 0u;  // count, turned into a prefix below
   }
   __syncthreads();
@@ -167,9 +163,10 @@ __global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int
   }
   __syncthreads();
 
-  for (int t = tid; t < tb; t += kPackThreads)
-    if (t0 + t <= ntiles) tile_start[t0 + t] = s_base + s_off[t * W];
-  if (tid == 0 && t0 + tb == ntiles) tile_start[ntiles] = s_base + total;  // the last range ends at the last tile
+  // the range also writes where it ends (the next range writes the same number there as its own
+  // start): the tiles of this range can then be consumed before the next range has been packed
+  for (int t = tid; t <= tb; t += kPackThreads)
+    if (t0 + t <= ntiles) tile_start[t0 + t] = s_base + (t < tb ? s_off[t * W] : total);
 
   for (int w = wave / team; w < W; w += kPackWaves / team) {
     const I* idx = static_cast<const I*>(a.indices[w]);
@@ -276,14 +273,15 @@ __device__ __forceinline__ void add_round(uint2 r, float* lt) {
 template <int MODE, int TILE, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_dec_tiles(const uint2* __restrict__ rec,
                                                    const unsigned long long* __restrict__ tile_start,
-                                                   unsigned long long nrec, int64_t n, int64_t ntiles,
-                                                   float* __restrict__ out, float c_apply) {
+                                                   unsigned long long nrec, int64_t n, int64_t t_begin,
+                                                   int64_t t_end, float* __restrict__ out, float c_apply,
+                                                   unsigned apply_dense_min) {
   __shared__ float tile_mem[WAVES][TILE];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* lt = tile_mem[wave];
   const int64_t stride = (int64_t)gridDim.x * WAVES;
 
-  for (int64_t tile = (int64_t)blockIdx.x * WAVES + wave; tile < ntiles; tile += stride) {
+  for (int64_t tile = t_begin + (int64_t)blockIdx.x * WAVES + wave; tile < t_end; tile += stride) {
     const int64_t base = tile * TILE;
     unsigned long long first = tile_start[tile], last = tile_start[tile + 1];
     if (last > nrec) last = nrec;
@@ -320,19 +318,52 @@ __global__ __launch_bounds__(WAVES * 64) void k_dec_tiles(const uint2* __restric
         const int lim = (int)(remain < TILE ? remain : TILE);
         for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
       }
+    } else if (total >= (unsigned long long)apply_dense_min && n - base >= TILE &&
+               ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
+      // A crowded tile (about one touched position per 128-byte line of theta, or more) is read and
+      // rewritten whole with full-width accesses: scattered 4-byte read-modify-writes move a 32-byte
+      // piece each way per position and run at a fraction of the streaming rate. Where nothing was
+      // named the sum is +0 and theta - fl32(c * +0) is theta itself, bit for bit.
+#pragma unroll 4
+      for (int i = 0; i < TILE / 256; ++i) {
+        const f32x4 sm = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
+        f32x4* p = reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4);
+        f32x4 th = *p;
+        th.x = __fsub_rn(th.x, __fmul_rn(c_apply, sm.x));
+        th.y = __fsub_rn(th.y, __fmul_rn(c_apply, sm.y));
+        th.z = __fsub_rn(th.z, __fmul_rn(c_apply, sm.z));
+        th.w = __fsub_rn(th.w, __fmul_rn(c_apply, sm.w));
+        *p = th;
+      }
     } else {
       // every touched position is claimed once (LDS exchange with a marker) and updated in place:
-      // theta - fl32(c * sum). Untouched positions have sum +0 and would not change anyway.
-      for (unsigned long long s0 = 0; s0 < total; s0 += 64) {
-        const unsigned long long p = s0 + (unsigned long long)lane;
-        if (p < total) {
-          const uint32_t pos = rec[first + p].x & 0xFFFFu;
-          const int64_t gi = base + (int64_t)pos;
-          if (pos < (uint32_t)TILE && gi < n) {
-            const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + pos, kClaimed);
-            if (old != kClaimed) out[gi] = __fsub_rn(out[gi], __fmul_rn(c_apply, __uint_as_float(old)));
+      // theta - fl32(c * sum). Untouched positions have sum +0 and would not change anyway. The
+      // loads of a batch of rounds are all issued before the first store.
+      for (unsigned long long s0 = 0; s0 < total; s0 += 64 * kDecRounds) {
+        int64_t gi[kDecRounds];
+        float sum[kDecRounds], th[kDecRounds];
+        bool mine[kDecRounds];
+#pragma unroll
+        for (int i = 0; i < kDecRounds; ++i) {
+          const unsigned long long p = s0 + (unsigned long long)(i * 64 + lane);
+          mine[i] = false;
+          gi[i] = 0;
+          sum[i] = 0.0f;
+          if (p < total) {
+            const uint32_t pos = rec[first + p].x & 0xFFFFu;
+            gi[i] = base + (int64_t)pos;
+            if (pos < (uint32_t)TILE && gi[i] < n) {
+              const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + pos, kClaimed);
+              mine[i] = old != kClaimed;
+              sum[i] = __uint_as_float(old);
+            }
           }
         }
+#pragma unroll
+        for (int i = 0; i < kDecRounds; ++i) th[i] = mine[i] ? out[gi[i]] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < kDecRounds; ++i)
+          if (mine[i]) out[gi[i]] = __fsub_rn(th[i], __fmul_rn(c_apply, sum[i]));
       }
     }
     wave_sync();
@@ -361,48 +392,45 @@ int dec_range_tiles(int W, int tshift, int64_t nrec, int64_t n) {
   return tb;
 }
 
-void launch_dec_brackets(const DecArgs& a, int W, int index_bits, int tb, int tshift, int64_t ntiles, uint32_t* brk,
-                         hipStream_t s) {
-  const int64_t nranges = (ntiles + tb - 1) / tb;
-  const dim3 grid((unsigned)(((nranges + 1) * W + 255) / 256));
-  if (index_bits == 32)
-    hipLaunchKernelGGL(k_dec_brackets<uint32_t>, grid, dim3(256), 0, s, a, W, tb, tshift, nranges, brk);
-  else
-    hipLaunchKernelGGL(k_dec_brackets<unsigned long long>, grid, dim3(256), 0, s, a, W, tb, tshift, nranges, brk);
-}
-
 void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift, int32_t block, int64_t ntiles,
-                     const uint32_t* brk, const long long* kprefix, const long long* sprefix, const long long* qprefix,
-                     int T, int codec, int weighted, void* rec, unsigned long long* tile_start, hipStream_t s) {
-  const dim3 grid((unsigned)((ntiles + tb - 1) / tb));
+                     int64_t r_first, int64_t r_count, const long long* kprefix, const long long* sprefix,
+                     const long long* qprefix, int T, int codec, int weighted, void* rec, unsigned long long* tile_start,
+                     hipStream_t s) {
+  const dim3 grid((unsigned)r_count);
   const size_t lds = sizeof(uint32_t) * (size_t)(2 * tb + 1) * W;  // at most 33 KB
   if (index_bits == 32)
-    hipLaunchKernelGGL(k_dec_pack<uint32_t>, grid, dim3(kPackThreads), lds, s, a, W, tb, tshift, block, ntiles, brk,
+    hipLaunchKernelGGL(k_dec_pack<uint32_t>, grid, dim3(kPackThreads), lds, s, a, W, tb, tshift, block, ntiles, r_first,
                        kprefix, sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
   else
     hipLaunchKernelGGL(k_dec_pack<unsigned long long>, grid, dim3(kPackThreads), lds, s, a, W, tb, tshift, block, ntiles,
-                       brk, kprefix, sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
+                       r_first, kprefix, sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
 }
 
 template <int TSHIFT, int WAVES>
 static void launch_tiles_shape(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int64_t n,
-                               int64_t ntiles, float* out, int apply, float c_apply, hipStream_t s) {
-  const int64_t want = (ntiles + WAVES - 1) / WAVES;
+                               int64_t t_begin, int64_t t_end, float* out, int apply, float c_apply,
+                               unsigned apply_dense_min, hipStream_t s) {
+  const int64_t want = (t_end - t_begin + WAVES - 1) / WAVES;
   const dim3 grid((unsigned)(want < kDecGrid ? want : kDecGrid)), blk(WAVES * 64);
   if (apply)
     hipLaunchKernelGGL((k_dec_tiles<1, (1 << TSHIFT), WAVES>), grid, blk, 0, s, (const uint2*)rec, tile_start,
-                       (unsigned long long)nrec, n, ntiles, out, c_apply);
+                       (unsigned long long)nrec, n, t_begin, t_end, out, c_apply, apply_dense_min);
   else
     hipLaunchKernelGGL((k_dec_tiles<0, (1 << TSHIFT), WAVES>), grid, blk, 0, s, (const uint2*)rec, tile_start,
-                       (unsigned long long)nrec, n, ntiles, out, c_apply);
+                       (unsigned long long)nrec, n, t_begin, t_end, out, c_apply, apply_dense_min);
 }
 
 void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int tshift, int64_t n,
-                      int64_t ntiles, float* out, int apply, float c_apply, hipStream_t s) {
+                      int64_t t_begin, int64_t t_end, float* out, int apply, float c_apply, unsigned apply_dense_min,
+                      hipStream_t s) {
+  if (t_end <= t_begin) return;
+  // apply_dense_min counts records per 4096 floats; a large tile holds four times as many
   if (tshift == kDecTileShiftLarge)
-    launch_tiles_shape<kDecTileShiftLarge, kDecWavesLarge>(rec, tile_start, nrec, n, ntiles, out, apply, c_apply, s);
+    launch_tiles_shape<kDecTileShiftLarge, kDecWavesLarge>(rec, tile_start, nrec, n, t_begin, t_end, out, apply, c_apply,
+                                                            apply_dense_min << (kDecTileShiftLarge - kDecTileShiftSmall), s);
   else
-    launch_tiles_shape<kDecTileShiftSmall, kDecWavesSmall>(rec, tile_start, nrec, n, ntiles, out, apply, c_apply, s);
+    launch_tiles_shape<kDecTileShiftSmall, kDecWavesSmall>(rec, tile_start, nrec, n, t_begin, t_end, out, apply, c_apply,
+                                                            apply_dense_min, s);
 }
 
 }  // namespace gc

@@ -140,7 +140,7 @@ struct OutBuf {
 // kernel ids for profiling
 enum KernelId : int32_t {
   kKInit = 0, kKSample, kKSampleThresh, kKMain, kKGroupSums, kKGroupScan, kKRoute, kKGather, kKHist,
-  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecBrackets, kKDecPack, kKDecTiles, kKDense, kKDenseSum, kKRowsGather, kKRowsFinish, kKRowsRemap, kKNum
+  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecPack, kKDecTiles, kKDense, kKDenseSum, kKRowsGather, kKRowsFinish, kKRowsRemap, kKNum
 };
 
 // launchers (defined in the .hip files next to their kernels)
@@ -232,14 +232,15 @@ struct DecArgs {
 int dec_tile_shift(int64_t nrec, int64_t n);
 int dec_tile_shift_of(bool large);
 int dec_range_tiles(int W, int tshift, int64_t nrec, int64_t n);
-// brk: (ranges + 1) * W entries; rec: one 8-byte record per pair of all workers; tile_start: ntiles + 1 entries.
-void launch_dec_brackets(const DecArgs& a, int W, int index_bits, int tb, int tshift, int64_t ntiles, uint32_t* brk,
-                         hipStream_t s);
+// rec: one 8-byte record per pair of all workers; tile_start: ntiles + 1 entries. The packing pass
+// takes ranges [r_first, r_first + r_count), the tile pass tiles [t_begin, t_end).
 void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift, int32_t block, int64_t ntiles,
-                     const uint32_t* brk, const long long* kprefix, const long long* sprefix, const long long* qprefix,
-                     int T, int codec, int weighted, void* rec, unsigned long long* tile_start, hipStream_t s);
+                     int64_t r_first, int64_t r_count, const long long* kprefix, const long long* sprefix,
+                     const long long* qprefix, int T, int codec, int weighted, void* rec, unsigned long long* tile_start,
+                     hipStream_t s);
 void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int tshift, int64_t n,
-                      int64_t ntiles, float* out, int apply, float c_apply, hipStream_t s);
+                      int64_t t_begin, int64_t t_end, float* out, int apply, float c_apply, unsigned apply_dense_min,
+                      hipStream_t s);
 
 // ---- dense codes (every entry kept, no indices) -----------------------------
 constexpr int kDenseMaxBlock = 8192;   // larger blocks do not fit one workgroup's registers

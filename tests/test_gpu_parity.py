@@ -544,15 +544,20 @@ def test_fused_aggregate_and_apply(gc, ctx, oracle, weighted):
     taus = [w % 5 for w in range(W)] if weighted else None
     theta0 = inputs.normal(n, 1.0, 5)
     theta0[::7] = -0.0                                   # signed zeros must survive untouched
-    for step, tile in ((0.0, -1), (0.01, 0), (0.01, 1), (1.0 / W, -1)):
+    # both tile sizes, and both ways a tile is updated: position by position (apply_dense_min out of
+    # reach) and rewritten whole (apply_dense_min = 1); 128 is the default
+    for step, tile, dmin in ((0.0, -1, 128), (0.01, 0, 1 << 30), (0.01, 1, 1 << 30), (0.01, 0, 1), (0.01, 1, 1),
+                             (1.0 / W, -1, 128), (1.0 / W, -1, 1 << 30)):
         ctx.set_option("dec_large_tile", tile)
+        ctx.set_option("apply_dense_min", dmin)
         theta = theta0.to(DEV).clone()
         gc.decompress_apply(ctx, bufs, theta, step, staleness=taus)
         torch.cuda.synchronize()
         rc, S = oracle.decompress_sum(refs, n, block, staleness=taus)
         want = theta0.numpy().copy()
         assert oracle.apply(want, S, step) == 0
-        assert np.array_equal(bits(theta.cpu().numpy()), bits(want)), (step, tile)
+        assert np.array_equal(bits(theta.cpu().numpy()), bits(want)), (step, tile, dmin)
+    ctx.set_option("apply_dense_min", 128)
     # the separate route gives the same parameters: dense aggregate, then the update
     theta = theta0.to(DEV).clone()
     gc.decompress_apply(ctx, bufs, theta, 0.03, staleness=taus)
