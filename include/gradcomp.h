@@ -79,9 +79,22 @@ typedef struct {
 } gc_stats;
 
 /* Create / destroy a context on HIP device `device`. Workspace grows on the
- * first call that needs it (that call synchronises the device once). */
+ * first call that needs more of it (that call waits for the device, frees and allocates);
+ * gc_reserve sizes it ahead of time. */
 gc_status gc_create(gc_ctx** ctx, int device);
 gc_status gc_destroy(gc_ctx* ctx);
+
+/* Size the workspace once, so that later calls neither allocate nor wait: after it, every
+ * single-tensor call (gc_compress, gc_compress_rows, the aggregates over up to max_W buffers of up
+ * to max_k pairs each, gc_decompress_sum_rows) with n (for rows: U * D) <= max_n and k <= max_k only
+ * queues kernels on the caller's stream, whatever its exact shape - such calls may sit inside a
+ * stream capture and their shape may change from call to call. Multi-tensor calls
+ * (gc_compress_multi, gc_decompress_sum_multi) with up to max_tensors tensors, max_n elements and
+ * max_k pairs in total, and no tensor denser than max_k / max_n, find the workspace large enough too,
+ * but still upload a small per-shape plan the first time a shape (offsets, k, block, code) is seen
+ * (eight shapes are remembered). Waits for the device once if anything has to grow.
+ * 1 <= max_k <= max_n, max_tensors >= 1, 0 <= max_W <= 64 (0: no aggregate workspace). */
+gc_status gc_reserve(gc_ctx* ctx, int64_t max_n, int64_t max_k, int32_t max_tensors, int32_t max_W);
 
 /* k = clamp(ceil(n * density), 1, n), n * density evaluated in IEEE double.
  * Pure host function. The paper names no k; this is the rule the workloads use. */

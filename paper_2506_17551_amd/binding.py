@@ -36,7 +36,7 @@ class _GcStats(ctypes.Structure):
                 ("tensors_fallback", ctypes.c_int64), ("candidates", ctypes.c_int64)]
 
 
-EXPORTS = ["gc_create", "gc_destroy", "gc_k_from_density", "gc_num_scales", "gc_num_code_bytes", "gc_compress",
+EXPORTS = ["gc_create", "gc_destroy", "gc_reserve", "gc_k_from_density", "gc_num_scales", "gc_num_code_bytes", "gc_compress",
            "gc_compress_multi", "gc_decompress_sum", "gc_decompress_sum_static", "gc_decompress_sum_multi", "gc_decompress_sum_weighted",
            "gc_decompress_apply", "gc_compress_rows", "gc_decompress_sum_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
            "gc_sync_status",
@@ -56,6 +56,7 @@ def lib() -> ctypes.CDLL:
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     L.gc_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int]
     L.gc_destroy.argtypes = [vp]
+    L.gc_reserve.argtypes = [vp, i64, i64, i32, i32]
     L.gc_k_from_density.argtypes = [i64, ctypes.c_double]
     L.gc_k_from_density.restype = i64
     L.gc_num_scales.argtypes = [i64, i32]
@@ -85,7 +86,7 @@ def lib() -> ctypes.CDLL:
     L.gc_set_option.restype = ctypes.c_int
     L.gc_status_string.argtypes = [ctypes.c_int]
     L.gc_status_string.restype = ctypes.c_char_p
-    for name in ("gc_create", "gc_destroy", "gc_compress", "gc_compress_multi", "gc_decompress_sum",
+    for name in ("gc_create", "gc_destroy", "gc_reserve", "gc_compress", "gc_compress_multi", "gc_decompress_sum",
                  "gc_decompress_sum_static",
                  "gc_decompress_sum_multi", "gc_decompress_sum_weighted", "gc_decompress_apply",
                  "gc_compress_rows", "gc_decompress_sum_rows", "gc_compress_dense", "gc_decompress_sum_dense", "gc_decompress_apply_dense",
@@ -147,6 +148,10 @@ class Context:
             self.destroy()
         except Exception:
             pass
+
+    def reserve(self, max_n: int, max_k: int, max_tensors: int = 1, max_W: int = 0) -> None:
+        """gc_reserve: size the workspace once; later calls within these bounds never allocate."""
+        _check(lib().gc_reserve(self.handle, int(max_n), int(max_k), int(max_tensors), int(max_W)), "gc_reserve")
 
     def set_option(self, name: str, value: int) -> None:
         _check(lib().gc_set_option(self.handle, name.encode(), int(value)), "gc_set_option")

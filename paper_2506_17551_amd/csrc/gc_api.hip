@@ -58,6 +58,7 @@ struct gc_ctx {
   uint32_t* host_flags = nullptr;  // pinned
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
   size_t host_ts_cap = 0;
+  Plan* single = nullptr;  // plan of the last single-tensor call: rebuilt per call on the host, never uploaded
   const Plan* last_plan = nullptr;
   int64_t last_dense_tensors = 0;  // tensors of the last compress call when it took the dense coder
   int64_t opt_main_lds_pad = 16384;  // dynamic LDS of the streaming pass: at most 8 workgroups per CU
@@ -236,6 +237,86 @@ bool same_plan(const Plan* P, const int64_t* offsets, const int64_t* k, int32_t 
          std::memcmp(P->k.data(), k, sizeof(int64_t) * T) == 0;
 }
 
+// What a compress call needs of the context's workspace, in entries of each array.
+struct Need {
+  size_t T = 0, ngroups = 0, slot_records = 0, cand = 0, max_chunks = 0, ktotal = 0, stotal = 0;
+  bool sampled = false;
+};
+
+Need need_of(const Plan* P) {
+  Need nd;
+  nd.T = P->td.size();
+  nd.ngroups = (size_t)P->ngroups;
+  nd.sampled = P->n_sampled > 0;
+  nd.slot_records = nd.sampled ? (size_t)P->ngroups * (size_t)P->slot_stride : 0;
+  nd.cand = nd.sampled ? (size_t)P->cand_total_cap : 0;
+  nd.max_chunks = (size_t)P->max_chunks;
+  nd.ktotal = (size_t)P->ktotal;
+  nd.stotal = (size_t)P->stotal;
+  return nd;
+}
+
+// Grows the workspace to what `nd` needs. Growing an array waits for the device, frees and allocates;
+// once the arrays are large enough (gc_reserve, or an earlier call of the same size) this does nothing.
+gc_status ensure_workspace(gc_ctx* ctx, const Need& nd) {
+  const size_t T = nd.T, ng = nd.ngroups, nent = nd.max_chunks * 4;
+  const size_t ngp = (ng + kScanBlock - 1) / kScanBlock, ncp = (nent + kScanBlock - 1) / kScanBlock;
+  gc_status st = ensure(ctx->ts, sizeof(TensorState) * T);
+  if (st == GC_OK) st = ensure(ctx->shist, sizeof(unsigned long long) * T * kSampleBins);
+  if (st == GC_OK) {  // the select histograms must start zeroed; every call leaves them zeroed again
+    const void* before = ctx->hist.p;
+    st = ensure(ctx->hist, sizeof(unsigned long long) * T * kSelBins);
+    if (st == GC_OK && ctx->hist.p != before && hipMemset(ctx->hist.p, 0, ctx->hist.bytes) != hipSuccess)
+      st = GC_ERR_DEVICE;
+  }
+  if (st == GC_OK) st = ensure(ctx->grp_cnt, sizeof(uint32_t) * ng);
+  if (st == GC_OK) st = ensure(ctx->grp_part, sizeof(unsigned long long) * ngp);
+  if (st == GC_OK) st = ensure(ctx->grp_off, sizeof(long long) * ng);
+  if (st == GC_OK) st = ensure(ctx->tg_base, sizeof(long long) * (T + 1));
+  if (nd.sampled) {
+    if (st == GC_OK) st = ensure(ctx->slots, sizeof(uint2) * nd.slot_records);
+    if (st == GC_OK) st = ensure(ctx->cand_val, sizeof(float) * nd.cand);
+    if (st == GC_OK) st = ensure(ctx->cand_idx, sizeof(long long) * nd.cand);
+  }
+  if (st == GC_OK) st = ensure(ctx->ch_gt, sizeof(uint32_t) * nent);
+  if (st == GC_OK) st = ensure(ctx->ch_eq, sizeof(uint32_t) * nent);
+  if (st == GC_OK) st = ensure(ctx->ch_part_gt, sizeof(unsigned long long) * ncp);
+  if (st == GC_OK) st = ensure(ctx->ch_part_eq, sizeof(unsigned long long) * ncp);
+  if (st == GC_OK) st = ensure(ctx->ch_goff, sizeof(long long) * nent);
+  if (st == GC_OK) st = ensure(ctx->ch_eoff, sizeof(long long) * nent);
+  if (st == GC_OK) st = ensure(ctx->tb_g, sizeof(long long) * T);
+  if (st == GC_OK) st = ensure(ctx->tb_e, sizeof(long long) * T);
+  if (st == GC_OK) st = ensure(ctx->totals, sizeof(long long) * 4);
+  if (st == GC_OK) st = ensure(ctx->kept_val, sizeof(float) * nd.ktotal);
+  if (st == GC_OK) st = ensure(ctx->blk_amax, sizeof(uint32_t) * nd.stotal);
+  if (st == GC_OK && ctx->host_ts_cap < T) {
+    if (ctx->host_ts) (void)hipHostFree(ctx->host_ts);
+    ctx->host_ts = nullptr;
+    ctx->host_ts_cap = 0;
+    if (hipHostMalloc((void**)&ctx->host_ts, sizeof(TensorState) * T, hipHostMallocDefault) != hipSuccess)
+      st = GC_ERR_WORKSPACE;
+    else
+      ctx->host_ts_cap = T;
+  }
+  return st;
+}
+
+// A single-tensor call needs no cache entry and no upload: its plan is a few numbers, rebuilt on
+// the host for every call and handed to the kernels by argument. A shape that changes from call to
+// call (the touched rows of an embedding gradient) therefore costs nothing extra.
+gc_status get_single_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_t block, int32_t codec,
+                          Plan** out) {
+  Plan* P = build_plan(offsets, k, 1, block, codec);
+  if (!P) return GC_ERR_WORKSPACE;
+  if (ctx->last_plan == ctx->single) ctx->last_plan = nullptr;
+  delete ctx->single;
+  ctx->single = P;
+  const gc_status st = ensure_workspace(ctx, need_of(P));
+  if (st != GC_OK) return st;
+  *out = P;
+  return GC_OK;
+}
+
 gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_t T, int32_t block,
                    int32_t codec, Plan** out) {
   for (size_t i = 0; i < ctx->plans.size(); ++i) {
@@ -261,45 +342,7 @@ gc_status get_plan(gc_ctx* ctx, const int64_t* offsets, const int64_t* k, int32_
       st = GC_ERR_DEVICE;
     std::vector<GroupRec>().swap(P->recs);
   }
-  const size_t ng = (size_t)P->ngroups, nent = (size_t)P->max_chunks * 4;
-  const size_t ngp = (ng + kScanBlock - 1) / kScanBlock, ncp = (nent + kScanBlock - 1) / kScanBlock;
-  if (st == GC_OK) st = ensure(ctx->ts, sizeof(TensorState) * T);
-  if (st == GC_OK) st = ensure(ctx->shist, sizeof(unsigned long long) * (size_t)T * kSampleBins);
-  if (st == GC_OK) {  // the select histograms must start zeroed; every call leaves them zeroed again
-    const void* before = ctx->hist.p;
-    st = ensure(ctx->hist, sizeof(unsigned long long) * (size_t)T * kSelBins);
-    if (st == GC_OK && ctx->hist.p != before && hipMemset(ctx->hist.p, 0, ctx->hist.bytes) != hipSuccess)
-      st = GC_ERR_DEVICE;
-  }
-  if (st == GC_OK) st = ensure(ctx->grp_cnt, sizeof(uint32_t) * ng);
-  if (st == GC_OK) st = ensure(ctx->grp_part, sizeof(unsigned long long) * ngp);
-  if (st == GC_OK) st = ensure(ctx->grp_off, sizeof(long long) * ng);
-  if (st == GC_OK) st = ensure(ctx->tg_base, sizeof(long long) * (T + 1));
-  if (P->n_sampled > 0) {
-    if (st == GC_OK) st = ensure(ctx->slots, sizeof(uint2) * ng * (size_t)P->slot_stride);
-    if (st == GC_OK) st = ensure(ctx->cand_val, sizeof(float) * (size_t)P->cand_total_cap);
-    if (st == GC_OK) st = ensure(ctx->cand_idx, sizeof(long long) * (size_t)P->cand_total_cap);
-  }
-  if (st == GC_OK) st = ensure(ctx->ch_gt, sizeof(uint32_t) * nent);
-  if (st == GC_OK) st = ensure(ctx->ch_eq, sizeof(uint32_t) * nent);
-  if (st == GC_OK) st = ensure(ctx->ch_part_gt, sizeof(unsigned long long) * ncp);
-  if (st == GC_OK) st = ensure(ctx->ch_part_eq, sizeof(unsigned long long) * ncp);
-  if (st == GC_OK) st = ensure(ctx->ch_goff, sizeof(long long) * nent);
-  if (st == GC_OK) st = ensure(ctx->ch_eoff, sizeof(long long) * nent);
-  if (st == GC_OK) st = ensure(ctx->tb_g, sizeof(long long) * T);
-  if (st == GC_OK) st = ensure(ctx->tb_e, sizeof(long long) * T);
-  if (st == GC_OK) st = ensure(ctx->totals, sizeof(long long) * 4);
-  if (st == GC_OK) st = ensure(ctx->kept_val, sizeof(float) * (size_t)P->ktotal);
-  if (st == GC_OK) st = ensure(ctx->blk_amax, sizeof(uint32_t) * (size_t)P->stotal);
-  if (st == GC_OK && ctx->host_ts_cap < (size_t)T) {
-    if (ctx->host_ts) (void)hipHostFree(ctx->host_ts);
-    ctx->host_ts = nullptr;
-    ctx->host_ts_cap = 0;
-    if (hipHostMalloc((void**)&ctx->host_ts, sizeof(TensorState) * T, hipHostMallocDefault) != hipSuccess)
-      st = GC_ERR_WORKSPACE;
-    else
-      ctx->host_ts_cap = T;
-  }
+  if (st == GC_OK) st = ensure_workspace(ctx, need_of(P));
   if (st != GC_OK) {
     release(P->td_dev);
     release(P->recs_dev);
@@ -392,13 +435,19 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   }
   ctx->last_dense_tensors = 0;
   Plan* P = nullptr;
-  gc_status st = get_plan(ctx, offsets, k, T, block, out->codec, &P);
+  gc_status st = T == 1 ? get_single_plan(ctx, offsets, k, block, out->codec, &P)
+                        : get_plan(ctx, offsets, k, T, block, out->codec, &P);
   if (st != GC_OK) return st;
   if (xcd_run_grid(P->ngroups) >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
 
   Workspace ws;
   std::memset(&ws, 0, sizeof(ws));
-  ws.td = (const TensorDesc*)P->td_dev.p;
+  if (T == 1) {
+    ws.td = nullptr;
+    ws.td1 = P->td[0];
+  } else {
+    ws.td = (const TensorDesc*)P->td_dev.p;
+  }
   ws.recs = (const GroupRec*)P->recs_dev.p;
   ws.n_single = offsets[T];
   ws.ts = (TensorState*)ctx->ts.p;
@@ -464,11 +513,17 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
 
 gc_status get_dec_plan(gc_ctx* ctx, const int64_t* k, int32_t T, int32_t block, int32_t codec,
                        DecPlan** out) {
-  for (DecPlan* D : ctx->dplans)
+  for (size_t i = 0; i < ctx->dplans.size(); ++i) {
+    DecPlan* D = ctx->dplans[i];
     if (D->block == block && D->codec == codec && (int32_t)D->k.size() == T && std::memcmp(D->k.data(), k, sizeof(int64_t) * T) == 0) {
+      if (i != 0) {  // keep the most recently used first: the last entry is the one evicted
+        ctx->dplans.erase(ctx->dplans.begin() + i);
+        ctx->dplans.insert(ctx->dplans.begin(), D);
+      }
       *out = D;
       return GC_OK;
     }
+  }
   DecPlan* D = new (std::nothrow) DecPlan();
   if (!D) return GC_ERR_WORKSPACE;
   D->k.assign(k, k + T);
@@ -689,11 +744,46 @@ gc_status gc_create(gc_ctx** out, int device) {
   return GC_OK;
 }
 
+gc_status gc_reserve(gc_ctx* ctx, int64_t max_n, int64_t max_k, int32_t max_tensors, int32_t max_W) {
+  if (!ctx || max_n < 1 || max_k < 1 || max_k > max_n || max_tensors < 1 || max_W < 0 || max_W > kMaxWorkers)
+    return GC_ERR_INVALID_ARG;
+  if (max_k >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
+  GC_HIP(hipSetDevice(ctx->device));
+  // Every array grows with n, k and the tensor count; the candidate slots also grow with the
+  // density k / n. The bound is the plan of one tensor of max_n elements keeping max_k (block 1:
+  // the most scales), widened by what max_tensors tensors add at their boundaries.
+  const int64_t offsets[2] = {0, max_n};
+  Plan* P = build_plan(offsets, &max_k, 1, 1, GC_CODEC_INT8);
+  if (!P) return GC_ERR_WORKSPACE;
+  Need nd = need_of(P);
+  const size_t T = (size_t)max_tensors;
+  const int32_t slot_stride = std::max(P->slot_stride, kSlotLine);
+  delete P;
+  nd.T = T;
+  nd.ngroups += 2 * T;
+  nd.max_chunks += 2 * T;
+  nd.sampled = true;
+  nd.slot_records = nd.ngroups * (size_t)slot_stride;
+  nd.cand = (size_t)std::min<int64_t>(max_n, 4 * max_k) + 4100 * T;
+  gc_status st = ensure_workspace(ctx, nd);
+  // the row-sparse step and the aggregates
+  if (st == GC_OK) st = ensure(ctx->rows_e, sizeof(float) * (size_t)max_n);
+  if (st == GC_OK) st = ensure(ctx->rows_idx, sizeof(uint32_t) * (size_t)max_k);
+  if (max_W > 0) {
+    const size_t pairs = (size_t)max_W * (size_t)max_k;
+    if (st == GC_OK) st = ensure(ctx->rows_cidx, sizeof(uint32_t) * pairs);
+    if (st == GC_OK) st = ensure(ctx->dec_rec, sizeof(uint2) * pairs);
+    if (st == GC_OK) st = ensure(ctx->dec_tile_start, sizeof(unsigned long long) * (size_t)((max_n >> kDecMinTileShift) + 2));
+  }
+  return st;
+}
+
 gc_status gc_destroy(gc_ctx* c) {
   if (!c) return GC_ERR_INVALID_ARG;
   (void)hipSetDevice(c->device);
   (void)hipDeviceSynchronize();
   for (Plan* P : c->plans) { release(P->td_dev); release(P->recs_dev); delete P; }
+  delete c->single;
   for (DecPlan* D : c->dplans) { release(D->kprefix); release(D->sprefix); release(D->qprefix); delete D; }
   DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
                    &c->slots, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void k_init(Workspace ws) {
   // sample histograms of the sampled tensors only; the select histograms are left zeroed by the
   // last digit's scan of the previous call (and are zero-filled when they are allocated)
   for (int64_t i = tid; i < ns; i += stride)
-    if (ws.td[i / kSampleBins].mode == kSampled) ws.shist[i] = 0ull;
+    if (ws.desc(i / kSampleBins).mode == kSampled) ws.shist[i] = 0ull;
   for (int64_t i = tid; i < ws.nblocks; i += stride) ws.blk_amax[i] = 0u;
   for (int64_t i = tid; i < ws.T; i += stride) {
     TensorState z;
@@ -112,8 +112,8 @@ __device__ __forceinline__ SampleItem<G> sample_fetch(const Workspace& ws, const
 #pragma unroll
   for (int c = 0; c < 4; ++c) it.gv[c] = it.ev[c] = 0.0f;
   if (s0 >= s_end) return it;
-  it.t = find_last_le(ws.T, s0, hint < 0 ? 0 : hint, [&](int i) { return (long long)ws.td[i].sgran_begin; });
-  const TensorDesc d = ws.td[it.t];
+  it.t = find_last_le(ws.T, s0, hint < 0 ? 0 : hint, [&](int i) { return (long long)ws.desc(i).sgran_begin; });
+  const TensorDesc d = ws.desc(it.t);
   const int64_t ls = s0 + wave - d.sgran_begin;  // sgran_begin is a multiple of 4 and nsgran padded
   if (ls >= d.nsgran) return it;
   it.active = true;
@@ -219,7 +219,7 @@ __device__ void find_from_top(const unsigned long long* __restrict__ h, unsigned
 
 __global__ __launch_bounds__(256) void k_sample_thresh(Workspace ws) {
   const int t = blockIdx.x;
-  const TensorDesc d = ws.td[t];
+  const TensorDesc d = ws.desc(t);
   if (d.mode != kSampled) return;
   uint32_t bin;
   unsigned long long above;
@@ -465,7 +465,7 @@ __global__ __launch_bounds__(256) void k_group_scan(Workspace ws) {
   scan_block(ws.grp_cnt, ws.ngroups, ws.grp_part, b, ws.grp_off, lds_out, sh);
   const int64_t lo = b * kScanBlock, hi = lo + kScanBlock;
   for (int t = threadIdx.x; t < ws.T; t += 256) {
-    const int64_t gb = ws.td[t].group_begin;
+    const int64_t gb = ws.desc(t).group_begin;
     if (gb >= lo && gb < hi) ws.tg_base[t] = lds_out[gb - lo];
   }
   if (threadIdx.x == 0 && hi >= ws.ngroups) ws.tg_base[ws.T] = lds_out[min((int64_t)kScanBlock, ws.ngroups - lo)];
@@ -485,7 +485,7 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
     long long nch = 0, vlen = 0, M = 0;
     uint32_t use = 0u;
     if (t < ws.T) {
-      const TensorDesc d = ws.td[t];
+      const TensorDesc d = ws.desc(t);
       vlen = d.n;
       if (d.mode == kSampled && any_sampled) {
         M = ws.tg_base[t + 1] - ws.tg_base[t];
@@ -534,9 +534,9 @@ __global__ __launch_bounds__(256) void k_gather(Workspace ws, const float* __res
   int glen = 0;
   uint32_t t_lo = 0u;
   if (grp < ws.ngroups) {
-    const int t = find_last_le(ws.T, grp, 0, [&](int i) { return (long long)ws.td[i].group_begin; });
+    const int t = find_last_le(ws.T, grp, 0, [&](int i) { return (long long)ws.desc(i).group_begin; });
     if (ws.ts[t].use_cand != 0u) {
-      const TensorDesc d = ws.td[t];
+      const TensorDesc d = ws.desc(t);
       const uint32_t cnt = ws.grp_cnt[grp];
       dst = d.cand_begin + (ws.grp_off[grp] - ws.tg_base[t]);
       const long long lg = grp - d.group_begin;
@@ -651,7 +651,7 @@ __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const flo
       }
       cur = t;
     }
-    const TensorDesc d = ws.td[t];
+    const TensorDesc d = ws.desc(t);
     const TensorState st = ws.ts[t];
     const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
     const uint32_t want = (level == 0) ? 0u : (st.prefix >> pshift);
@@ -683,7 +683,7 @@ __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const flo
 // ---------------------------------------------------------------- k_select_scan
 __global__ __launch_bounds__(256) void k_select_scan(Workspace ws, int level) {
   const int t = blockIdx.x;
-  const TensorDesc d = ws.td[t];
+  const TensorDesc d = ws.desc(t);
   unsigned long long* h = ws.hist + (int64_t)t * kSelBins;
   const unsigned long long k_rem = (level == 0) ? (unsigned long long)d.k : ws.ts[t].k_rem;
   uint32_t bin;
@@ -705,7 +705,7 @@ __global__ __launch_bounds__(256) void k_count(Workspace ws, const float* __rest
   for (long long a = blockIdx.x; a < A; a += gridDim.x) {
     const int t = find_last_le(ws.T, a, cur, [&](int i) { return ws.ts[i].achunk_begin; });
     cur = t;
-    const TensorDesc d = ws.td[t];
+    const TensorDesc d = ws.desc(t);
     const TensorState st = ws.ts[t];
     const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
     const uint32_t thr = st.prefix;
@@ -789,7 +789,7 @@ __global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restr
   for (long long a = blockIdx.x; a < A; a += gridDim.x) {
     const int t = find_last_le(ws.T, a, cur, [&](int i) { return ws.ts[i].achunk_begin; });
     cur = t;
-    const TensorDesc d = ws.td[t];
+    const TensorDesc d = ws.desc(t);
     const TensorState st = ws.ts[t];
     const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
     if (s.len == 0) continue;
@@ -882,10 +882,10 @@ __global__ __launch_bounds__(256) void k_quant(Workspace ws, float* __restrict__
                                                float* __restrict__ scales, int32_t block, long long ktotal) {
   const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
   if (j >= ktotal) return;
-  const int t = find_last_le(ws.T, j, 0, [&](int i) { return (long long)ws.td[i].kprefix; });
-  const uint32_t rel = (uint32_t)(j - ws.td[t].kprefix);  // < k < 2^32: 32-bit division
+  const int t = find_last_le(ws.T, j, 0, [&](int i) { return (long long)ws.desc(i).kprefix; });
+  const uint32_t rel = (uint32_t)(j - ws.desc(t).kprefix);  // < k < 2^32: 32-bit division
   const uint32_t rblk = rel / (uint32_t)block;
-  const long long blk = ws.td[t].sprefix + rblk;
+  const long long blk = ws.desc(t).sprefix + rblk;
   const uint32_t akey = ws.blk_amax[blk];
   const bool finite = akey < 0x7F800000u;
   float s = __fdiv_rn(__uint_as_float(akey), 127.0f);
@@ -918,8 +918,8 @@ __global__ __launch_bounds__(256) void k_quant_sign(Workspace ws, float* __restr
                                                     float* __restrict__ scales, int32_t block) {
   __shared__ double sh[256];
   const int64_t gb = blockIdx.x;
-  const int t = find_last_le(ws.T, gb, 0, [&](int i) { return (long long)ws.td[i].sprefix; });
-  const TensorDesc d = ws.td[t];
+  const int t = find_last_le(ws.T, gb, 0, [&](int i) { return (long long)ws.desc(i).sprefix; });
+  const TensorDesc d = ws.desc(t);
   const int64_t lb = gb - d.sprefix;
   const int64_t j0 = d.kprefix + lb * block;
   const int len = (int)min((int64_t)block, d.k - lb * block);

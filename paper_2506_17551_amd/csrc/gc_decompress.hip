@@ -231,7 +231,7 @@ __global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int
 // vectors at low density (7B at 0.1 %, 16 workers: 66 records per 4096 floats) spend less per tile
 // on everything but the write (5.35 against 5.8 ms), while crowded tiles (1.3B at 0.5 %: 330
 // records) do better small (1.2 against 2.0 ms). One persistent workgroup per compute unit.
-constexpr int kDecTileShiftSmall = 12, kDecWavesSmall = 8;
+constexpr int kDecTileShiftSmall = kDecMinTileShift, kDecWavesSmall = 8;
 constexpr int kDecTileShiftLarge = 14, kDecWavesLarge = 2;
 constexpr int kDecGrid = 256;
 static_assert(kDecTileShiftLarge <= 16, "a record keeps the position in 16 bits");

@@ -87,7 +87,9 @@ struct GroupRec {
 };
 
 struct Workspace {  // device pointers into the context's scratch
-  const TensorDesc* td;
+  const TensorDesc* td;             // null for a single-tensor call: its plan travels in td1
+  TensorDesc td1;                   // the only tensor's plan, by kernel argument (no upload, no plan cache)
+  __host__ __device__ const TensorDesc& desc(int t) const { return td ? td[t] : td1; }
   const GroupRec* recs;       // null when the call has a single tensor
   TensorState* ts;
   unsigned long long* shist;  // [T][kSampleBins]
@@ -228,6 +230,7 @@ struct DecArgs {
   uint32_t k[kMaxWorkers];
   float denom[kMaxWorkers];  // 1 + staleness of the worker (weighted aggregate)
 };
+constexpr int kDecMinTileShift = 12;  // the smallest output tile of the aggregate: 4096 floats
 // log2 of the output tile (floats) for a call, and tiles per range of the packing pass.
 int dec_tile_shift(int64_t nrec, int64_t n);
 int dec_tile_shift_of(bool large);

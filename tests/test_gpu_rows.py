@@ -256,3 +256,68 @@ def test_rows_size_products_are_checked_without_overflow(gc, ctx):
         st = L.gc_decompress_sum_rows(ctx.handle, arr, 1, rows.data_ptr(), Ru, D, None, vals.data_ptr(), None)
         assert st == binding.GC_ERR_UNSUPPORTED, (Ru, D, st)
     assert gc.sync_status(ctx, raise_on_error=False) == binding.GC_OK
+
+
+def test_rows_steps_with_changing_row_counts_inside_one_capture(gc, oracle):
+    """After gc_reserve a call only queues kernels, whatever its shape: 50 gc_compress_rows calls whose
+    touched-row count differs every time (as an embedding gradient's does), each followed by
+    gc_decompress_sum_rows, are recorded in ONE stream capture - a host wait, a copy from pageable
+    memory or an allocation inside it would fail the capture. The replayed results equal the eager
+    ones, which are checked against the oracle."""
+    R, D, block, steps = 60_000, 64, 64, 50
+    rng = np.random.default_rng(5)
+    us = [int(u) for u in rng.integers(40, 3000, size=steps)]
+    assert len(set(us)) > 40
+    rows = [np.sort(rng.choice(R, size=u, replace=False)).astype(np.int64) for u in us]
+    rows_d = [torch.from_numpy(r).to(DEV) for r in rows]
+    vals = [inputs.normal(u * D, 0.01, inputs.seed_for(3, 0, s, 5)).to(DEV) for s, u in enumerate(us)]
+    ks = [gc.k_from_density(u * D, 0.01) for u in us]
+    table0 = inputs.normal(R * D, 0.002, 99).reshape(R, D)
+
+    def fresh_bufs():
+        return [gc.CompressedBuf.allocate(R * D, k, gc.num_scales(k, block), block, 32, DEV) for k in ks]
+
+    def run_all(ctx, table, bufs, outs):
+        for s in range(steps):
+            gc.compress_rows(ctx, vals[s], table, rows_d[s], ks[s], block, out=bufs[s])
+            gc.decompress_sum_rows(ctx, [bufs[s]], rows_d[s], D, out=outs[s])
+
+    # eager, on a context that grows as it goes; the oracle follows step by step
+    ctx_a = gc.Context(0)
+    table_a = table0.to(DEV).clone()
+    bufs_a, outs_a = fresh_bufs(), [torch.empty(u, D, device=DEV) for u in us]
+    run_all(ctx_a, table_a, bufs_a, outs_a)
+    gc.sync_status(ctx_a)
+    table_ref = table0.numpy().copy()
+    for s in range(steps):
+        rc, idx, q, sc = oracle.compress_rows(vals[s].cpu().numpy(), table_ref, rows[s], ks[s], block, index_bits=32)
+        assert rc == 0
+        assert np.array_equal(bufs_a[s].indices_numpy(), idx) and np.array_equal(bufs_a[s].q.cpu().numpy(), q), s
+        assert np.array_equal(bits(bufs_a[s].scales.cpu().numpy()), bits(sc)), s
+        rc, want = oracle.decompress_sum_rows([(idx, q, sc)], rows[s], D, block)
+        assert rc == 0 and np.array_equal(bits(outs_a[s].cpu().numpy()), bits(want)), s
+    assert np.array_equal(bits(table_a.cpu().numpy()), bits(table_ref))
+    ctx_a.destroy()
+
+    # captured, on a fresh context that has only been told the bounds
+    ctx_b = gc.Context(0)
+    ctx_b.reserve(3000 * D, max(ks), 1, 1)
+    table_b = table0.to(DEV).clone()
+    bufs_b, outs_b = fresh_bufs(), [torch.full((u, D), float("nan"), device=DEV) for u in us]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run_all(ctx_b, table_b, bufs_b, outs_b)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert gc.sync_status(ctx_b, raise_on_error=False) == 0
+    for s in range(steps):
+        assert torch.equal(bufs_b[s].indices, bufs_a[s].indices) and torch.equal(bufs_b[s].q, bufs_a[s].q), s
+        assert torch.equal(bufs_b[s].scales.view(torch.int32), bufs_a[s].scales.view(torch.int32)), s
+        assert torch.equal(outs_b[s].view(torch.int32), outs_a[s].view(torch.int32)), s
+    assert torch.equal(table_b.view(torch.int32), table_a.view(torch.int32))
+    ctx_b.destroy()
