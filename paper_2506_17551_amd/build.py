@@ -33,8 +33,29 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
     return LIB_PATH
 
 
+def stale_sources():
+    """HIP sources and headers that are newer than the built library (empty if it is up to date)."""
+    if not os.path.exists(LIB_PATH):
+        return list(SOURCES)
+    built = os.path.getmtime(LIB_PATH)
+    deps = [os.path.join(_CSRC, f) for f in os.listdir(_CSRC)] + [os.path.join(os.path.dirname(_PKG), "include", "gradcomp.h")]
+    return [os.path.basename(d) for d in deps if os.path.exists(d) and os.path.getmtime(d) > built]
+
+
 def ensure_library() -> str:
-    """Path of the built library; builds it only if it is missing."""
+    """Path of the built library. Builds it only if it is missing (a GPU run loads what was built
+    beforehand); if a source is newer than the library it says so, loudly, instead of silently
+    testing a stale binary: run `python -m paper_2506_17551_amd.build` after editing csrc/."""
     if not os.path.exists(LIB_PATH):
         build_library()
+    else:
+        newer = stale_sources()
+        if newer:
+            import sys
+            print(f"paper_2506_17551_amd: WARNING: {os.path.basename(LIB_PATH)} is older than {', '.join(sorted(newer))}; "
+                  "rebuild with `python -m paper_2506_17551_amd.build`", file=sys.stderr, flush=True)
     return LIB_PATH
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))

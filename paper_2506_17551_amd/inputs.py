@@ -115,12 +115,24 @@ def offsets_of(sizes) -> np.ndarray:
     return off
 
 
+_ZIPF_CDF = {}
+
+
+def _zipf_cdf(num_rows: int, s: float) -> np.ndarray:
+    key = (int(num_rows), float(s))
+    if key not in _ZIPF_CDF:
+        w = np.arange(1, num_rows + 1, dtype=np.float64) ** (-s)
+        cdf = np.cumsum(w)
+        cdf /= cdf[-1]
+        _ZIPF_CDF.clear()          # one table at a time (80 MB at 10M rows)
+        _ZIPF_CDF[key] = cdf
+    return _ZIPF_CDF[key]
+
+
 def zipf_unique_rows(num_lookups: int, num_rows: int, s: float, seed: int) -> np.ndarray:
     """Sorted unique row ids hit by `num_lookups` draws from Zipf(s) over 1..num_rows
     (inverse CDF in double precision on the host)."""
-    w = np.arange(1, num_rows + 1, dtype=np.float64) ** (-s)
-    cdf = np.cumsum(w)
-    cdf /= cdf[-1]
+    cdf = _zipf_cdf(num_rows, s)
     rng = np.random.Generator(np.random.Philox(key=int(seed) % (1 << 64)))
     u = rng.random(num_lookups)
     ids = np.searchsorted(cdf, u, side="left")
@@ -194,9 +206,10 @@ def workload(config: int, scale: float = 1.0) -> Workload:
     raise ValueError(config)
 
 
-def embedding_rows_workload(worker: int, device="cpu"):
+def embedding_rows_workload(worker: int, device="cpu", step: int = 0):
     """Config 3's row-sparse embedding gradient: sorted unique rows hit by 65,536 Zipf(1.1)
-    lookups over a 10M-row table, and an (U x 128) fp32 value block ~ N(0, 0.01)."""
-    rows = zipf_unique_rows(65536, 10_000_000, 1.1, seed_for(3, worker, 0, 1))
-    vals = normal(rows.shape[0] * 128, 0.01, seed_for(3, worker, 0, 2), device)
+    lookups over a 10M-row table, and an (U x 128) fp32 value block ~ N(0, 0.01). Every
+    (worker, step) draws its own batch, so the number of touched rows changes from step to step."""
+    rows = zipf_unique_rows(65536, 10_000_000, 1.1, seed_for(3, worker, step, 1))
+    vals = normal(rows.shape[0] * 128, 0.01, seed_for(3, worker, step, 2), device)
     return rows, vals
