@@ -189,7 +189,7 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
       const double target = std::ceil(ks + 6.0 * std::sqrt(ks) + 8.0);
       d.sample_target = (uint32_t)std::min<double>(target, 4.0e9);
       max_lambda = std::max(max_lambda, target / m * (double)kGroup);  // candidates expected per group
-      d.cand_cap = std::min<int64_t>(d.n, 4 * d.k + 4096);
+      d.cand_cap = std::min<int64_t>(d.n, 8 * d.k + 4096);  // room for ties around the threshold before the dense route
       cb += round_up(d.cand_cap, 4);  // every region starts 16-byte aligned (128-bit loads)
       est += (std::min<int64_t>(d.cand_cap, 2 * d.k) + kChunkElems - 1) / kChunkElems + 1;
       P->n_sampled++;
@@ -480,7 +480,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   ws.ngroups = P->ngroups;
   ws.nsgran = P->nsgran;
   ws.max_chunks = P->max_chunks;
-  ws.est_chunk_wgs = (int32_t)std::min<int64_t>(P->est_chunks, 1 << 20);
+  ws.max_chunk_wgs = (int32_t)std::min<int64_t>(P->max_chunks, 1 << 20);
   ws.main_lds_pad = (int32_t)ctx->opt_main_lds_pad;
   OutBuf ob{out->indices, out->q, out->scales, out->index_bits, block, out->codec};
   hipStream_t s = (hipStream_t)hip_stream;
@@ -764,7 +764,7 @@ gc_status gc_reserve(gc_ctx* ctx, int64_t max_n, int64_t max_k, int32_t max_tens
   nd.max_chunks += 2 * T;
   nd.sampled = true;
   nd.slot_records = nd.ngroups * (size_t)slot_stride;
-  nd.cand = (size_t)std::min<int64_t>(max_n, 4 * max_k) + 4100 * T;
+  nd.cand = (size_t)std::min<int64_t>(max_n, 8 * max_k) + 4100 * T;
   gc_status st = ensure_workspace(ctx, nd);
   // the row-sparse step and the aggregates
   if (st == GC_OK) st = ensure(ctx->rows_e, sizeof(float) * (size_t)max_n);

@@ -88,6 +88,21 @@ __device__ __forceinline__ void flush_lds_hist(uint32_t* lh, unsigned long long*
   }
 }
 
+// One count per lane into an LDS histogram. When every participating lane of the wavefront hits the
+// same bin (long runs of equal keys: ties, exact zeros) a single lane adds the whole count: 64
+// atomics on one LDS address would be executed one after the other.
+__device__ __forceinline__ void hist_add(uint32_t* lh, bool on, uint32_t bin) {
+  const uint64_t act = __ballot(on);
+  if (act == 0ull) return;
+  const int first = __ffsll((unsigned long long)act) - 1;
+  const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, first);
+  if (__ballot(on && bin != b0) == 0ull) {
+    if ((int)(threadIdx.x & 63) == first) atomicAdd(&lh[b0], (uint32_t)__popcll(act));
+  } else if (on) {
+    atomicAdd(&lh[bin], 1u);
+  }
+}
+
 // ---------------------------------------------------------------- k_sample
 __device__ __forceinline__ uint32_t mix_hash(uint64_t x) {
   x *= 0x9E3779B97F4A7C15ull;
@@ -631,15 +646,16 @@ __device__ __forceinline__ SubSrc sub_source(const Workspace& ws, const TensorDe
 // ---------------------------------------------------------------- k_hist
 __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const float* __restrict__ e) {
   __shared__ uint32_t lh[kSelBins];
+  const long long A = ws.totals[0];
+  const long long per = (A + gridDim.x - 1) / gridDim.x;  // one contiguous run of chunks per workgroup
+  const long long a_end = min(A, ((long long)blockIdx.x + 1) * per);
+  if ((long long)blockIdx.x * per >= a_end) return;  // the grid is sized for the worst case (the dense route)
   for (int b = threadIdx.x; b < kSelBins; b += 256) lh[b] = 0u;
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int shift = sel_shift(level);
   const uint32_t mask = (1u << sel_bits(level)) - 1u;
   const int pshift = shift + sel_bits(level);  // bits above this digit must match the prefix
-  const long long A = ws.totals[0];
-  const long long per = (A + gridDim.x - 1) / gridDim.x;  // one contiguous run of chunks per workgroup
-  const long long a_end = min(A, ((long long)blockIdx.x + 1) * per);
   int cur = -1;
   for (long long a = (long long)blockIdx.x * per; a < a_end; ++a) {
     const int t = find_last_le(ws.T, a, cur < 0 ? 0 : cur, [&](int i) { return ws.ts[i].achunk_begin; });
@@ -665,12 +681,13 @@ __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const flo
         const uint32_t key[4] = {key_of(x[u].x), key_of(x[u].y), key_of(x[u].z), key_of(x[u].w)};
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-          if (level == 0 || (key[c] >> pshift) == want) atomicAdd(&lh[(key[c] >> shift) & mask], 1u);
+          hist_add(lh, level == 0 || (key[c] >> pshift) == want, (key[c] >> shift) & mask);
       }
     } else {
-      for (int j = lane; j < s.len; j += 64) {
-        const uint32_t key = key_of(s.val[j]);
-        if (level == 0 || (key >> pshift) == want) atomicAdd(&lh[(key >> shift) & mask], 1u);
+      for (int j0 = 0; j0 < s.len; j0 += 64) {  // uniform trip count: hist_add is a wavefront-wide call
+        const int j = j0 + lane;
+        const uint32_t key = j < s.len ? key_of(s.val[j]) : 0u;
+        hist_add(lh, j < s.len && (level == 0 || (key >> pshift) == want), (key >> shift) & mask);
       }
     }
   }
@@ -797,6 +814,9 @@ __global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restr
     const long long quota = (long long)st.k_rem;
     const long long ent = a * 4 + wave;
     long long G = ws.ch_goff[ent] - ws.tb_g[t], E = ws.ch_eoff[ent] - ws.tb_e[t];
+    // nothing to emit here: no entry above the threshold, and the tie quota is used up (or there is
+    // no tie). On the dense route this skips nearly everything: at most k entries are kept.
+    if (ws.ch_gt[ent] == 0u && (ws.ch_eq[ent] == 0u || E >= quota)) continue;
     uint32_t run_blk = 0u, run_max = 0u;  // block whose maximum is being carried (0: none), wave-uniform
     // the whole sub-chunk is requested before the first entry is used
     constexpr int kIter = kChunk / 64;
@@ -1008,7 +1028,7 @@ void launch_group_sums(const Workspace& ws, hipStream_t s) {
 }
 
 void launch_chunk_sums(const Workspace& ws, hipStream_t s) {
-  const int64_t blocks = ((int64_t)ws.est_chunk_wgs * 4 + kScanBlock - 1) / kScanBlock;
+  const int64_t blocks = ((int64_t)ws.max_chunk_wgs * 4 + kScanBlock - 1) / kScanBlock;
   hipLaunchKernelGGL(k_chunk_sums, dim3(clamp_grid(blocks, 512)), dim3(256), 0, s, ws);
 }
 
@@ -1028,7 +1048,7 @@ void launch_gather(const Workspace& ws, const float* e, hipStream_t s) {
 }
 
 void launch_hist(const Workspace& ws, int level, const float* e, hipStream_t s) {
-  hipLaunchKernelGGL(k_hist, dim3(clamp_grid((ws.est_chunk_wgs + 1) / 2, 1024)), dim3(256), 0, s, ws, level, e);
+  hipLaunchKernelGGL(k_hist, dim3(clamp_grid((ws.max_chunk_wgs + 1) / 2, 1024)), dim3(256), 0, s, ws, level, e);
 }
 
 void launch_select_scan(const Workspace& ws, int level, hipStream_t s) {
@@ -1036,16 +1056,16 @@ void launch_select_scan(const Workspace& ws, int level, hipStream_t s) {
 }
 
 void launch_count(const Workspace& ws, const float* e, hipStream_t s) {
-  hipLaunchKernelGGL(k_count, dim3(clamp_grid(ws.est_chunk_wgs, 2048)), dim3(256), 0, s, ws, e);
+  hipLaunchKernelGGL(k_count, dim3(clamp_grid(ws.max_chunk_wgs, 2048)), dim3(256), 0, s, ws, e);
 }
 
 void launch_chunk_scan(const Workspace& ws, hipStream_t s) {
-  const int64_t blocks = ((int64_t)ws.est_chunk_wgs * 4 + kScanBlock - 1) / kScanBlock;
+  const int64_t blocks = ((int64_t)ws.max_chunk_wgs * 4 + kScanBlock - 1) / kScanBlock;
   hipLaunchKernelGGL(k_chunk_scan, dim3(clamp_grid(blocks, 512)), dim3(256), 0, s, ws);
 }
 
 void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStream_t s) {
-  const dim3 grid(clamp_grid(ws.est_chunk_wgs, 2048));
+  const dim3 grid(clamp_grid(ws.max_chunk_wgs, 2048));
   if (out.index_bits == 32)
     hipLaunchKernelGGL(k_emit<uint32_t>, grid, dim3(256), 0, s, ws, e, (uint32_t*)out.indices, out.block);
   else

@@ -126,7 +126,8 @@ struct Workspace {  // device pointers into the context's scratch
   int64_t max_chunks;               // capacity of the per-chunk arrays
   int64_t n_single;                 // elements of the only tensor (single-tensor calls)
   int64_t nblocks;                  // quantization blocks over all tensors
-  int32_t est_chunk_wgs;            // grid of the chunk kernels (host estimate; kernels grid-stride)
+  int32_t max_chunk_wgs;            // chunks of the call on the dense route: the grid of the chunk kernels is
+                                    // sized for it (they grid-stride; workgroups without a chunk leave at once)
   int32_t main_lds_pad;             // dynamic LDS bytes of the streaming pass (occupancy control)
 };
 

@@ -125,6 +125,23 @@ def test_massive_ties_force_the_dense_route(gc, ctx, oracle):
     assert np.array_equal(buf.indices_numpy(), np.arange(k, dtype=np.uint32))
 
 
+def test_tie_heavy_inputs_on_the_dense_route(gc, ctx, oracle):
+    """Inputs whose threshold sits inside a huge run of equal keys - fewer non-zeros than k, values on a
+    coarse grid - overflow the candidate list and are re-selected from the residual itself; the
+    emit pass skips every stretch that keeps nothing. Same bits as the oracle, several quantization
+    blocks, a ragged tail."""
+    n, k = 3_000_017, 3001
+    g = inputs.normal(n, 1e-3, 51)
+    g[torch.rand(n, generator=torch.Generator().manual_seed(3)) < 0.9995] = 0.0   # ~1500 non-zeros < k: T = 0
+    check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 256, tag="fewer non-zeros than k", expect_fallback=True)
+    g = (inputs.normal(n, 1e-3, 52) * 1e3).round() * 1e-3                           # values on a grid of 1e-3
+    check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 256, tag="coarse grid", expect_fallback=True)
+    g = torch.full((n,), -0.0)
+    g[::3] = 0.0
+    g[1_500_000] = 1e-30
+    check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 1000, tag="signed zeros and one value", expect_fallback=True)
+
+
 def test_clustered_winners(gc, ctx, oracle):
     # all winners sit in one short stretch (more candidates per group than slots): the gather
     # re-reads those groups from the residual; whatever route is taken, the result is the oracle's
