@@ -28,6 +28,8 @@ struct Plan {  // everything that depends only on (offsets, k, block)
   int32_t gather_team = 1;    // lanes that copy one group's candidates
   int64_t ngroups = 0, nsgran = 0, cand_total_cap = 0, ktotal = 0, stotal = 0, max_chunks = 0;
   int64_t n_sampled = 0, est_chunks = 0;
+  int64_t n_small = 0;      // tensors finished by one workgroup (k_finish)
+  int64_t n_general = 0;    // tensors that take the chain of grid-wide kernels
   std::vector<GroupRec> recs;  // one per group, only when there are several tensors
   DevBuf td_dev, recs_dev;
 };
@@ -170,11 +172,17 @@ Plan* build_plan(const int64_t* offsets, const int64_t* k, int32_t T, int32_t bl
     d.cand_begin = cb;
     const bool sampled = d.n >= kMinSampledN && d.k >= kMinSampledK && d.k * kMaxDensityInv <= d.n;
     d.mode = sampled ? kSampled : kDense;
+    d.small = (sampled ? (d.n <= kSmallMaxN && d.k <= kSmallMaxK) : d.n <= kSmallMaxDenseN) ? 1 : 0;
+    if (d.small) P->n_small++; else P->n_general++;
     if (sampled) {
       // sample about 32 expected winners, between 1/256 and 1/4 of the data: a thin sample only
       // makes the candidate list a little longer, and candidates are cheap (and a sample that
       // undershoots only sends the tensor down the dense route, never changes the result)
       double f = 32.0 / (double)d.k;
+      // where the tensor is small in absolute terms a denser sample (up to 65536 elements, about
+      // 1024 expected winners) costs nothing and halves the candidate list, which the one
+      // workgroup that finishes a small tensor then holds in LDS
+      f = std::max(f, std::min(1024.0 / (double)d.k, 65536.0 / (double)d.n));
       f = std::min(0.25, std::max(1.0 / 256.0, f));
       int64_t stride = std::max<int64_t>(4, std::min<int64_t>(256, (int64_t)std::floor(1.0 / f)));
       // a very large k leaves thousands of winners in a thinner sample still (at least 4096 expected)
@@ -262,7 +270,12 @@ gc_status ensure_workspace(gc_ctx* ctx, const Need& nd) {
   const size_t T = nd.T, ng = nd.ngroups, nent = nd.max_chunks * 4;
   const size_t ngp = (ng + kScanBlock - 1) / kScanBlock, ncp = (nent + kScanBlock - 1) / kScanBlock;
   gc_status st = ensure(ctx->ts, sizeof(TensorState) * T);
-  if (st == GC_OK) st = ensure(ctx->shist, sizeof(unsigned long long) * T * kSampleBins);
+  if (st == GC_OK) {  // the sample histograms start zeroed too, and the threshold kernel leaves them so
+    const void* before = ctx->shist.p;
+    st = ensure(ctx->shist, sizeof(unsigned long long) * T * kSampleBins);
+    if (st == GC_OK && ctx->shist.p != before && hipMemset(ctx->shist.p, 0, ctx->shist.bytes) != hipSuccess)
+      st = GC_ERR_DEVICE;
+  }
   if (st == GC_OK) {  // the select histograms must start zeroed; every call leaves them zeroed again
     const void* before = ctx->hist.p;
     st = ensure(ctx->hist, sizeof(unsigned long long) * T * kSelBins);
@@ -475,6 +488,7 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   ws.nblocks = P->stotal;
   ws.flags = (uint32_t*)ctx->flags.p;
   ws.T = T;
+  ws.block = block;
   ws.cap = P->cap;
   ws.gather_team = P->gather_team;
   ws.ngroups = P->ngroups;
@@ -486,27 +500,32 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   hipStream_t s = (hipStream_t)hip_stream;
   const bool any_sampled = P->n_sampled > 0;
 
-  { Scope sc(ctx, kKInit, s); launch_init(ws, s); }
+  const bool any_general = P->n_general > 0;
   if (any_sampled) {
     { Scope sc(ctx, kKSample, s); launch_sample(ws, grad, (int)dtype, residual, s); }
     { Scope sc(ctx, kKSampleThresh, s); launch_sample_thresh(ws, s); }
   }
   { Scope sc(ctx, kKMain, s); launch_main(ws, grad, (int)dtype, residual, s); }
-  if (any_sampled) {
-    { Scope sc(ctx, kKGroupSums, s); launch_group_sums(ws, s); }
-    { Scope sc(ctx, kKGroupScan, s); launch_group_scan(ws, s); }
+  // small tensors: one workgroup each does everything that is left, in one launch
+  if (P->n_small > 0) { Scope sc(ctx, kKFinish, s); launch_finish(ws, residual, ob, s); }
+  if (any_general) {
+    if (any_sampled) {
+      { Scope sc(ctx, kKGroupSums, s); launch_group_sums(ws, s); }
+      { Scope sc(ctx, kKGroupScan, s); launch_group_scan(ws, s); }
+    }
+    { Scope sc(ctx, kKRoute, s); launch_route(ws, s); }
+    if (any_sampled) { Scope sc(ctx, kKGather, s); launch_gather(ws, residual, s); }
+    for (int level = 0; level < kSelLevels; ++level) {
+      { Scope sc(ctx, kKHist, s); launch_hist(ws, level, residual, s); }
+      { Scope sc(ctx, kKSelectScan, s); launch_select_scan(ws, level, s); }
+    }
+    { Scope sc(ctx, kKCount, s); launch_count(ws, residual, s); }
+    { Scope sc(ctx, kKChunkSums, s); launch_chunk_sums(ws, s); }
+    { Scope sc(ctx, kKChunkScan, s); launch_chunk_scan(ws, s); }
+    { Scope sc(ctx, kKEmit, s); launch_emit(ws, residual, ob, s); }
   }
-  { Scope sc(ctx, kKRoute, s); launch_route(ws, s); }
-  if (any_sampled) { Scope sc(ctx, kKGather, s); launch_gather(ws, residual, s); }
-  for (int level = 0; level < kSelLevels; ++level) {
-    { Scope sc(ctx, kKHist, s); launch_hist(ws, level, residual, s); }
-    { Scope sc(ctx, kKSelectScan, s); launch_select_scan(ws, level, s); }
-  }
-  { Scope sc(ctx, kKCount, s); launch_count(ws, residual, s); }
-  { Scope sc(ctx, kKChunkSums, s); launch_chunk_sums(ws, s); }
-  { Scope sc(ctx, kKChunkScan, s); launch_chunk_scan(ws, s); }
-  { Scope sc(ctx, kKEmit, s); launch_emit(ws, residual, ob, s); }
-  { Scope sc(ctx, kKQuant, s); launch_quant(ws, residual, ob, P->ktotal, s); }
+  // the grid-wide coder: every block of the sign code, and the int8 code of the general tensors
+  if (any_general || out->codec == GC_CODEC_SIGN1) { Scope sc(ctx, kKQuant, s); launch_quant(ws, residual, ob, P->ktotal, s); }
   ctx->last_plan = P;
   return launch_status();
 }
@@ -696,9 +715,9 @@ gc_status dense_sum_impl(gc_ctx* ctx, const void* const* q, const float* const* 
   return launch_status();
 }
 
-const char* const kKernelNames[kKNum] = {"k_init", "k_sample", "k_sample_thresh", "k_main", "k_group_sums", "k_group_scan",
+const char* const kKernelNames[kKNum] = {"k_sample", "k_sample_thresh", "k_main", "k_group_sums", "k_group_scan",
                                          "k_route", "k_gather", "k_hist", "k_select_scan", "k_count",
-                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_dec_pack", "k_dec_tiles",
+                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_finish", "k_dec_pack", "k_dec_tiles",
                                          "k_dense", "k_dense_sum", "k_rows_gather", "k_rows_finish", "k_rows_remap"};
 
 }  // namespace

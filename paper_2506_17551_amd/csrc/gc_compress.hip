@@ -57,25 +57,6 @@ __device__ __forceinline__ unsigned long long block_sum(unsigned long long v, un
   return t;
 }
 
-// ---------------------------------------------------------------- k_init
-__global__ __launch_bounds__(256) void k_init(Workspace ws) {
-  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  const int64_t ns = ws.nsgran > 0 ? (int64_t)ws.T * kSampleBins : 0;
-  // sample histograms of the sampled tensors only; the select histograms are left zeroed by the
-  // last digit's scan of the previous call (and are zero-filled when they are allocated)
-  for (int64_t i = tid; i < ns; i += stride)
-    if (ws.desc(i / kSampleBins).mode == kSampled) ws.shist[i] = 0ull;
-  for (int64_t i = tid; i < ws.nblocks; i += stride) ws.blk_amax[i] = 0u;
-  for (int64_t i = tid; i < ws.T; i += stride) {
-    TensorState z;
-    z.k_rem = 0ull; z.vlen = 0; z.achunk_begin = 0; z.cand_total = 0;
-    z.t_lo = 0u; z.spare_ = 0u; z.prefix = 0u; z.use_cand = 0u;
-    ws.ts[i] = z;
-  }
-  if (tid == 0) ws.totals[0] = 0;
-}
-
 // ---------------------------------------------------------------- LDS histogram flush
 template <int NB>
 __device__ __forceinline__ void flush_lds_hist(uint32_t* lh, unsigned long long* gh) {
@@ -198,30 +179,48 @@ __global__ __launch_bounds__(256) void k_sample(Workspace ws, const G* __restric
 
 // ---------------------------------------------------------------- crossing search
 // Largest bin b with sum_{j >= b} h[j] >= target; `above` = sum_{j > b} h[j].
-// If the total is below target: b = 0. All 256 threads of the block call it;
-// the result is valid in every thread.
-template <int NB>
-__device__ void find_from_top(const unsigned long long* __restrict__ h, unsigned long long target,
-                              uint32_t& bin, unsigned long long& above) {
-  constexpr int P = NB / 256;
-  __shared__ unsigned long long part[256];
+// If the total is below target: b = 0. All threads of the block call it (blockDim.x = NT);
+// the result is valid in every thread. h may live in global memory or in LDS.
+template <int NB, int NT, typename H>
+__device__ void find_from_top(const H* __restrict__ h, unsigned long long target, uint32_t& bin,
+                              unsigned long long& above) {
+  constexpr int P = NB / NT;  // bins per thread
+  constexpr int NW = NT / 64;
+  __shared__ unsigned long long s_wsum[NW];
+  __shared__ int s_wcnt[NW];
   __shared__ uint32_t s_bin;
   __shared__ unsigned long long s_above;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   unsigned long long mine = 0;
-  for (int j = 0; j < P; ++j) mine += h[threadIdx.x * P + j];
-  part[threadIdx.x] = mine;
+#pragma unroll
+  for (int j = 0; j < P; ++j) mine += (unsigned long long)h[threadIdx.x * P + j];
+  // from_here = sum over this thread's bins and all bins above them: a suffix sum over the threads
+  unsigned long long incl = mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned long long u = __shfl_down(incl, off);
+    if (lane + off < 64) incl += u;
+  }
+  if (lane == 0) s_wsum[wave] = incl;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned long long acc = 0;
-    int c = 255;
-    for (; c > 0; --c) {
-      if (acc + part[c] >= target) break;
-      acc += part[c];
-    }
+  unsigned long long after = 0;
+  for (int w = wave + 1; w < NW; ++w) after += s_wsum[w];
+  const unsigned long long from_here = incl + after;
+  // from_here falls with the thread number, so the threads that still reach the target are
+  // 0 .. c, c being the thread whose bins hold the crossing
+  const uint64_t reach = __ballot(from_here >= target);
+  if (lane == 0) s_wcnt[wave] = __popcll(reach);
+  __syncthreads();
+  int c = -1;
+  for (int w = 0; w < NW; ++w) c += s_wcnt[w];
+  if (c < 0) c = 0;
+  if ((int)threadIdx.x == c) {
+    unsigned long long acc = from_here - mine;  // everything above this thread's bins
     int b = c * P + P - 1;
     for (; b > c * P; --b) {
-      if (acc + h[b] >= target) break;
-      acc += h[b];
+      const unsigned long long hb = (unsigned long long)h[b];
+      if (acc + hb >= target) break;
+      acc += hb;
     }
     s_bin = (uint32_t)b;
     s_above = acc;
@@ -238,9 +237,10 @@ __global__ __launch_bounds__(256) void k_sample_thresh(Workspace ws) {
   if (d.mode != kSampled) return;
   uint32_t bin;
   unsigned long long above;
-  find_from_top<kSampleBins>(ws.shist + (int64_t)t * kSampleBins, (unsigned long long)d.sample_target,
-                             bin, above);
+  unsigned long long* sh = ws.shist + (int64_t)t * kSampleBins;
+  find_from_top<kSampleBins, 256>(sh, (unsigned long long)d.sample_target, bin, above);
   if (threadIdx.x == 0) ws.ts[t].t_lo = bin << kSampleShift;
+  for (int b = threadIdx.x; b < kSampleBins; b += 256) sh[b] = 0ull;  // left zeroed for the next call
 }
 
 // ---------------------------------------------------------------- k_main
@@ -499,14 +499,16 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
     const int t = t0 + threadIdx.x;
     long long nch = 0, vlen = 0, M = 0;
     uint32_t use = 0u;
+    bool small = false;
     if (t < ws.T) {
       const TensorDesc d = ws.desc(t);
+      small = d.small != 0;  // finished by k_finish: no chunks in the grid-wide passes
       vlen = d.n;
-      if (d.mode == kSampled && any_sampled) {
+      if (d.mode == kSampled && any_sampled && !small) {
         M = ws.tg_base[t + 1] - ws.tg_base[t];
         if (M >= d.k && M <= d.cand_cap) { use = 1u; vlen = M; }
       }
-      nch = (vlen + (use ? 0 : d.group_shift) + kChunkElems - 1) / kChunkElems;
+      nch = small ? 0 : (vlen + (use ? 0 : d.group_shift) + kChunkElems - 1) / kChunkElems;
     }
     long long incl = nch;
 #pragma unroll
@@ -520,10 +522,12 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
     long long x = carry + incl - nch;
     for (int w = 0; w < wave; ++w) x += (long long)sh[w];
     if (t < ws.T) {
-      ws.ts[t].vlen = vlen;
       ws.ts[t].achunk_begin = x;
-      ws.ts[t].cand_total = M;
-      ws.ts[t].use_cand = use;
+      if (!small) {  // k_finish has written these for its tensors
+        ws.ts[t].vlen = vlen;
+        ws.ts[t].cand_total = M;
+        ws.ts[t].use_cand = use;
+      }
     }
     __syncthreads();
     if (threadIdx.x == 255) carry = x + nch;
@@ -550,7 +554,7 @@ __global__ __launch_bounds__(256) void k_gather(Workspace ws, const float* __res
   uint32_t t_lo = 0u;
   if (grp < ws.ngroups) {
     const int t = find_last_le(ws.T, grp, 0, [&](int i) { return (long long)ws.desc(i).group_begin; });
-    if (ws.ts[t].use_cand != 0u) {
+    if (!ws.desc(t).small && ws.ts[t].use_cand != 0u) {
       const TensorDesc d = ws.desc(t);
       const uint32_t cnt = ws.grp_cnt[grp];
       dst = d.cand_begin + (ws.grp_off[grp] - ws.tg_base[t]);
@@ -701,16 +705,21 @@ __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const flo
 __global__ __launch_bounds__(256) void k_select_scan(Workspace ws, int level) {
   const int t = blockIdx.x;
   const TensorDesc d = ws.desc(t);
+  if (d.small) return;
   unsigned long long* h = ws.hist + (int64_t)t * kSelBins;
   const unsigned long long k_rem = (level == 0) ? (unsigned long long)d.k : ws.ts[t].k_rem;
   uint32_t bin;
   unsigned long long above;
-  find_from_top<kSelBins>(h, k_rem, bin, above);
+  find_from_top<kSelBins, 256>(h, k_rem, bin, above);
   for (int b = threadIdx.x; b < kSelBins; b += 256) h[b] = 0ull;  // ready for the next digit
   if (threadIdx.x == 0) {
     ws.ts[t].k_rem = k_rem - above;
     const uint32_t p = (level == 0) ? 0u : ws.ts[t].prefix;
     ws.ts[t].prefix = p | (bin << sel_shift(level));
+  }
+  if (level == kSelLevels - 1) {  // the block maxima that the emit pass collects start from zero
+    const long long nb = (d.k + ws.block - 1) / ws.block;
+    for (long long b = threadIdx.x; b < nb; b += 256) ws.blk_amax[d.sprefix + b] = 0u;
   }
 }
 
@@ -903,6 +912,7 @@ __global__ __launch_bounds__(256) void k_quant(Workspace ws, float* __restrict__
   const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
   if (j >= ktotal) return;
   const int t = find_last_le(ws.T, j, 0, [&](int i) { return (long long)ws.desc(i).kprefix; });
+  if (ws.desc(t).small) return;  // coded by k_finish
   const uint32_t rel = (uint32_t)(j - ws.desc(t).kprefix);  // < k < 2^32: 32-bit division
   const uint32_t rblk = rel / (uint32_t)block;
   const long long blk = ws.desc(t).sprefix + rblk;
@@ -987,14 +997,357 @@ __global__ __launch_bounds__(256) void k_quant_sign(Workspace ws, float* __restr
   }
 }
 
+// ---------------------------------------------------------------- k_finish
+// One workgroup of 1024 threads finishes one SMALL tensor after the streaming pass: what the chain
+// k_group_sums .. k_quant does with a dozen grid-wide launches is done here with workgroup
+// barriers in between. Same arithmetic, same order, same bits:
+//   1. prefix sum of the tensor's group counts (sampled tensors)
+//   2. the select source in ascending index order: the candidates, packed from the groups' slots (a
+//      group with more candidates than slots is re-read from the residual); or, with too few or
+//      too many candidates and for tensors selected from their residual by plan, the residual
+//      itself. A source of up to kFinishLds entries is held in LDS (value bits and index), a longer
+//      one stays in memory (candidates: in the tensor's region of the candidate arrays).
+//   3. exact radix select (three digits, LDS histogram) of the k-th largest key and the tie quota
+//   4. ordered emit: kept entries compacted in place (LDS), or written to the output (memory)
+//   5. per block of kept entries: amax (LDS), scale, int8 codes, residual at the kept positions
+//      (with the sign code, step 5 only leaves the block maxima and kept values; k_quant_sign follows)
+constexpr int kFinishLds = 16384;     // entries of the LDS-resident source (128 KB)
+constexpr int kFinishMaxGroups = 4096;
+constexpr int kFinishAmaxWindow = 4096;
+
+template <typename I>
+__global__ __launch_bounds__(kFinishThreads) void k_finish(Workspace ws, float* __restrict__ e,
+                                                            I* __restrict__ out_idx, int8_t* __restrict__ q,
+                                                            float* __restrict__ scales, int32_t block, int codec) {
+  constexpr int NT = kFinishThreads, NW = NT / 64;
+  const int t = blockIdx.x;
+  const TensorDesc d = ws.desc(t);
+  if (!d.small) return;
+  __shared__ uint32_t lk[kFinishLds];  // value bits of the source / of the kept entries
+  __shared__ uint32_t li[kFinishLds];  // element index inside the tensor
+  // one region used three times: group offsets (steps 1-2), select histogram (3), block maxima (5)
+  __shared__ uint32_t scratch[kFinishMaxGroups + 1];
+  static_assert(kSelBins <= kFinishMaxGroups + 1 && kFinishAmaxWindow <= kFinishMaxGroups + 1, "scratch too small");
+  uint32_t* goff = scratch;
+  uint32_t* lh = scratch;
+  uint32_t* amax = scratch;
+  __shared__ unsigned long long s_red[NW];
+  __shared__ uint32_t s_flag;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // the source when it stays in memory
+  const float* gval = e + d.off;
+  const long long* gidx = nullptr;
+  long long len = d.n;
+  bool in_lds = false;
+  uint32_t use_cand = 0u;
+  long long M = 0;
+  if (d.mode == kSampled) {
+    // ---- 1. group counts -> offsets (GPT consecutive groups per thread)
+    constexpr int GPT = kFinishMaxGroups / NT;
+    const int ng = (int)d.ngroups;
+    uint32_t c[GPT];
+    uint32_t mine = 0u;
+#pragma unroll
+    for (int j = 0; j < GPT; ++j) {
+      const int g = tid * GPT + j;
+      c[j] = g < ng ? ws.grp_cnt[d.group_begin + g] : 0u;
+      mine += c[j];
+    }
+    uint32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t u = __shfl_up(incl, off);
+      if (lane >= off) incl += u;
+    }
+    if (lane == 63) s_red[wave] = incl;
+    if (tid == 0) s_flag = 0u;
+    __syncthreads();
+    uint32_t x = incl - mine;
+    unsigned long long total = 0ull;
+    for (int w = 0; w < NW; ++w) {
+      if (w < wave) x += (uint32_t)s_red[w];
+      total += s_red[w];
+    }
+    M = (long long)total;
+#pragma unroll
+    for (int j = 0; j < GPT; ++j) {
+      goff[tid * GPT + j] = x;
+      x += c[j];
+    }
+    if (tid == NT - 1) goff[kFinishMaxGroups] = x;
+    use_cand = (M >= d.k && M <= d.cand_cap) ? 1u : 0u;
+    if (use_cand) {
+      // ---- 2. pack the candidates: one thread per group; the loads of a round are issued together
+      in_lds = M <= kFinishLds;
+      const uint32_t t_lo = ws.ts[t].t_lo;
+      float* cv = ws.cand_val + d.cand_begin;
+      long long* ci = ws.cand_idx + d.cand_begin;
+      bool any_big = false;
+      __syncthreads();  // goff is complete
+      // groups are dealt out round robin here (the scan above had four neighbours per thread), so
+      // that a tensor with few groups still keeps every thread busy with one group
+#pragma unroll 1
+      for (int g = tid; g < ng; g += NT) {
+        const uint32_t dst = goff[g];
+        const uint32_t cnt = goff[g + 1] - dst;
+        if (cnt == 0u) continue;
+        if (cnt > (uint32_t)ws.cap) { any_big = true; continue; }
+        const long long first = max(0ll, (long long)g * kGroup - d.group_shift);
+        const uint2* __restrict__ rec = ws.slots + (d.group_begin + g) * (int64_t)ws.slot_stride;
+        for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {
+          uint2 r[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) r[u] = (j0 + u < cnt) ? rec[j0 + u] : make_uint2(0u, 0u);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            if (j0 + u < cnt) {
+              if (in_lds) {
+                lk[dst + j0 + u] = r[u].x;
+                li[dst + j0 + u] = (uint32_t)(first + r[u].y);
+              } else {
+                cv[dst + j0 + u] = __uint_as_float(r[u].x);
+                ci[dst + j0 + u] = first + r[u].y;
+              }
+            }
+          }
+        }
+      }
+      if (any_big) s_flag = 1u;
+      __syncthreads();
+      if (s_flag) {
+        // groups with more candidates than slots: a wavefront re-reads the group from the residual
+        // (it holds acc by now) and appends with ballot-ordered ranks
+        for (int g = wave; g < ng; g += NW) {
+          const uint32_t cnt_g = goff[g + 1] - goff[g];  // goff has an entry past the last group
+          if (cnt_g <= (uint32_t)ws.cap) continue;       // uniform over the wavefront
+          const long long first = max(0ll, (long long)g * kGroup - d.group_shift);
+          const int glen = (int)(min((long long)d.n, (long long)(g + 1) * kGroup - d.group_shift) - first);
+          long long w = goff[g];
+          for (int j0 = 0; j0 < glen; j0 += 64) {
+            const int j = j0 + lane;
+            const float v = j < glen ? e[d.off + first + j] : 0.0f;
+            const bool cnd = j < glen && key_of(v) >= t_lo;
+            const uint64_t m = __ballot(cnd);
+            if (cnd) {
+              const long long pos = w + mbcnt64(m);
+              if (in_lds) {
+                lk[pos] = __float_as_uint(v);
+                li[pos] = (uint32_t)(first + j);
+              } else {
+                cv[pos] = v;
+                ci[pos] = first + j;
+              }
+            }
+            w += __popcll(m);
+          }
+        }
+      }
+      gval = cv;
+      gidx = ci;
+      len = M;
+    }
+    __syncthreads();  // the packed candidates are visible to the whole workgroup; goff is free
+  }
+  if (!use_cand && len <= kFinishLds) {  // a short residual is held in LDS too
+    in_lds = true;
+    for (int i = tid; i < (int)len; i += NT) {
+      lk[i] = __float_as_uint(gval[i]);
+      li[i] = (uint32_t)i;
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {  // what gc_last_stats reports
+    ws.ts[t].cand_total = M;
+    ws.ts[t].use_cand = use_cand;
+    ws.ts[t].vlen = len;
+  }
+
+  // ---- 3. exact select: T = k-th largest key, quota = how many entries equal to T are kept.
+  // A radix select on key - kmin (order preserving), its digits laid over the range the keys really
+  // span: the keys of a candidate list share their top bits, and digits cut from the full 31 bits
+  // would pile them into a few bins of the first histogram (LDS atomics on one address run one
+  // after the other). With the range [kmin, kmax] cut into at most 2048 bins the first digit
+  // spreads them, and the later digits only see the few keys of one bin.
+  uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+  for (long long i = tid; i < len; i += NT) {
+    const uint32_t key = (in_lds ? lk[i] : __float_as_uint(gval[i])) & 0x7FFFFFFFu;
+    kmin = min(kmin, key);
+    kmax = max(kmax, key);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off));
+  }
+  if (lane == 0) s_red[wave] = ((unsigned long long)kmax << 32) | kmin;
+  __syncthreads();
+  for (int w = 0; w < NW; ++w) {
+    kmin = min(kmin, (uint32_t)s_red[w]);
+    kmax = max(kmax, (uint32_t)(s_red[w] >> 32));
+  }
+  int shift = 0;  // low bits below the current digit
+  while (((kmax - kmin) >> shift) >= (uint32_t)kSelBins) ++shift;
+  uint32_t prefix = 0u;  // resolved high part of T - kmin (bits above the current digit)
+  int pshift = 32;       // bits of (key - kmin) at or above pshift must match the prefix
+  unsigned long long k_rem = (unsigned long long)d.k;
+  for (;;) {
+    for (int b = tid; b < kSelBins; b += NT) lh[b] = 0u;
+    __syncthreads();
+    for (long long i0 = 0; i0 < len; i0 += NT) {
+      const long long i = i0 + tid;
+      const bool valid = i < len;
+      const uint32_t rel = valid ? (((in_lds ? lk[i] : __float_as_uint(gval[i])) & 0x7FFFFFFFu) - kmin) : 0u;
+      const bool match = pshift >= 32 || (rel >> pshift) == (prefix >> pshift);
+      hist_add(lh, valid && match, (rel >> shift) & (uint32_t)(kSelBins - 1));
+    }
+    __syncthreads();
+    uint32_t bin;
+    unsigned long long above;
+    find_from_top<kSelBins, NT>(lh, k_rem, bin, above);
+    k_rem -= above;
+    prefix |= bin << shift;
+    if (shift == 0) break;
+    pshift = shift;
+    shift = shift > 11 ? shift - 11 : 0;
+  }
+  prefix += kmin;
+  const uint32_t thr = prefix;
+  const long long quota = (long long)k_rem;
+
+  // ---- 4. ordered emit, four tiles of 1024 entries per pair of barriers
+  __shared__ uint32_t s_wg4[4][NW], s_we4[4][NW];
+  long long G = 0, E = 0;  // entries above / equal to the threshold before the current tiles
+  for (long long i0 = 0; i0 < len; i0 += 4 * NT) {
+    uint32_t vb[4], ib[4];
+    long long ig[4];
+    bool isgt[4], iseq[4];
+    uint64_t mg[4], me[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long i = i0 + u * NT + tid;
+      const bool valid = i < len;
+      vb[u] = 0u; ib[u] = 0u; ig[u] = 0;
+      if (valid) {
+        if (in_lds) { vb[u] = lk[i]; ib[u] = li[i]; }
+        else { vb[u] = __float_as_uint(gval[i]); ig[u] = gidx ? gidx[i] : i; }
+      }
+      const uint32_t key = vb[u] & 0x7FFFFFFFu;
+      isgt[u] = valid && key > thr;
+      iseq[u] = valid && key == thr;
+      mg[u] = __ballot(isgt[u]);
+      me[u] = __ballot(iseq[u]);
+      if (lane == 0) {
+        s_wg4[u][wave] = (uint32_t)__popcll(mg[u]);
+        s_we4[u][wave] = (uint32_t)__popcll(me[u]);
+      }
+    }
+    __syncthreads();  // every entry of these tiles is in registers: their LDS slots may be overwritten
+    long long gt_all = 0, eq_all = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      // lanes 0..15 hold the 16 wavefronts' counts of tile u; an inclusive scan over them gives
+      // this wavefront's base (exclusive) and the tile's totals
+      uint32_t cg = lane < NW ? s_wg4[u][lane] : 0u, ce = lane < NW ? s_we4[u][lane] : 0u;
+      uint32_t sg = cg, se = ce;
+#pragma unroll
+      for (int off = 1; off < NW; off <<= 1) {
+        const uint32_t ug = __shfl_up(sg, off), ue = __shfl_up(se, off);
+        if (lane >= off) { sg += ug; se += ue; }
+      }
+      const long long gb = G + gt_all + (long long)(uint32_t)__builtin_amdgcn_readlane((int)(sg - cg), wave);
+      const long long eb = E + eq_all + (long long)(uint32_t)__builtin_amdgcn_readlane((int)(se - ce), wave);
+      gt_all += (uint32_t)__builtin_amdgcn_readlane((int)sg, NW - 1);
+      eq_all += (uint32_t)__builtin_amdgcn_readlane((int)se, NW - 1);
+      const long long grank = gb + mbcnt64(mg[u]), erank = eb + mbcnt64(me[u]);
+      if (isgt[u] || (iseq[u] && erank < quota)) {
+        const long long rel = grank + (erank < quota ? erank : quota);  // <= i: compaction moves entries down only
+        if (in_lds) {
+          lk[rel] = vb[u];
+          li[rel] = ib[u];
+        } else {
+          out_idx[d.kprefix + rel] = (I)(d.off + ig[u]);
+          ws.kept_val[d.kprefix + rel] = __uint_as_float(vb[u]);
+        }
+      }
+    }
+    G += gt_all;
+    E += eq_all;
+    __syncthreads();  // the counts are rewritten by the next round
+  }
+  if (in_lds) {  // the kept entries now are lk / li [0, k): indices (and, for k_quant_sign, values) go out
+    for (int j = tid; j < (int)d.k; j += NT) {
+      out_idx[d.kprefix + j] = (I)(d.off + (long long)li[j]);
+      if (codec != 0) ws.kept_val[d.kprefix + j] = __uint_as_float(lk[j]);
+    }
+  }
+
+  // ---- 5. blocks of kept entries: amax, scale, code, residual (windows of kFinishAmaxWindow blocks)
+  const long long nblk = (d.k + block - 1) / block;
+  for (long long b0 = 0; b0 < nblk; b0 += kFinishAmaxWindow) {
+    const long long b1 = min(nblk, b0 + (long long)kFinishAmaxWindow);
+    for (int b = tid; b < (int)(b1 - b0); b += NT) amax[b] = 0u;
+    __syncthreads();
+    const long long j_begin = b0 * block, j_end = min((long long)d.k, b1 * block);
+    for (long long j0 = j_begin; j0 < j_end; j0 += NT) {
+      const long long j = j0 + tid;
+      const bool on = j < j_end;
+      uint32_t kb = 0u, bl = 0u;
+      if (on) {
+        kb = (in_lds ? lk[j] : __float_as_uint(ws.kept_val[d.kprefix + j])) & 0x7FFFFFFFu;
+        bl = (uint32_t)j / (uint32_t)block - (uint32_t)b0;
+      }
+      // nearly always the wavefront's 64 consecutive entries lie in one block: one atomic then
+      const uint64_t act = __ballot(on);
+      const uint32_t bl0 = (uint32_t)__builtin_amdgcn_readlane((int)bl, act ? __ffsll((unsigned long long)act) - 1 : 0);
+      if (__ballot(on && bl != bl0) == 0ull) {
+        uint32_t m = kb;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+        if (lane == 0 && act) atomicMax(&amax[bl0], m);
+      } else if (on) {
+        atomicMax(&amax[bl], kb);
+      }
+    }
+    __syncthreads();
+    for (int b = tid; b < (int)(b1 - b0); b += NT) {
+      const uint32_t akey = amax[b];
+      ws.blk_amax[d.sprefix + b0 + b] = akey;
+      if (codec == 0) {
+        const bool finite = akey < 0x7F800000u;
+        float sc = __fdiv_rn(__uint_as_float(akey), 127.0f);
+        if (!finite || !(sc >= 1.17549435e-38f)) sc = 0.0f;
+        scales[d.sprefix + b0 + b] = sc;
+        if (!finite) ws.flags[0] = 1u;
+      }
+    }
+    if (codec == 0) {
+      for (long long j0 = j_begin; j0 < j_end; j0 += NT) {
+        const long long j = j0 + tid;
+        if (j >= j_end) continue;
+        const uint32_t akey = amax[(uint32_t)j / (uint32_t)block - (uint32_t)b0];
+        const bool finite = akey < 0x7F800000u;
+        float sc = __fdiv_rn(__uint_as_float(akey), 127.0f);
+        if (!finite || !(sc >= 1.17549435e-38f)) sc = 0.0f;
+        const float v = in_lds ? __uint_as_float(lk[j]) : ws.kept_val[d.kprefix + j];
+        const long long pos = in_lds ? d.off + (long long)li[j] : (long long)out_idx[d.kprefix + j];
+        int code = 0;
+        if (sc != 0.0f) {
+          float r = rintf(__fdiv_rn(v, sc));
+          r = fminf(fmaxf(r, -127.0f), 127.0f);
+          code = (int)r;
+        }
+        q[d.kprefix + j] = (int8_t)code;
+        if (finite) e[pos] = __fsub_rn(v, __fmul_rn((float)code, sc));
+      }
+    }
+    __syncthreads();  // amax is rewritten by the next window
+  }
+}
+
 inline int clamp_grid(int64_t want, int64_t cap) { return (int)(want < 1 ? 1 : (want > cap ? cap : want)); }
 
 }  // namespace
-
-void launch_init(const Workspace& ws, hipStream_t s) {
-  const int64_t work = (int64_t)ws.T * kSampleBins;
-  hipLaunchKernelGGL(k_init, dim3(clamp_grid((work + 255) / 256, 2048)), dim3(256), 0, s, ws);
-}
 
 void launch_sample(const Workspace& ws, const void* g, int dtype, const float* e, hipStream_t s) {
   // every workgroup clears and flushes an 8192-bin histogram: 1024 workgroups measured best (256: the
@@ -1071,6 +1424,16 @@ void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStre
   else
     hipLaunchKernelGGL(k_emit<unsigned long long>, grid, dim3(256), 0, s, ws, e,
                        (unsigned long long*)out.indices, out.block);
+}
+
+void launch_finish(const Workspace& ws, float* e, const OutBuf& out, hipStream_t s) {
+  const dim3 grid((unsigned)ws.T), blk(kFinishThreads);
+  if (out.index_bits == 32)
+    hipLaunchKernelGGL(k_finish<uint32_t>, grid, blk, 0, s, ws, e, (uint32_t*)out.indices, out.q, out.scales, out.block,
+                       out.codec);
+  else
+    hipLaunchKernelGGL(k_finish<unsigned long long>, grid, blk, 0, s, ws, e, (unsigned long long*)out.indices, out.q,
+                       out.scales, out.block, out.codec);
 }
 
 void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktotal, hipStream_t s) {

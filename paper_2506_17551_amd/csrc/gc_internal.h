@@ -47,6 +47,20 @@ constexpr int kScanBlock = 1024;
 
 enum Mode : int32_t { kDense = 0, kSampled = 1 };
 
+// Small tensors: one workgroup finishes the tensor after the streaming pass (candidate gather,
+// exact select, ordered emit, codes, residual) in ONE launch instead of the chain of a dozen
+// grid-wide kernels, whose launch gaps dominate when there is little to do. A sampled tensor
+// qualifies with at most kSmallMaxK kept entries and kSmallMaxN elements (the bound on what the one
+// workgroup re-reads if the candidates turn out unusable), a tensor selected from its residual
+// directly with at most kSmallMaxDenseN elements.
+constexpr int64_t kSmallMaxK = 12288;         // candidates (about 1.2 k) then fit the LDS of the one workgroup
+constexpr int64_t kSmallMaxN = 4096 * 1024 - 4;   // at most 4096 groups
+constexpr int64_t kSmallMaxDenseN = 65536;
+#ifndef GC_FINISH_THREADS
+#define GC_FINISH_THREADS 1024
+#endif
+constexpr int kFinishThreads = GC_FINISH_THREADS;
+
 // Immutable per-tensor plan, built on the host, read by every kernel.
 struct TensorDesc {
   int64_t off;          // first element in the flat gradient / residual
@@ -65,6 +79,8 @@ struct TensorDesc {
   int32_t sample_stride;   // one granule out of this many is sampled
   uint32_t sample_target;  // sample count that the candidate threshold must cover
   int32_t group_shift;     // elements by which the tensor's first group is shortened (0..3)
+  int32_t small;           // 1: everything after the streaming pass is done by one workgroup (k_finish)
+  int32_t pad_;
 };
 
 // Per-tensor state of one compress call, zeroed by the first kernel of the call.
@@ -118,6 +134,7 @@ struct Workspace {  // device pointers into the context's scratch
   uint32_t* blk_amax;               // [sum ceil(k/block)] largest key of each quantization block
   uint32_t* flags;                  // [0] non-finite seen
   int32_t T;
+  int32_t block;                    // kept entries per quantization block
   int32_t cap;                      // candidate slots per group
   int32_t slot_stride;              // records reserved per group (= cap: 8, or a multiple of 16)
   int32_t gather_team;              // lanes per group in the gather (1 or 16)
@@ -142,12 +159,11 @@ struct OutBuf {
 
 // kernel ids for profiling
 enum KernelId : int32_t {
-  kKInit = 0, kKSample, kKSampleThresh, kKMain, kKGroupSums, kKGroupScan, kKRoute, kKGather, kKHist,
-  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKDecPack, kKDecTiles, kKDense, kKDenseSum, kKRowsGather, kKRowsFinish, kKRowsRemap, kKNum
+  kKSample = 0, kKSampleThresh, kKMain, kKGroupSums, kKGroupScan, kKRoute, kKGather, kKHist,
+  kKSelectScan, kKCount, kKChunkSums, kKChunkScan, kKEmit, kKQuant, kKFinish, kKDecPack, kKDecTiles, kKDense, kKDenseSum, kKRowsGather, kKRowsFinish, kKRowsRemap, kKNum
 };
 
 // launchers (defined in the .hip files next to their kernels)
-void launch_init(const Workspace& ws, hipStream_t s);
 void launch_sample(const Workspace& ws, const void* g, int dtype, const float* e, hipStream_t s);
 void launch_sample_thresh(const Workspace& ws, hipStream_t s);
 void launch_main(const Workspace& ws, const void* g, int dtype, float* e, hipStream_t s);
@@ -162,6 +178,7 @@ void launch_count(const Workspace& ws, const float* e, hipStream_t s);
 void launch_chunk_scan(const Workspace& ws, hipStream_t s);
 void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStream_t s);
 void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktotal, hipStream_t s);
+void launch_finish(const Workspace& ws, float* e, const OutBuf& out, hipStream_t s);
 
 // ---- die-aware order of one-shot workgroups ---------------------------------
 // Workgroup b runs on compute die b % 8. Work item number xcd_run_index(b) makes every die walk

@@ -142,6 +142,40 @@ def test_tie_heavy_inputs_on_the_dense_route(gc, ctx, oracle):
     check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 1000, tag="signed zeros and one value", expect_fallback=True)
 
 
+def test_single_workgroup_finish_paths(gc, ctx, oracle):
+    """Small tensors are finished by one workgroup after the streaming pass. Its branches, each
+    against the oracle: candidates held in LDS; a candidate list too long for LDS (20,000 ties at the
+    threshold) that stays in memory; more quantization blocks than one LDS window (block 1); a group
+    with more candidates than slots; a short tensor selected from its residual; several such
+    tensors in one call beside a large one that takes the grid-wide kernels; the sign code."""
+    n, k = 1_000_003, 12_000
+    g = inputs.normal(n, 0.1, 61)
+    perm = torch.randperm(n, generator=torch.Generator().manual_seed(62))
+    g[perm[:20_000]] = 3.0 * torch.where(torch.rand(20_000, generator=torch.Generator().manual_seed(63)) < 0.5, -1.0, 1.0)
+    g[perm[20_000:25_000]] = 4.0 + torch.rand(5_000, generator=torch.Generator().manual_seed(64))
+    e = inputs.normal(n, 1e-3, 65)
+    e[perm[:20_000]] = 0.0                          # the ties stay exact ties after acc = g + e
+    buf, _, _ = check_compress(gc, ctx, oracle, g, e, k, 64, tag="25,000 candidates, 7,000 of 20,000 ties kept",
+                               expect_fallback=False)
+    assert gc.last_stats(ctx)["candidates"] >= 25_000
+    check_compress(gc, ctx, oracle, inputs.normal(n, 1.0, 66), inputs.normal(n, 0.2, 67), 9_000, 1,
+                   tag="block 1: 9,000 blocks", expect_fallback=False)
+    for codec in (0, 1):
+        gg, ee = inputs.normal(300_000, 1.0, 68), inputs.normal(300_000, 0.2, 69)
+        gg[150_000:150_700] += 9.0                  # 700 winners inside one group of 1024
+        e_ref = ee.numpy().copy()
+        rc, idx, q, sc = oracle.compress(gg.numpy(), e_ref, 3_000, 256, codec=codec)
+        ed = ee.to(DEV)
+        b = gc.compress(ctx, gg.to(DEV), ed, 3_000, 256, codec=codec)
+        gc.sync_status(ctx)
+        assert rc == 0 and np.array_equal(b.indices_numpy(), idx) and np.array_equal(b.q.cpu().numpy(), q), codec
+        assert np.array_equal(bits(b.scales.cpu().numpy()), bits(sc)) and np.array_equal(bits(ed.cpu().numpy()), bits(e_ref))
+    # one call: short tensors (residual route in LDS and in memory), small sampled ones, a large one
+    sizes = [5, 3000, 40_000, 65_536, 65_537, 200_000, 1_500_000, 9_000_000, 17, 70_000]
+    st = _multi_case(gc, ctx, oracle, sizes, 0.004, 32, W=2, seed=900, sigma=0.5)
+    assert st["tensors"] == len(sizes) and st["tensors_fallback"] == 0
+
+
 def test_clustered_winners(gc, ctx, oracle):
     # all winners sit in one short stretch (more candidates per group than slots): the gather
     # re-reads those groups from the residual; whatever route is taken, the result is the oracle's
