@@ -17,8 +17,9 @@ holds the whole report:
   roofline            the streaming kernel k_main: algorithmic 12 B/element over its HIP-event time
                       against the 8 TB/s HBM peak, with the operands where a placement probe put
                       them AND where plain allocation puts them
-  roofline_decompress the aggregate (k_dec_pack + k_dec_tiles): 4 n + W (k (index + code) + scales)
-                      bytes over the time of the whole gc_decompress_sum call
+  roofline_decompress the aggregate (k_dec_fused where output tiles are thinly filled, else k_dec_pack +
+                      k_dec_tiles): 4 n + W (k (index + code) + scales) bytes over the time of the
+                      whole gc_decompress_sum call
   copy_ceiling        a plain device copy of the same size in the same run
   cpu_baseline        the CPU oracle on a bounded sample: one thread, and its W compress calls spread
                       one per core
@@ -727,7 +728,9 @@ def main():
                    "wall_s_including_generation": round(r["wall_s"], 1),
                    "workloads": records},
         "roofline": roofline,
-        "roofline_decompress": {"bound": "hbm", "kernel": "k_dec_pack + k_dec_tiles (one gc_decompress_sum call)",
+        "roofline_decompress": {"bound": "hbm",
+                                "kernel": ("k_dec_fused" if "k_dec_fused" in kernels and "k_dec_tiles" not in kernels
+                                           else "k_dec_pack + k_dec_tiles") + " (one gc_decompress_sum call)",
                                 "achieved": round(r["dec_achieved"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                 "frac": round(r["dec_achieved"] / HBM_PEAK_GBS, 4), "traffic": dec_traffic,
                                 "traffic_source": roofline["traffic_source"],

@@ -261,6 +261,9 @@ gc_status gc_profile_read(gc_ctx* ctx, int32_t id, double* total_ms, int64_t* la
  *                   larger ones by a workgroup (0..2048; default 1024).
  *   "dec_large_tile"  the aggregate's output tile held in LDS by one wavefront: 16384 floats (1),
  *                   4096 floats (0), or chosen from the vector's length and filling (-1; default).
+ *   "dec_fused"     the aggregate as one kernel that reads the workers' lists tile by tile (1), as two
+ *                   kernels with a packed record stream in between (0), or chosen from how thinly the
+ *                   output tiles are filled (-1; default).
  *   "apply_dense_min"  fused apply: an output tile with at least this many pairs per 4096 floats is
  *                   read and rewritten whole instead of position by position (1..2^30; default 128).
  * Unknown names or out-of-range values return GC_ERR_INVALID_ARG. */

@@ -67,6 +67,7 @@ struct gc_ctx {
   int64_t opt_dense_wave_block = 1024;  // dense coder: blocks up to this size are held by one wavefront
   int64_t opt_dense_lds_pad = -1;       // dense coder: dynamic LDS per workgroup (occupancy bound); -1: by shape
   int64_t opt_dec_large_tile = -1;      // aggregate: 16384-float tiles (1), 4096-float tiles (0), or by shape (-1)
+  int64_t opt_dec_fused = -1;           // aggregate: the one-kernel route without the record stream (1), the two-kernel route (0), by filling (-1)
   int64_t opt_apply_dense_min = 128;    // fused apply: tiles with at least this many records per 4096 floats are rewritten whole
   // profiling
   int prof = 0;  // 0 off, 1 every kernel, 2 only the streaming pass
@@ -636,6 +637,18 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   if (ntiles >= (int64_t(1) << 31)) return GC_ERR_UNSUPPORTED;
   const int tb = dec_range_tiles(W, tshift, nrec, n);
   const int64_t nranges = (ntiles + tb - 1) / tb;
+  hipStream_t s = (hipStream_t)hip_stream;
+  // The one-kernel route reads a tile's pairs straight from the workers' lists: faster where tiles
+  // are thinly filled (7B at 0.1 %, 16 workers: 66 pairs per 4096 floats: 5.70 against 5.94 ms; a
+  // 1M-element vector: one launch instead of two), slower where they are crowded (1.3B at 0.5 %, 330
+  // pairs per tile: 2.13 against 1.81 ms), where the packed record stream pays for itself.
+  const bool thin = (double)nrec * 4096.0 <= 128.0 * (double)n;
+  if ((ctx->opt_dec_fused == 1 || (ctx->opt_dec_fused < 0 && thin)) && !apply && T <= 1) {
+    // no record stream, no workspace
+    Scope sc(static_scratch ? nullptr : ctx, kKDecFused, s);
+    launch_dec_fused(a, W, ib, block, codec, staleness ? 1 : 0, n, out, s);
+    return launch_status();
+  }
   const size_t rec_bytes = sizeof(uint2) * (size_t)std::max<int64_t>(nrec, 1);
   const size_t ts_bytes = sizeof(unsigned long long) * (size_t)(ntiles + 1);
   void* rec = nullptr;
@@ -660,7 +673,6 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     rec = ctx->dec_rec.p;
     tile_start = (unsigned long long*)ctx->dec_tile_start.p;
   }
-  hipStream_t s = (hipStream_t)hip_stream;
   gc_ctx* pc = static_scratch ? nullptr : ctx;  // event pairs are created on demand: not in the static variant
   {
     Scope sc(pc, kKDecPack, s);
@@ -717,7 +729,7 @@ gc_status dense_sum_impl(gc_ctx* ctx, const void* const* q, const float* const* 
 
 const char* const kKernelNames[kKNum] = {"k_sample", "k_sample_thresh", "k_main", "k_group_sums", "k_group_scan",
                                          "k_route", "k_gather", "k_hist", "k_select_scan", "k_count",
-                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_finish", "k_dec_pack", "k_dec_tiles",
+                                         "k_chunk_sums", "k_chunk_scan", "k_emit", "k_quant", "k_finish", "k_dec_pack", "k_dec_tiles", "k_dec_fused",
                                          "k_dense", "k_dense_sum", "k_rows_gather", "k_rows_finish", "k_rows_remap"};
 
 }  // namespace
@@ -1061,6 +1073,11 @@ gc_status gc_set_option(gc_ctx* ctx, const char* name, int64_t value) {
   if (std::strcmp(name, "dec_large_tile") == 0) {
     if (value < -1 || value > 1) return GC_ERR_INVALID_ARG;
     ctx->opt_dec_large_tile = value;
+    return GC_OK;
+  }
+  if (std::strcmp(name, "dec_fused") == 0) {
+    if (value < -1 || value > 1) return GC_ERR_INVALID_ARG;
+    ctx->opt_dec_fused = value;
     return GC_OK;
   }
   if (std::strcmp(name, "apply_dense_min") == 0) {

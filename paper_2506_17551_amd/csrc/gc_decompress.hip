@@ -370,6 +370,216 @@ __global__ __launch_bounds__(WAVES * 64) void k_dec_tiles(const uint2* __restric
   }
 }
 
+// ---------------------------------------------------------------- fused aggregate
+// One kernel, no record stream: a workgroup (4 wavefronts) takes a range of `tb` tiles, finds every
+// worker's pairs in it (binary searches, then the "pair j opens the tiles up to its own" pass over
+// the range's indices, exactly as k_dec_pack does) and keeps the table of (tile, worker) segment
+// starts in LDS. Its wavefronts then take the range's tiles one by one: a tile's pairs are read
+// straight from the workers' lists, the lanes dealt out over the tile's pairs in (worker, index)
+// order - lane f finds its worker in the scan of the 64 segment lengths - decoded in registers and
+// added into the LDS tile worker by worker, as k_dec_tiles adds records. The merged stream of
+// 8-byte records is never written or read back: that stream is 1.8 GB of the 31.9 GB the two-kernel
+// call moves at 7B, and a third of what it moves at 1.3B.
+// lower_bound by eight lanes at a time: every step probes eight positions that cut [lo, hi) into
+// nine pieces, so the chain of dependent loads is 8 deep instead of 23 for a list of 7 M indices.
+// All eight lanes of a group (consecutive lanes, group g = lane / 8) call it with the same arguments
+// and get the same result; lanes of a group with nothing to search pass hi = 0.
+template <typename I>
+__device__ __forceinline__ uint32_t lower_bound_idx8(const I* __restrict__ idx, uint32_t hi, unsigned long long target,
+                                                     int lane) {
+  const int sub = lane & 7, gsh = lane & ~7;
+  uint32_t lo = 0u;
+  while (__ballot(lo < hi) != 0ull) {  // the wavefront leaves together: the ballots below need every lane
+    const uint32_t width = hi > lo ? hi - lo : 0u;
+    const uint32_t stepw = width / 9u + 1u;
+    const uint32_t p = lo + (uint32_t)(sub + 1) * stepw - 1u;  // probe position of this lane
+    bool less = false;
+    if (lo < hi && p < hi) less = (unsigned long long)idx[p] < target;
+    const uint32_t field = (uint32_t)((__ballot(less) >> gsh) & 0xFFull);  // sorted list: the true lanes are a prefix
+    const uint32_t c = (uint32_t)__popc(field);
+    if (lo < hi) {
+      const uint32_t nlo = lo + c * stepw;                 // one past the last probe that was below the target
+      const uint32_t nhi_p = lo + (c + 1u) * stepw - 1u;   // the first probe at or above it
+      if (c < 8u && nhi_p < hi) hi = nhi_p;
+      lo = nlo < hi ? nlo : hi;
+    }
+  }
+  return lo;
+}
+
+struct FusedWorker {  // one worker's arrays, copied to LDS so that a lane can index them by its worker
+  const void* idx;
+  const int8_t* q;
+  const float* sc;
+  float denom;
+  uint32_t k;
+};
+
+constexpr int kFusedWaves = 4, kFusedThreads = kFusedWaves * 64;
+constexpr int kFusedTileShift = kDecMinTileShift, kFusedTile = 1 << kFusedTileShift;
+
+template <typename I>
+__global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, int tb, int32_t block, int64_t ntiles,
+                                                             int64_t nranges, int codec, int weighted, int64_t n,
+                                                             float* __restrict__ out) {
+  extern __shared__ uint32_t s_dyn[];      // [tb + 1][W]: first pair of worker w at or after local tile t
+  uint32_t* s_lo = s_dyn;
+  __shared__ float tile_mem[kFusedWaves][kFusedTile];
+  __shared__ FusedWorker s_wk[kMaxWorkers];
+  __shared__ uint32_t s_br0[kMaxWorkers], s_br1[kMaxWorkers];
+  __shared__ uint32_t s_incl[kFusedWaves][kMaxWorkers];  // per wavefront: inclusive scan of a tile's segment lengths
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  constexpr int tshift = kFusedTileShift;
+  if (tid < W) {
+    FusedWorker f;
+    f.idx = a.indices[tid];
+    f.q = a.q[tid];
+    f.sc = a.scales[tid];
+    f.denom = a.denom[tid];
+    f.k = a.k[tid];
+    s_wk[tid] = f;
+  }
+  __syncthreads();
+  float* lt = tile_mem[wave];
+  const int team = W >= kFusedWaves ? 1 : kFusedWaves / W;  // wavefronts that share one worker's pairs in pass 1
+  const unsigned long long step = 64ull * team;
+
+  for (int64_t r = blockIdx.x; r < nranges; r += gridDim.x) {
+    const int64_t t0 = r * tb;
+    // every worker's first pair at or after the start of this range and of the next one
+    for (int s0 = 0; s0 < 2 * W; s0 += kFusedThreads / 8) {  // eight lanes per search
+      const int s = s0 + tid / 8;
+      const bool on = s < 2 * W;
+      const int w = on ? (s < W ? s : s - W) : 0;
+      const unsigned long long target = ((unsigned long long)(r + (s < W ? 0 : 1)) * (unsigned long long)tb) << tshift;
+      const uint32_t b = lower_bound_idx8<I>(static_cast<const I*>(s_wk[w].idx), on ? s_wk[w].k : 0u, target, lane);
+      if (on && (tid & 7) == 0) {
+        if (s < W) s_br0[w] = b; else s_br1[w] = b;
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < (tb + 1) * W; i += kFusedThreads) {  // a tile after a worker's last pair starts at its end
+      const int w = i % W;
+      const uint32_t b0 = s_br0[w], b1 = s_br1[w];
+      s_lo[i] = b1 > b0 ? b1 : b0;
+    }
+    __syncthreads();
+    // the first pair at or after the start of every tile: pair j opens all tiles after its predecessor's, up to its own
+    for (int w = wave / team; w < W; w += kFusedWaves / team) {
+      const I* idx = static_cast<const I*>(s_wk[w].idx);
+      const unsigned long long j0 = s_br0[w], j1 = s_br1[w] > s_br0[w] ? s_br1[w] : s_br0[w];
+      for (unsigned long long jb = j0 + (unsigned)((wave % team) * 64 + lane); jb < j1; jb += step * kPackBatch) {
+        unsigned long long cur[kPackBatch], prev[kPackBatch];
+#pragma unroll
+        for (int u = 0; u < kPackBatch; ++u) {  // the batch's loads are in flight together
+          const unsigned long long j = jb + u * step;
+          cur[u] = 0ull;
+          prev[u] = 0ull;
+          if (j < j1) {
+            cur[u] = (unsigned long long)idx[j];
+            if (j > j0) prev[u] = (unsigned long long)idx[j - 1];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < kPackBatch; ++u) {
+          const unsigned long long j = jb + u * step;
+          const int64_t tc = (int64_t)(cur[u] >> tshift) - t0;
+          if (j < j1 && tc >= 0 && tc < tb) {  // outside only with indices out of order
+            int64_t tp = -1;
+            if (j > j0) {
+              tp = (int64_t)(prev[u] >> tshift) - t0;
+              if (tp < -1) tp = -1;
+            }
+            for (int64_t t = tp + 1; t <= tc; ++t) s_lo[t * W + w] = (uint32_t)j;
+          }
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---- the range's tiles, one wavefront each
+    for (int ltile = wave; ltile < tb; ltile += kFusedWaves) {
+      const int64_t tile = t0 + ltile;
+      if (tile >= ntiles) break;
+      const int64_t base = tile << tshift;
+      // segment of worker `lane` in this tile, and the scan of the segment lengths
+      uint32_t lo = 0u, cnt = 0u;
+      if (lane < W) {
+        lo = s_lo[ltile * W + lane];
+        const uint32_t hi = s_lo[(ltile + 1) * W + lane];
+        cnt = hi > lo ? hi - lo : 0u;
+      }
+      uint32_t incl = cnt;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t u = __shfl_up(incl, off);
+        if (lane >= off) incl += u;
+      }
+      const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+      s_incl[wave][lane] = incl;
+      const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int i = 0; i < kFusedTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
+      wave_sync();
+
+      for (uint32_t f0 = 0; f0 < total; f0 += 64 * kDecRounds) {
+        uint2 rr[kDecRounds];
+#pragma unroll
+        for (int i = 0; i < kDecRounds; ++i) {  // the loads of all rounds are issued before any is used
+          const uint32_t f = f0 + (uint32_t)(i * 64 + lane);
+          rr[i] = make_uint2(kNoRecord, 0u);
+          if (f < total) {
+            // the worker of flat position f: the first w with incl[w] > f
+            int wl = 0, wh = W - 1;
+            while (wl < wh) {
+              const int mid = (wl + wh) >> 1;
+              if (s_incl[wave][mid] > f) wh = mid; else wl = mid + 1;
+            }
+            const int w = wl;
+            const uint32_t before = w > 0 ? s_incl[wave][w - 1] : 0u;
+            const uint32_t j = s_lo[ltile * W + w] + (f - before);
+            const FusedWorker wk = s_wk[w];
+            if (j < wk.k) {  // always, for lists that keep the contract
+              const unsigned long long gi = (unsigned long long)static_cast<const I*>(wk.idx)[j];
+              const uint32_t blk = j / (uint32_t)block;
+              const float sc = wk.sc[blk];
+              float val;
+              if (codec == 0) {
+                val = __fmul_rn((float)wk.q[j], sc);
+              } else {  // sign code (Eq. 10): bit number j - blk * block of the block's bytes
+                const uint32_t bit = j - blk * (uint32_t)block;
+                const uint32_t byte = (uint8_t)wk.q[(long long)blk * ((block + 7) / 8) + (bit >> 3)];
+                val = ((byte >> (bit & 7u)) & 1u) ? sc : -sc;
+              }
+              if (weighted) val = __fdiv_rn(val, wk.denom);  // Eq. 12: a stale worker counts for less
+              const unsigned long long rel = gi - (unsigned long long)base;
+              const uint32_t pos = (gi >= (unsigned long long)base && rel < (unsigned long long)kFusedTile) ? (uint32_t)rel : 0xFFFFu;
+              rr[i] = make_uint2(pos | ((uint32_t)w << 16), __float_as_uint(val));
+            }
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < kDecRounds; ++i) add_round<kFusedTile>(rr[i], lt);
+      }
+      wave_sync();
+
+      const int64_t remain = n - base;
+      if (remain >= kFusedTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
+#pragma unroll
+        for (int i = 0; i < kFusedTile / 256; ++i) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
+          __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
+        }
+      } else {
+        const int lim = (int)(remain < kFusedTile ? remain : kFusedTile);
+        for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
+      }
+      wave_sync();
+    }
+    __syncthreads();  // the table is rewritten for the next range
+  }
+}
+
 }  // namespace
 
 // log2 of the tile size for a call: large tiles for long, thinly filled vectors.
@@ -390,6 +600,30 @@ int dec_range_tiles(int W, int tshift, int64_t nrec, int64_t n) {
   int tb = (W <= 32 ? (1 << 19) : (1 << 18)) >> tshift;
   while (tb > 8 && (per_tile * tb > 32768.0 || ntiles / tb < 2048)) tb >>= 1;
   return tb;
+}
+
+// Tiles per range of the fused kernel: the LDS table holds (tb + 1) * W entries (about 8 KB), and
+// there should be enough ranges to keep two workgroups per compute unit busy. A power of two >= 4.
+int dec_fused_range_tiles(int W, int64_t n) {
+  const int64_t ntiles = (n + kFusedTile - 1) >> kFusedTileShift;
+  int tb = 128;
+  while (tb > 4 && ((tb + 1) * W > 2112 || ntiles / tb < 4096)) tb >>= 1;
+  return tb;
+}
+
+void launch_dec_fused(const DecArgs& a, int W, int index_bits, int32_t block, int codec, int weighted, int64_t n,
+                      float* out, hipStream_t s) {
+  const int tb = dec_fused_range_tiles(W, n);
+  const int64_t ntiles = (n + kFusedTile - 1) >> kFusedTileShift;
+  const int64_t nranges = (ntiles + tb - 1) / tb;
+  const dim3 grid((unsigned)(nranges < 512 ? nranges : 512));
+  const size_t lds = sizeof(uint32_t) * (size_t)(tb + 1) * W;
+  if (index_bits == 32)
+    hipLaunchKernelGGL(k_dec_fused<uint32_t>, grid, dim3(kFusedThreads), lds, s, a, W, tb, block, ntiles, nranges, codec,
+                       weighted, n, out);
+  else
+    hipLaunchKernelGGL(k_dec_fused<unsigned long long>, grid, dim3(kFusedThreads), lds, s, a, W, tb, block, ntiles,
+                       nranges, codec, weighted, n, out);
 }
 
 void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift, int32_t block, int64_t ntiles,

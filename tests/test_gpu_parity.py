@@ -816,12 +816,17 @@ def _random_buffer(rng, gc, n, ks, block, index_bits, codec):
     return buf, (idx, q, s)
 
 
-@pytest.fixture(params=[-1, 0, 1], ids=["tile-auto", "tile-4096", "tile-16384"])
+@pytest.fixture(params=[-1, 0, 1, "fused"], ids=["tile-auto", "tile-4096", "tile-16384", "one-kernel"])
 def tile_ctx(gc, request):
-    """A context with the aggregate's tile size forced (the large tile is otherwise only chosen
-    for vectors of 2^28 elements and more)."""
+    """A context with the aggregate's route forced: the two-kernel route with either tile size (the
+    large tile is otherwise only chosen for vectors of 2^28 elements and more), or the one-kernel
+    route without the record stream."""
     c = gc.Context(0)
-    c.set_option("dec_large_tile", request.param)
+    if request.param == "fused":
+        c.set_option("dec_fused", 1)
+    else:
+        c.set_option("dec_fused", 0 if request.param >= 0 else -1)
+        c.set_option("dec_large_tile", request.param)
     yield c
     c.destroy()
 
