@@ -643,10 +643,20 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   // 1M-element vector: one launch instead of two), slower where they are crowded (1.3B at 0.5 %, 330
   // pairs per tile: 2.13 against 1.81 ms), where the packed record stream pays for itself.
   const bool thin = (double)nrec * 4096.0 <= 128.0 * (double)n;
-  if ((ctx->opt_dec_fused == 1 || (ctx->opt_dec_fused < 0 && thin)) && !apply && T <= 1) {
-    // no record stream, no workspace
+  // (the in-place update keeps the two-kernel route: its scattered read-modify-writes want every
+  // wavefront of the compute unit on them - 7B: 5.89 against 6.29 ms)
+  if (ctx->opt_dec_fused == 1 || (ctx->opt_dec_fused < 0 && thin && !apply)) {
+    // no record stream, no workspace (multi-tensor buffers bring their small prefix tables)
+    DecPlan* Df = nullptr;
+    if (T > 1) {
+      if (static_scratch) return GC_ERR_UNSUPPORTED;
+      const gc_status pst = get_dec_plan(ctx, k, T, block, codec, &Df);
+      if (pst != GC_OK) return pst;
+    }
     Scope sc(static_scratch ? nullptr : ctx, kKDecFused, s);
-    launch_dec_fused(a, W, ib, block, codec, staleness ? 1 : 0, n, out, s);
+    launch_dec_fused(a, W, ib, block, codec, staleness ? 1 : 0, n, Df ? (const long long*)Df->kprefix.p : nullptr,
+                     Df ? (const long long*)Df->sprefix.p : nullptr, Df ? (const long long*)Df->qprefix.p : nullptr,
+                     Df ? T : 1, out, apply ? 1 : 0, c_apply, s);
     return launch_status();
   }
   const size_t rec_bytes = sizeof(uint2) * (size_t)std::max<int64_t>(nrec, 1);

@@ -418,10 +418,14 @@ struct FusedWorker {  // one worker's arrays, copied to LDS so that a lane can i
 constexpr int kFusedWaves = 4, kFusedThreads = kFusedWaves * 64;
 constexpr int kFusedTileShift = kDecMinTileShift, kFusedTile = 1 << kFusedTileShift;
 
-template <typename I>
+// MODE 0: out[tile] = sum (dense write).  MODE 1: theta[i] -= c * sum[i] at the touched i only.
+template <typename I, int MODE>
 __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, int tb, int32_t block, int64_t ntiles,
                                                              int64_t nranges, int codec, int weighted, int64_t n,
-                                                             float* __restrict__ out) {
+                                                             const long long* __restrict__ kprefix,
+                                                             const long long* __restrict__ sprefix,
+                                                             const long long* __restrict__ qprefix, int T,
+                                                             float* __restrict__ out, float c_apply) {
   extern __shared__ uint32_t s_dyn[];      // [tb + 1][W]: first pair of worker w at or after local tile t
   uint32_t* s_lo = s_dyn;
   __shared__ float tile_mem[kFusedWaves][kFusedTile];
@@ -516,12 +520,24 @@ __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, i
         if (lane >= off) incl += u;
       }
       const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+      if (MODE == 1 && total == 0u) continue;  // nothing to apply in an empty tile
       s_incl[wave][lane] = incl;
       const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int i = 0; i < kFusedTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
       wave_sync();
 
+      // the pair at flat position f of this tile: its worker is the first w with incl[w] > f
+      auto pair_of = [&](uint32_t f, int& w, uint32_t& j) {
+        int wl = 0, wh = W - 1;
+        while (wl < wh) {
+          const int mid = (wl + wh) >> 1;
+          if (s_incl[wave][mid] > f) wh = mid; else wl = mid + 1;
+        }
+        w = wl;
+        const uint32_t before = w > 0 ? s_incl[wave][w - 1] : 0u;
+        j = s_lo[ltile * W + w] + (f - before);
+      };
       for (uint32_t f0 = 0; f0 < total; f0 += 64 * kDecRounds) {
         uint2 rr[kDecRounds];
 #pragma unroll
@@ -529,26 +545,32 @@ __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, i
           const uint32_t f = f0 + (uint32_t)(i * 64 + lane);
           rr[i] = make_uint2(kNoRecord, 0u);
           if (f < total) {
-            // the worker of flat position f: the first w with incl[w] > f
-            int wl = 0, wh = W - 1;
-            while (wl < wh) {
-              const int mid = (wl + wh) >> 1;
-              if (s_incl[wave][mid] > f) wh = mid; else wl = mid + 1;
-            }
-            const int w = wl;
-            const uint32_t before = w > 0 ? s_incl[wave][w - 1] : 0u;
-            const uint32_t j = s_lo[ltile * W + w] + (f - before);
+            int w;
+            uint32_t j;
+            pair_of(f, w, j);
             const FusedWorker wk = s_wk[w];
             if (j < wk.k) {  // always, for lists that keep the contract
               const unsigned long long gi = (unsigned long long)static_cast<const I*>(wk.idx)[j];
-              const uint32_t blk = j / (uint32_t)block;
-              const float sc = wk.sc[blk];
+              uint32_t rel_j = j;  // pair inside its tensor; sbase, qbase: the tensor's first scale and code byte
+              long long sbase = 0, qbase = 0;
+              if (T > 1) {  // blocks restart at every tensor: find the tensor that owns pair j
+                int tl = 0, th = T - 1;
+                while (tl < th) {
+                  const int mid = (tl + th + 1) >> 1;
+                  if (kprefix[mid] <= (long long)j) tl = mid; else th = mid - 1;
+                }
+                rel_j = (uint32_t)((long long)j - kprefix[tl]);
+                sbase = sprefix[tl];
+                qbase = qprefix[tl];
+              }
+              const uint32_t blk = rel_j / (uint32_t)block;
+              const float sc = wk.sc[sbase + blk];
               float val;
               if (codec == 0) {
-                val = __fmul_rn((float)wk.q[j], sc);
-              } else {  // sign code (Eq. 10): bit number j - blk * block of the block's bytes
-                const uint32_t bit = j - blk * (uint32_t)block;
-                const uint32_t byte = (uint8_t)wk.q[(long long)blk * ((block + 7) / 8) + (bit >> 3)];
+                val = __fmul_rn((float)wk.q[qbase + rel_j], sc);
+              } else {  // sign code (Eq. 10): bit number rel_j - blk * block of the block's bytes
+                const uint32_t bit = rel_j - blk * (uint32_t)block;
+                const uint32_t byte = (uint8_t)wk.q[qbase + (long long)blk * ((block + 7) / 8) + (bit >> 3)];
                 val = ((byte >> (bit & 7u)) & 1u) ? sc : -sc;
               }
               if (weighted) val = __fdiv_rn(val, wk.denom);  // Eq. 12: a stale worker counts for less
@@ -564,15 +586,53 @@ __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, i
       wave_sync();
 
       const int64_t remain = n - base;
-      if (remain >= kFusedTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
+      if (MODE == 0) {
+        if (remain >= kFusedTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
 #pragma unroll
-        for (int i = 0; i < kFusedTile / 256; ++i) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
-          __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
+          for (int i = 0; i < kFusedTile / 256; ++i) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
+          }
+        } else {
+          const int lim = (int)(remain < kFusedTile ? remain : kFusedTile);
+          for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
         }
-      } else {
-        const int lim = (int)(remain < kFusedTile ? remain : kFusedTile);
-        for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
+      } else if (total != 0u) {
+        // every named position is claimed once (LDS exchange with a marker) and updated in place:
+        // theta - fl32(c * sum). The positions are read again from the workers' lists (the lines were
+        // fetched a moment ago); the loads of a batch of rounds are issued before its first store.
+        for (uint32_t f0 = 0; f0 < total; f0 += 64 * kDecRounds) {
+          int64_t gi[kDecRounds];
+          float sum[kDecRounds], th[kDecRounds];
+          bool mine[kDecRounds];
+#pragma unroll
+          for (int i = 0; i < kDecRounds; ++i) {
+            const uint32_t f = f0 + (uint32_t)(i * 64 + lane);
+            mine[i] = false;
+            gi[i] = 0;
+            sum[i] = 0.0f;
+            if (f < total) {
+              int w;
+              uint32_t j;
+              pair_of(f, w, j);
+              if (j < s_wk[w].k) {
+                const unsigned long long g = (unsigned long long)static_cast<const I*>(s_wk[w].idx)[j];
+                const unsigned long long rel = g - (unsigned long long)base;
+                if (g >= (unsigned long long)base && rel < (unsigned long long)kFusedTile && (int64_t)g < n) {
+                  const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + (uint32_t)rel, kClaimed);
+                  mine[i] = old != kClaimed;
+                  sum[i] = __uint_as_float(old);
+                  gi[i] = (int64_t)g;
+                }
+              }
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < kDecRounds; ++i) th[i] = mine[i] ? out[gi[i]] : 0.0f;
+#pragma unroll
+          for (int i = 0; i < kDecRounds; ++i)
+            if (mine[i]) out[gi[i]] = __fsub_rn(th[i], __fmul_rn(c_apply, sum[i]));
+        }
       }
       wave_sync();
     }
@@ -607,23 +667,27 @@ int dec_range_tiles(int W, int tshift, int64_t nrec, int64_t n) {
 int dec_fused_range_tiles(int W, int64_t n) {
   const int64_t ntiles = (n + kFusedTile - 1) >> kFusedTileShift;
   int tb = 128;
-  while (tb > 4 && ((tb + 1) * W > 2112 || ntiles / tb < 4096)) tb >>= 1;
+  while (tb > 4 && ((tb + 1) * W > 2112 || ntiles / tb < 1024)) tb >>= 1;
   return tb;
 }
 
 void launch_dec_fused(const DecArgs& a, int W, int index_bits, int32_t block, int codec, int weighted, int64_t n,
-                      float* out, hipStream_t s) {
+                      const long long* kprefix, const long long* sprefix, const long long* qprefix, int T, float* out,
+                      int apply, float c_apply, hipStream_t s) {
   const int tb = dec_fused_range_tiles(W, n);
   const int64_t ntiles = (n + kFusedTile - 1) >> kFusedTileShift;
   const int64_t nranges = (ntiles + tb - 1) / tb;
-  const dim3 grid((unsigned)(nranges < 512 ? nranges : 512));
+  const dim3 grid((unsigned)(nranges < 512 ? nranges : 512)), blk(kFusedThreads);
   const size_t lds = sizeof(uint32_t) * (size_t)(tb + 1) * W;
-  if (index_bits == 32)
-    hipLaunchKernelGGL(k_dec_fused<uint32_t>, grid, dim3(kFusedThreads), lds, s, a, W, tb, block, ntiles, nranges, codec,
-                       weighted, n, out);
-  else
-    hipLaunchKernelGGL(k_dec_fused<unsigned long long>, grid, dim3(kFusedThreads), lds, s, a, W, tb, block, ntiles,
-                       nranges, codec, weighted, n, out);
+#define GC_LAUNCH_FUSED(ITYPE, MODE)                                                                                  \
+  hipLaunchKernelGGL((k_dec_fused<ITYPE, MODE>), grid, blk, lds, s, a, W, tb, block, ntiles, nranges, codec, weighted, n, \
+                     kprefix, sprefix, qprefix, T, out, c_apply)
+  if (index_bits == 32) {
+    if (apply) GC_LAUNCH_FUSED(uint32_t, 1); else GC_LAUNCH_FUSED(uint32_t, 0);
+  } else {
+    if (apply) GC_LAUNCH_FUSED(unsigned long long, 1); else GC_LAUNCH_FUSED(unsigned long long, 0);
+  }
+#undef GC_LAUNCH_FUSED
 }
 
 void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift, int32_t block, int64_t ntiles,
