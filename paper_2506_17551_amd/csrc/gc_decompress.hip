@@ -41,6 +41,33 @@ __device__ __forceinline__ uint32_t lower_bound_idx(const I* __restrict__ idx, u
   return lo;
 }
 
+// lower_bound by eight lanes at a time: every step probes eight positions that cut [lo, hi) into
+// nine pieces, so the chain of dependent loads is 8 deep instead of 23 for a list of 7 M indices.
+// All eight lanes of a group (consecutive lanes, group g = lane / 8) call it with the same arguments
+// and get the same result; lanes of a group with nothing to search pass hi = 0.
+template <typename I>
+__device__ __forceinline__ uint32_t lower_bound_idx8(const I* __restrict__ idx, uint32_t hi, unsigned long long target,
+                                                     int lane) {
+  const int sub = lane & 7, gsh = lane & ~7;
+  uint32_t lo = 0u;
+  while (__ballot(lo < hi) != 0ull) {  // the wavefront leaves together: the ballots below need every lane
+    const uint32_t width = hi > lo ? hi - lo : 0u;
+    const uint32_t stepw = width / 9u + 1u;
+    const uint32_t p = lo + (uint32_t)(sub + 1) * stepw - 1u;  // probe position of this lane
+    bool less = false;
+    if (lo < hi && p < hi) less = (unsigned long long)idx[p] < target;
+    const uint32_t field = (uint32_t)((__ballot(less) >> gsh) & 0xFFull);  // sorted list: the true lanes are a prefix
+    const uint32_t c = (uint32_t)__popc(field);
+    if (lo < hi) {
+      const uint32_t nlo = lo + c * stepw;                 // one past the last probe that was below the target
+      const uint32_t nhi_p = lo + (c + 1u) * stepw - 1u;   // the first probe at or above it
+      if (c < 8u && nhi_p < hi) hi = nhi_p;
+      lo = nlo < hi ? nlo : hi;
+    }
+  }
+  return lo;
+}
+
 // The wavefronts of a workgroup share out the workers (several wavefronts per worker when there are
 // few workers); every lane issues the loads of a batch of pairs before it uses any of them.
 #ifndef GC_PACK_THREADS
@@ -70,14 +97,18 @@ __global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int
   const unsigned long long step = 64ull * team;
   const int64_t r = r_first + blockIdx.x, t0 = r * tb;
 
-  // every worker's first pair at or after the start of this range and of the next one: 2 W binary
-  // searches side by side (W <= 64, so they fit the first two wavefronts)
+  // every worker's first pair at or after the start of this range and of the next one: 2 W lower
+  // bounds, eight lanes each (8 dependent loads instead of 23 for a list of 7 M indices)
   __shared__ uint32_t s_br1[kMaxWorkers];
-  if (tid < 2 * W) {
-    const int w = tid < W ? tid : tid - W;
-    const unsigned long long target = ((unsigned long long)(r + (tid < W ? 0 : 1)) * (unsigned long long)tb) << tshift;
-    const uint32_t b = lower_bound_idx<I>(static_cast<const I*>(a.indices[w]), 0u, a.k[w], target);
-    if (tid < W) s_br0[w] = b; else s_br1[w] = b;
+  for (int s0 = 0; s0 < 2 * W; s0 += kPackThreads / 8) {
+    const int sidx = s0 + tid / 8;
+    const bool on = sidx < 2 * W;
+    const int w = on ? (sidx < W ? sidx : sidx - W) : 0;
+    const unsigned long long target = ((unsigned long long)(r + (sidx < W ? 0 : 1)) * (unsigned long long)tb) << tshift;
+    const uint32_t b = lower_bound_idx8<I>(static_cast<const I*>(a.indices[w]), on ? a.k[w] : 0u, target, lane);
+    if (on && (tid & 7) == 0) {
+      if (sidx < W) s_br0[w] = b; else s_br1[w] = b;
+    }
   }
   __syncthreads();
   if (tid < W) {
@@ -380,33 +411,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_dec_tiles(const uint2* __restric
 // added into the LDS tile worker by worker, as k_dec_tiles adds records. The merged stream of
 // 8-byte records is never written or read back: that stream is 1.8 GB of the 31.9 GB the two-kernel
 // call moves at 7B, and a third of what it moves at 1.3B.
-// lower_bound by eight lanes at a time: every step probes eight positions that cut [lo, hi) into
-// nine pieces, so the chain of dependent loads is 8 deep instead of 23 for a list of 7 M indices.
-// All eight lanes of a group (consecutive lanes, group g = lane / 8) call it with the same arguments
-// and get the same result; lanes of a group with nothing to search pass hi = 0.
-template <typename I>
-__device__ __forceinline__ uint32_t lower_bound_idx8(const I* __restrict__ idx, uint32_t hi, unsigned long long target,
-                                                     int lane) {
-  const int sub = lane & 7, gsh = lane & ~7;
-  uint32_t lo = 0u;
-  while (__ballot(lo < hi) != 0ull) {  // the wavefront leaves together: the ballots below need every lane
-    const uint32_t width = hi > lo ? hi - lo : 0u;
-    const uint32_t stepw = width / 9u + 1u;
-    const uint32_t p = lo + (uint32_t)(sub + 1) * stepw - 1u;  // probe position of this lane
-    bool less = false;
-    if (lo < hi && p < hi) less = (unsigned long long)idx[p] < target;
-    const uint32_t field = (uint32_t)((__ballot(less) >> gsh) & 0xFFull);  // sorted list: the true lanes are a prefix
-    const uint32_t c = (uint32_t)__popc(field);
-    if (lo < hi) {
-      const uint32_t nlo = lo + c * stepw;                 // one past the last probe that was below the target
-      const uint32_t nhi_p = lo + (c + 1u) * stepw - 1u;   // the first probe at or above it
-      if (c < 8u && nhi_p < hi) hi = nhi_p;
-      lo = nlo < hi ? nlo : hi;
-    }
-  }
-  return lo;
-}
-
 struct FusedWorker {  // one worker's arrays, copied to LDS so that a lane can index them by its worker
   const void* idx;
   const int8_t* q;
