@@ -514,7 +514,8 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
       { Scope sc(ctx, kKGroupSums, s); launch_group_sums(ws, s); }
       { Scope sc(ctx, kKGroupScan, s); launch_group_scan(ws, s); }
     }
-    { Scope sc(ctx, kKRoute, s); launch_route(ws, s); }
+    // (a single sampled tensor is routed by the last block of k_group_scan)
+    if (!(T == 1 && any_sampled)) { Scope sc(ctx, kKRoute, s); launch_route(ws, s); }
     if (any_sampled) { Scope sc(ctx, kKGather, s); launch_gather(ws, residual, s); }
     for (int level = 0; level < kSelLevels; ++level) {
       { Scope sc(ctx, kKHist, s); launch_hist(ws, level, residual, s); }
@@ -973,15 +974,23 @@ gc_status gc_decompress_sum_rows(gc_ctx* ctx, const gc_buf* bufs, int32_t W, con
   hipStream_t s = (hipStream_t)hip_stream;
   std::vector<gc_buf> tmp(bufs, bufs + W);
   uint32_t* cidx = (uint32_t*)ctx->rows_cidx.p;
+  if (ktotal >= (int64_t(1) << 32)) return GC_ERR_UNSUPPORTED;
+  RowsRemapArgs ra;
+  std::memset(&ra, 0, sizeof(ra));
   int64_t at = 0;
   for (int32_t w = 0; w < W; ++w) {
-    Scope sc(ctx, kKRowsRemap, s);
-    launch_rows_remap(bufs[w].indices, bufs[w].index_bits, bufs[w].k, reinterpret_cast<const long long*>(urows), Ru, D,
-                      cidx + at, (uint32_t*)ctx->flags.p, s);
+    ra.idx[w] = bufs[w].indices;
+    ra.k[w] = (uint32_t)bufs[w].k;
+    ra.at[w] = (uint32_t)at;
+    ra.bits[w] = (uint8_t)bufs[w].index_bits;
     tmp[w].indices = cidx + at;
     tmp[w].index_bits = 32;
     tmp[w].n = m;
     at += bufs[w].k;
+  }
+  {
+    Scope sc(ctx, kKRowsRemap, s);
+    launch_rows_remap(ra, W, reinterpret_cast<const long long*>(urows), Ru, D, cidx, (uint32_t*)ctx->flags.p, s);
   }
   return decompress_impl(ctx, tmp.data(), W, nullptr, 0, staleness, false, 0.0f, out, m, hip_stream);
 }

@@ -483,7 +483,22 @@ __global__ __launch_bounds__(256) void k_group_scan(Workspace ws) {
     const int64_t gb = ws.desc(t).group_begin;
     if (gb >= lo && gb < hi) ws.tg_base[t] = lds_out[gb - lo];
   }
-  if (threadIdx.x == 0 && hi >= ws.ngroups) ws.tg_base[ws.T] = lds_out[min((int64_t)kScanBlock, ws.ngroups - lo)];
+  if (threadIdx.x == 0 && hi >= ws.ngroups) {
+    const long long total = lds_out[min((int64_t)kScanBlock, ws.ngroups - lo)];
+    ws.tg_base[ws.T] = total;
+    if (ws.T == 1) {
+      // a single tensor needs no routing kernel: the block that knows the candidate total decides
+      // where the select reads from (what k_route does per tensor when there are several)
+      const TensorDesc d = ws.desc(0);
+      const bool use = total >= d.k && total <= d.cand_cap;
+      const long long vlen = use ? total : d.n;
+      ws.ts[0].vlen = vlen;
+      ws.ts[0].achunk_begin = 0;
+      ws.ts[0].cand_total = total;
+      ws.ts[0].use_cand = use ? 1u : 0u;
+      ws.totals[0] = (vlen + (use ? 0 : d.group_shift) + kChunkElems - 1) / kChunkElems;
+    }
+  }
 }
 
 // ---------------------------------------------------------------- k_route

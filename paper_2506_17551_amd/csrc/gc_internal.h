@@ -287,8 +287,14 @@ void launch_dense_sum(const DenseDecArgs& a, int W, int32_t block, int64_t n, in
 // ---- row-sparse gradients (touched rows of a table-shaped residual) ----------
 void launch_rows_gather(const float* table, const long long* rows, int64_t U, int64_t D, int64_t R, float* ec,
                         uint32_t* flags, hipStream_t s);
-void launch_rows_remap(const void* idx, int index_bits, int64_t k, const long long* urows, int64_t Ru, int64_t D,
-                       uint32_t* out, uint32_t* flags, hipStream_t s);
+struct RowsRemapArgs {  // every worker's index list for the one launch that rewrites them all
+  const void* idx[kMaxWorkers];
+  uint32_t k[kMaxWorkers];
+  uint32_t at[kMaxWorkers];   // first compact position of the worker in the output
+  uint8_t bits[kMaxWorkers];  // 32 or 64
+};
+void launch_rows_remap(const RowsRemapArgs& a, int W, const long long* urows, int64_t Ru, int64_t D, uint32_t* out,
+                       uint32_t* flags, hipStream_t s);
 void launch_rows_finish(float* table, const long long* rows, int64_t U, int64_t D, int64_t R, const float* ec,
                         const uint32_t* compact_idx, int64_t k, void* out_idx, int index_bits, hipStream_t s);
 

@@ -63,14 +63,15 @@ __global__ __launch_bounds__(256) void k_rows_finish(float* __restrict__ table, 
 // (Ru x D) output over the row list urows. lower_bound is monotone, so the rewritten positions stay
 // ascending; a row that is missing from the list is flagged and lands on a neighbouring listed row
 // (the result is then unspecified, but every position stays inside the output).
-template <typename I>
-__global__ __launch_bounds__(256) void k_rows_remap(const I* __restrict__ idx, long long k,
-                                                    const long long* __restrict__ urows, long long Ru,
+// All workers in one launch: blockIdx.y is the worker, whose compact positions go to out + at[w].
+__global__ __launch_bounds__(256) void k_rows_remap(RowsRemapArgs a, const long long* __restrict__ urows, long long Ru,
                                                     long long D, uint32_t* __restrict__ out,
                                                     uint32_t* __restrict__ flags) {
+  const int w = blockIdx.y;
   const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (j >= k) return;
-  const unsigned long long pos = (unsigned long long)idx[j];
+  if (j >= (long long)a.k[w]) return;
+  const unsigned long long pos = a.bits[w] == 32 ? (unsigned long long)static_cast<const uint32_t*>(a.idx[w])[j]
+                                                 : static_cast<const unsigned long long*>(a.idx[w])[j];
   const long long row = (long long)(pos / (unsigned long long)D);
   const long long col = (long long)(pos - (unsigned long long)row * (unsigned long long)D);
   long long lo = 0, hi = Ru;  // first r with urows[r] >= row
@@ -82,21 +83,18 @@ __global__ __launch_bounds__(256) void k_rows_remap(const I* __restrict__ idx, l
     flags[1] = 1u;
     if (lo >= Ru) lo = Ru - 1;
   }
-  out[j] = (uint32_t)(lo * D + col);
+  out[a.at[w] + j] = (uint32_t)(lo * D + col);
 }
 
 }  // namespace
 
-void launch_rows_remap(const void* idx, int index_bits, int64_t k, const long long* urows, int64_t Ru, int64_t D,
-                       uint32_t* out, uint32_t* flags, hipStream_t s) {
-  if (k <= 0) return;
-  const dim3 grid((unsigned)((k + 255) / 256));
-  if (index_bits == 32)
-    hipLaunchKernelGGL(k_rows_remap<uint32_t>, grid, dim3(256), 0, s, (const uint32_t*)idx, (long long)k, urows,
-                       (long long)Ru, (long long)D, out, flags);
-  else
-    hipLaunchKernelGGL(k_rows_remap<unsigned long long>, grid, dim3(256), 0, s, (const unsigned long long*)idx,
-                       (long long)k, urows, (long long)Ru, (long long)D, out, flags);
+void launch_rows_remap(const RowsRemapArgs& a, int W, const long long* urows, int64_t Ru, int64_t D, uint32_t* out,
+                       uint32_t* flags, hipStream_t s) {
+  uint32_t kmax = 0;
+  for (int w = 0; w < W; ++w) kmax = a.k[w] > kmax ? a.k[w] : kmax;
+  if (kmax == 0) return;
+  const dim3 grid((unsigned)((kmax + 255) / 256), (unsigned)W);
+  hipLaunchKernelGGL(k_rows_remap, grid, dim3(256), 0, s, a, urows, (long long)Ru, (long long)D, out, flags);
 }
 
 void launch_rows_gather(const float* table, const long long* rows, int64_t U, int64_t D, int64_t R, float* ec,
