@@ -170,6 +170,11 @@ def test_single_workgroup_finish_paths(gc, ctx, oracle):
         gc.sync_status(ctx)
         assert rc == 0 and np.array_equal(b.indices_numpy(), idx) and np.array_equal(b.q.cpu().numpy(), q), codec
         assert np.array_equal(bits(b.scales.cpu().numpy()), bits(sc)) and np.array_equal(bits(ed.cpu().numpy()), bits(e_ref))
+    # the limits of the route: 12,288 kept entries of 4,194,300 elements are finished by the one
+    # workgroup, one more kept entry or four more elements take the grid-wide kernels
+    for n_, k_ in ((4_194_300, 12_288), (4_194_300, 12_289), (4_194_304, 12_288)):
+        check_compress(gc, ctx, oracle, inputs.normal(n_, 1.0, 70 + k_ % 7), inputs.normal(n_, 0.3, 71), k_, 128,
+                       tag=f"route limit n={n_} k={k_}", expect_fallback=False)
     # one call: short tensors (residual route in LDS and in memory), small sampled ones, a large one
     sizes = [5, 3000, 40_000, 65_536, 65_537, 200_000, 1_500_000, 9_000_000, 17, 70_000]
     st = _multi_case(gc, ctx, oracle, sizes, 0.004, 32, W=2, seed=900, sigma=0.5)
