@@ -55,7 +55,7 @@ struct gc_ctx {
   DevBuf rows_e, rows_idx;  // compact residual and compact positions of a row-sparse step
   DevBuf rows_cidx;         // compact positions of all workers' pairs (aggregate over a row list)
   DevBuf ts, shist, hist, grp_cnt, grp_part, grp_off, tg_base, slots, cand_val, cand_idx, ch_gt,
-      ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, blk_amax, flags;
+      ch_eq, ch_part_gt, ch_part_eq, ch_goff, ch_eoff, tb_g, tb_e, totals, kept_val, flags;
   DevBuf dec_rec, dec_tile_start;  // aggregate: packed pair records, first record of every tile
   uint32_t* host_flags = nullptr;  // pinned
   TensorState* host_ts = nullptr;  // pinned copy for gc_last_stats
@@ -302,7 +302,6 @@ gc_status ensure_workspace(gc_ctx* ctx, const Need& nd) {
   if (st == GC_OK) st = ensure(ctx->tb_e, sizeof(long long) * T);
   if (st == GC_OK) st = ensure(ctx->totals, sizeof(long long) * 4);
   if (st == GC_OK) st = ensure(ctx->kept_val, sizeof(float) * nd.ktotal);
-  if (st == GC_OK) st = ensure(ctx->blk_amax, sizeof(uint32_t) * nd.stotal);
   if (st == GC_OK && ctx->host_ts_cap < T) {
     if (ctx->host_ts) (void)hipHostFree(ctx->host_ts);
     ctx->host_ts = nullptr;
@@ -485,7 +484,6 @@ gc_status compress_impl(gc_ctx* ctx, const void* grad, gc_dtype dtype, float* re
   ws.tb_e = (long long*)ctx->tb_e.p;
   ws.totals = (long long*)ctx->totals.p;
   ws.kept_val = (float*)ctx->kept_val.p;
-  ws.blk_amax = (uint32_t*)ctx->blk_amax.p;
   ws.nblocks = P->stotal;
   ws.flags = (uint32_t*)ctx->flags.p;
   ws.T = T;
@@ -830,7 +828,7 @@ gc_status gc_destroy(gc_ctx* c) {
   DevBuf* all[] = {&c->ts, &c->shist, &c->hist, &c->grp_cnt, &c->grp_part, &c->grp_off, &c->tg_base,
                    &c->slots, &c->cand_val, &c->cand_idx, &c->ch_gt, &c->ch_eq,
                    &c->ch_part_gt, &c->ch_part_eq, &c->ch_goff, &c->ch_eoff, &c->tb_g, &c->tb_e,
-                   &c->totals, &c->kept_val, &c->blk_amax, &c->flags, &c->dec_rec, &c->dec_tile_start, &c->rows_e, &c->rows_idx, &c->rows_cidx};
+                   &c->totals, &c->kept_val, &c->flags, &c->dec_rec, &c->dec_tile_start, &c->rows_e, &c->rows_idx, &c->rows_cidx};
   for (DevBuf* b : all) release(*b);
   if (c->host_flags) (void)hipHostFree(c->host_flags);
   if (c->host_ts) (void)hipHostFree(c->host_ts);

@@ -472,6 +472,121 @@ __global__ __launch_bounds__(256) void k_chunk_sums(Workspace ws) {
   }
 }
 
+// ---------------------------------------------------------------- a threshold inside a huge tie
+// A sampled tensor whose candidate list overflows usually does so because the k-th magnitude sits in
+// a long run of EQUAL keys (fewer non-zeros than k: the run of zeros; all-equal data; values on a
+// coarse grid). Then one counting pass settles the select: if K is that key, c_gt = #(key > K) < k
+// and c_gt + #(key == K) >= k, then K is the k-th largest key and k - c_gt of its entries are kept,
+// and the three histogram passes over the whole residual are not needed. K is only GUESSED here,
+// from the first candidate record of 64 groups spread over the tensor (the smallest key among
+// them, if nearly all of them agree); the counts that verify it are exact, and when they do not
+// the digit passes run as usual. Single-tensor calls only.
+__device__ uint32_t tie_hint_of(const Workspace& ws, const TensorDesc& d) {
+  const long long stride = d.ngroups / 64 > 0 ? d.ngroups / 64 : 1;
+  uint32_t kmin = kNoTieHint;
+  int valid = 0, equal = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int i = 0; i < 64; ++i) {
+      const long long g = d.group_begin + min((long long)i * stride, (long long)d.ngroups - 1);
+      if (ws.grp_cnt[g] == 0u) continue;
+      const uint32_t key = ws.slots[g * (int64_t)ws.slot_stride].x & 0x7FFFFFFFu;
+      if (pass == 0) {
+        kmin = min(kmin, key);
+        ++valid;
+      } else if (key == kmin) {
+        ++equal;
+      }
+    }
+  }
+  return (valid >= 8 && equal * 8 >= valid * 7) ? kmin : kNoTieHint;
+}
+
+// The counting pass, run in the launch of k_gather (which has nothing to gather for such a tensor):
+// a workgroup takes the groups the gather would have given it; per group of 1024 elements - the same
+// pieces the dense route's count and emit passes use - the entries above and equal to the hinted
+// key, written where k_count would write them, and the workgroup's totals as one pair of partial
+// sums (in the group offsets' array, unused on this route; no atomics).
+__device__ void tie_spec_count(const Workspace& ws, const float* __restrict__ e, uint32_t hint, int groups_per_wg) {
+  __shared__ unsigned long long sh_g[4], sh_e[4];
+  const TensorDesc d = ws.desc(0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long long g0 = (long long)blockIdx.x * groups_per_wg;
+  const long long g1 = min((long long)d.ngroups, g0 + groups_per_wg);
+  unsigned long long tot_g = 0ull, tot_e = 0ull;
+  for (long long lg = g0 + wave; lg < g1; lg += 4) {
+    const long long first = max(0ll, lg * (long long)kGroup - d.group_shift);
+    const int len = (int)(min((long long)d.n, (lg + 1) * (long long)kGroup - d.group_shift) - first);
+    const float* src = e + d.off + first;
+    uint32_t gt = 0u, eq = 0u;
+    if (len == kChunk && (reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+      f32x4 x[kChunk / 256];
+#pragma unroll
+      for (int u = 0; u < kChunk / 256; ++u) x[u] = *reinterpret_cast<const f32x4*>(src + u * 256 + lane * 4);
+#pragma unroll
+      for (int u = 0; u < kChunk / 256; ++u) {
+        const uint32_t key[4] = {key_of(x[u].x), key_of(x[u].y), key_of(x[u].z), key_of(x[u].w)};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          gt += key[c] > hint ? 1u : 0u;
+          eq += key[c] == hint ? 1u : 0u;
+        }
+      }
+    } else {
+      for (int j = lane; j < len; j += 64) {
+        const uint32_t key = key_of(src[j]);
+        gt += key > hint ? 1u : 0u;
+        eq += key == hint ? 1u : 0u;
+      }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      gt += __shfl_xor(gt, off);
+      eq += __shfl_xor(eq, off);
+    }
+    if (lane == 0) {
+      ws.ch_gt[lg] = gt;  // the sub-chunk numbering of a single tensor is its group numbering
+      ws.ch_eq[lg] = eq;
+    }
+    tot_g += gt;
+    tot_e += eq;
+  }
+  if (g1 == d.ngroups && threadIdx.x < 4) {  // the last chunk's pieces past the tensor's end hold nothing
+    const long long lg = d.ngroups + threadIdx.x;
+    if (lg < ((d.ngroups + 3) & ~3ll)) {
+      ws.ch_gt[lg] = 0u;
+      ws.ch_eq[lg] = 0u;
+    }
+  }
+  if (lane == 0) {
+    sh_g[wave] = tot_g;
+    sh_e[wave] = tot_e;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    ws.grp_off[2 * (long long)blockIdx.x] = (long long)(sh_g[0] + sh_g[1] + sh_g[2] + sh_g[3]);
+    ws.grp_off[2 * (long long)blockIdx.x + 1] = (long long)(sh_e[0] + sh_e[1] + sh_e[2] + sh_e[3]);
+  }
+}
+
+// Whether the hinted key is the threshold: the sums of the counting pass's partials (all 256 threads).
+__device__ bool tie_verify(const Workspace& ws, unsigned long long* sh, unsigned long long& c_gt,
+                           unsigned long long& c_eq) {
+  const long long nwg = (ws.ngroups * ws.gather_team + 255) / 256;  // workgroups of the k_gather launch
+  unsigned long long g = 0ull, q = 0ull;
+  for (long long i = threadIdx.x; i < nwg; i += 256) {
+    g += (unsigned long long)ws.grp_off[2 * i];
+    q += (unsigned long long)ws.grp_off[2 * i + 1];
+  }
+  c_gt = block_sum(g, sh);
+  c_eq = block_sum(q, sh);
+  const unsigned long long k = (unsigned long long)ws.desc(0).k;
+  return c_gt < k && c_gt + c_eq >= k;
+}
+
+__device__ __forceinline__ bool tie_hinted(const Workspace& ws) {
+  return ws.T == 1 && ws.ts[0].use_cand == 0u && ws.ts[0].tie_hint != kNoTieHint;
+}
+
 // ---------------------------------------------------------------- k_group_scan
 __global__ __launch_bounds__(256) void k_group_scan(Workspace ws) {
   __shared__ long long lds_out[kScanBlock + 1];
@@ -496,6 +611,8 @@ __global__ __launch_bounds__(256) void k_group_scan(Workspace ws) {
       ws.ts[0].achunk_begin = 0;
       ws.ts[0].cand_total = total;
       ws.ts[0].use_cand = use ? 1u : 0u;
+      ws.ts[0].resolved = 0u;
+      ws.ts[0].tie_hint = (!use && total > d.cand_cap) ? tie_hint_of(ws, d) : kNoTieHint;
       ws.totals[0] = (vlen + (use ? 0 : d.group_shift) + kChunkElems - 1) / kChunkElems;
     }
   }
@@ -539,6 +656,8 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
     if (t < ws.T) {
       ws.ts[t].achunk_begin = x;
       if (!small) {  // k_finish has written these for its tensors
+        ws.ts[t].tie_hint = kNoTieHint;
+        ws.ts[t].resolved = 0u;
         ws.ts[t].vlen = vlen;
         ws.ts[t].cand_total = M;
         ws.ts[t].use_cand = use;
@@ -560,6 +679,10 @@ __global__ __launch_bounds__(256) void k_route(Workspace ws, int any_sampled) {
 // appends. Only the tensor-wide totals can still send a tensor down the dense route.
 template <int TEAM>
 __global__ __launch_bounds__(256) void k_gather(Workspace ws, const float* __restrict__ e) {
+  if (tie_hinted(ws)) {  // nothing to gather: this launch counts around the hinted tie instead
+    tie_spec_count(ws, e, ws.ts[0].tie_hint, 256 / TEAM);
+    return;
+  }
   const int lane = threadIdx.x & 63;
   const int sub = threadIdx.x % TEAM;  // lane inside the team
   const int64_t grp = ((int64_t)blockIdx.x * 256 + threadIdx.x) / TEAM;
@@ -665,6 +788,15 @@ __device__ __forceinline__ SubSrc sub_source(const Workspace& ws, const TensorDe
 // ---------------------------------------------------------------- k_hist
 __global__ __launch_bounds__(256) void k_hist(Workspace ws, int level, const float* __restrict__ e) {
   __shared__ uint32_t lh[kSelBins];
+  if (tie_hinted(ws)) {  // a verified tie at the threshold needs no digit passes
+    if (level == 0) {
+      __shared__ unsigned long long sh_v[4];
+      unsigned long long c_gt, c_eq;
+      if (tie_verify(ws, sh_v, c_gt, c_eq)) return;
+    } else if (ws.ts[0].resolved) {
+      return;
+    }
+  }
   const long long A = ws.totals[0];
   const long long per = (A + gridDim.x - 1) / gridDim.x;  // one contiguous run of chunks per workgroup
   const long long a_end = min(A, ((long long)blockIdx.x + 1) * per);
@@ -721,25 +853,39 @@ __global__ __launch_bounds__(256) void k_select_scan(Workspace ws, int level) {
   const int t = blockIdx.x;
   const TensorDesc d = ws.desc(t);
   if (d.small) return;
-  unsigned long long* h = ws.hist + (int64_t)t * kSelBins;
-  const unsigned long long k_rem = (level == 0) ? (unsigned long long)d.k : ws.ts[t].k_rem;
-  uint32_t bin;
-  unsigned long long above;
-  find_from_top<kSelBins, 256>(h, k_rem, bin, above);
-  for (int b = threadIdx.x; b < kSelBins; b += 256) h[b] = 0ull;  // ready for the next digit
-  if (threadIdx.x == 0) {
-    ws.ts[t].k_rem = k_rem - above;
-    const uint32_t p = (level == 0) ? 0u : ws.ts[t].prefix;
-    ws.ts[t].prefix = p | (bin << sel_shift(level));
+  bool resolved = false;
+  if (tie_hinted(ws)) {
+    if (level == 0) {
+      __shared__ unsigned long long sh_v[4];
+      unsigned long long c_gt, c_eq;
+      resolved = tie_verify(ws, sh_v, c_gt, c_eq);
+      if (resolved && threadIdx.x == 0) {  // the hinted key IS the k-th largest: threshold and tie quota
+        ws.ts[0].prefix = ws.ts[0].tie_hint;
+        ws.ts[0].k_rem = (unsigned long long)d.k - c_gt;
+        ws.ts[0].resolved = 1u;
+      }
+    } else {
+      resolved = ws.ts[0].resolved != 0u;
+    }
   }
-  if (level == kSelLevels - 1) {  // the block maxima that the emit pass collects start from zero
-    const long long nb = (d.k + ws.block - 1) / ws.block;
-    for (long long b = threadIdx.x; b < nb; b += 256) ws.blk_amax[d.sprefix + b] = 0u;
+  if (!resolved) {
+    unsigned long long* h = ws.hist + (int64_t)t * kSelBins;
+    const unsigned long long k_rem = (level == 0) ? (unsigned long long)d.k : ws.ts[t].k_rem;
+    uint32_t bin;
+    unsigned long long above;
+    find_from_top<kSelBins, 256>(h, k_rem, bin, above);
+    for (int b = threadIdx.x; b < kSelBins; b += 256) h[b] = 0ull;  // ready for the next digit
+    if (threadIdx.x == 0) {
+      ws.ts[t].k_rem = k_rem - above;
+      const uint32_t p = (level == 0) ? 0u : ws.ts[t].prefix;
+      ws.ts[t].prefix = p | (bin << sel_shift(level));
+    }
   }
 }
 
 // ---------------------------------------------------------------- k_count
 __global__ __launch_bounds__(256) void k_count(Workspace ws, const float* __restrict__ e) {
+  if (tie_hinted(ws) && ws.ts[0].resolved) return;  // the counting pass around the tie has left these counts
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const long long A = ws.totals[0];
   int cur = 0;
@@ -821,133 +967,220 @@ __global__ __launch_bounds__(256) void k_chunk_scan(Workspace ws) {
 }
 
 // ---------------------------------------------------------------- k_emit
+// Ordered compaction: kept entry number r of a tensor (entries above the threshold, plus the first
+// ties in index order up to the quota) goes to position r of the tensor's output, with its value.
+//
+// Every wavefront works on its own. Piece p (1024 entries) belongs to wavefront p mod (number of
+// wavefronts); a wavefront looks at 64 of its pieces at once, one per lane, finds which of them
+// keep anything at all, and walks only those. A piece keeps nothing when it has no entry above
+// the threshold and its ties are past the quota (or it has none): on the dense route that is
+// nearly every piece, since at most k entries are kept. Neighbouring pieces go to different
+// wavefronts, so a stretch of pieces that all keep something (the front of a huge tie) is spread.
+// The walk is a chain of memory round trips per piece, so the lanes fetch their pieces' offsets
+// during the look, and the entries of the next piece are requested before the current one is used.
+struct EmitPiece {
+  SubSrc s;
+  long long G, E;      // kept entries above the threshold / ties before this piece, inside the tensor
+  long long out0;      // the tensor's first output position
+  long long off;       // the tensor's first element in the flat buffer
+  long long quota;
+  uint32_t thr;
+};
+
+__device__ __forceinline__ long long readlane64(long long v, int l) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((unsigned long long)v >> 32), l);
+  return (long long)(((unsigned long long)hi << 32) | lo);
+}
+
 template <typename I>
-__global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restrict__ e,
-                                              I* __restrict__ out_idx, int32_t block) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const long long A = ws.totals[0];
-  int cur = 0;
-  for (long long a = blockIdx.x; a < A; a += gridDim.x) {
-    const int t = find_last_le(ws.T, a, cur, [&](int i) { return ws.ts[i].achunk_begin; });
-    cur = t;
-    const TensorDesc d = ws.desc(t);
-    const TensorState st = ws.ts[t];
-    const SubSrc s = sub_source(ws, d, st, a - st.achunk_begin, wave, e);
-    if (s.len == 0) continue;
-    const uint32_t thr = st.prefix;
-    const long long quota = (long long)st.k_rem;
-    const long long ent = a * 4 + wave;
-    long long G = ws.ch_goff[ent] - ws.tb_g[t], E = ws.ch_eoff[ent] - ws.tb_e[t];
-    // nothing to emit here: no entry above the threshold, and the tie quota is used up (or there is
-    // no tie). On the dense route this skips nearly everything: at most k entries are kept.
-    if (ws.ch_gt[ent] == 0u && (ws.ch_eq[ent] == 0u || E >= quota)) continue;
-    uint32_t run_blk = 0u, run_max = 0u;  // block whose maximum is being carried (0: none), wave-uniform
-    // the whole sub-chunk is requested before the first entry is used
-    constexpr int kIter = kChunk / 64;
-    float vals[kIter];
-    long long idxs[kIter];
-#pragma unroll
-    for (int u = 0; u < kIter; ++u) {
-      const int j = u * 64 + lane;
-      vals[u] = j < s.len ? s.val[j] : 0.0f;
-      idxs[u] = (s.idx && j < s.len) ? s.idx[j] : (s.first + j);
-    }
-#pragma unroll
-    for (int u = 0; u < kIter; ++u) {
-      const int j0 = u * 64;
-      if (j0 >= s.len) continue;  // uniform over the wavefront
-      const int j = j0 + lane;
-      const bool valid = j < s.len;
-      const float v = vals[u];
-      const uint32_t key = key_of(v);
-      const bool isgt = valid && key > thr, iseq = valid && key == thr;
-      const uint64_t mg = __ballot(isgt), me = __ballot(iseq);
-      const long long grank = G + mbcnt64(mg), erank = E + mbcnt64(me);
-      const bool keep = isgt || (iseq && erank < quota);
-      uint32_t blk = 0u, bkey = 0u;  // quantization block of this lane's kept entry, and its key
-      if (keep) {
-        const long long rel = grank + (erank < quota ? erank : quota);  // position inside the tensor
-        const long long pos = d.kprefix + rel;
-        out_idx[pos] = (I)(d.off + idxs[u]);
-        ws.kept_val[pos] = v;
-        // rel < k < 2^32, so the block number comes from one 32-bit division
-        blk = (uint32_t)d.sprefix + (uint32_t)rel / (uint32_t)block + 1u;  // +1 so that 0 means "no entry"
-        bkey = key;
-      }
-      // Per-block amax for the quantizer: one atomic per block and wavefront iteration. Kept
-      // positions ascend with the lane, so the lanes of one block form a contiguous run. Nearly
-      // always the whole iteration falls into one block: a plain wavefront maximum then does.
-      // Otherwise a segmented max-scan leaves each run's maximum in its last lane.
-      const uint64_t mk = __ballot(keep);
-      if (mk) {
-        const uint32_t blk_first = __shfl(blk, __ffsll((unsigned long long)mk) - 1);
-        if (__ballot(keep && blk != blk_first) == 0ull) {
-          uint32_t m = bkey;
-#pragma unroll
-          for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
-          // the maximum is carried over the iterations of the sub-chunk while the block stays
-          if (blk_first != run_blk) {
-            if (lane == 0 && run_blk != 0u && run_max != 0u) atomicMax(&ws.blk_amax[run_blk - 1u], run_max);
-            run_blk = blk_first;
-            run_max = 0u;
-          }
-          run_max = max(run_max, m);
-        } else {
-          if (lane == 0 && run_blk != 0u && run_max != 0u) atomicMax(&ws.blk_amax[run_blk - 1u], run_max);
-          run_blk = 0u;
-          run_max = 0u;
-#pragma unroll
-          for (int off = 1; off < 64; off <<= 1) {  // lanes without an entry inherit the block to their left
-            const uint32_t ob = __shfl_up(blk, off);
-            if (lane >= off && blk == 0u) blk = ob;
-          }
-#pragma unroll
-          for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t ok = __shfl_up(bkey, off), ob = __shfl_up(blk, off);
-            if (lane >= off && ob == blk) bkey = max(bkey, ok);
-          }
-          const uint32_t nb = __shfl_down(blk, 1);
-          if (blk != 0u && (lane == 63 || nb != blk) && bkey != 0u) atomicMax(&ws.blk_amax[blk - 1u], bkey);
+__global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restrict__ e, I* __restrict__ out_idx) {
+  constexpr int kIter = kChunk / 64;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const long long N4 = ws.totals[0] * 4;
+  const long long gw = (long long)blockIdx.x * 4 + wave, nwv = (long long)gridDim.x * 4;
+  for (long long base = gw; base < N4; base += nwv * 64) {
+    bool need = false;
+    long long my_g = 0, my_e = 0;
+    int my_t = 0;
+    {
+      const long long ent_l = base + lane * nwv;
+      if (ent_l < N4) {
+        const uint32_t gt = ws.ch_gt[ent_l], eq = ws.ch_eq[ent_l];
+        if ((gt | eq) != 0u) {
+          my_t = find_last_le(ws.T, ent_l >> 2, 0, [&](int i) { return ws.ts[i].achunk_begin; });
+          my_e = ws.ch_eoff[ent_l] - ws.tb_e[my_t];
+          need = gt != 0u || my_e < (long long)ws.ts[my_t].k_rem;
+          if (need) my_g = ws.ch_goff[ent_l] - ws.tb_g[my_t];
         }
       }
-      G += __popcll(mg);
-      E += __popcll(me);
     }
-    if (lane == 0 && run_blk != 0u && run_max != 0u) atomicMax(&ws.blk_amax[run_blk - 1u], run_max);
+    uint64_t todo = __ballot(need);
+    if (todo == 0ull) continue;
+    // the piece of lane `bit`: where its entries are, and the request for them
+    auto open = [&](int bit, EmitPiece& p, float (&vals)[kIter]) {
+      const long long ent = base + bit * nwv, a = ent >> 2;
+      const int t = __builtin_amdgcn_readlane(my_t, bit);
+      const TensorDesc d = ws.desc(t);
+      const TensorState st = ws.ts[t];
+      p.s = sub_source(ws, d, st, a - st.achunk_begin, (int)(ent & 3), e);
+      p.G = readlane64(my_g, bit);
+      p.E = readlane64(my_e, bit);
+      p.out0 = d.kprefix;
+      p.off = d.off;
+      p.quota = (long long)st.k_rem;
+      p.thr = st.prefix;
+#pragma unroll
+      for (int u = 0; u < kIter; ++u) {
+        const int j = u * 64 + lane;
+        vals[u] = j < p.s.len ? p.s.val[j] : 0.0f;
+      }
+    };
+    EmitPiece cur, nxt;
+    float vals[kIter], nvals[kIter];
+    open(__builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)todo) - 1), cur, vals);
+    todo &= todo - 1;
+    while (true) {
+      const bool more = todo != 0ull;
+      if (more) {
+        open(__builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)todo) - 1), nxt, nvals);
+        todo &= todo - 1;
+      }
+      long long idxs[kIter];
+#pragma unroll
+      for (int u = 0; u < kIter; ++u) {
+        const int j = u * 64 + lane;
+        idxs[u] = (cur.s.idx && j < cur.s.len) ? cur.s.idx[j] : (cur.s.first + j);
+      }
+      long long G = cur.G, E = cur.E;
+#pragma unroll
+      for (int u = 0; u < kIter; ++u) {
+        const int j0 = u * 64;
+        if (j0 >= cur.s.len) continue;  // uniform over the wavefront
+        const bool valid = j0 + lane < cur.s.len;
+        const float v = vals[u];
+        const uint32_t key = key_of(v);
+        const bool isgt = valid && key > cur.thr, iseq = valid && key == cur.thr;
+        const uint64_t mg = __ballot(isgt), me = __ballot(iseq);
+        if ((mg | me) == 0ull) continue;  // nothing at or above the threshold in these 64 entries
+        const long long grank = G + mbcnt64(mg), erank = E + mbcnt64(me);
+        if (isgt || (iseq && erank < cur.quota)) {
+          const long long pos = cur.out0 + grank + (erank < cur.quota ? erank : cur.quota);
+          out_idx[pos] = (I)(cur.off + idxs[u]);
+          ws.kept_val[pos] = v;
+        }
+        G += __popcll(mg);
+        E += __popcll(me);
+      }
+      if (!more) break;
+      cur = nxt;
+#pragma unroll
+      for (int u = 0; u < kIter; ++u) vals[u] = nvals[u];
+    }
   }
 }
 
 // ---------------------------------------------------------------- k_quant
-// One thread per kept entry: scale of its block from the block's amax key (left by k_emit),
-// int8 code, and the residual at the kept position, e' = acc - fl32(q * s) (Eq. 11).
+// Per-block int8 code of the kept values (Eq. 9) and the residual at the kept positions,
+// e' = acc - fl32(q * s) (Eq. 11). The kept entries of all tensors form one array of sum(k)
+// positions, cut into blocks tensor by tensor. A workgroup codes its own kQuantSpan positions; the
+// largest magnitude of every block that reaches into them it finds itself, by reading those blocks
+// whole (wavefront maximum, then one LDS atomic; a maximum does not depend on the order).
+// Neighbouring workgroups read the same block again, out of the cache, which is little beside the
+// scattered residual stores. No block maximum ever goes through memory.
+// Blocks longer than kQuantSharedBlock would make that re-reading the main cost: then a workgroup
+// owns the blocks that START inside its positions instead and codes all of their entries.
+constexpr int kQuantSharedBlock = 4096;
+constexpr int kQuantSpan = 1024;  // kept positions per workgroup
+
+// Start of the block that holds kept position x < ktotal, and of the first block at or after x.
+__device__ __forceinline__ long long this_block_start(const Workspace& ws, long long x, int32_t block) {
+  const int t = find_last_le(ws.T, x, 0, [&](int i) { return (long long)ws.desc(i).kprefix; });
+  const long long kp = ws.desc(t).kprefix;
+  return kp + (long long)((uint32_t)(x - kp) / (uint32_t)block) * block;  // x - kp < k < 2^32
+}
+__device__ __forceinline__ long long next_block_start(const Workspace& ws, long long x, int32_t block, long long ktotal) {
+  if (x >= ktotal) return ktotal;
+  const int t = find_last_le(ws.T, x, 0, [&](int i) { return (long long)ws.desc(i).kprefix; });
+  const long long kp = ws.desc(t).kprefix, rel = x - kp;
+  const uint32_t rb = (uint32_t)rel / (uint32_t)block;
+  if ((long long)rb * block == rel) return x;
+  return kp + min((long long)ws.desc(t).k, ((long long)rb + 1) * block);
+}
+
 template <typename I>
 __global__ __launch_bounds__(256) void k_quant(Workspace ws, float* __restrict__ e,
                                                const I* __restrict__ idx, int8_t* __restrict__ q,
                                                float* __restrict__ scales, int32_t block, long long ktotal) {
-  const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (j >= ktotal) return;
-  const int t = find_last_le(ws.T, j, 0, [&](int i) { return (long long)ws.desc(i).kprefix; });
-  if (ws.desc(t).small) return;  // coded by k_finish
-  const uint32_t rel = (uint32_t)(j - ws.desc(t).kprefix);  // < k < 2^32: 32-bit division
-  const uint32_t rblk = rel / (uint32_t)block;
-  const long long blk = ws.desc(t).sprefix + rblk;
-  const uint32_t akey = ws.blk_amax[blk];
-  const bool finite = akey < 0x7F800000u;
-  float s = __fdiv_rn(__uint_as_float(akey), 127.0f);
-  if (!finite || !(s >= 1.17549435e-38f)) s = 0.0f;
-  if (rel == rblk * (uint32_t)block) {
-    scales[blk] = s;
-    if (!finite) ws.flags[0] = 1u;
+  // blocks that reach into the span: one may start at each position, one more may have started before
+  __shared__ uint32_t amax[kQuantSpan + 1];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const long long lo = (long long)blockIdx.x * kQuantSpan, hi = min(ktotal, lo + kQuantSpan);
+  long long m_lo, m_hi, c_lo, c_hi;  // positions read for the maxima, positions coded
+  if (block <= kQuantSharedBlock) {
+    m_lo = this_block_start(ws, lo, block);
+    m_hi = next_block_start(ws, hi, block, ktotal);
+    c_lo = lo;
+    c_hi = hi;
+  } else {
+    m_lo = c_lo = next_block_start(ws, lo, block, ktotal);
+    m_hi = c_hi = next_block_start(ws, lo + kQuantSpan, block, ktotal);
+    if (c_lo >= c_hi) return;  // no block starts here
   }
-  const float v = ws.kept_val[j];
-  int code = 0;
-  if (s != 0.0f) {
-    float r = rintf(__fdiv_rn(v, s));
-    r = fminf(fmaxf(r, -127.0f), 127.0f);
-    code = (int)r;
+  const int t_s = find_last_le(ws.T, m_lo, 0, [&](int i) { return (long long)ws.desc(i).kprefix; });
+  const long long blk_s = ws.desc(t_s).sprefix + (uint32_t)(m_lo - ws.desc(t_s).kprefix) / (uint32_t)block;
+  for (int b = tid; b < kQuantSpan + 1; b += 256) amax[b] = 0u;
+  __syncthreads();
+  for (long long j0 = m_lo; j0 < m_hi; j0 += 256) {  // uniform trip count
+    const long long j = j0 + tid;
+    bool on = j < m_hi;
+    uint32_t key = 0u, bl = 0u;
+    if (on) {
+      const int t = find_last_le(ws.T, j, t_s, [&](int i) { return (long long)ws.desc(i).kprefix; });
+      on = !ws.desc(t).small;  // coded by k_finish
+      bl = (uint32_t)(ws.desc(t).sprefix - blk_s) + (uint32_t)(j - ws.desc(t).kprefix) / (uint32_t)block;
+      if (on) key = key_of(ws.kept_val[j]);
+    }
+    // nearly always the wavefront's 64 consecutive entries lie in one block: one atomic then
+    const uint64_t act = __ballot(on);
+    if (act == 0ull) continue;
+    const uint32_t bl0 = (uint32_t)__builtin_amdgcn_readlane((int)bl, __ffsll((unsigned long long)act) - 1);
+    if (__ballot(on && bl != bl0) == 0ull) {
+      uint32_t m = key;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+      if (lane == 0) atomicMax(&amax[bl0], m);
+    } else if (on) {
+      atomicMax(&amax[bl], key);
+    }
   }
-  q[j] = (int8_t)code;
-  if (finite) e[(int64_t)idx[j]] = __fsub_rn(v, __fmul_rn((float)code, s));
+  __syncthreads();
+  for (long long j0 = c_lo; j0 < c_hi; j0 += 256) {
+    const long long j = j0 + tid;
+    if (j >= c_hi) continue;
+    const int t = find_last_le(ws.T, j, t_s, [&](int i) { return (long long)ws.desc(i).kprefix; });
+    if (ws.desc(t).small) continue;
+    const uint32_t rel = (uint32_t)(j - ws.desc(t).kprefix);  // < k < 2^32: 32-bit division
+    const uint32_t rblk = rel / (uint32_t)block;
+    const long long blk = ws.desc(t).sprefix + rblk;
+    const uint32_t akey = amax[blk - blk_s];
+    const bool finite = akey < 0x7F800000u;
+    float s = __fdiv_rn(__uint_as_float(akey), 127.0f);
+    if (!finite || !(s >= 1.17549435e-38f)) s = 0.0f;
+    if (rel == rblk * (uint32_t)block) {
+      scales[blk] = s;
+      if (!finite) ws.flags[0] = 1u;
+    }
+    const float v = ws.kept_val[j];
+    int code = 0;
+    if (s != 0.0f) {
+      float r = rintf(__fdiv_rn(v, s));
+      r = fminf(fmaxf(r, -127.0f), 127.0f);
+      code = (int)r;
+    }
+    q[j] = (int8_t)code;
+    if (finite) e[(int64_t)idx[j]] = __fsub_rn(v, __fmul_rn((float)code, s));
+  }
 }
 
 // ---------------------------------------------------------------- k_quant_sign
@@ -990,8 +1223,8 @@ __global__ __launch_bounds__(256) void k_quant_sign(Workspace ws, float* __restr
     if ((int)threadIdx.x < stride) sh[threadIdx.x] = sh[threadIdx.x] + sh[threadIdx.x + stride];
     __syncthreads();
   }
-  const uint32_t akey = ws.blk_amax[gb];
-  const bool finite = akey < 0x7F800000u;
+  // an entry that is not finite makes the fp64 sum infinite or NaN; finite entries cannot (2^13 * 2^128)
+  const bool finite = sh[0] < (double)INFINITY;
   float s = (float)(sh[0] / (double)len);
   if (!finite || !(s >= 1.17549435e-38f)) s = 0.0f;
   if (threadIdx.x == 0) {
@@ -1025,7 +1258,7 @@ __global__ __launch_bounds__(256) void k_quant_sign(Workspace ws, float* __restr
 //   3. exact radix select (three digits, LDS histogram) of the k-th largest key and the tie quota
 //   4. ordered emit: kept entries compacted in place (LDS), or written to the output (memory)
 //   5. per block of kept entries: amax (LDS), scale, int8 codes, residual at the kept positions
-//      (with the sign code, step 5 only leaves the block maxima and kept values; k_quant_sign follows)
+//      (with the sign code there is no step 5: the kept values go out and k_quant_sign follows)
 constexpr int kFinishLds = 16384;     // entries of the LDS-resident source (128 KB)
 constexpr int kFinishMaxGroups = 4096;
 constexpr int kFinishAmaxWindow = 4096;
@@ -1298,6 +1531,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(Workspace ws, float* 
   }
 
   // ---- 5. blocks of kept entries: amax, scale, code, residual (windows of kFinishAmaxWindow blocks)
+  if (codec != 0) return;  // uniform over the workgroup
   const long long nblk = (d.k + block - 1) / block;
   for (long long b0 = 0; b0 < nblk; b0 += kFinishAmaxWindow) {
     const long long b1 = min(nblk, b0 + (long long)kFinishAmaxWindow);
@@ -1327,16 +1561,13 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(Workspace ws, float* 
     __syncthreads();
     for (int b = tid; b < (int)(b1 - b0); b += NT) {
       const uint32_t akey = amax[b];
-      ws.blk_amax[d.sprefix + b0 + b] = akey;
-      if (codec == 0) {
-        const bool finite = akey < 0x7F800000u;
-        float sc = __fdiv_rn(__uint_as_float(akey), 127.0f);
-        if (!finite || !(sc >= 1.17549435e-38f)) sc = 0.0f;
-        scales[d.sprefix + b0 + b] = sc;
-        if (!finite) ws.flags[0] = 1u;
-      }
+      const bool finite = akey < 0x7F800000u;
+      float sc = __fdiv_rn(__uint_as_float(akey), 127.0f);
+      if (!finite || !(sc >= 1.17549435e-38f)) sc = 0.0f;
+      scales[d.sprefix + b0 + b] = sc;
+      if (!finite) ws.flags[0] = 1u;
     }
-    if (codec == 0) {
+    {
       for (long long j0 = j_begin; j0 < j_end; j0 += NT) {
         const long long j = j0 + tid;
         if (j >= j_end) continue;
@@ -1435,10 +1666,10 @@ void launch_chunk_scan(const Workspace& ws, hipStream_t s) {
 void launch_emit(const Workspace& ws, const float* e, const OutBuf& out, hipStream_t s) {
   const dim3 grid(clamp_grid(ws.max_chunk_wgs, 2048));
   if (out.index_bits == 32)
-    hipLaunchKernelGGL(k_emit<uint32_t>, grid, dim3(256), 0, s, ws, e, (uint32_t*)out.indices, out.block);
+    hipLaunchKernelGGL(k_emit<uint32_t>, grid, dim3(256), 0, s, ws, e, (uint32_t*)out.indices);
   else
     hipLaunchKernelGGL(k_emit<unsigned long long>, grid, dim3(256), 0, s, ws, e,
-                       (unsigned long long*)out.indices, out.block);
+                       (unsigned long long*)out.indices);
 }
 
 void launch_finish(const Workspace& ws, float* e, const OutBuf& out, hipStream_t s) {
@@ -1462,7 +1693,7 @@ void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktot
                          (const unsigned long long*)out.indices, (uint8_t*)out.q, out.scales, out.block);
     return;
   }
-  const dim3 grid((unsigned)((ktotal + 255) / 256));
+  const dim3 grid((unsigned)((ktotal + kQuantSpan - 1) / kQuantSpan));
   if (out.index_bits == 32)
     hipLaunchKernelGGL(k_quant<uint32_t>, grid, dim3(256), 0, s, ws, e, (const uint32_t*)out.indices, out.q,
                        out.scales, out.block, (long long)ktotal);

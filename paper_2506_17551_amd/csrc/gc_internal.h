@@ -90,10 +90,13 @@ struct TensorState {
   long long achunk_begin;    // first active chunk of this tensor in the call-wide chunk numbering
   long long cand_total;      // candidates gathered by the streaming pass
   uint32_t t_lo;             // candidate threshold key (sampled tensors)
-  uint32_t spare_;
+  uint32_t tie_hint;         // key that may be the threshold with a huge tie (kNoTieHint: none); see tie_spec_count
   uint32_t prefix;           // resolved high bits of the threshold key; after the last level: T
   uint32_t use_cand;         // 1: select from the gathered candidates, 0: from the dense residual
+  uint32_t resolved;         // 1: the hinted key was verified as the threshold, the digit passes are skipped
+  uint32_t pad_;
 };
+constexpr uint32_t kNoTieHint = 0xFFFFFFFFu;
 
 // One record per group of the streaming pass (only built when a call has several tensors).
 struct GroupRec {
@@ -131,7 +134,6 @@ struct Workspace {  // device pointers into the context's scratch
   long long* tb_e;
   long long* totals;                // [0] active chunks of the call
   float* kept_val;                  // [sum k] accumulated values of the kept entries, ascending
-  uint32_t* blk_amax;               // [sum ceil(k/block)] largest key of each quantization block
   uint32_t* flags;                  // [0] non-finite seen
   int32_t T;
   int32_t block;                    // kept entries per quantization block

@@ -95,6 +95,24 @@ def test_block_sizes(gc, ctx, oracle, block):
     assert np.array_equal(bits(out.cpu().numpy()), bits(want))
 
 
+@pytest.mark.parametrize("block", [4096, 4097, 10000, 70000])
+def test_blocks_longer_than_a_workgroup_rereads(gc, ctx, oracle, block):
+    """Above 4096 entries per block the quantizer changes its work split (a workgroup codes the blocks that
+    start inside its positions): several such blocks, a short last one, and the limit itself."""
+    n, k = 900_000, 150_001
+    g = inputs.normal(n, 1.0, 3 * block)
+    e = inputs.normal(n, 0.1, 3 * block + 1)
+    check_compress(gc, ctx, oracle, g, e, k, block, tag="long block")
+
+
+@pytest.mark.parametrize("block", [100, 4096, 5000])
+def test_blocks_across_tensor_boundaries_and_routes(gc, ctx, oracle, block):
+    """Blocks restart at every tensor; small tensors (coded by the one-workgroup route) sit between
+    tensors coded by the general route, so a workgroup's 256 kept positions span both kinds."""
+    sizes = [3_000_000, 40, 700, 2_500_000, 1, 65_000, 5_000_000, 300, 300, 1_200_000]
+    _multi_case(gc, ctx, oracle, sizes, 0.004, block, W=2, seed=4100 + block)
+
+
 @pytest.mark.parametrize("density", [1.0, 0.5, 0.126, 0.124, 0.05, 0.02, 0.01, 0.003, 1e-4, 1e-6])
 def test_densities(gc, ctx, oracle, density):
     n = 1_500_000
@@ -140,6 +158,40 @@ def test_tie_heavy_inputs_on_the_dense_route(gc, ctx, oracle):
     g[::3] = 0.0
     g[1_500_000] = 1e-30
     check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 1000, tag="signed zeros and one value", expect_fallback=True)
+
+
+def test_threshold_inside_a_huge_tie_on_large_tensors(gc, ctx, oracle):
+    """Tensors too large for the one-workgroup route whose candidate list overflows: the select is
+    settled by one counting pass around a guessed tie key when the guess verifies (all-equal data,
+    fewer non-zeros than k, a coarse grid), and by the three digit passes when it does not (the k-th
+    magnitude lies just above a long run of equal values). Same bits as the oracle either way."""
+    n, k = 6_000_013, 6001
+    g = torch.full((n,), 0.25)
+    buf, _, _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 256, tag="large all-equal", expect_fallback=True)
+    assert np.array_equal(buf.indices_numpy(), np.arange(k, dtype=np.uint32))
+    g = inputs.normal(n, 1e-3, 81)
+    g[torch.rand(n, generator=torch.Generator().manual_seed(82)) < 0.9995] = 0.0   # ~3000 non-zeros < k
+    check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 256, tag="large, fewer non-zeros than k", expect_fallback=True)
+    g = (inputs.normal(n, 1e-3, 83) * 1e3).round() * 1e-3
+    check_compress(gc, ctx, oracle, g, inputs.tie_alphabet(n, (0.0, -0.0), 84), k, 1000, tag="large coarse grid",
+                   expect_fallback=True)
+    # the guess fails: 5.4 M entries equal 1.0, but 7000 entries lie just above it (same candidate bin)
+    g = inputs.normal(n, 0.1, 85).clamp_(-0.9, 0.9)
+    perm = torch.randperm(n, generator=torch.Generator().manual_seed(86))
+    g[perm[:5_400_000]] = 1.0
+    g[perm[5_400_000:5_407_000]] = 1.0 + torch.rand(7000, generator=torch.Generator().manual_seed(87)) * 1e-4
+    buf, (idx, _, _), _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 256, tag="large tie below the threshold",
+                                         expect_fallback=True)
+    assert float(g[torch.from_numpy(idx.astype(np.int64))].min()) > 1.0      # no entry of the run was kept
+    # bf16 gradient, 64-bit indices, the sign code
+    g = torch.full((n,), -0.5).to(torch.bfloat16)
+    e_ref = np.zeros(n, np.float32)
+    rc, idx, q, sc = oracle.compress(inputs.bf16_bits(g), e_ref, k, 64, index_bits=64, codec=1)
+    ed = torch.zeros(n, device=DEV)
+    b = gc.compress(ctx, g.to(DEV), ed, k, 64, index_bits=64, codec=1)
+    gc.sync_status(ctx)
+    assert rc == 0 and np.array_equal(b.indices_numpy(), idx) and np.array_equal(b.q.cpu().numpy(), q)
+    assert np.array_equal(bits(b.scales.cpu().numpy()), bits(sc)) and np.array_equal(bits(ed.cpu().numpy()), bits(e_ref))
 
 
 def test_single_workgroup_finish_paths(gc, ctx, oracle):
