@@ -19,6 +19,8 @@
 //        kept entries: key > T, or key == T among the first `quota` such entries.
 //   6. k_quant   per block of kept entries: amax, scale, int8 codes, and the residual at the
 //        kept positions, acc - q*s (Eq. 11 with ghat = q*s).
+//   On the dense route of a single tensor, a counting pass around a guessed tie key (tie_spec_count,
+//   inside k_gather's launch) replaces steps 4 and k_count when the guess verifies exactly.
 //   Small or dense tensors skip 1 and 3: steps 4-5 then read the residual itself (it holds
 //   acc after step 2). A sampled tensor whose candidates turn out too few or too many takes
 //   that same dense route, decided on the device; candidates clustered beyond a group's slots
