@@ -150,7 +150,8 @@ gc_status gc_decompress_sum(gc_ctx* ctx, const gc_buf* bufs, int32_t W, float* o
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): gc_decompress_sum for single-tensor buffers, with the
  * same result bit for bit, that allocates nothing - no hipMalloc, no hipFree, no workspace growth,
- * no events. Its work arrays (the merged record stream, tile starts) live in one static device array
+ * no events. It always runs the two-kernel route of the aggregate, whatever gc_decompress_sum would
+ * choose; that route's work arrays (the merged record stream, tile starts) live in one static device array
  * of GC_STATIC_SCRATCH_BYTES that every device the library runs on holds until the process ends. A
  * call whose arrays would not fit returns GC_ERR_UNSUPPORTED and writes nothing:
  *   8 * (ceil(n / 4096) + 1) + 8 * (sum of the buffers' k) + 256
@@ -268,8 +269,10 @@ gc_status gc_profile_read(gc_ctx* ctx, int32_t id, double* total_ms, int64_t* la
  *   "dec_large_tile"  the aggregate's output tile held in LDS by one wavefront: 16384 floats (1),
  *                   4096 floats (0), or chosen from the vector's length and filling (-1; default).
  *   "dec_fused"     the aggregate as one kernel that reads the workers' lists tile by tile (1), as two
- *                   kernels with a packed record stream in between (0), or chosen from how thinly the
- *                   output tiles are filled (-1; default).
+ *                   kernels with a packed record stream in between (0), or chosen from the number of
+ *                   workers and how the output tiles are filled (-1; default).
+ *   "dec_fused_tile"  the one-kernel aggregate's tile: 2048 floats, 8 wavefronts per workgroup (1),
+ *                   4096 floats, 4 wavefronts (0), or chosen from the filling (-1; default).
  *   "apply_dense_min"  fused apply: an output tile with at least this many pairs per 4096 floats is
  *                   read and rewritten whole instead of position by position (1..2^30; default 128).
  * Unknown names or out-of-range values return GC_ERR_INVALID_ARG. */

@@ -22,6 +22,9 @@
 //                   worker never collide, and the fixed worker order makes the fp32 sum
 //                   reproducible bit for bit.
 //
+// Up to 32 workers the call takes k_dec_fused (further down) instead: one kernel that reads a
+// tile's pairs straight from the workers' lists and never writes the merged stream.
+//
 // Index lists that break the contract (not ascending, duplicates, out of range) give an unspecified
 // sum, but every access stays inside the caller's and the library's arrays: records are only
 // written inside their segment, and positions and workers read back from records are range-checked.
@@ -80,7 +83,8 @@ constexpr int kPackThreads = GC_PACK_THREADS, kPackWaves = kPackThreads / 64;
 constexpr int kPackBatch = GC_PACK_BATCH;  // pairs per lane whose loads are issued before any is used
 
 template <typename I>
-__global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int tb, int tshift, int32_t block, int64_t ntiles,
+__global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int tb, int tshift, int32_t block, FastDiv bdiv,
+                                                           int64_t ntiles,
                                                            int64_t r_first,
                                                            const long long* __restrict__ kprefix,
                                                            const long long* __restrict__ sprefix,
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(kPackThreads) void k_dec_pack(DecArgs a, int W, int
             sbase = sprefix[tl];
             qbase = qprefix[tl];
           }
-          const uint32_t blk = rel / (uint32_t)block;
+          const uint32_t blk = fast_div(rel, bdiv);
           const float sc = scw[sbase + blk];
           if (codec == 0) {
             val[u] = __fmul_rn((float)qw[qbase + rel], sc);
@@ -290,8 +294,8 @@ __device__ __forceinline__ void add_round(uint2 r, float* lt) {
   const bool act = pos < (uint32_t)TILE;
   const uint64_t am = __ballot(act);
   if (am == 0ull) return;
-  const int w_first = __shfl(w, __ffsll((unsigned long long)am) - 1);
-  const int w_last = __shfl(w, 63 - __clzll((unsigned long long)am));
+  const int w_first = __builtin_amdgcn_readlane(w, __ffsll((unsigned long long)am) - 1);
+  const int w_last = __builtin_amdgcn_readlane(w, 63 - __clzll((unsigned long long)am));
   const float val = __uint_as_float(r.y);
   for (int x = w_first; x <= w_last; ++x) {
     if (act && w == x) (void)__hip_atomic_fetch_add(lt + pos, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
@@ -404,13 +408,19 @@ __global__ __launch_bounds__(WAVES * 64) void k_dec_tiles(const uint2* __restric
 // ---------------------------------------------------------------- fused aggregate
 // One kernel, no record stream: a workgroup (4 wavefronts) takes a range of `tb` tiles, finds every
 // worker's pairs in it (binary searches, then the "pair j opens the tiles up to its own" pass over
-// the range's indices, exactly as k_dec_pack does) and keeps the table of (tile, worker) segment
-// starts in LDS. Its wavefronts then take the range's tiles one by one: a tile's pairs are read
-// straight from the workers' lists, the lanes dealt out over the tile's pairs in (worker, index)
-// order - lane f finds its worker in the scan of the 64 segment lengths - decoded in registers and
-// added into the LDS tile worker by worker, as k_dec_tiles adds records. The merged stream of
-// 8-byte records is never written or read back: that stream is 1.8 GB of the 31.9 GB the two-kernel
-// call moves at 7B, and a third of what it moves at 1.3B.
+// the range's indices, as k_dec_pack does) and keeps the table of (tile, worker) segment starts in
+// LDS. Its wavefronts then take the range's tiles one by one: a tile's pairs are read straight from
+// the workers' lists, the lanes dealt out over the tile's pairs in (worker, index) order, decoded in
+// registers and added into the LDS tile worker by worker, as k_dec_tiles adds records. The merged
+// stream of 8-byte records is never written or read back: that stream is 1.8 GB of the 31.9 GB the
+// two-kernel call moves at 7B, and a third of what it moves at 1.3B.
+//
+// A tile is a chain of memory round trips (table, pairs, adds, store), and a compute unit holds only
+// eight tiles at a time, so the chain is kept short: a lane finds the worker of its pair by
+// comparing its flat position with the W segment starts broadcast from registers (no search through
+// LDS), the pairs of the wavefront's NEXT tile are requested before the current tile is summed (what
+// arrives is kept raw - index, code byte, scale - and decoded when it is used), and the first pass
+// over a range's indices keeps 8 or 16 loads per lane in flight.
 struct FusedWorker {  // one worker's arrays, copied to LDS so that a lane can index them by its worker
   const void* idx;
   const int8_t* q;
@@ -419,12 +429,53 @@ struct FusedWorker {  // one worker's arrays, copied to LDS so that a lane can i
   uint32_t k;
 };
 
-constexpr int kFusedWaves = 4, kFusedThreads = kFusedWaves * 64;
-constexpr int kFusedTileShift = kDecMinTileShift, kFusedTile = 1 << kFusedTileShift;
+// Tiles of 4096 floats and 4 wavefronts per workgroup where tiles are thinly filled; tiles of 2048
+// floats and 8 wavefronts (twice as many tiles in flight per compute unit) where they are crowded.
+constexpr int kFusedTileShift = kDecMinTileShift, kFusedWaves = 4;
+constexpr int kFusedTileShiftSmall = 11, kFusedWavesSmall = 8;
+constexpr uint32_t kNoPair = 0xFFFFFFFFu;
+constexpr int kFusedLdsTensors = 256;  // prefix tables of up to this many tensors are staged in LDS (3 KB)
+
+template <typename I>
+struct FusedRaw {  // one pair as it comes out of memory
+  I gi;           // global index
+  float sc;       // scale of its block
+  uint32_t qb;    // its code byte (int8 code, or the byte that holds its sign bit)
+  uint32_t aux;   // worker << 16 | bit inside the byte (sign code); kNoPair: no pair in this lane
+};
+
+struct FusedTile {  // a tile's segments, one worker per lane
+  uint32_t lo;    // first pair of this lane's worker in the tile
+  uint32_t cnt;   // and how many
+  uint32_t total;
+};
+
+// The pairs at flat positions f0 + i * 64 + lane, i < NR, of a tile: worker and pair number. The
+// worker of position f is the last one whose segment starts at or before f (an empty segment
+// starts where the next one does, and is overruled by it). The segment starts are a running sum of
+// the counts, broadcast from the lanes that hold them: scalar work beside NR compares per worker.
+template <int NR, int R>
+__device__ __forceinline__ void fused_select(const FusedTile& h, int W, uint32_t f0, int lane, int (&ws)[R],
+                                             uint32_t (&js)[R]) {
+  uint32_t run = 0u;
+  for (int w = 0; w < W; ++w) {
+    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)h.cnt, w);
+    const uint32_t ad = (uint32_t)__builtin_amdgcn_readlane((int)h.lo, w) - run;
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      const uint32_t f = f0 + (uint32_t)(i * 64 + lane);
+      if (f >= run) {
+        ws[i] = w;
+        js[i] = f + ad;
+      }
+    }
+    run += c;
+  }
+}
 
 // MODE 0: out[tile] = sum (dense write).  MODE 1: theta[i] -= c * sum[i] at the touched i only.
-template <typename I, int MODE>
-__global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, int tb, int32_t block, int64_t ntiles,
+template <typename I, int MODE, int TSHIFT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 2, WAVES / 2))) void k_dec_fused(DecArgs a, int W, int tb, int32_t block, FastDiv bdiv, int64_t ntiles,
                                                              int64_t nranges, int codec, int weighted, int64_t n,
                                                              const long long* __restrict__ kprefix,
                                                              const long long* __restrict__ sprefix,
@@ -432,12 +483,26 @@ __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, i
                                                              float* __restrict__ out, float c_apply) {
   extern __shared__ uint32_t s_dyn[];      // [tb + 1][W]: first pair of worker w at or after local tile t
   uint32_t* s_lo = s_dyn;
+  constexpr int kFusedTile = 1 << TSHIFT, kFusedWaves = WAVES, kFusedThreads = WAVES * 64;
   __shared__ float tile_mem[kFusedWaves][kFusedTile];
   __shared__ FusedWorker s_wk[kMaxWorkers];
   __shared__ uint32_t s_br0[kMaxWorkers], s_br1[kMaxWorkers];
-  __shared__ uint32_t s_incl[kFusedWaves][kMaxWorkers];  // per wavefront: inclusive scan of a tile's segment lengths
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  constexpr int tshift = kFusedTileShift;
+  constexpr int tshift = TSHIFT;
+  constexpr int R = kDecRounds;
+  static_assert(R == 4, "fused_select is dispatched for up to four rounds");
+  // indices per lane in flight in the first pass: what the register budget of the shape allows
+  constexpr int kScan = WAVES > 4 ? 8 : (sizeof(I) == 4 ? 32 : 16);
+  // per-tensor prefix tables of a multi-tensor buffer: a pair's tensor is found by a binary search,
+  // a chain of dependent reads that is ten times shorter out of LDS than out of memory
+  __shared__ uint32_t s_tp[3][kFusedLdsTensors];
+  if (T > 1 && T <= kFusedLdsTensors) {
+    for (int t = tid; t < T; t += kFusedThreads) {
+      s_tp[0][t] = (uint32_t)kprefix[t];
+      s_tp[1][t] = (uint32_t)sprefix[t];
+      s_tp[2][t] = (uint32_t)qprefix[t];
+    }
+  }
   if (tid < W) {
     FusedWorker f;
     f.idx = a.indices[tid];
@@ -449,8 +514,10 @@ __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, i
   }
   __syncthreads();
   float* lt = tile_mem[wave];
-  const int team = W >= kFusedWaves ? 1 : kFusedWaves / W;  // wavefronts that share one worker's pairs in pass 1
-  const unsigned long long step = 64ull * team;
+  int G = 64;  // lanes per worker in the first pass over a range's indices
+  while (G > 1 && G * W > kFusedThreads) G >>= 1;
+  const int gl = tid & (G - 1);
+  const uint32_t sign_bytes = (uint32_t)((block + 7) / 8);
 
   for (int64_t r = blockIdx.x; r < nranges; r += gridDim.x) {
     const int64_t t0 = r * tb;
@@ -472,30 +539,41 @@ __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, i
       s_lo[i] = b1 > b0 ? b1 : b0;
     }
     __syncthreads();
-    // the first pair at or after the start of every tile: pair j opens all tiles after its predecessor's, up to its own
-    for (int w = wave / team; w < W; w += kFusedWaves / team) {
-      const I* idx = static_cast<const I*>(s_wk[w].idx);
-      const unsigned long long j0 = s_br0[w], j1 = s_br1[w] > s_br0[w] ? s_br1[w] : s_br0[w];
-      for (unsigned long long jb = j0 + (unsigned)((wave % team) * 64 + lane); jb < j1; jb += step * kPackBatch) {
-        unsigned long long cur[kPackBatch], prev[kPackBatch];
+    // the first pair at or after the start of every tile: pair j opens all tiles after its
+    // predecessor's, up to its own. The predecessor's index comes from the lane to the left.
+    // Every worker has a group of G consecutive lanes, all workers at once (as many as fit): the
+    // whole pass is a few rounds of loads, however many workers there are.
+    for (int w0 = 0; w0 < W; w0 += kFusedThreads / G) {
+      const int w = w0 + tid / G;
+      const bool wn = w < W;
+      const I* idx = static_cast<const I*>(s_wk[wn ? w : 0].idx);
+      const unsigned long long j0 = wn ? s_br0[w] : 0ull;
+      const unsigned long long j1 = wn ? (s_br1[w] > s_br0[w] ? s_br1[w] : s_br0[w]) : 0ull;
+      for (unsigned long long jg = j0; __ballot(jg < j1) != 0ull; jg += (unsigned long long)(G * kScan)) {
+        I cur[kScan], left[kScan];
+        int nu = kScan;  // a short range ends the batch early (uniform over the wavefront)
 #pragma unroll
-        for (int u = 0; u < kPackBatch; ++u) {  // the batch's loads are in flight together
-          const unsigned long long j = jb + u * step;
-          cur[u] = 0ull;
-          prev[u] = 0ull;
-          if (j < j1) {
-            cur[u] = (unsigned long long)idx[j];
-            if (j > j0) prev[u] = (unsigned long long)idx[j - 1];
+        for (int u = 0; u < kScan; ++u) {  // the batch's loads are in flight together
+          const unsigned long long j = jg + (unsigned)(u * G + gl);
+          if (u < nu && __ballot(j < j1) == 0ull) nu = u;
+          cur[u] = (I)0;
+          left[u] = (I)0;
+          if (u < nu) {
+            cur[u] = j < j1 ? idx[j] : (I)0;
+            left[u] = (gl == 0 && j < j1 && j > j0) ? idx[j - 1] : (I)0;
           }
         }
 #pragma unroll
-        for (int u = 0; u < kPackBatch; ++u) {
-          const unsigned long long j = jb + u * step;
-          const int64_t tc = (int64_t)(cur[u] >> tshift) - t0;
+        for (int u = 0; u < kScan; ++u) {
+          if (u >= nu) break;
+          const unsigned long long j = jg + (unsigned)(u * G + gl);
+          const I up = __shfl_up(cur[u], 1);
+          const unsigned long long prev = gl == 0 ? (unsigned long long)left[u] : (unsigned long long)up;
+          const int64_t tc = (int64_t)((unsigned long long)cur[u] >> tshift) - t0;
           if (j < j1 && tc >= 0 && tc < tb) {  // outside only with indices out of order
             int64_t tp = -1;
             if (j > j0) {
-              tp = (int64_t)(prev[u] >> tshift) - t0;
+              tp = (int64_t)(prev >> tshift) - t0;
               if (tp < -1) tp = -1;
             }
             for (int64_t t = tp + 1; t <= tc; ++t) s_lo[t * W + w] = (uint32_t)j;
@@ -506,59 +584,62 @@ __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, i
     __syncthreads();
 
     // ---- the range's tiles, one wavefront each
-    for (int ltile = wave; ltile < tb; ltile += kFusedWaves) {
-      const int64_t tile = t0 + ltile;
-      if (tile >= ntiles) break;
-      const int64_t base = tile << tshift;
-      // segment of worker `lane` in this tile, and the scan of the segment lengths
-      uint32_t lo = 0u, cnt = 0u;
+    // segments of local tile `ltile`: worker `lane`'s first pair and count
+    auto open_tile = [&](int ltile, FusedTile& h) {
+      h.lo = 0u;
+      h.cnt = 0u;
       if (lane < W) {
-        lo = s_lo[ltile * W + lane];
+        h.lo = s_lo[ltile * W + lane];
         const uint32_t hi = s_lo[(ltile + 1) * W + lane];
-        cnt = hi > lo ? hi - lo : 0u;
+        h.cnt = hi > h.lo ? hi - h.lo : 0u;
       }
-      uint32_t incl = cnt;
+      uint32_t total = 0u;
+      for (int w = 0; w < W; ++w) total += (uint32_t)__builtin_amdgcn_readlane((int)h.cnt, w);
+      h.total = total;
+    };
+    auto select = [&](const FusedTile& h, uint32_t f0, int (&ws)[R], uint32_t (&js)[R]) {
 #pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t u = __shfl_up(incl, off);
-        if (lane >= off) incl += u;
+      for (int i = 0; i < R; ++i) {
+        ws[i] = 0;
+        js[i] = 0u;
       }
-      const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-      if (MODE == 1 && total == 0u) continue;  // nothing to apply in an empty tile
-      s_incl[wave][lane] = incl;
-      const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
+      const uint32_t left = h.total > f0 ? h.total - f0 : 0u;  // only rounds that hold a pair are looked up
+      if (left > 192u) fused_select<4>(h, W, f0, lane, ws, js);
+      else if (left > 128u) fused_select<3>(h, W, f0, lane, ws, js);
+      else if (left > 64u) fused_select<2>(h, W, f0, lane, ws, js);
+      else if (left > 0u) fused_select<1>(h, W, f0, lane, ws, js);
+    };
+    // requests a batch of pairs; nothing here waits for what it asks for (one tensor; with several,
+    // the search for the pair's tensor does)
+    auto fetch = [&](const FusedTile& h, uint32_t f0, FusedRaw<I> (&raw)[R]) {
+      int ws[R];
+      uint32_t js[R];
+      select(h, f0, ws, js);
 #pragma unroll
-      for (int i = 0; i < kFusedTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
-      wave_sync();
-
-      // the pair at flat position f of this tile: its worker is the first w with incl[w] > f
-      auto pair_of = [&](uint32_t f, int& w, uint32_t& j) {
-        int wl = 0, wh = W - 1;
-        while (wl < wh) {
-          const int mid = (wl + wh) >> 1;
-          if (s_incl[wave][mid] > f) wh = mid; else wl = mid + 1;
-        }
-        w = wl;
-        const uint32_t before = w > 0 ? s_incl[wave][w - 1] : 0u;
-        j = s_lo[ltile * W + w] + (f - before);
-      };
-      for (uint32_t f0 = 0; f0 < total; f0 += 64 * kDecRounds) {
-        uint2 rr[kDecRounds];
-#pragma unroll
-        for (int i = 0; i < kDecRounds; ++i) {  // the loads of all rounds are issued before any is used
-          const uint32_t f = f0 + (uint32_t)(i * 64 + lane);
-          rr[i] = make_uint2(kNoRecord, 0u);
-          if (f < total) {
-            int w;
-            uint32_t j;
-            pair_of(f, w, j);
-            const FusedWorker wk = s_wk[w];
-            if (j < wk.k) {  // always, for lists that keep the contract
-              const unsigned long long gi = (unsigned long long)static_cast<const I*>(wk.idx)[j];
-              uint32_t rel_j = j;  // pair inside its tensor; sbase, qbase: the tensor's first scale and code byte
-              long long sbase = 0, qbase = 0;
-              if (T > 1) {  // blocks restart at every tensor: find the tensor that owns pair j
-                int tl = 0, th = T - 1;
+      for (int i = 0; i < R; ++i) {
+        const uint32_t f = f0 + (uint32_t)(i * 64 + lane);
+        raw[i].gi = (I)0;
+        raw[i].sc = 0.0f;
+        raw[i].qb = 0u;
+        raw[i].aux = kNoPair;
+        if (f < h.total) {
+          const FusedWorker wk = s_wk[ws[i]];
+          const uint32_t j = js[i];
+          if (j < wk.k) {  // always, for lists that keep the contract
+            raw[i].gi = static_cast<const I*>(wk.idx)[j];
+            uint32_t rel_j = j;  // pair inside its tensor; sbase, qbase: the tensor's first scale and code byte
+            long long sbase = 0, qbase = 0;
+            if (T > 1) {  // blocks restart at every tensor: find the tensor that owns pair j
+              int tl = 0, th = T - 1;
+              if (T <= kFusedLdsTensors) {  // the tables are in LDS (every entry is below 2^32)
+                while (tl < th) {
+                  const int mid = (tl + th + 1) >> 1;
+                  if (s_tp[0][mid] <= j) tl = mid; else th = mid - 1;
+                }
+                rel_j = j - s_tp[0][tl];
+                sbase = (long long)s_tp[1][tl];
+                qbase = (long long)s_tp[2][tl];
+              } else {
                 while (tl < th) {
                   const int mid = (tl + th + 1) >> 1;
                   if (kprefix[mid] <= (long long)j) tl = mid; else th = mid - 1;
@@ -567,60 +648,84 @@ __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, i
                 sbase = sprefix[tl];
                 qbase = qprefix[tl];
               }
-              const uint32_t blk = rel_j / (uint32_t)block;
-              const float sc = wk.sc[sbase + blk];
-              float val;
-              if (codec == 0) {
-                val = __fmul_rn((float)wk.q[qbase + rel_j], sc);
-              } else {  // sign code (Eq. 10): bit number rel_j - blk * block of the block's bytes
-                const uint32_t bit = rel_j - blk * (uint32_t)block;
-                const uint32_t byte = (uint8_t)wk.q[qbase + (long long)blk * ((block + 7) / 8) + (bit >> 3)];
-                val = ((byte >> (bit & 7u)) & 1u) ? sc : -sc;
-              }
-              if (weighted) val = __fdiv_rn(val, wk.denom);  // Eq. 12: a stale worker counts for less
-              const unsigned long long rel = gi - (unsigned long long)base;
-              const uint32_t pos = (gi >= (unsigned long long)base && rel < (unsigned long long)kFusedTile) ? (uint32_t)rel : 0xFFFFu;
-              rr[i] = make_uint2(pos | ((uint32_t)w << 16), __float_as_uint(val));
+            }
+            const uint32_t blk = fast_div(rel_j, bdiv);
+            raw[i].sc = wk.sc[sbase + blk];
+            if (codec == 0) {
+              raw[i].qb = (uint32_t)(uint8_t)wk.q[qbase + rel_j];
+              raw[i].aux = (uint32_t)ws[i] << 16;
+            } else {  // sign code (Eq. 10): bit number rel_j - blk * block of the block's bytes
+              const uint32_t bit = rel_j - blk * (uint32_t)block;
+              raw[i].qb = (uint32_t)(uint8_t)wk.q[qbase + (long long)blk * sign_bytes + (bit >> 3)];
+              raw[i].aux = ((uint32_t)ws[i] << 16) | (bit & 7u);
             }
           }
         }
-#pragma unroll
-        for (int i = 0; i < kDecRounds; ++i) add_round<kFusedTile>(rr[i], lt);
       }
-      wave_sync();
+    };
+    // value and position of a fetched pair, as a record of k_dec_tiles
+    auto decode = [&](const FusedRaw<I>& p, int64_t base) -> uint2 {
+      if (p.aux == kNoPair) return make_uint2(kNoRecord, 0u);
+      const uint32_t w = p.aux >> 16;
+      float val;
+      if (codec == 0) val = __fmul_rn((float)(int8_t)(uint8_t)p.qb, p.sc);
+      else val = ((p.qb >> (p.aux & 7u)) & 1u) ? p.sc : -p.sc;
+      if (weighted) val = __fdiv_rn(val, s_wk[w].denom);  // Eq. 12: a stale worker counts for less
+      const unsigned long long gi = (unsigned long long)p.gi, rel = gi - (unsigned long long)base;
+      const uint32_t pos = (gi >= (unsigned long long)base && rel < (unsigned long long)kFusedTile) ? (uint32_t)rel : 0xFFFFu;
+      return make_uint2(pos | (w << 16), __float_as_uint(val));
+    };
 
-      const int64_t remain = n - base;
-      if (MODE == 0) {
-        if (remain >= kFusedTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
+    // sums one tile whose first batch of pairs has been requested, and writes it
+    auto finish_tile = [&](const FusedTile& hc, FusedRaw<I> (&rc)[R], int ltile) {
+      const int64_t base = (t0 + ltile) << tshift;
+      const uint32_t total = hc.total;
+      if (!(MODE == 1 && total == 0u)) {  // nothing to apply in an empty tile
+        const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-          for (int i = 0; i < kFusedTile / 256; ++i) {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
-            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
+        for (int i = 0; i < kFusedTile / 256; ++i) *reinterpret_cast<f32x4*>(lt + (i * 64 + lane) * 4) = z;
+        wave_sync();
+#pragma unroll
+        for (int i = 0; i < R; ++i) add_round<kFusedTile>(decode(rc[i], base), lt);
+        for (uint32_t f0 = 64 * R; f0 < total; f0 += 64 * R) {  // a crowded tile: the rest, batch by batch
+          FusedRaw<I> rx[R];
+          fetch(hc, f0, rx);
+#pragma unroll
+          for (int i = 0; i < R; ++i) add_round<kFusedTile>(decode(rx[i], base), lt);
+        }
+        wave_sync();
+
+        const int64_t remain = n - base;
+        if (MODE == 0) {
+          if (remain >= kFusedTile && ((reinterpret_cast<uintptr_t>(out) & 15u) == 0)) {
+#pragma unroll
+            for (int i = 0; i < kFusedTile / 256; ++i) {
+              const f32x4 v = *reinterpret_cast<const f32x4*>(lt + (i * 64 + lane) * 4);
+              __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + base + (i * 64 + lane) * 4));
+            }
+          } else {
+            const int lim = (int)(remain < kFusedTile ? remain : kFusedTile);
+            for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
           }
         } else {
-          const int lim = (int)(remain < kFusedTile ? remain : kFusedTile);
-          for (int i = lane; i < lim; i += 64) out[base + i] = lt[i];
-        }
-      } else if (total != 0u) {
-        // every named position is claimed once (LDS exchange with a marker) and updated in place:
-        // theta - fl32(c * sum). The positions are read again from the workers' lists (the lines were
-        // fetched a moment ago); the loads of a batch of rounds are issued before its first store.
-        for (uint32_t f0 = 0; f0 < total; f0 += 64 * kDecRounds) {
-          int64_t gi[kDecRounds];
-          float sum[kDecRounds], th[kDecRounds];
-          bool mine[kDecRounds];
+          // every named position is claimed once (LDS exchange with a marker) and updated in place:
+          // theta - fl32(c * sum). The positions are read again from the workers' lists (the lines were
+          // fetched a moment ago); the loads of a batch of rounds are issued before its first store.
+          for (uint32_t f0 = 0; f0 < total; f0 += 64 * R) {
+            int ws[R];
+            uint32_t js[R];
+            select(hc, f0, ws, js);
+            int64_t gi[R];
+            float sum[R], th[R];
+            bool mine[R];
 #pragma unroll
-          for (int i = 0; i < kDecRounds; ++i) {
-            const uint32_t f = f0 + (uint32_t)(i * 64 + lane);
-            mine[i] = false;
-            gi[i] = 0;
-            sum[i] = 0.0f;
-            if (f < total) {
-              int w;
-              uint32_t j;
-              pair_of(f, w, j);
-              if (j < s_wk[w].k) {
-                const unsigned long long g = (unsigned long long)static_cast<const I*>(s_wk[w].idx)[j];
+            for (int i = 0; i < R; ++i) {
+              const uint32_t f = f0 + (uint32_t)(i * 64 + lane);
+              mine[i] = false;
+              gi[i] = 0;
+              sum[i] = 0.0f;
+              if (f < total && js[i] < s_wk[ws[i]].k) {
+                const unsigned long long g = (unsigned long long)static_cast<const I*>(s_wk[ws[i]].idx)[js[i]];
                 const unsigned long long rel = g - (unsigned long long)base;
                 if (g >= (unsigned long long)base && rel < (unsigned long long)kFusedTile && (int64_t)g < n) {
                   const uint32_t old = atomicExch(reinterpret_cast<uint32_t*>(lt) + (uint32_t)rel, kClaimed);
@@ -630,15 +735,45 @@ __global__ __launch_bounds__(kFusedThreads) void k_dec_fused(DecArgs a, int W, i
                 }
               }
             }
+#pragma unroll
+            for (int i = 0; i < R; ++i) th[i] = mine[i] ? out[gi[i]] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < R; ++i)
+              if (mine[i]) out[gi[i]] = __fsub_rn(th[i], __fmul_rn(c_apply, sum[i]));
           }
-#pragma unroll
-          for (int i = 0; i < kDecRounds; ++i) th[i] = mine[i] ? out[gi[i]] : 0.0f;
-#pragma unroll
-          for (int i = 0; i < kDecRounds; ++i)
-            if (mine[i]) out[gi[i]] = __fsub_rn(th[i], __fmul_rn(c_apply, sum[i]));
         }
+        wave_sync();
       }
-      wave_sync();
+    };
+    // Two sets of registers take turns: while one tile is summed out of one set, the next tile's
+    // pairs arrive in the other (a copy between the sets would have to wait for them).
+    FusedTile ha, hb;
+    FusedRaw<I> ra[R], rb[R];
+    int lt_cur = wave;
+    auto tile_ok = [&](int ltile) { return ltile < tb && t0 + ltile < ntiles; };
+    if (tile_ok(lt_cur)) {
+      open_tile(lt_cur, ha);
+      fetch(ha, 0u, ra);
+      while (true) {
+        int lt_next = lt_cur + kFusedWaves;
+        bool more = tile_ok(lt_next);
+        if (more) {
+          open_tile(lt_next, hb);
+          fetch(hb, 0u, rb);
+        }
+        finish_tile(ha, ra, lt_cur);
+        if (!more) break;
+        lt_cur = lt_next;
+        lt_next = lt_cur + kFusedWaves;
+        more = tile_ok(lt_next);
+        if (more) {
+          open_tile(lt_next, ha);
+          fetch(ha, 0u, ra);
+        }
+        finish_tile(hb, rb, lt_cur);
+        if (!more) break;
+        lt_cur = lt_next;
+      }
     }
     __syncthreads();  // the table is rewritten for the next range
   }
@@ -668,24 +803,26 @@ int dec_range_tiles(int W, int tshift, int64_t nrec, int64_t n) {
 
 // Tiles per range of the fused kernel: the LDS table holds (tb + 1) * W entries (about 8 KB), and
 // there should be enough ranges to keep two workgroups per compute unit busy. A power of two >= 4.
-int dec_fused_range_tiles(int W, int64_t n) {
-  const int64_t ntiles = (n + kFusedTile - 1) >> kFusedTileShift;
+int dec_fused_range_tiles(int W, int64_t n, int tshift) {
+  const int64_t ntiles = (n + (int64_t(1) << tshift) - 1) >> tshift;
   int tb = 128;
   while (tb > 4 && ((tb + 1) * W > 2112 || ntiles / tb < 1024)) tb >>= 1;
   return tb;
 }
 
-void launch_dec_fused(const DecArgs& a, int W, int index_bits, int32_t block, int codec, int weighted, int64_t n,
-                      const long long* kprefix, const long long* sprefix, const long long* qprefix, int T, float* out,
-                      int apply, float c_apply, hipStream_t s) {
-  const int tb = dec_fused_range_tiles(W, n);
-  const int64_t ntiles = (n + kFusedTile - 1) >> kFusedTileShift;
+template <int TSHIFT, int WAVES>
+static void launch_fused_shape(const DecArgs& a, int W, int index_bits, int32_t block, int codec, int weighted, int64_t n,
+                               const long long* kprefix, const long long* sprefix, const long long* qprefix, int T,
+                               float* out, int apply, float c_apply, hipStream_t s) {
+  const int tb = dec_fused_range_tiles(W, n, TSHIFT);
+  const int64_t ntiles = (n + (int64_t(1) << TSHIFT) - 1) >> TSHIFT;
   const int64_t nranges = (ntiles + tb - 1) / tb;
-  const dim3 grid((unsigned)(nranges < 512 ? nranges : 512)), blk(kFusedThreads);
+  const dim3 grid((unsigned)(nranges < 512 ? nranges : 512)), blk(WAVES * 64);
   const size_t lds = sizeof(uint32_t) * (size_t)(tb + 1) * W;
-#define GC_LAUNCH_FUSED(ITYPE, MODE)                                                                                  \
-  hipLaunchKernelGGL((k_dec_fused<ITYPE, MODE>), grid, blk, lds, s, a, W, tb, block, ntiles, nranges, codec, weighted, n, \
-                     kprefix, sprefix, qprefix, T, out, c_apply)
+  const FastDiv bdiv = make_fastdiv((uint32_t)block);
+#define GC_LAUNCH_FUSED(ITYPE, MODE)                                                                               \
+  hipLaunchKernelGGL((k_dec_fused<ITYPE, MODE, TSHIFT, WAVES>), grid, blk, lds, s, a, W, tb, block, bdiv, ntiles, nranges, \
+                     codec, weighted, n, kprefix, sprefix, qprefix, T, out, c_apply)
   if (index_bits == 32) {
     if (apply) GC_LAUNCH_FUSED(uint32_t, 1); else GC_LAUNCH_FUSED(uint32_t, 0);
   } else {
@@ -694,17 +831,29 @@ void launch_dec_fused(const DecArgs& a, int W, int index_bits, int32_t block, in
 #undef GC_LAUNCH_FUSED
 }
 
+void launch_dec_fused(const DecArgs& a, int W, int index_bits, int32_t block, int codec, int weighted, int64_t n,
+                      const long long* kprefix, const long long* sprefix, const long long* qprefix, int T, float* out,
+                      int apply, float c_apply, int small_tile, hipStream_t s) {
+  if (small_tile)
+    launch_fused_shape<kFusedTileShiftSmall, kFusedWavesSmall>(a, W, index_bits, block, codec, weighted, n, kprefix, sprefix,
+                                                               qprefix, T, out, apply, c_apply, s);
+  else
+    launch_fused_shape<kFusedTileShift, kFusedWaves>(a, W, index_bits, block, codec, weighted, n, kprefix, sprefix, qprefix,
+                                                     T, out, apply, c_apply, s);
+}
+
 void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift, int32_t block, int64_t ntiles,
                      int64_t r_first, int64_t r_count, const long long* kprefix, const long long* sprefix,
                      const long long* qprefix, int T, int codec, int weighted, void* rec, unsigned long long* tile_start,
                      hipStream_t s) {
   const dim3 grid((unsigned)r_count);
   const size_t lds = sizeof(uint32_t) * (size_t)(2 * tb + 1) * W;  // at most 33 KB
+  const FastDiv bdiv = make_fastdiv((uint32_t)block);
   if (index_bits == 32)
-    hipLaunchKernelGGL(k_dec_pack<uint32_t>, grid, dim3(kPackThreads), lds, s, a, W, tb, tshift, block, ntiles, r_first,
+    hipLaunchKernelGGL(k_dec_pack<uint32_t>, grid, dim3(kPackThreads), lds, s, a, W, tb, tshift, block, bdiv, ntiles, r_first,
                        kprefix, sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
   else
-    hipLaunchKernelGGL(k_dec_pack<unsigned long long>, grid, dim3(kPackThreads), lds, s, a, W, tb, tshift, block, ntiles,
+    hipLaunchKernelGGL(k_dec_pack<unsigned long long>, grid, dim3(kPackThreads), lds, s, a, W, tb, tshift, block, bdiv, ntiles,
                        r_first, kprefix, sprefix, qprefix, T, codec, weighted, (uint2*)rec, tile_start);
 }
 

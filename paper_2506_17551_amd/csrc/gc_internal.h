@@ -216,6 +216,26 @@ __device__ __forceinline__ uint32_t mbcnt64(uint64_t m) {
 }
 __device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
 
+// Exact unsigned 32-bit division by a divisor fixed for the launch, as a multiplication and two
+// shifts (Granlund and Montgomery 1994, the round-up multiplier with an add-back): a pair's block is
+// (pair number) / block, once per pair, and the hardware has no integer divide.
+struct FastDiv {
+  uint32_t m, s1, s2;
+};
+inline FastDiv make_fastdiv(uint32_t d) {  // 1 <= d < 2^31
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  FastDiv f;
+  f.m = (uint32_t)((((1ull << l) - d) << 32) / d + 1ull);
+  f.s1 = l < 1u ? l : 1u;
+  f.s2 = l > 1u ? l - 1u : 0u;
+  return f;
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t x, FastDiv f) {
+  const uint32_t t = __umulhi(f.m, x);
+  return (t + ((x - t) >> f.s1)) >> f.s2;
+}
+
 template <typename G> __device__ __forceinline__ float load_grad(const G* g, int64_t i);
 template <> __device__ __forceinline__ float load_grad<float>(const float* g, int64_t i) { return g[i]; }
 template <> __device__ __forceinline__ float load_grad<uint16_t>(const uint16_t* g, int64_t i) {
@@ -265,7 +285,7 @@ void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift
 // prefix tables of multi-tensor buffers (T > 1), else null.
 void launch_dec_fused(const DecArgs& a, int W, int index_bits, int32_t block, int codec, int weighted, int64_t n,
                       const long long* kprefix, const long long* sprefix, const long long* qprefix, int T, float* out,
-                      int apply, float c_apply, hipStream_t s);
+                      int apply, float c_apply, int small_tile, hipStream_t s);
 void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int tshift, int64_t n,
                       int64_t t_begin, int64_t t_end, float* out, int apply, float c_apply, unsigned apply_dense_min,
                       hipStream_t s);

@@ -34,6 +34,21 @@ def bits(a):
     return a.view(np.uint32)
 
 
+# Every way the aggregate can be routed: the choice by shape, the two-kernel route (record stream)
+# with either tile size, the one-kernel route with either tile size. "auto" comes last so that a
+# shared context is left as it was.
+ROUTES = [("two-kernel 4096", {"dec_fused": 0, "dec_large_tile": 0}),
+          ("two-kernel 16384", {"dec_fused": 0, "dec_large_tile": 1}),
+          ("one-kernel 4096", {"dec_fused": 1, "dec_fused_tile": 0}),
+          ("one-kernel 2048", {"dec_fused": 1, "dec_fused_tile": 1}),
+          ("auto", {})]
+
+
+def set_route(ctx, opts):
+    for name in ("dec_fused", "dec_large_tile", "dec_fused_tile"):
+        ctx.set_option(name, opts.get(name, -1))
+
+
 def check_compress(gc, ctx, oracle, g_cpu, e_cpu, k, block, index_bits=32, tag="", expect_fallback=None):
     """Run one step on both sides from the same bytes; returns (gpu buf, oracle triple, new residual)."""
     n = g_cpu.numel()
@@ -409,11 +424,11 @@ def test_decompress_sum_sixteen_workers_with_collisions(gc, ctx, oracle):
     assert (counts >= 3).sum() > 1000  # the order of the fp32 adds matters for these
     for Wsub in (1, 2, 3, 5, 16):
         rc, want = oracle.decompress_sum(refs[:Wsub], n, block)
-        for tile in (0, 1, -1):  # both tile sizes of the aggregate, then back to the choice by shape
-            ctx.set_option("dec_large_tile", tile)
+        for route, opts in ROUTES:
+            set_route(ctx, opts)
             out = gc.decompress_sum(ctx, bufs[:Wsub], n)
             torch.cuda.synchronize()
-            assert np.array_equal(bits(out.cpu().numpy()), bits(want)), (Wsub, tile)
+            assert np.array_equal(bits(out.cpu().numpy()), bits(want)), (Wsub, route)
     for Wbig in (33, 64):  # many workers (the same buffers again and again: every position is shared)
         pick = [(7 * i) % W for i in range(Wbig)]
         stale = [i % 3 for i in range(Wbig)]
@@ -469,12 +484,12 @@ def test_decompress_sum_edge_shapes(gc, ctx, oracle):
         g = inputs.normal(n, 1.0, n)
         buf, ref, _ = check_compress(gc, ctx, oracle, g, torch.zeros(n), k, 8, tag="dec edge")
         rc, want = oracle.decompress_sum([ref] * 3, n, 8)
-        for tile in (0, 1, -1):
-            ctx.set_option("dec_large_tile", tile)
+        for route, opts in ROUTES:
+            set_route(ctx, opts)
             out = torch.full((n + 8,), 7.0, device=DEV)
             gc.decompress_sum(ctx, [buf, buf, buf], n, out=out[:n])
             torch.cuda.synchronize()
-            assert np.array_equal(bits(out[:n].cpu().numpy()), bits(want)), (n, k, tile)
+            assert np.array_equal(bits(out[:n].cpu().numpy()), bits(want)), (n, k, route)
             assert torch.all(out[n:] == 7.0)  # nothing written past n
     # an unaligned output pointer
     n, k = 50001, 500
@@ -654,9 +669,11 @@ def test_fused_aggregate_and_apply(gc, ctx, oracle, weighted):
     theta0[::7] = -0.0                                   # signed zeros must survive untouched
     # both tile sizes, and both ways a tile is updated: position by position (apply_dense_min out of
     # reach) and rewritten whole (apply_dense_min = 1); 128 is the default
-    for step, tile, dmin in ((0.0, -1, 128), (0.01, 0, 1 << 30), (0.01, 1, 1 << 30), (0.01, 0, 1), (0.01, 1, 1),
-                             (1.0 / W, -1, 128), (1.0 / W, -1, 1 << 30)):
-        ctx.set_option("dec_large_tile", tile)
+    R = dict(ROUTES)
+    for step, route, dmin in ((0.0, "auto", 128), (0.01, "two-kernel 4096", 1 << 30), (0.01, "two-kernel 16384", 1 << 30),
+                              (0.01, "two-kernel 4096", 1), (0.01, "two-kernel 16384", 1), (0.01, "one-kernel 4096", 128),
+                              (0.01, "one-kernel 2048", 128), (1.0 / W, "auto", 128), (1.0 / W, "auto", 1 << 30)):
+        set_route(ctx, R[route])
         ctx.set_option("apply_dense_min", dmin)
         theta = theta0.to(DEV).clone()
         gc.decompress_apply(ctx, bufs, theta, step, staleness=taus)
@@ -664,8 +681,9 @@ def test_fused_aggregate_and_apply(gc, ctx, oracle, weighted):
         rc, S = oracle.decompress_sum(refs, n, block, staleness=taus)
         want = theta0.numpy().copy()
         assert oracle.apply(want, S, step) == 0
-        assert np.array_equal(bits(theta.cpu().numpy()), bits(want)), (step, tile, dmin)
+        assert np.array_equal(bits(theta.cpu().numpy()), bits(want)), (step, route, dmin)
     ctx.set_option("apply_dense_min", 128)
+    set_route(ctx, {})
     # the separate route gives the same parameters: dense aggregate, then the update
     theta = theta0.to(DEV).clone()
     gc.decompress_apply(ctx, bufs, theta, 0.03, staleness=taus)
@@ -873,17 +891,13 @@ def _random_buffer(rng, gc, n, ks, block, index_bits, codec):
     return buf, (idx, q, s)
 
 
-@pytest.fixture(params=[-1, 0, 1, "fused"], ids=["tile-auto", "tile-4096", "tile-16384", "one-kernel"])
+@pytest.fixture(params=[o for _, o in ROUTES], ids=[r.replace(" ", "-") for r, _ in ROUTES])
 def tile_ctx(gc, request):
-    """A context with the aggregate's route forced: the two-kernel route with either tile size (the
-    large tile is otherwise only chosen for vectors of 2^28 elements and more), or the one-kernel
-    route without the record stream."""
+    """A context with the aggregate's route forced (ROUTES): the large tile of the two-kernel route is
+    otherwise only chosen for vectors of 2^28 elements and more, and the routes by filling and
+    number of workers."""
     c = gc.Context(0)
-    if request.param == "fused":
-        c.set_option("dec_fused", 1)
-    else:
-        c.set_option("dec_fused", 0 if request.param >= 0 else -1)
-        c.set_option("dec_large_tile", request.param)
+    set_route(c, request.param)
     yield c
     c.destroy()
 
