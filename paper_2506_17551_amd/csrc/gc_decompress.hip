@@ -450,6 +450,15 @@ struct FusedTile {  // a tile's segments, one worker per lane
   uint32_t total;
 };
 
+// The value held by the lane to the left inside a row of 16 lanes (the first lane of a row keeps its
+// own): a shift in the vector unit, without the trip through LDS that a general shuffle takes.
+__device__ __forceinline__ uint32_t lane_left(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x111 /* row_shr:1 */, 0xF, 0xF, false);
+}
+__device__ __forceinline__ unsigned long long lane_left(unsigned long long v) {
+  return ((unsigned long long)lane_left((uint32_t)(v >> 32)) << 32) | lane_left((uint32_t)v);
+}
+
 // The pairs at flat positions f0 + i * 64 + lane, i < NR, of a tile: worker and pair number. The
 // worker of position f is the last one whose segment starts at or before f (an empty segment
 // starts where the next one does, and is overruled by it). The segment starts are a running sum of
@@ -517,6 +526,9 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
   int G = 64;  // lanes per worker in the first pass over a range's indices
   while (G > 1 && G * W > kFusedThreads) G >>= 1;
   const int gl = tid & (G - 1);
+  // lanes whose left neighbour is not their predecessor in the worker's list (first of a group), or is
+  // out of reach of the row shift (first of a row of 16): they load the predecessor's index themselves
+  const bool edge = gl == 0 || (lane & 15) == 0;
   const uint32_t sign_bytes = (uint32_t)((block + 7) / 8);
 
   for (int64_t r = blockIdx.x; r < nranges; r += gridDim.x) {
@@ -560,15 +572,15 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
           left[u] = (I)0;
           if (u < nu) {
             cur[u] = j < j1 ? idx[j] : (I)0;
-            left[u] = (gl == 0 && j < j1 && j > j0) ? idx[j - 1] : (I)0;
+            left[u] = (edge && j < j1 && j > j0) ? idx[j - 1] : (I)0;
           }
         }
 #pragma unroll
         for (int u = 0; u < kScan; ++u) {
           if (u >= nu) break;
           const unsigned long long j = jg + (unsigned)(u * G + gl);
-          const I up = __shfl_up(cur[u], 1);
-          const unsigned long long prev = gl == 0 ? (unsigned long long)left[u] : (unsigned long long)up;
+          const I from_left = lane_left(cur[u]);  // every lane takes part, also those that will not use it
+          const unsigned long long prev = edge ? (unsigned long long)left[u] : (unsigned long long)from_left;
           const int64_t tc = (int64_t)((unsigned long long)cur[u] >> tshift) - t0;
           if (j < j1 && tc >= 0 && tc < tb) {  // outside only with indices out of order
             int64_t tp = -1;
