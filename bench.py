@@ -17,7 +17,7 @@ holds the whole report:
   roofline            the streaming kernel k_main: algorithmic 12 B/element over its HIP-event time
                       against the 8 TB/s HBM peak, with the operands where a placement probe put
                       them AND where plain allocation puts them
-  roofline_decompress the aggregate (k_dec_fused where output tiles are thinly filled, else k_dec_pack +
+  roofline_decompress the aggregate (k_dec_fused up to 32 workers, else k_dec_pack +
                       k_dec_tiles): 4 n + W (k (index + code) + scales) bytes over the time of the
                       whole gc_decompress_sum call
   copy_ceiling        a plain device copy of the same size in the same run
