@@ -46,6 +46,18 @@ __device__ __forceinline__ int find_last_le(int T, long long x, int hint, F begi
   return lo;
 }
 
+// The same inside a known range of tensors [t_lo, t_hi] (begin(t_lo) <= x, and x lies before the
+// tensor after t_hi): the search of a position whose neighbourhood has been located already.
+template <typename F>
+__device__ __forceinline__ int find_last_le_in(int t_lo, int t_hi, long long x, F begin) {
+  int lo = t_lo, hi = t_hi;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (begin(mid) <= x) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
 // Sum over the block of one value per thread (blockDim.x a multiple of 64, <= 1024).
 __device__ __forceinline__ unsigned long long block_sum(unsigned long long v, unsigned long long* sh) {
 #pragma unroll
@@ -1095,93 +1107,164 @@ __global__ __launch_bounds__(256) void k_emit(Workspace ws, const float* __restr
 constexpr int kQuantSharedBlock = 4096;
 constexpr int kQuantSpan = 1024;  // kept positions per workgroup
 
-// Start of the block that holds kept position x < ktotal, and of the first block at or after x.
-__device__ __forceinline__ long long this_block_start(const Workspace& ws, long long x, int32_t block) {
-  const int t = find_last_le(ws.T, x, 0, [&](int i) { return (long long)ws.desc(i).kprefix; });
-  const long long kp = ws.desc(t).kprefix;
-  return kp + (long long)((uint32_t)(x - kp) / (uint32_t)block) * block;  // x - kp < k < 2^32
-}
-__device__ __forceinline__ long long next_block_start(const Workspace& ws, long long x, int32_t block, long long ktotal) {
-  if (x >= ktotal) return ktotal;
-  const int t = find_last_le(ws.T, x, 0, [&](int i) { return (long long)ws.desc(i).kprefix; });
-  const long long kp = ws.desc(t).kprefix, rel = x - kp;
-  const uint32_t rb = (uint32_t)rel / (uint32_t)block;
+constexpr int kQuantLdsTensors = 1024;  // the tensors' first kept positions are staged in LDS up to this many
+
+// Start of the first block at or after kept position x (x itself if a block starts there), given
+// the tensor t that holds x. kp(i): first kept position of tensor i.
+template <typename KP>
+__device__ __forceinline__ long long next_block_start(const Workspace& ws, KP kp, int t, long long x, FastDiv bdiv,
+                                                      int32_t block) {
+  const long long k0 = kp(t), rel = x - k0;  // rel < k < 2^32
+  const uint32_t rb = fast_div((uint32_t)rel, bdiv);
   if ((long long)rb * block == rel) return x;
-  return kp + min((long long)ws.desc(t).k, ((long long)rb + 1) * block);
+  return k0 + min((long long)ws.desc(t).k, ((long long)rb + 1) * block);
 }
 
 template <typename I>
 __global__ __launch_bounds__(256) void k_quant(Workspace ws, float* __restrict__ e,
                                                const I* __restrict__ idx, int8_t* __restrict__ q,
-                                               float* __restrict__ scales, int32_t block, long long ktotal) {
+                                               float* __restrict__ scales, int32_t block, FastDiv bdiv, long long ktotal) {
   // blocks that reach into the span: one may start at each position, one more may have started before
   __shared__ uint32_t amax[kQuantSpan + 1];
+  // Which tensor a kept position belongs to is a binary search over the tensors' first positions:
+  // out of LDS, not a chain of dependent loads from memory, when there are several tensors. Their
+  // first blocks and their routes are staged with them.
+  __shared__ uint32_t s_kp[kQuantLdsTensors], s_sp[kQuantLdsTensors];
+  __shared__ uint8_t s_small[kQuantLdsTensors];
   const int tid = threadIdx.x, lane = tid & 63;
+  const bool staged = ws.T > 1 && ws.T <= kQuantLdsTensors;  // uniform over the grid
+  if (staged) {
+    for (int t = tid; t < ws.T; t += 256) {
+      s_kp[t] = (uint32_t)ws.desc(t).kprefix;  // both below 2^32
+      s_sp[t] = (uint32_t)ws.desc(t).sprefix;
+      s_small[t] = ws.desc(t).small ? 1 : 0;
+    }
+    __syncthreads();
+  }
+  auto kp = [&](int i) -> long long { return staged ? (long long)s_kp[i] : (long long)ws.desc(i).kprefix; };
+  auto sp = [&](int i) -> long long { return staged ? (long long)s_sp[i] : (long long)ws.desc(i).sprefix; };
+  auto small = [&](int i) -> bool { return staged ? s_small[i] != 0 : ws.desc(i).small != 0; };
   const long long lo = (long long)blockIdx.x * kQuantSpan, hi = min(ktotal, lo + kQuantSpan);
+  const bool own = block <= kQuantSharedBlock;  // the workgroup codes its own positions
+  constexpr int kU = kQuantSpan / 256;  // strides of 256 positions whose loads are in flight together
+  // its own entries are asked for before anything else: nothing below depends on them until the codes
+  float v_own[kU];
+  I at_own[kU];
+#pragma unroll
+  for (int u = 0; u < kU; ++u) {
+    const long long j = lo + u * 256 + tid;
+    v_own[u] = (own && j < hi) ? ws.kept_val[j] : 0.0f;
+    at_own[u] = (own && j < hi) ? idx[j] : (I)0;
+  }
+  const int t_lo = find_last_le(ws.T, lo, 0, kp);  // one search; the tensors after it by hint
+  const int t_hi = hi < ktotal ? find_last_le(ws.T, hi, t_lo, kp) : ws.T - 1;
+  const long long e_hi = hi < ktotal ? next_block_start(ws, kp, t_hi, hi, bdiv, block) : ktotal;
   long long m_lo, m_hi, c_lo, c_hi;  // positions read for the maxima, positions coded
-  if (block <= kQuantSharedBlock) {
-    m_lo = this_block_start(ws, lo, block);
-    m_hi = next_block_start(ws, hi, block, ktotal);
+  if (own) {
+    m_lo = kp(t_lo) + (long long)fast_div((uint32_t)(lo - kp(t_lo)), bdiv) * block;  // start of the block that holds lo
+    m_hi = e_hi;
     c_lo = lo;
     c_hi = hi;
   } else {
-    m_lo = c_lo = next_block_start(ws, lo, block, ktotal);
-    m_hi = c_hi = next_block_start(ws, lo + kQuantSpan, block, ktotal);
-    if (c_lo >= c_hi) return;  // no block starts here
+    m_lo = c_lo = next_block_start(ws, kp, t_lo, lo, bdiv, block);
+    m_hi = c_hi = e_hi;
+    if (c_lo >= c_hi) return;  // no block starts here (uniform over the workgroup)
   }
-  const int t_s = find_last_le(ws.T, m_lo, 0, [&](int i) { return (long long)ws.desc(i).kprefix; });
-  const long long blk_s = ws.desc(t_s).sprefix + (uint32_t)(m_lo - ws.desc(t_s).kprefix) / (uint32_t)block;
+  const int t_s = find_last_le(ws.T, m_lo, t_lo, kp);
+  // a span that only small tensors reach into has nothing to do here (they are coded by k_finish):
+  // with many small tensors that is most workgroups, and their per-position searches were the
+  // longest thing in the launch
+  {
+    int general = 0;
+    for (int t = t_s + tid; t <= t_hi; t += 256) general |= small(t) ? 0 : 1;
+    if (__syncthreads_or(general) == 0) return;
+  }
+  const long long blk_s = sp(t_s) + fast_div((uint32_t)(m_lo - kp(t_s)), bdiv);
   for (int b = tid; b < kQuantSpan + 1; b += 256) amax[b] = 0u;
   __syncthreads();
-  for (long long j0 = m_lo; j0 < m_hi; j0 += 256) {  // uniform trip count
-    const long long j = j0 + tid;
-    bool on = j < m_hi;
-    uint32_t key = 0u, bl = 0u;
-    if (on) {
-      const int t = find_last_le(ws.T, j, t_s, [&](int i) { return (long long)ws.desc(i).kprefix; });
-      on = !ws.desc(t).small;  // coded by k_finish
-      bl = (uint32_t)(ws.desc(t).sprefix - blk_s) + (uint32_t)(j - ws.desc(t).kprefix) / (uint32_t)block;
-      if (on) key = key_of(ws.kept_val[j]);
-    }
-    // nearly always the wavefront's 64 consecutive entries lie in one block: one atomic then
-    const uint64_t act = __ballot(on);
-    if (act == 0ull) continue;
-    const uint32_t bl0 = (uint32_t)__builtin_amdgcn_readlane((int)bl, __ffsll((unsigned long long)act) - 1);
-    if (__ballot(on && bl != bl0) == 0ull) {
-      uint32_t m = key;
+  constexpr int kM = 8;  // the same for the maxima: a block before and a block after the span
+  for (long long j0 = m_lo; j0 < m_hi; j0 += 256 * kM) {  // uniform trip count
+    bool on[kM];
+    uint32_t bl[kM];
+    float v[kM];
 #pragma unroll
-      for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
-      if (lane == 0) atomicMax(&amax[bl0], m);
-    } else if (on) {
-      atomicMax(&amax[bl], key);
+    for (int u = 0; u < kM; ++u) {
+      const long long j = j0 + u * 256 + tid;
+      on[u] = j < m_hi;
+      bl[u] = 0u;
+      v[u] = 0.0f;
+      if (on[u]) {
+        const int t = find_last_le_in(t_s, t_hi, j, kp);
+        on[u] = !small(t);  // small tensors are coded by k_finish
+        bl[u] = (uint32_t)(sp(t) - blk_s) + fast_div((uint32_t)(j - kp(t)), bdiv);
+        if (on[u]) v[u] = ws.kept_val[j];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kM; ++u) {
+      const uint32_t key = key_of(v[u]);
+      // nearly always the wavefront's 64 consecutive entries lie in one block: one atomic then
+      const uint64_t act = __ballot(on[u]);
+      if (act == 0ull) continue;
+      const uint32_t bl0 = (uint32_t)__builtin_amdgcn_readlane((int)bl[u], __ffsll((unsigned long long)act) - 1);
+      if (__ballot(on[u] && bl[u] != bl0) == 0ull) {
+        uint32_t m = on[u] ? key : 0u;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+        if (lane == 0) atomicMax(&amax[bl0], m);
+      } else if (on[u]) {
+        atomicMax(&amax[bl[u]], key);
+      }
     }
   }
   __syncthreads();
-  for (long long j0 = c_lo; j0 < c_hi; j0 += 256) {
-    const long long j = j0 + tid;
-    if (j >= c_hi) continue;
-    const int t = find_last_le(ws.T, j, t_s, [&](int i) { return (long long)ws.desc(i).kprefix; });
-    if (ws.desc(t).small) continue;
-    const uint32_t rel = (uint32_t)(j - ws.desc(t).kprefix);  // < k < 2^32: 32-bit division
-    const uint32_t rblk = rel / (uint32_t)block;
-    const long long blk = ws.desc(t).sprefix + rblk;
-    const uint32_t akey = amax[blk - blk_s];
-    const bool finite = akey < 0x7F800000u;
-    float s = __fdiv_rn(__uint_as_float(akey), 127.0f);
-    if (!finite || !(s >= 1.17549435e-38f)) s = 0.0f;
-    if (rel == rblk * (uint32_t)block) {
-      scales[blk] = s;
-      if (!finite) ws.flags[0] = 1u;
+  for (long long j0 = c_lo; j0 < c_hi; j0 += 256 * kU) {
+    bool on[kU];
+    uint32_t rel[kU], rblk[kU];
+    long long blk[kU];
+    float v[kU];
+    I at[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const long long j = j0 + u * 256 + tid;
+      on[u] = j < c_hi;
+      rel[u] = rblk[u] = 0u;
+      blk[u] = blk_s;
+      v[u] = 0.0f;
+      at[u] = (I)0;
+      if (on[u]) {
+        const int t = find_last_le_in(t_s, t_hi, j, kp);
+        on[u] = !small(t);
+        rel[u] = (uint32_t)(j - kp(t));  // < k < 2^32
+        rblk[u] = fast_div(rel[u], bdiv);
+        blk[u] = sp(t) + rblk[u];
+        if (on[u]) {
+          v[u] = own ? v_own[u] : ws.kept_val[j];  // own: one batch, j = lo + u * 256 + tid
+          at[u] = own ? at_own[u] : idx[j];
+        }
+      }
     }
-    const float v = ws.kept_val[j];
-    int code = 0;
-    if (s != 0.0f) {
-      float r = rintf(__fdiv_rn(v, s));
-      r = fminf(fmaxf(r, -127.0f), 127.0f);
-      code = (int)r;
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      if (!on[u]) continue;
+      const long long j = j0 + u * 256 + tid;
+      const uint32_t akey = amax[blk[u] - blk_s];
+      const bool finite = akey < 0x7F800000u;
+      float s = __fdiv_rn(__uint_as_float(akey), 127.0f);
+      if (!finite || !(s >= 1.17549435e-38f)) s = 0.0f;
+      if (rel[u] == rblk[u] * (uint32_t)block) {
+        scales[blk[u]] = s;
+        if (!finite) ws.flags[0] = 1u;
+      }
+      int code = 0;
+      if (s != 0.0f) {
+        float r = rintf(__fdiv_rn(v[u], s));
+        r = fminf(fmaxf(r, -127.0f), 127.0f);
+        code = (int)r;
+      }
+      q[j] = (int8_t)code;
+      if (finite) e[(int64_t)at[u]] = __fsub_rn(v[u], __fmul_rn((float)code, s));
     }
-    q[j] = (int8_t)code;
-    if (finite) e[(int64_t)idx[j]] = __fsub_rn(v, __fmul_rn((float)code, s));
   }
 }
 
@@ -1696,12 +1779,13 @@ void launch_quant(const Workspace& ws, float* e, const OutBuf& out, int64_t ktot
     return;
   }
   const dim3 grid((unsigned)((ktotal + kQuantSpan - 1) / kQuantSpan));
+  const FastDiv bdiv = make_fastdiv((uint32_t)out.block);
   if (out.index_bits == 32)
     hipLaunchKernelGGL(k_quant<uint32_t>, grid, dim3(256), 0, s, ws, e, (const uint32_t*)out.indices, out.q,
-                       out.scales, out.block, (long long)ktotal);
+                       out.scales, out.block, bdiv, (long long)ktotal);
   else
     hipLaunchKernelGGL(k_quant<unsigned long long>, grid, dim3(256), 0, s, ws, e,
-                       (const unsigned long long*)out.indices, out.q, out.scales, out.block, (long long)ktotal);
+                       (const unsigned long long*)out.indices, out.q, out.scales, out.block, bdiv, (long long)ktotal);
 }
 
 }  // namespace gc
