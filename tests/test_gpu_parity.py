@@ -631,6 +631,17 @@ def test_many_small_tensors(gc, ctx, oracle):
     assert st["tensors"] == len(sizes)
 
 
+def test_many_tensors_with_large_ones_in_between(gc, ctx, oracle):
+    """More tensors than the kernels stage lookup tables for (1024 in the quantizer, 256 in the
+    aggregate), with tensors of the grid-wide route between runs of small ones: a workgroup's span of
+    kept positions then crosses both kinds, and the position -> tensor searches go through memory."""
+    rng = np.random.Generator(np.random.Philox(key=11))
+    small = [int(x) for x in rng.integers(1, 3000, size=1500)]
+    sizes = small[:700] + [2_000_000] + small[700:701] + [1_300_000, 5] + small[701:] + [3_000_000]
+    st = _multi_case(gc, ctx, oracle, sizes, 0.02, 100, W=2, seed=1900)
+    assert st["tensors"] == len(sizes)
+
+
 # ---------------------------------------------------------------------------------- Eq. 12 / Eq. 9
 def _workers(gc, ctx, oracle, n, k, block, W, seed, bits=32):
     bufs, refs = [], []
