@@ -496,6 +496,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
   __shared__ float tile_mem[kFusedWaves][kFusedTile];
   __shared__ FusedWorker s_wk[kMaxWorkers];
   __shared__ uint32_t s_br0[kMaxWorkers], s_br1[kMaxWorkers];
+  __shared__ int s_next;  // next tile of the range that no wavefront has taken yet
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   constexpr int tshift = TSHIFT;
   constexpr int R = kDecRounds;
@@ -545,6 +546,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
       }
     }
     __syncthreads();
+    if (tid == 0) s_next = kFusedWaves;  // tiles 0 .. waves-1 are taken without the counter
     for (int i = tid; i < (tb + 1) * W; i += kFusedThreads) {  // a tile after a worker's last pair starts at its end
       const int w = i % W;
       const uint32_t b0 = s_br0[w], b1 = s_br1[w];
@@ -761,13 +763,21 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     // pairs arrive in the other (a copy between the sets would have to wait for them).
     FusedTile ha, hb;
     FusedRaw<I> ra[R], rb[R];
+    // The first tile of a wavefront is its own number; after that it takes whichever tile of the
+    // range is next (a counter in LDS), so that the wavefronts reach the end of the range together
+    // whatever their tiles hold.
     int lt_cur = wave;
     auto tile_ok = [&](int ltile) { return ltile < tb && t0 + ltile < ntiles; };
+    auto take_tile = [&]() {
+      int v = 0;
+      if (lane == 0) v = atomicAdd(&s_next, 1);
+      return __builtin_amdgcn_readfirstlane(v);
+    };
     if (tile_ok(lt_cur)) {
       open_tile(lt_cur, ha);
       fetch(ha, 0u, ra);
       while (true) {
-        int lt_next = lt_cur + kFusedWaves;
+        int lt_next = take_tile();
         bool more = tile_ok(lt_next);
         if (more) {
           open_tile(lt_next, hb);
@@ -776,7 +786,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         finish_tile(ha, ra, lt_cur);
         if (!more) break;
         lt_cur = lt_next;
-        lt_next = lt_cur + kFusedWaves;
+        lt_next = take_tile();
         more = tile_ok(lt_next);
         if (more) {
           open_tile(lt_next, ha);
