@@ -102,6 +102,28 @@ def check_aggregate(gc, oracle, ctx, bufs, n, block, codec=0):
     return out, int(multi)
 
 
+def check_apply(gc, oracle, ctx, bufs, out, n, step, seed):
+    """gc_decompress_apply at full size (Eq. 8-9 fused): theta - fl32(step * sum) at every position the
+    buffers name, by the oracle's update on those positions with the aggregate `out` that
+    check_aggregate has just pinned; every other position of theta unchanged, bit for bit."""
+    theta0 = inputs.normal(n, 1.0, seed, DEV)
+    theta = theta0.clone()
+    gc.decompress_apply(ctx, bufs, theta, step)
+    assert gc.sync_status(ctx, raise_on_error=False) == 0
+    union = torch.unique(torch.cat([_idx64(b) for b in bufs]))
+    want = theta0[union].cpu().numpy()
+    assert oracle.apply(want, out[union].cpu().numpy(), step) == 0
+    got = theta[union].cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), "updated parameters differ"
+    changed_in_union = int((want.view(np.uint32) != theta0[union].cpu().numpy().view(np.uint32)).sum())
+    changed = 0
+    for a in range(0, n, CH):
+        b = min(n, a + CH)
+        changed += int(torch.count_nonzero(theta[a:b].view(torch.int32) != theta0[a:b].view(torch.int32)))
+    assert changed == changed_in_union, "a parameter outside the named positions changed"
+    del theta, theta0
+
+
 def shifted(gc, buf, delta, n):
     """A second worker's buffer made from `buf`: same codes and scales, indices moved by delta."""
     idx = _idx64(buf) + delta
@@ -169,6 +191,8 @@ def test_config5_sixteen_independent_workers(gc, oracle, progress):
     # independent workers mostly name different positions; the union is nearly 16 k
     union = torch.unique(torch.cat([_idx64(b) for b in bufs])).numel()
     assert 15 * k < union < 16 * k
+    progress("config 5: decompress_apply(W=16) on 28 GB of parameters")
+    check_apply(gc, oracle, ctx, bufs, out, wl.n, 0.01, 55)
     del out
     ctx.destroy()
 
@@ -205,6 +229,9 @@ def test_config4_ten_steps_sixteen_workers(gc, oracle, progress):
         if step == 0 or last:
             progress(f"config 4: step {step}, decompress_sum(W=16)")
             out, _ = check_aggregate(gc, oracle, ctx, bufs, wl.n, wl.block)
+            if last:  # 330 pairs per 4096 parameters: the filling at which the update runs in one kernel
+                progress("config 4: decompress_apply(W=16)")
+                check_apply(gc, oracle, ctx, bufs, out, wl.n, 1.0 / wl.W, 44)
             del out
     ctx.destroy()
 
