@@ -723,9 +723,16 @@ __global__ __launch_bounds__(256) void k_gather(Workspace ws, const float* __res
         const uint2* __restrict__ rec = ws.slots + grp * (int64_t)ws.slot_stride;
         if (TEAM == 1) {
           for (uint32_t j0 = 0; j0 < cnt; j0 += 8) {  // all loads of a round are issued before the stores
+            // two records per 128-bit load (a group has 8 or a multiple of 16 slots, 64-byte aligned,
+            // and cnt is at most their number: every pair that is read lies inside them)
             uint2 r[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) r[u] = (j0 + u < cnt) ? rec[j0 + u] : make_uint2(0u, 0u);
+            for (int u = 0; u < 4; ++u) {
+              uint4 x = make_uint4(0u, 0u, 0u, 0u);
+              if (j0 + 2 * u < cnt) x = reinterpret_cast<const uint4*>(rec + j0)[u];
+              r[2 * u] = make_uint2(x.x, x.y);
+              r[2 * u + 1] = make_uint2(x.z, x.w);
+            }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
               if (j0 + u < cnt) {
