@@ -271,8 +271,10 @@ gc_status gc_profile_read(gc_ctx* ctx, int32_t id, double* total_ms, int64_t* la
  *   "dec_fused"     the aggregate as one kernel that reads the workers' lists tile by tile (1), as two
  *                   kernels with a packed record stream in between (0), or chosen from the number of
  *                   workers and how the output tiles are filled (-1; default).
- *   "dec_fused_tile"  the one-kernel aggregate's tile: 2048 floats, 8 wavefronts per workgroup (1),
- *                   4096 floats, 4 wavefronts (0), or chosen from the filling (-1; default).
+ *   "dec_fused_tile"  the one-kernel aggregate's launch shape: two workgroups per compute unit whose
+ *                   wavefronts prepare a range of tiles together and then sum it (1: for crowded
+ *                   tiles), one workgroup with two wavefronts that only prepare the next range (0: for
+ *                   thinly filled tiles), or chosen from the filling and the number of workers (-1; default).
  *   "apply_dense_min"  fused apply: an output tile with at least this many pairs per 4096 floats is
  *                   read and rewritten whole instead of position by position (1..2^30; default 128).
  * Unknown names or out-of-range values return GC_ERR_INVALID_ARG. */

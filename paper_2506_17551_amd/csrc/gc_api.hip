@@ -67,7 +67,7 @@ struct gc_ctx {
   int64_t opt_dense_wave_block = 1024;  // dense coder: blocks up to this size are held by one wavefront
   int64_t opt_dense_lds_pad = -1;       // dense coder: dynamic LDS per workgroup (occupancy bound); -1: by shape
   int64_t opt_dec_large_tile = -1;      // aggregate: 16384-float tiles (1), 4096-float tiles (0), or by shape (-1)
-  int64_t opt_dec_fused_tile = -1;      // one-kernel aggregate: tiles of 4096 floats (0), of 2048 (1), by filling (-1)
+  int64_t opt_dec_fused_tile = -1;      // one-kernel aggregate: the shape for thin tiles (0), for crowded ones (1), by filling (-1)
   int64_t opt_dec_fused = -1;           // aggregate: the one-kernel route without the record stream (1), the two-kernel route (0), by filling (-1)
   int64_t opt_apply_dense_min = 128;    // fused apply: tiles with at least this many records per 4096 floats are rewritten whole
   // profiling
@@ -642,10 +642,11 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   // merged record stream. Its cost per tile grows with the number of workers (every lane looks its
   // pair up among W segments), so it is taken up to 32 workers: measured at n = 5e8, 4 to 32 workers,
   // 3 to 2000 pairs per 4096 floats, it is ahead of the two-kernel route everywhere (1.3B at 0.5 %,
-  // 16 workers: 1.63 against 1.82 ms; 7B at 0.1 %: 5.6 against 6.2 ms), and behind it from 48 workers on.
-  // Tiles of 2048 floats where they are crowded, 4096 where thinly filled.
+  // 16 workers: 1.6 against 1.8 ms; 7B at 0.1 %: 5.35 against 6.2 ms), and behind it from 48 workers on.
+  // Its shape with preparing wavefronts where tiles are thinly filled, the cooperative one where they
+  // are crowded or the workers many.
   // The in-place update is faster in one kernel only in a middle band of fillings (at 16 workers,
-  // 330 pairs per 4096 floats: 0.98 against 1.21 ms; thin and very crowded tiles: the reverse).
+  // 330 pairs per 4096 floats: 0.96 against 1.21 ms; thin and very crowded tiles: the reverse).
   // The variant that allocates nothing always takes the two-kernel route: that is the route whose
   // scratch arrays it provides.
   const double ppt = (double)nrec * 4096.0 / (double)(n > 0 ? n : 1);  // pairs per 4096 floats of output
@@ -655,8 +656,8 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
   else if (ctx->opt_dec_fused >= 0) fused = ctx->opt_dec_fused == 1;
   else if (apply) fused = W <= 32 && ppt >= 96.0 && ppt <= 400.0;
   else fused = W <= 32 || (thin && n <= (int64_t(1) << 22));
-  const int fused_small_tile = ctx->opt_dec_fused_tile >= 0 ? (int)ctx->opt_dec_fused_tile
-                                                            : ((ppt >= 160.0 || W > 16 || apply) ? 1 : 0);
+  const int fused_crowded = ctx->opt_dec_fused_tile >= 0 ? (int)ctx->opt_dec_fused_tile
+                                                         : ((ppt >= 128.0 || W > 16 || apply) ? 1 : 0);
   if (fused) {
     // no record stream, no workspace (multi-tensor buffers bring their small prefix tables)
     DecPlan* Df = nullptr;
@@ -669,7 +670,7 @@ gc_status decompress_impl(gc_ctx* ctx, const gc_buf* bufs, int32_t W, const int6
     launch_dec_fused(a, W, ib, block, codec, staleness ? 1 : 0, n, Df ? (const long long*)Df->kprefix.p : nullptr,
                      Df ? (const long long*)Df->sprefix.p : nullptr, Df ? (const long long*)Df->qprefix.p : nullptr,
                      Df ? T : 1, out, apply ? 1 : 0, c_apply,
-                     fused_small_tile, s);
+                     fused_crowded, s);
     return launch_status();
   }
   const size_t rec_bytes = sizeof(uint2) * (size_t)std::max<int64_t>(nrec, 1);

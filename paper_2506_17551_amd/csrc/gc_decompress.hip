@@ -429,10 +429,13 @@ struct FusedWorker {  // one worker's arrays, copied to LDS so that a lane can i
   uint32_t k;
 };
 
-// Tiles of 4096 floats and 4 wavefronts per workgroup where tiles are thinly filled; tiles of 2048
-// floats and 8 wavefronts (twice as many tiles in flight per compute unit) where they are crowded.
-constexpr int kFusedTileShift = kDecMinTileShift, kFusedWaves = 4;
-constexpr int kFusedTileShiftSmall = 11, kFusedWavesSmall = 8;
+// Tiles of 2048 floats, one per wavefront, in two shapes. Crowded tiles: two workgroups of 8
+// wavefronts per compute unit, all of which prepare a range together and then take its tiles (the
+// first pass over a crowded range's indices needs every lane). Thinly filled tiles: one workgroup of
+// 14 tile wavefronts and 2 that only prepare the next range, so the 14 never stop writing.
+constexpr int kFusedTileShift = 11;
+constexpr int kFusedWavesCrowded = 8;
+constexpr int kFusedWavesThin = 14, kFusedPrepThin = 2;
 constexpr uint32_t kNoPair = 0xFFFFFFFFu;
 constexpr int kFusedLdsTensors = 256;  // prefix tables of up to this many tensors are staged in LDS (3 KB)
 
@@ -483,26 +486,39 @@ __device__ __forceinline__ void fused_select(const FusedTile& h, int W, uint32_t
 }
 
 // MODE 0: out[tile] = sum (dense write).  MODE 1: theta[i] -= c * sum[i] at the touched i only.
-template <typename I, int MODE, int TSHIFT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 2, WAVES / 2))) void k_dec_fused(DecArgs a, int W, int tb, int32_t block, FastDiv bdiv, int64_t ntiles,
-                                                             int64_t nranges, int codec, int weighted, int64_t n,
-                                                             const long long* __restrict__ kprefix,
-                                                             const long long* __restrict__ sprefix,
-                                                             const long long* __restrict__ qprefix, int T,
-                                                             float* __restrict__ out, float c_apply) {
-  extern __shared__ uint32_t s_dyn[];      // [tb + 1][W]: first pair of worker w at or after local tile t
-  uint32_t* s_lo = s_dyn;
-  constexpr int kFusedTile = 1 << TSHIFT, kFusedWaves = WAVES, kFusedThreads = WAVES * 64;
+// PROD > 0 adds that many wavefronts that do nothing but prepare: while the WAVES others sum and
+// write the tiles of one range out of one table, they search the brackets of the workgroup's next
+// range and fill the other table, each for its own share of the workers and without a word to the
+// others, so that the tile wavefronts never stop writing (two tables, one barrier per range). With
+// PROD = 0 all wavefronts prepare a range together, then take its tiles.
+template <typename I, int MODE, int TSHIFT, int WAVES, int PROD>
+__device__ __forceinline__ void dec_fused_body(const DecArgs& a, int W, int tb, int32_t block, FastDiv bdiv, int64_t ntiles,
+                                               int64_t nranges, int codec, int weighted, int64_t n,
+                                               const long long* __restrict__ kprefix,
+                                               const long long* __restrict__ sprefix,
+                                               const long long* __restrict__ qprefix, int T,
+                                               float* __restrict__ out, float c_apply) {
+  // one table, or two with preparing wavefronts, of [tb + 1][W]: first pair of worker w at or after local tile t
+  extern __shared__ uint32_t s_dyn[];
+  constexpr int kFusedTile = 1 << TSHIFT, kFusedWaves = WAVES, kFusedThreads = (WAVES + PROD) * 64;
+  constexpr int kBuild = PROD ? 64 : kFusedThreads;  // threads that prepare a range together
   __shared__ float tile_mem[kFusedWaves][kFusedTile];
   __shared__ FusedWorker s_wk[kMaxWorkers];
   __shared__ uint32_t s_br0[kMaxWorkers], s_br1[kMaxWorkers];
-  __shared__ int s_next;  // next tile of the range that no wavefront has taken yet
+  __shared__ int s_next_tile[2];  // per table: next tile of the range that no wavefront has taken yet
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int btid = PROD ? lane : tid;  // number of this thread among those that prepare together
+  const int tab_len = (tb + 1) * W;
+  // the workers this thread's group prepares: all of them, or the share of its preparing wavefront
+  const int w_per = PROD ? (W + PROD - 1) / PROD : W;
+  const int w_begin = PROD ? min(W, max(0, wave - WAVES) * w_per) : 0;
+  const int w_end = PROD ? min(W, w_begin + w_per) : W;
+  const int Wl = w_end - w_begin;
   constexpr int tshift = TSHIFT;
   constexpr int R = kDecRounds;
   static_assert(R == 4, "fused_select is dispatched for up to four rounds");
   // indices per lane in flight in the first pass: what the register budget of the shape allows
-  constexpr int kScan = WAVES > 4 ? 8 : (sizeof(I) == 4 ? 32 : 16);
+  constexpr int kScan = (WAVES > 4 || PROD) ? 8 : (sizeof(I) == 4 ? 32 : 16);
   // per-tensor prefix tables of a multi-tensor buffer: a pair's tensor is found by a binary search,
   // a chain of dependent reads that is ten times shorter out of LDS than out of memory
   __shared__ uint32_t s_tp[3][kFusedLdsTensors];
@@ -523,43 +539,48 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     s_wk[tid] = f;
   }
   __syncthreads();
-  float* lt = tile_mem[wave];
+  float* lt = tile_mem[wave < kFusedWaves ? wave : 0];  // the preparing wavefront has no tile
   int G = 64;  // lanes per worker in the first pass over a range's indices
-  while (G > 1 && G * W > kFusedThreads) G >>= 1;
-  const int gl = tid & (G - 1);
+  while (G > 1 && G * Wl > kBuild) G >>= 1;
+  const int gl = btid & (G - 1);
   // lanes whose left neighbour is not their predecessor in the worker's list (first of a group), or is
   // out of reach of the row shift (first of a row of 16): they load the predecessor's index themselves
   const bool edge = gl == 0 || (lane & 15) == 0;
   const uint32_t sign_bytes = (uint32_t)((block + 7) / 8);
 
-  for (int64_t r = blockIdx.x; r < nranges; r += gridDim.x) {
+  // the threads that prepare wait for each other: one wavefront for itself, else the workgroup
+  auto build_sync = [&]() {
+    if (PROD) wave_sync(); else __syncthreads();
+  };
+  // ---- prepares range r: its table of segment starts and its tile counter
+  auto build = [&](int64_t r, uint32_t* s_lo, int* s_next) {
     const int64_t t0 = r * tb;
     // every worker's first pair at or after the start of this range and of the next one
-    for (int s0 = 0; s0 < 2 * W; s0 += kFusedThreads / 8) {  // eight lanes per search
-      const int s = s0 + tid / 8;
-      const bool on = s < 2 * W;
-      const int w = on ? (s < W ? s : s - W) : 0;
-      const unsigned long long target = ((unsigned long long)(r + (s < W ? 0 : 1)) * (unsigned long long)tb) << tshift;
+    for (int s0 = 0; s0 < 2 * Wl; s0 += kBuild / 8) {  // eight lanes per search
+      const int s = s0 + btid / 8;
+      const bool on = s < 2 * Wl;
+      const int w = on ? w_begin + (s < Wl ? s : s - Wl) : 0;
+      const unsigned long long target = ((unsigned long long)(r + (s < Wl ? 0 : 1)) * (unsigned long long)tb) << tshift;
       const uint32_t b = lower_bound_idx8<I>(static_cast<const I*>(s_wk[w].idx), on ? s_wk[w].k : 0u, target, lane);
-      if (on && (tid & 7) == 0) {
-        if (s < W) s_br0[w] = b; else s_br1[w] = b;
+      if (on && (btid & 7) == 0) {
+        if (s < Wl) s_br0[w] = b; else s_br1[w] = b;
       }
     }
-    __syncthreads();
-    if (tid == 0) s_next = kFusedWaves;  // tiles 0 .. waves-1 are taken without the counter
-    for (int i = tid; i < (tb + 1) * W; i += kFusedThreads) {  // a tile after a worker's last pair starts at its end
-      const int w = i % W;
+    build_sync();
+    if (btid == 0 && w_begin == 0) *s_next = kFusedWaves;  // tiles 0 .. waves-1 are taken without the counter
+    for (int i = btid; i < (tb + 1) * Wl; i += kBuild) {  // a tile after a worker's last pair starts at its end
+      const int w = w_begin + i % Wl;
       const uint32_t b0 = s_br0[w], b1 = s_br1[w];
-      s_lo[i] = b1 > b0 ? b1 : b0;
+      s_lo[(i / Wl) * W + w] = b1 > b0 ? b1 : b0;
     }
-    __syncthreads();
+    build_sync();
     // the first pair at or after the start of every tile: pair j opens all tiles after its
     // predecessor's, up to its own. The predecessor's index comes from the lane to the left.
     // Every worker has a group of G consecutive lanes, all workers at once (as many as fit): the
     // whole pass is a few rounds of loads, however many workers there are.
-    for (int w0 = 0; w0 < W; w0 += kFusedThreads / G) {
-      const int w = w0 + tid / G;
-      const bool wn = w < W;
+    for (int w0 = w_begin; w0 < w_end; w0 += kBuild / G) {
+      const int w = w0 + btid / G;
+      const bool wn = w < w_end;
       const I* idx = static_cast<const I*>(s_wk[wn ? w : 0].idx);
       const unsigned long long j0 = wn ? s_br0[w] : 0ull;
       const unsigned long long j1 = wn ? (s_br1[w] > s_br0[w] ? s_br1[w] : s_br0[w]) : 0ull;
@@ -595,9 +616,12 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         }
       }
     }
-    __syncthreads();
+    build_sync();  // the next search rewrites the brackets
+  };
 
-    // ---- the range's tiles, one wavefront each
+  // ---- the tiles of range r, one wavefront each
+  auto consume = [&](int64_t r, const uint32_t* s_lo, int* s_next) {
+    const int64_t t0 = r * tb;
     // segments of local tile `ltile`: worker `lane`'s first pair and count
     auto open_tile = [&](int ltile, FusedTile& h) {
       h.lo = 0u;
@@ -770,7 +794,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     auto tile_ok = [&](int ltile) { return ltile < tb && t0 + ltile < ntiles; };
     auto take_tile = [&]() {
       int v = 0;
-      if (lane == 0) v = atomicAdd(&s_next, 1);
+      if (lane == 0) v = atomicAdd(s_next, 1);
       return __builtin_amdgcn_readfirstlane(v);
     };
     if (tile_ok(lt_cur)) {
@@ -797,8 +821,50 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         lt_cur = lt_next;
       }
     }
-    __syncthreads();  // the table is rewritten for the next range
+  };
+
+  if (PROD) {
+    const bool prepares = wave >= kFusedWaves;
+    int64_t r = blockIdx.x;
+    int cur = 0;
+    if (prepares && r < nranges) build(r, s_dyn, &s_next_tile[0]);
+    __syncthreads();
+    for (; r < nranges; r += gridDim.x, cur ^= 1) {
+      const int64_t rn = r + gridDim.x;
+      if (prepares) {
+        if (rn < nranges) build(rn, s_dyn + (cur ^ 1) * tab_len, &s_next_tile[cur ^ 1]);
+      } else {
+        consume(r, s_dyn + cur * tab_len, &s_next_tile[cur]);
+      }
+      __syncthreads();  // the next range's table is complete, and this one's may be rewritten
+    }
+  } else {
+    for (int64_t r = blockIdx.x; r < nranges; r += gridDim.x) {
+      build(r, s_dyn, &s_next_tile[0]);
+      consume(r, s_dyn, &s_next_tile[0]);
+      __syncthreads();  // the table is rewritten for the next range
+    }
   }
+}
+
+// All wavefronts prepare and take tiles (WAVES / 2 wavefronts per SIMD: two workgroups per compute unit).
+template <typename I, int MODE, int TSHIFT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 2, WAVES / 2))) void k_dec_fused(
+    DecArgs a, int W, int tb, int32_t block, FastDiv bdiv, int64_t ntiles, int64_t nranges, int codec, int weighted,
+    int64_t n, const long long* __restrict__ kprefix, const long long* __restrict__ sprefix,
+    const long long* __restrict__ qprefix, int T, float* __restrict__ out, float c_apply) {
+  dec_fused_body<I, MODE, TSHIFT, WAVES, 0>(a, W, tb, block, bdiv, ntiles, nranges, codec, weighted, n, kprefix, sprefix,
+                                            qprefix, T, out, c_apply);
+}
+
+// With PROD preparing wavefronts: one workgroup per compute unit (its tiles take most of the LDS).
+template <typename I, int MODE, int TSHIFT, int WAVES, int PROD>
+__global__ __launch_bounds__((WAVES + PROD) * 64) void k_dec_fused_prep(
+    DecArgs a, int W, int tb, int32_t block, FastDiv bdiv, int64_t ntiles, int64_t nranges, int codec, int weighted,
+    int64_t n, const long long* __restrict__ kprefix, const long long* __restrict__ sprefix,
+    const long long* __restrict__ qprefix, int T, float* __restrict__ out, float c_apply) {
+  dec_fused_body<I, MODE, TSHIFT, WAVES, PROD>(a, W, tb, block, bdiv, ntiles, nranges, codec, weighted, n, kprefix,
+                                               sprefix, qprefix, T, out, c_apply);
 }
 
 }  // namespace
@@ -825,26 +891,33 @@ int dec_range_tiles(int W, int tshift, int64_t nrec, int64_t n) {
 
 // Tiles per range of the fused kernel: the LDS table holds (tb + 1) * W entries (about 8 KB), and
 // there should be enough ranges to keep two workgroups per compute unit busy. A power of two >= 4.
-int dec_fused_range_tiles(int W, int64_t n, int tshift) {
+int dec_fused_range_tiles(int W, int64_t n, int tshift, int tables) {
   const int64_t ntiles = (n + (int64_t(1) << tshift) - 1) >> tshift;
   int tb = 128;
   while (tb > 4 && ((tb + 1) * W > 2112 || ntiles / tb < 1024)) tb >>= 1;
   return tb;
 }
 
-template <int TSHIFT, int WAVES>
+template <int TSHIFT, int WAVES, int PROD>
 static void launch_fused_shape(const DecArgs& a, int W, int index_bits, int32_t block, int codec, int weighted, int64_t n,
                                const long long* kprefix, const long long* sprefix, const long long* qprefix, int T,
                                float* out, int apply, float c_apply, hipStream_t s) {
-  const int tb = dec_fused_range_tiles(W, n, TSHIFT);
+  const int tb = dec_fused_range_tiles(W, n, TSHIFT, PROD ? 2 : 1);
   const int64_t ntiles = (n + (int64_t(1) << TSHIFT) - 1) >> TSHIFT;
   const int64_t nranges = (ntiles + tb - 1) / tb;
-  const dim3 grid((unsigned)(nranges < 512 ? nranges : 512)), blk(WAVES * 64);
-  const size_t lds = sizeof(uint32_t) * (size_t)(tb + 1) * W;
+  const int64_t wgs = PROD ? 256 : 512;  // one workgroup per compute unit with preparing wavefronts, else two
+  const dim3 grid((unsigned)(nranges < wgs ? nranges : wgs)), blk((WAVES + PROD) * 64);
+  const size_t lds = sizeof(uint32_t) * (size_t)(tb + 1) * W * (PROD ? 2 : 1);
   const FastDiv bdiv = make_fastdiv((uint32_t)block);
-#define GC_LAUNCH_FUSED(ITYPE, MODE)                                                                               \
-  hipLaunchKernelGGL((k_dec_fused<ITYPE, MODE, TSHIFT, WAVES>), grid, blk, lds, s, a, W, tb, block, bdiv, ntiles, nranges, \
-                     codec, weighted, n, kprefix, sprefix, qprefix, T, out, c_apply)
+#define GC_LAUNCH_FUSED(ITYPE, MODE)                                                                                 \
+  do {                                                                                                               \
+    if constexpr (PROD != 0)                                                                                         \
+      hipLaunchKernelGGL((k_dec_fused_prep<ITYPE, MODE, TSHIFT, WAVES, PROD>), grid, blk, lds, s, a, W, tb,            \
+                         block, bdiv, ntiles, nranges, codec, weighted, n, kprefix, sprefix, qprefix, T, out, c_apply); \
+    else                                                                                                             \
+      hipLaunchKernelGGL((k_dec_fused<ITYPE, MODE, TSHIFT, WAVES>), grid, blk, lds, s, a, W, tb, block, bdiv, ntiles,  \
+                         nranges, codec, weighted, n, kprefix, sprefix, qprefix, T, out, c_apply);                    \
+  } while (0)
   if (index_bits == 32) {
     if (apply) GC_LAUNCH_FUSED(uint32_t, 1); else GC_LAUNCH_FUSED(uint32_t, 0);
   } else {
@@ -855,13 +928,13 @@ static void launch_fused_shape(const DecArgs& a, int W, int index_bits, int32_t 
 
 void launch_dec_fused(const DecArgs& a, int W, int index_bits, int32_t block, int codec, int weighted, int64_t n,
                       const long long* kprefix, const long long* sprefix, const long long* qprefix, int T, float* out,
-                      int apply, float c_apply, int small_tile, hipStream_t s) {
-  if (small_tile)
-    launch_fused_shape<kFusedTileShiftSmall, kFusedWavesSmall>(a, W, index_bits, block, codec, weighted, n, kprefix, sprefix,
+                      int apply, float c_apply, int crowded, hipStream_t s) {
+  if (crowded)
+    launch_fused_shape<kFusedTileShift, kFusedWavesCrowded, 0>(a, W, index_bits, block, codec, weighted, n, kprefix, sprefix,
                                                                qprefix, T, out, apply, c_apply, s);
   else
-    launch_fused_shape<kFusedTileShift, kFusedWaves>(a, W, index_bits, block, codec, weighted, n, kprefix, sprefix, qprefix,
-                                                     T, out, apply, c_apply, s);
+    launch_fused_shape<kFusedTileShift, kFusedWavesThin, kFusedPrepThin>(a, W, index_bits, block, codec, weighted, n, kprefix,
+                                                                         sprefix, qprefix, T, out, apply, c_apply, s);
 }
 
 void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift, int32_t block, int64_t ntiles,

@@ -285,7 +285,7 @@ void launch_dec_pack(const DecArgs& a, int W, int index_bits, int tb, int tshift
 // prefix tables of multi-tensor buffers (T > 1), else null.
 void launch_dec_fused(const DecArgs& a, int W, int index_bits, int32_t block, int codec, int weighted, int64_t n,
                       const long long* kprefix, const long long* sprefix, const long long* qprefix, int T, float* out,
-                      int apply, float c_apply, int small_tile, hipStream_t s);
+                      int apply, float c_apply, int crowded, hipStream_t s);
 void launch_dec_tiles(const void* rec, const unsigned long long* tile_start, uint64_t nrec, int tshift, int64_t n,
                       int64_t t_begin, int64_t t_end, float* out, int apply, float c_apply, unsigned apply_dense_min,
                       hipStream_t s);

@@ -35,12 +35,12 @@ def bits(a):
 
 
 # Every way the aggregate can be routed: the choice by shape, the two-kernel route (record stream)
-# with either tile size, the one-kernel route with either tile size. "auto" comes last so that a
+# with either tile size, the one-kernel route in either launch shape. "auto" comes last so that a
 # shared context is left as it was.
 ROUTES = [("two-kernel 4096", {"dec_fused": 0, "dec_large_tile": 0}),
           ("two-kernel 16384", {"dec_fused": 0, "dec_large_tile": 1}),
-          ("one-kernel 4096", {"dec_fused": 1, "dec_fused_tile": 0}),
-          ("one-kernel 2048", {"dec_fused": 1, "dec_fused_tile": 1}),
+          ("one-kernel thin", {"dec_fused": 1, "dec_fused_tile": 0}),
+          ("one-kernel crowded", {"dec_fused": 1, "dec_fused_tile": 1}),
           ("auto", {})]
 
 
@@ -682,8 +682,8 @@ def test_fused_aggregate_and_apply(gc, ctx, oracle, weighted):
     # reach) and rewritten whole (apply_dense_min = 1); 128 is the default
     R = dict(ROUTES)
     for step, route, dmin in ((0.0, "auto", 128), (0.01, "two-kernel 4096", 1 << 30), (0.01, "two-kernel 16384", 1 << 30),
-                              (0.01, "two-kernel 4096", 1), (0.01, "two-kernel 16384", 1), (0.01, "one-kernel 4096", 128),
-                              (0.01, "one-kernel 2048", 128), (1.0 / W, "auto", 128), (1.0 / W, "auto", 1 << 30)):
+                              (0.01, "two-kernel 4096", 1), (0.01, "two-kernel 16384", 1), (0.01, "one-kernel thin", 128),
+                              (0.01, "one-kernel crowded", 128), (1.0 / W, "auto", 128), (1.0 / W, "auto", 1 << 30)):
         set_route(ctx, R[route])
         ctx.set_option("apply_dense_min", dmin)
         theta = theta0.to(DEV).clone()
