@@ -416,7 +416,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_dec_tiles(const uint2* __restric
 // two-kernel call moves at 7B, and a third of what it moves at 1.3B.
 //
 // A tile is a chain of memory round trips (table, pairs, adds, store), and a compute unit holds only
-// eight tiles at a time, so the chain is kept short: a lane finds the worker of its pair by
+// 14 or 16 tiles at a time, so the chain is kept short: a lane finds the worker of its pair by
 // comparing its flat position with the W segment starts broadcast from registers (no search through
 // LDS), the pairs of the wavefront's NEXT tile are requested before the current tile is summed (what
 // arrives is kept raw - index, code byte, scale - and decoded when it is used), and the first pass
