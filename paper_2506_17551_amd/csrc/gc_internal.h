@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "gc_fastdiv.h"
 
 namespace gc {
 
@@ -216,21 +217,7 @@ __device__ __forceinline__ uint32_t mbcnt64(uint64_t m) {
 }
 __device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
 
-// Exact unsigned 32-bit division by a divisor fixed for the launch, as a multiplication and two
-// shifts (Granlund and Montgomery 1994, the round-up multiplier with an add-back): a pair's block is
-// (pair number) / block, once per pair, and the hardware has no integer divide.
-struct FastDiv {
-  uint32_t m, s1, s2;
-};
-inline FastDiv make_fastdiv(uint32_t d) {  // 1 <= d < 2^31
-  uint32_t l = 0;
-  while ((1ull << l) < d) ++l;
-  FastDiv f;
-  f.m = (uint32_t)((((1ull << l) - d) << 32) / d + 1ull);
-  f.s1 = l < 1u ? l : 1u;
-  f.s2 = l > 1u ? l - 1u : 0u;
-  return f;
-}
+// x / d for the divisor behind f (gc_fastdiv.h): a multiplication and two shifts.
 __device__ __forceinline__ uint32_t fast_div(uint32_t x, FastDiv f) {
   const uint32_t t = __umulhi(f.m, x);
   return (t + ((x - t) >> f.s1)) >> f.s2;

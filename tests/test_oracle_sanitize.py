@@ -28,3 +28,19 @@ def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
     assert run.returncode == 0, run.stdout + run.stderr
     assert "oracle sanitizer run: ok" in run.stdout
     assert "runtime error" not in run.stderr and "AddressSanitizer" not in run.stderr
+
+
+def test_launch_constant_division_is_exact(tmp_path):
+    """Host logic of the library: the multiply-shift constants that replace `pair / block` in the
+    kernels (csrc/gc_fastdiv.h), compiled for the host and checked against the plain quotient on
+    edge and random dividends for fixed and random divisors."""
+    gxx = shutil.which("g++")
+    if gxx is None:
+        pytest.skip("no g++")
+    exe = str(tmp_path / "fastdiv")
+    built = subprocess.run([gxx, "-std=c++17", "-O2", os.path.join(ROOT, "tests", "san", "fastdiv_main.cpp"), "-o", exe],
+                           capture_output=True, text=True)
+    assert built.returncode == 0, built.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert "0 mismatches" in run.stdout
