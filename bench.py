@@ -689,6 +689,9 @@ def main():
                                   "calibrated on a plain copy; not counted in this run)",
                 "algorithmic_bytes_per_launch": r["main_bytes"], "avg_launch_ms": round(r["km_avg"], 5),
                 "launches": r["km_n"]}
+    if roofline["traffic"]:
+        # the counted bytes over this run's kernel time: what the HBM pins actually carried
+        roofline["frac_counted_traffic"] = round(roofline["traffic"] / (r["km_avg"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     extra = {}
     if r["unplaced_ms"]:
         # the headline figure has the operands where the placement probe put them; a caller that
@@ -739,6 +742,9 @@ def main():
         "kernels": kernels,
         **extra,
     }
+    if dec_traffic:
+        result["roofline_decompress"]["frac_counted_traffic"] = round(
+            dec_traffic / (r["ms_d"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     if cpu is not None:
         result["cpu_baseline"] = cpu
     print(json.dumps(result))
